@@ -1,0 +1,135 @@
+"""CPU oracle for the LCMA GEMM path.  TEST INFRASTRUCTURE ONLY.
+
+Only tests/, __graft_entry__.smoke() and bench.py's cpu_baseline leg may import
+this package.  It shares no code with the GPU library and never imports it.
+
+The arithmetic lives in lcma_oracle.c (plain C, fp64 / int64, compiled with gcc);
+this module builds it, loads it through ctypes and wraps the calls for numpy
+arrays.  Every wrapper names the passage of the paper it evaluates.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+from . import schemes  # noqa: F401  (re-exported)
+from .schemes import Scheme
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "lcma_oracle.c")
+_LIB = os.path.join(_HERE, "liblcma_oracle.so")
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile lcma_oracle.c with gcc (OpenMP over output rows)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        tmp = _LIB + f".tmp{os.getpid()}"
+        subprocess.check_call(["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-std=c11",
+                               "-Wall", "-o", tmp, _SRC])
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        lib = ctypes.CDLL(_LIB)
+        i64, p, i32 = ctypes.c_int64, ctypes.c_void_p, ctypes.c_int
+        lib.oracle_num_threads.restype = ctypes.c_int
+        for fn in (lib.oracle_gemm_f64, lib.oracle_gemm_i64):
+            fn.argtypes = [i64, i64, i64, p, i64, p, i64, p, i64]
+            fn.restype = None
+        for fn in (lib.oracle_lcma_f64, lib.oracle_lcma_i64):
+            fn.argtypes = [i32, i32, i32, i32, p, p, p, i64, i64, i64, p, i64, p, i64, p, i64]
+            fn.restype = ctypes.c_int
+        lib.oracle_brent_residual.argtypes = [i32, i32, i32, i32, p, p, p, ctypes.POINTER(i64)]
+        lib.oracle_brent_residual.restype = i64
+        _lib = lib
+    return _lib
+
+
+def num_threads() -> int:
+    return int(_load().oracle_num_threads())
+
+
+def _ptr(a: np.ndarray):
+    return ctypes.c_void_p(a.ctypes.data)
+
+
+def _rowmajor(a: np.ndarray, dtype) -> np.ndarray:
+    a = np.asarray(a)
+    if a.dtype != dtype or a.ndim != 2 or a.strides[1] != a.itemsize or a.strides[0] % a.itemsize:
+        a = np.ascontiguousarray(a, dtype=dtype)
+    return a
+
+
+def _ld(a: np.ndarray) -> int:
+    return a.strides[0] // a.itemsize if a.shape[0] > 1 else max(a.shape[1], 1)
+
+
+def gemm(A: np.ndarray, B: np.ndarray) -> np.ndarray:
+    """C = A x B by the triple loop (paper Eq. 1).  int64 inputs stay exact
+    integers; anything else is evaluated in fp64 on the values as given."""
+    integer = A.dtype == np.int64 and B.dtype == np.int64
+    dt = np.int64 if integer else np.float64
+    A, B = _rowmajor(A, dt), _rowmajor(B, dt)
+    M, K = A.shape
+    K2, N = B.shape
+    assert K == K2
+    C = np.empty((M, N), dt)
+    fn = _load().oracle_gemm_i64 if integer else _load().oracle_gemm_f64
+    fn(M, N, K, _ptr(A), _ld(A), _ptr(B), _ld(B), _ptr(C), N)
+    return C
+
+
+def gemm_rows(A: np.ndarray, B: np.ndarray, rows) -> np.ndarray:
+    """Selected rows of C = A x B (same triple loop, on a row subset of A)."""
+    rows = np.asarray(rows, dtype=np.int64)
+    return gemm(np.ascontiguousarray(np.asarray(A)[rows]).astype(np.float64), np.asarray(B).astype(np.float64))
+
+
+def lcma(s: Scheme, A: np.ndarray, B: np.ndarray) -> np.ndarray:
+    """C by the four-stage LCMA workflow (paper Eq. 3-6 / Algorithm 1)."""
+    integer = A.dtype == np.int64 and B.dtype == np.int64
+    dt = np.int64 if integer else np.float64
+    A, B = _rowmajor(A, dt), _rowmajor(B, dt)
+    M, K = A.shape
+    K2, N = B.shape
+    assert K == K2
+    U = np.ascontiguousarray(s.U, np.int32)
+    V = np.ascontiguousarray(s.V, np.int32)
+    W = np.ascontiguousarray(s.W, np.int32)
+    C = np.empty((M, N), dt)
+    fn = _load().oracle_lcma_i64 if integer else _load().oracle_lcma_f64
+    rc = fn(s.m, s.k, s.n, s.R, _ptr(U), _ptr(V), _ptr(W), M, N, K,
+            _ptr(A), _ld(A), _ptr(B), _ld(B), _ptr(C), N)
+    if rc == 1:
+        raise ValueError(f"shape ({M},{N},{K}) is not divisible by the scheme grid ({s.m},{s.n},{s.k})")
+    if rc:
+        raise MemoryError("oracle_lcma: out of memory")
+    return C
+
+
+def brent(s: Scheme):
+    """(number of violated Brent equations, flat index of the first or -1)."""
+    U = np.ascontiguousarray(s.U, np.int32)
+    V = np.ascontiguousarray(s.V, np.int32)
+    W = np.ascontiguousarray(s.W, np.int32)
+    first = ctypes.c_int64(-1)
+    bad = _load().oracle_brent_residual(s.m, s.k, s.n, s.R, _ptr(U), _ptr(V), _ptr(W),
+                                        ctypes.byref(first))
+    return int(bad), int(first.value)
+
+
+def rel_frobenius(C: np.ndarray, Cref: np.ndarray) -> float:
+    """||C - Cref||_F / ||Cref||_F in fp64 (the parity metric)."""
+    C = np.asarray(C, np.float64)
+    Cref = np.asarray(Cref, np.float64)
+    den = float(np.sqrt(np.sum(Cref * Cref)))
+    num = float(np.sqrt(np.sum((C - Cref) ** 2)))
+    return num / den if den > 0 else num
