@@ -1,0 +1,157 @@
+/*
+ * lcma.h - C ABI of the MI355X (gfx950) lower-complexity matrix multiplication library.
+ *
+ * The library computes C = A x B (paper Eq. 1) either with a plain MFMA GEMM or with
+ * an LCMA, a bilinear scheme L = <m,k,n,R,U,V,W> (paper Sec. 2.1): A, B and C are cut
+ * into m x k, k x n and m x n grids of blocks, R operand combinations are formed
+ * (Eq. 3, Eq. 4), R block products are taken (Eq. 5) and combined into the blocks of C
+ * (Eq. 6).  On the GPU the four stages run as ONE launch: combinations are formed on
+ * chip while tiles are staged, the R products of a group (Sec. 3.2, Group-Parallel
+ * Optimization) stay in registers and W is applied in fp32 before one final rounding.
+ *
+ * General conventions
+ *   - Matrices are row-major, never transposed; ld* are in ELEMENTS (not bytes).
+ *   - A, B, C are DEVICE pointers owned by the caller; the library neither keeps nor
+ *     frees them and they must not overlap.  C is overwritten (no alpha/beta).
+ *   - Scheme handles and everything else are HOST objects.
+ *   - No function aborts or throws; every failure is a status code, and
+ *     lcma_last_error() returns a thread-local description of the latest one.
+ */
+#ifndef LCMA_H
+#define LCMA_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    LCMA_OK = 0,
+    LCMA_ERR_ARG = 1,      /* null pointer, negative size, misaligned pointer or ld  */
+    LCMA_ERR_IO = 2,       /* scheme file cannot be read                              */
+    LCMA_ERR_PARSE = 3,    /* scheme text is malformed                                */
+    LCMA_ERR_BRENT = 4,    /* coefficients do not multiply matrices                   */
+    LCMA_ERR_SHAPE = 5,    /* M, N, K not divisible by the scheme grid times the tile */
+    LCMA_ERR_DTYPE = 6,    /* unknown dtype                                           */
+    LCMA_ERR_NOKERNEL = 7, /* no kernel was generated for this scheme / dtype         */
+    LCMA_ERR_HIP = 8       /* the HIP runtime reported an error                       */
+} lcma_status;
+
+/* Storage type of A, B and C.  Accumulation is always fp32. */
+typedef enum { LCMA_F32 = 0, LCMA_BF16 = 1, LCMA_F16 = 2 } lcma_dtype;
+
+/* Built-in scheme ids, also the return values of lcma_select. */
+enum { LCMA_PLAIN = 0, LCMA_STRASSEN = 1, LCMA_STRASSEN2 = 2, LCMA_LADERMAN = 3 };
+
+typedef struct lcma_scheme lcma_scheme; /* opaque, immutable once loaded */
+
+/* ------------------------------------------------------------------ schemes (Sec. 2.1)
+ * lcma_scheme_load: `spec` is "builtin:strassen" (<2,2,2;7>), "builtin:strassen2"
+ * (<4,4,4;49>, the Kronecker square of Strassen), "builtin:laderman" (<3,3,3;23>), or
+ * the path of a text file: first line `m k n R`, then R lines of m*k integers (U[r],
+ * row-major over (i,l)), R lines of k*n integers (V[r] over (l,j)), R lines of m*n
+ * integers (W[r] over (i,j)); '#' starts a comment; coefficients must fit in int8.
+ * On success *out owns a new handle (release with lcma_scheme_free).  The handle is
+ * NOT yet verified.  Errors: ARG, IO, PARSE.
+ */
+lcma_status lcma_scheme_load(const char *spec, lcma_scheme **out);
+
+/* lcma_scheme_verify: exact integer check of the Brent identity
+ *   sum_r U[r,i,a] V[r,b,j] W[r,c,d] == [a==b][i==c][j==d]
+ * (Eq. 3-5 substituted into Eq. 6, coefficient of A_{i,a}B_{b,j} in C_{c,d}).
+ * Returns LCMA_OK or LCMA_ERR_BRENT; when first_bad is not NULL it receives the flat
+ * row-major index over (i,a,b,j,c,d), extents (m,k,k,n,m,n), of the first violated
+ * equation, or -1.  The verdict is cached in the handle (thread-safe).
+ */
+lcma_status lcma_scheme_verify(const lcma_scheme *s, int64_t *first_bad);
+
+void lcma_scheme_free(lcma_scheme *s);
+
+/* Grid, rank and the non-zero counts ||U||_0, ||V||_0, ||W||_0 (any pointer may be NULL). */
+lcma_status lcma_scheme_info(const lcma_scheme *s, int *m, int *k, int *n, int *R,
+                             int *nnzU, int *nnzV, int *nnzW);
+
+/* Copies the coefficients out: U holds R*m*k, V R*k*n, W R*m*n int8 values (host memory). */
+lcma_status lcma_scheme_coeffs(const lcma_scheme *s, int8_t *U, int8_t *V, int8_t *W);
+
+/* ------------------------------------------------------------------ the GEMM (Eq. 1, Eq. 3-6, Algorithm 2)
+ * lcma_gemm: C[M x N] = A[M x K] x B[K x N] on the current device, asynchronously on
+ * `stream` (a hipStream_t; NULL = the default stream).  `dtype` is the storage type of
+ * all three matrices.  scheme == NULL runs the plain MFMA GEMM; otherwise the scheme
+ * must pass lcma_scheme_verify (run and cached on first use) and have a generated
+ * kernel, and M, N, K must be multiples of m*TM, n*TN, k*TK of that kernel's tile.
+ * Pointers must be 16-byte aligned and lda, ldb, ldc multiples of 16 bytes; each
+ * matrix must span less than 2 GiB.  With 16-bit inputs the combinations of Eq. 3/4 are
+ * formed and multiplied in fp16 (bf16 inputs are converted exactly for |x| in
+ * [2^-14, 65504]; larger magnitudes overflow, smaller ones lose bits); H_r (Eq. 5) and
+ * the W-combination (Eq. 6) stay in fp32 and C is rounded once.
+ * Errors: ARG, BRENT, SHAPE, DTYPE, NOKERNEL, HIP.  Nothing is launched on error.
+ */
+lcma_status lcma_gemm(int64_t M, int64_t N, int64_t K,
+                      const void *A, int64_t lda, const void *B, int64_t ldb,
+                      void *C, int64_t ldc, lcma_dtype dtype,
+                      const lcma_scheme *scheme, void *stream);
+
+/* Generated kernels ("variants": one per scheme x dtype x tile shape x dataflow, Sec. 3.1
+ * Automated Code Generation).  lcma_gemm picks the preferred variant that fits the shape;
+ * lcma_gemm_variant runs the named one (same contract as lcma_gemm; the scheme is the one
+ * the variant was generated for).  Names look like "strassen_bf16_t128x64x16_c7".
+ */
+int lcma_variant_count(void);
+const char *lcma_variant_name(int index); /* NULL when out of range */
+/* Describes variant `index`: builtin scheme id, dtype, tile sizes and the multiples of
+ * M, N, K it needs (any pointer may be NULL). */
+lcma_status lcma_variant_info(int index, int *scheme_id, int *dtype, int *TM, int *TN, int *TK,
+                              int *mult_M, int *mult_N, int *mult_K);
+lcma_status lcma_gemm_variant(const char *variant, int64_t M, int64_t N, int64_t K,
+                              const void *A, int64_t lda, const void *B, int64_t ldb,
+                              void *C, int64_t ldc, void *stream);
+
+/* ------------------------------------------------------------------ Decision Module (Sec. 3.3)
+ * lcma_select: predicted-fastest algorithm for the shape on MI355X among
+ * {plain, <2,2,2;7>, <4,4,4;49>, <3,3,3;23>}; returns a built-in scheme id, or a
+ * negative value on bad arguments.  Pure host arithmetic.
+ */
+int lcma_select(int64_t M, int64_t N, int64_t K, lcma_dtype dtype);
+
+/* The hardware tuple of Sec. 3.3: multiply rate, add rate (operations/s) and off-chip
+ * bandwidth in ELEMENTS/s of the dtype. */
+typedef struct { double flops_mul, flops_add, beta; } lcma_hw;
+/* Published MI355X figures for a dtype (dense MFMA peak, fp32 vector rate, 8 TB/s). */
+lcma_status lcma_hw_mi355x(lcma_dtype dtype, lcma_hw *out);
+
+/* Per-stage operation and element-traffic counts of Table 2, and the stage times of the
+ * roofline rule of Sec. 3.3 (time = max(flops/rate, elements/beta)). Index: 0 Combine A,
+ * 1 Combine B, 2 GEMM, 3 Combine H.  scheme == NULL gives the standard GEMM in slot 2. */
+typedef struct { double flops[4], elems[4], seconds[4]; } lcma_stage_costs;
+lcma_status lcma_model_stages(const lcma_scheme *s, int64_t M, int64_t N, int64_t K,
+                              const lcma_hw *hw, lcma_stage_costs *out);
+/* Left-hand sides of Eq. 8 (plain GEMM intensity), Eq. 9 and Eq. 10 (fused Combine H),
+ * to be compared with flops_mul / beta. */
+lcma_status lcma_model_intensity(const lcma_scheme *s, int64_t M, int64_t N, int64_t K,
+                                 double *eq8, double *eq9, double *eq10);
+/* The model lcma_select uses for THIS library's fused kernels: predicted seconds of the
+ * preferred variant of built-in `scheme_id` (LCMA_PLAIN..LCMA_LADERMAN) on MI355X, or a
+ * negative value when no variant fits the shape. */
+double lcma_predict_seconds(int scheme_id, int64_t M, int64_t N, int64_t K, lcma_dtype dtype);
+
+/* ------------------------------------------------------------------ tile scheduling (Sec. 3.2, Split-Group Parallelism)
+ * Wave counts for `groups` groups of R tile-products on `units` compute units:
+ * tile-level scheduling needs ceil(groups*R/units) waves, group-level ceil(groups/units)*R.
+ */
+lcma_status lcma_sched_waves(int64_t groups, int R, int units,
+                             int64_t *tile_level, int64_t *group_level);
+/* Split-Group assignment: tile-products are numbered group-major (job = group*R + r) and
+ * unit u of `units` owns the contiguous range [*begin, *end) with capacity
+ * ceil(total/units); a group can therefore straddle at most two units. */
+lcma_status lcma_sched_range(int64_t groups, int R, int units, int unit,
+                             int64_t *begin, int64_t *end);
+
+const char *lcma_status_str(lcma_status st);
+const char *lcma_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LCMA_H */

@@ -1,0 +1,219 @@
+"""Thin ctypes binding of liblcma.so: argument marshalling only, same names as include/lcma.h.
+
+Every step of the GEMM runs in the library's HIP kernels.  There is no CPU or PyTorch
+fallback: if the shared library is missing, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "liblcma.so")
+
+LCMA_OK = 0
+STATUS_NAMES = ["OK", "ERR_ARG", "ERR_IO", "ERR_PARSE", "ERR_BRENT", "ERR_SHAPE", "ERR_DTYPE",
+                "ERR_NOKERNEL", "ERR_HIP"]
+(LCMA_ERR_ARG, LCMA_ERR_IO, LCMA_ERR_PARSE, LCMA_ERR_BRENT, LCMA_ERR_SHAPE, LCMA_ERR_DTYPE,
+ LCMA_ERR_NOKERNEL, LCMA_ERR_HIP) = range(1, 9)
+LCMA_F32, LCMA_BF16, LCMA_F16 = 0, 1, 2
+LCMA_PLAIN, LCMA_STRASSEN, LCMA_STRASSEN2, LCMA_LADERMAN = 0, 1, 2, 3
+DTYPE_IDS = {"f32": LCMA_F32, "bf16": LCMA_BF16, "f16": LCMA_F16}
+SCHEME_NAMES = {LCMA_PLAIN: "plain", LCMA_STRASSEN: "strassen", LCMA_STRASSEN2: "strassen2",
+                LCMA_LADERMAN: "laderman"}
+
+EXPORTS = [
+    "lcma_scheme_load", "lcma_scheme_verify", "lcma_scheme_free", "lcma_scheme_info", "lcma_scheme_coeffs",
+    "lcma_gemm", "lcma_variant_count", "lcma_variant_name", "lcma_variant_info", "lcma_gemm_variant",
+    "lcma_select", "lcma_hw_mi355x", "lcma_model_stages", "lcma_model_intensity", "lcma_predict_seconds",
+    "lcma_sched_waves", "lcma_sched_range", "lcma_status_str", "lcma_last_error",
+]
+
+
+class LcmaError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"LCMA_{STATUS_NAMES[status] if 0 <= status < len(STATUS_NAMES) else status}: {message}")
+        self.status = status
+
+
+class lcma_hw(ctypes.Structure):
+    _fields_ = [("flops_mul", ctypes.c_double), ("flops_add", ctypes.c_double), ("beta", ctypes.c_double)]
+
+
+class lcma_stage_costs(ctypes.Structure):
+    _fields_ = [("flops", ctypes.c_double * 4), ("elems", ctypes.c_double * 4), ("seconds", ctypes.c_double * 4)]
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """The loaded library (raises if it has not been built: run `python -m paper_2605_06057_amd.build`)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(f"{LIB_PATH} is missing: build it with `python -m paper_2605_06057_amd.build`")
+        # PyTorch ships its own HIP runtime; it must be the one already in the process when
+        # this library's dependency on libamdhip64 is resolved, or two runtimes would coexist.
+        import torch  # noqa: F401
+        L = ctypes.CDLL(LIB_PATH)
+        i64, i32, vp, cp = ctypes.c_int64, ctypes.c_int, ctypes.c_void_p, ctypes.c_char_p
+        pi32, pi64, pd = ctypes.POINTER(i32), ctypes.POINTER(i64), ctypes.POINTER(ctypes.c_double)
+        L.lcma_scheme_load.argtypes = [cp, ctypes.POINTER(vp)]
+        L.lcma_scheme_verify.argtypes = [vp, pi64]
+        L.lcma_scheme_free.argtypes = [vp]
+        L.lcma_scheme_free.restype = None
+        L.lcma_scheme_info.argtypes = [vp] + [pi32] * 7
+        L.lcma_scheme_coeffs.argtypes = [vp, vp, vp, vp]
+        L.lcma_gemm.argtypes = [i64, i64, i64, vp, i64, vp, i64, vp, i64, i32, vp, vp]
+        L.lcma_variant_count.argtypes = []
+        L.lcma_variant_name.argtypes = [i32]
+        L.lcma_variant_name.restype = cp
+        L.lcma_variant_info.argtypes = [i32] + [pi32] * 8
+        L.lcma_gemm_variant.argtypes = [cp, i64, i64, i64, vp, i64, vp, i64, vp, i64, vp]
+        L.lcma_select.argtypes = [i64, i64, i64, i32]
+        L.lcma_hw_mi355x.argtypes = [i32, ctypes.POINTER(lcma_hw)]
+        L.lcma_model_stages.argtypes = [vp, i64, i64, i64, ctypes.POINTER(lcma_hw), ctypes.POINTER(lcma_stage_costs)]
+        L.lcma_model_intensity.argtypes = [vp, i64, i64, i64, pd, pd, pd]
+        L.lcma_predict_seconds.argtypes = [i32, i64, i64, i64, i32]
+        L.lcma_predict_seconds.restype = ctypes.c_double
+        L.lcma_sched_waves.argtypes = [i64, i32, i32, pi64, pi64]
+        L.lcma_sched_range.argtypes = [i64, i32, i32, i32, pi64, pi64]
+        L.lcma_status_str.argtypes = [i32]
+        L.lcma_status_str.restype = cp
+        L.lcma_last_error.argtypes = []
+        L.lcma_last_error.restype = cp
+        _lib = L
+    return _lib
+
+
+def _check(status: int):
+    if status != LCMA_OK:
+        raise LcmaError(status, lib().lcma_last_error().decode())
+
+
+class Scheme:
+    """Owns an lcma_scheme handle."""
+
+    def __init__(self, spec: str):
+        self.handle = ctypes.c_void_p()
+        _check(lib().lcma_scheme_load(spec.encode(), ctypes.byref(self.handle)))
+
+    def __del__(self):
+        if getattr(self, "handle", None) and _lib is not None:
+            _lib.lcma_scheme_free(self.handle)
+            self.handle = None
+
+
+def lcma_scheme_load(spec: str) -> Scheme:
+    return Scheme(spec)
+
+
+def lcma_scheme_verify(s: Scheme) -> int:
+    """Returns -1 when the Brent identity holds, raises LcmaError(ERR_BRENT) otherwise
+    (the error carries .first_bad)."""
+    first = ctypes.c_int64(-1)
+    st = lib().lcma_scheme_verify(s.handle, ctypes.byref(first))
+    if st != LCMA_OK:
+        err = LcmaError(st, lib().lcma_last_error().decode())
+        err.first_bad = int(first.value)
+        raise err
+    return int(first.value)
+
+
+def lcma_scheme_info(s: Scheme) -> dict:
+    v = [ctypes.c_int() for _ in range(7)]
+    _check(lib().lcma_scheme_info(s.handle, *[ctypes.byref(x) for x in v]))
+    return dict(zip(["m", "k", "n", "R", "nnzU", "nnzV", "nnzW"], [int(x.value) for x in v]))
+
+
+def lcma_scheme_coeffs(s: Scheme):
+    import numpy as np
+    d = lcma_scheme_info(s)
+    U = np.zeros((d["R"], d["m"], d["k"]), np.int8)
+    V = np.zeros((d["R"], d["k"], d["n"]), np.int8)
+    W = np.zeros((d["R"], d["m"], d["n"]), np.int8)
+    _check(lib().lcma_scheme_coeffs(s.handle, U.ctypes.data, V.ctypes.data, W.ctypes.data))
+    return U, V, W
+
+
+def _dtype_of(t) -> int:
+    import torch
+    return {torch.float32: LCMA_F32, torch.bfloat16: LCMA_BF16, torch.float16: LCMA_F16}[t.dtype]
+
+
+def _marshal(A, B, C):
+    """(M, N, K, ptrs and leading dimensions, stream) of three row-major device tensors."""
+    import torch
+    assert A.is_cuda and B.is_cuda and C.is_cuda, "matrices must live on the GPU"
+    assert A.dim() == B.dim() == C.dim() == 2 and A.stride(1) == B.stride(1) == C.stride(1) == 1
+    assert A.dtype == B.dtype == C.dtype
+    M, K = A.shape
+    K2, N = B.shape
+    assert K == K2 and tuple(C.shape) == (M, N)
+    stream = torch.cuda.current_stream(A.device).cuda_stream
+    return M, N, K, A.data_ptr(), A.stride(0), B.data_ptr(), B.stride(0), C.data_ptr(), C.stride(0), stream
+
+
+def lcma_gemm(A, B, C, scheme: Scheme | None = None):
+    """C = A x B on the current stream (torch tensors carry pointers and strides only)."""
+    M, N, K, pa, lda, pb, ldb, pc, ldc, stream = _marshal(A, B, C)
+    _check(lib().lcma_gemm(M, N, K, pa, lda, pb, ldb, pc, ldc, _dtype_of(A),
+                           scheme.handle if scheme is not None else None, stream))
+    return C
+
+
+def lcma_gemm_variant(variant: str, A, B, C):
+    M, N, K, pa, lda, pb, ldb, pc, ldc, stream = _marshal(A, B, C)
+    _check(lib().lcma_gemm_variant(variant.encode(), M, N, K, pa, lda, pb, ldb, pc, ldc, stream))
+    return C
+
+
+def lcma_variants() -> list[dict]:
+    out = []
+    for i in range(lib().lcma_variant_count()):
+        v = [ctypes.c_int() for _ in range(8)]
+        _check(lib().lcma_variant_info(i, *[ctypes.byref(x) for x in v]))
+        d = dict(zip(["scheme_id", "dtype", "TM", "TN", "TK", "mult_M", "mult_N", "mult_K"],
+                     [int(x.value) for x in v]))
+        d["name"] = lib().lcma_variant_name(i).decode()
+        out.append(d)
+    return out
+
+
+def lcma_select(M: int, N: int, K: int, dtype: int) -> int:
+    return int(lib().lcma_select(M, N, K, dtype))
+
+
+def lcma_predict_seconds(scheme_id: int, M: int, N: int, K: int, dtype: int) -> float:
+    return float(lib().lcma_predict_seconds(scheme_id, M, N, K, dtype))
+
+
+def lcma_hw_mi355x(dtype: int) -> lcma_hw:
+    hw = lcma_hw()
+    _check(lib().lcma_hw_mi355x(dtype, ctypes.byref(hw)))
+    return hw
+
+
+def lcma_model_stages(s: Scheme | None, M: int, N: int, K: int, hw: lcma_hw) -> lcma_stage_costs:
+    out = lcma_stage_costs()
+    _check(lib().lcma_model_stages(s.handle if s else None, M, N, K, ctypes.byref(hw), ctypes.byref(out)))
+    return out
+
+
+def lcma_model_intensity(s: Scheme | None, M: int, N: int, K: int):
+    e = [ctypes.c_double() for _ in range(3)]
+    _check(lib().lcma_model_intensity(s.handle if s else None, M, N, K, *[ctypes.byref(x) for x in e]))
+    return tuple(float(x.value) for x in e)
+
+
+def lcma_sched_waves(groups: int, R: int, units: int):
+    a, b = ctypes.c_int64(), ctypes.c_int64()
+    _check(lib().lcma_sched_waves(groups, R, units, ctypes.byref(a), ctypes.byref(b)))
+    return int(a.value), int(b.value)
+
+
+def lcma_sched_range(groups: int, R: int, units: int, unit: int):
+    a, b = ctypes.c_int64(), ctypes.c_int64()
+    _check(lib().lcma_sched_range(groups, R, units, unit, ctypes.byref(a), ctypes.byref(b)))
+    return int(a.value), int(b.value)

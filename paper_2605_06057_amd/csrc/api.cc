@@ -1,0 +1,171 @@
+// C ABI entry points: argument checks, variant choice, kernel launch.
+#include "host_common.h"
+
+#include <cstdarg>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+
+namespace lcma {
+
+static thread_local char g_error[512] = "";
+
+lcma_status fail(lcma_status st, const char *fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    std::vsnprintf(g_error, sizeof g_error, fmt, ap);
+    va_end(ap);
+    return st;
+}
+
+static bool fits(const Variant &v, int64_t M, int64_t N, int64_t K) {
+    return M % ((int64_t)v.m * v.TM) == 0 && N % ((int64_t)v.n * v.TN) == 0 && K % ((int64_t)v.k * v.TK) == 0;
+}
+
+const Variant *pick_variant(int scheme_id, int dtype, int64_t M, int64_t N, int64_t K) {
+    const Variant *best = nullptr;
+    for (int i = 0; i < kVariantCount; ++i) {
+        const Variant &v = kVariants[i];
+        if (v.scheme_id != scheme_id || v.dtype != dtype || !fits(v, M, N, K)) continue;
+        if (!best || v.rank < best->rank) best = &v;
+    }
+    return best;
+}
+
+static const Variant *find_variant(const char *name) {
+    for (int i = 0; i < kVariantCount; ++i)
+        if (!std::strcmp(kVariants[i].name, name)) return &kVariants[i];
+    return nullptr;
+}
+
+static lcma_status run(const Variant &v, int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const void *B,
+                       int64_t ldb, void *C, int64_t ldc, void *stream) {
+    const int es = dtype_size(v.dtype);
+    if (M < 0 || N < 0 || K < 0) return fail(LCMA_ERR_ARG, "lcma_gemm: negative size");
+    if (M == 0 || N == 0) return LCMA_OK; // nothing to write
+    if (K == 0) return fail(LCMA_ERR_SHAPE, "lcma_gemm: K = 0 is not supported");
+    if (!A || !B || !C) return fail(LCMA_ERR_ARG, "lcma_gemm: null matrix pointer");
+    if (lda < K || ldb < N || ldc < N) return fail(LCMA_ERR_ARG, "lcma_gemm: leading dimension smaller than the row");
+    if (((uintptr_t)A | (uintptr_t)B | (uintptr_t)C) & 15)
+        return fail(LCMA_ERR_ARG, "lcma_gemm: matrix pointers must be 16-byte aligned");
+    if (((lda * es) | (ldb * es) | (ldc * es)) & 15)
+        return fail(LCMA_ERR_ARG, "lcma_gemm: leading dimensions must be multiples of 16 bytes");
+    if (!fits(v, M, N, K))
+        return fail(LCMA_ERR_SHAPE, "lcma_gemm: (%lld,%lld,%lld) is not a multiple of (%d,%d,%d) needed by %s",
+                    (long long)M, (long long)N, (long long)K, v.m * v.TM, v.n * v.TN, v.k * v.TK, v.name);
+    const int64_t a_bytes = ((M - 1) * lda + K) * es, b_bytes = ((K - 1) * ldb + N) * es,
+                  c_bytes = ((M - 1) * ldc + N) * es;
+    const int64_t lim = (int64_t)1 << 31;
+    if (a_bytes >= lim || b_bytes >= lim || c_bytes >= lim)
+        return fail(LCMA_ERR_SHAPE, "lcma_gemm: a matrix spans 2 GiB or more");
+    const int64_t bm = M / v.m, bn = N / v.n, bk = K / v.k;
+    Params p;
+    p.A = A;
+    p.B = B;
+    p.C = C;
+    p.a_bytes = (uint32_t)a_bytes;
+    p.b_bytes = (uint32_t)b_bytes;
+    p.c_bytes = (uint32_t)c_bytes;
+    p.lda_b = (uint32_t)(lda * es);
+    p.ldb_b = (uint32_t)(ldb * es);
+    p.ldc_b = (uint32_t)(ldc * es);
+    p.a_brow = (uint32_t)(bm * lda * es);
+    p.a_bcol = (uint32_t)(bk * es);
+    p.b_brow = (uint32_t)(bk * ldb * es);
+    p.b_bcol = (uint32_t)(bn * es);
+    p.c_brow = (uint32_t)(bm * ldc * es);
+    p.c_bcol = (uint32_t)(bn * es);
+    p.nx = (int32_t)(bm / v.TM);
+    p.nz = (int32_t)(bn / v.TN);
+    p.ny = (int32_t)(bk / v.TK);
+    const int64_t grid = (int64_t)p.nx * p.nz;
+    if (grid >= lim) return fail(LCMA_ERR_SHAPE, "lcma_gemm: too many tiles");
+    int panel = 8;
+    if (const char *e = std::getenv("LCMA_PANEL")) panel = std::atoi(e);
+    if (panel < 1) panel = 1;
+    p.panel = panel < p.nz ? panel : p.nz;
+    const int err = v.launch(&p, (int)grid, stream);
+    if (err) return fail(LCMA_ERR_HIP, "lcma_gemm: launch of %s failed with HIP error %d", v.name, err);
+    return LCMA_OK;
+}
+
+} // namespace lcma
+
+using namespace lcma;
+
+extern "C" lcma_status lcma_gemm(int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const void *B,
+                                 int64_t ldb, void *C, int64_t ldc, lcma_dtype dtype, const lcma_scheme *scheme,
+                                 void *stream) {
+    if (!dtype_size(dtype)) return fail(LCMA_ERR_DTYPE, "lcma_gemm: unknown dtype %d", (int)dtype);
+    int id = LCMA_PLAIN;
+    if (scheme) {
+        const lcma_status st = lcma_scheme_verify(scheme, nullptr);
+        if (st != LCMA_OK) return st;
+        id = scheme->builtin;
+        if (!id)
+            return fail(LCMA_ERR_NOKERNEL, "lcma_gemm: no kernel was generated for scheme <%d,%d,%d;%d> (hash %016llx)",
+                        scheme->m, scheme->k, scheme->n, scheme->R, (unsigned long long)scheme->hash);
+    }
+    if (M < 0 || N < 0 || K < 0) return fail(LCMA_ERR_ARG, "lcma_gemm: negative size");
+    if (M == 0 || N == 0) return LCMA_OK;
+    const Variant *v = nullptr;
+    if (const char *force = std::getenv("LCMA_VARIANT")) { // ablation override
+        v = find_variant(force);
+        if (v && (v->scheme_id != id || v->dtype != (int)dtype)) v = nullptr;
+    }
+    if (!v) v = pick_variant(id, dtype, M, N, K);
+    if (!v) {
+        bool any = false;
+        for (int i = 0; i < kVariantCount; ++i) any |= kVariants[i].scheme_id == id && kVariants[i].dtype == (int)dtype;
+        if (!any) return fail(LCMA_ERR_NOKERNEL, "lcma_gemm: no kernel for scheme id %d with dtype %d", id, (int)dtype);
+        return fail(LCMA_ERR_SHAPE, "lcma_gemm: no tile of scheme id %d divides (%lld,%lld,%lld)", id, (long long)M,
+                    (long long)N, (long long)K);
+    }
+    return run(*v, M, N, K, A, lda, B, ldb, C, ldc, stream);
+}
+
+extern "C" lcma_status lcma_gemm_variant(const char *variant, int64_t M, int64_t N, int64_t K, const void *A,
+                                         int64_t lda, const void *B, int64_t ldb, void *C, int64_t ldc, void *stream) {
+    if (!variant) return fail(LCMA_ERR_ARG, "lcma_gemm_variant: null name");
+    const Variant *v = find_variant(variant);
+    if (!v) return fail(LCMA_ERR_NOKERNEL, "lcma_gemm_variant: no variant named '%s'", variant);
+    return run(*v, M, N, K, A, lda, B, ldb, C, ldc, stream);
+}
+
+extern "C" int lcma_variant_count(void) { return kVariantCount; }
+
+extern "C" const char *lcma_variant_name(int index) {
+    return (index >= 0 && index < kVariantCount) ? kVariants[index].name : nullptr;
+}
+
+extern "C" lcma_status lcma_variant_info(int index, int *scheme_id, int *dtype, int *TM, int *TN, int *TK, int *mult_M,
+                                         int *mult_N, int *mult_K) {
+    if (index < 0 || index >= kVariantCount) return fail(LCMA_ERR_ARG, "lcma_variant_info: index out of range");
+    const Variant &v = kVariants[index];
+    if (scheme_id) *scheme_id = v.scheme_id;
+    if (dtype) *dtype = v.dtype;
+    if (TM) *TM = v.TM;
+    if (TN) *TN = v.TN;
+    if (TK) *TK = v.TK;
+    if (mult_M) *mult_M = v.m * v.TM;
+    if (mult_N) *mult_N = v.n * v.TN;
+    if (mult_K) *mult_K = v.k * v.TK;
+    return LCMA_OK;
+}
+
+extern "C" const char *lcma_status_str(lcma_status st) {
+    switch (st) {
+    case LCMA_OK: return "ok";
+    case LCMA_ERR_ARG: return "bad argument";
+    case LCMA_ERR_IO: return "cannot read scheme";
+    case LCMA_ERR_PARSE: return "malformed scheme text";
+    case LCMA_ERR_BRENT: return "scheme violates the Brent equations";
+    case LCMA_ERR_SHAPE: return "shape not supported by the tile";
+    case LCMA_ERR_DTYPE: return "unknown dtype";
+    case LCMA_ERR_NOKERNEL: return "no generated kernel";
+    case LCMA_ERR_HIP: return "HIP error";
+    }
+    return "unknown status";
+}
+
+extern "C" const char *lcma_last_error(void) { return g_error; }

@@ -1,0 +1,51 @@
+// Host-side shared declarations of the LCMA library (not part of the public ABI).
+#pragma once
+#include <atomic>
+#include <cstdint>
+#include <mutex>
+#include <string>
+#include <vector>
+
+#include "../../include/lcma.h"
+#include "lcma_params.h"
+
+struct lcma_scheme {
+    int m = 0, k = 0, n = 0, R = 0;
+    std::vector<int8_t> U, V, W; // R*m*k, R*k*n, R*m*n, row-major
+    uint64_t hash = 0;
+    int builtin = 0;                          // LCMA_STRASSEN.. when the coefficients are a built-in's, else 0
+    mutable std::atomic<int> verified{0};     // 0 not checked, 1 Brent identity holds, 2 violated
+    mutable int64_t first_bad = -1;
+    mutable std::mutex mu;
+};
+
+namespace lcma {
+
+// Records a thread-local message and returns `st`.
+lcma_status fail(lcma_status st, const char *fmt, ...) __attribute__((format(printf, 2, 3)));
+
+uint64_t scheme_hash(int m, int k, int n, int R, const int8_t *U, const int8_t *V, const int8_t *W);
+const lcma_scheme *builtin_scheme(int id); // verified, cached; nullptr for LCMA_PLAIN / unknown
+int builtin_id_of(const char *name);
+
+// One generated kernel (scheme x dtype x tile x dataflow).
+struct Variant {
+    const char *name;
+    int scheme_id;      // LCMA_PLAIN .. LCMA_LADERMAN
+    int dtype;          // lcma_dtype
+    int m, k, n, R;     // grid of the scheme it was generated for (1,1,1,1 for plain)
+    uint64_t hash;      // scheme_hash of its coefficients (0 for plain)
+    int TM, TN, TK;     // tile of one block product
+    int chunk;          // products resident per pass (R: all H_r live, 1: Algorithm 2's r loop)
+    int rank;           // preference among variants of the same scheme and dtype (lower first)
+    int (*launch)(const Params *p, int grid, void *stream); // returns a hipError_t
+};
+extern const Variant kVariants[];
+extern const int kVariantCount;
+
+int dtype_size(int dtype); // bytes, or 0
+
+// Preferred variant of (scheme_id, dtype) whose tile divides the shape; nullptr if none.
+const Variant *pick_variant(int scheme_id, int dtype, int64_t M, int64_t N, int64_t K);
+
+} // namespace lcma

@@ -1,0 +1,368 @@
+"""Kernel generator: one gfx950 HIP translation unit per (scheme, dtype, tile, chunking).
+
+This is the build-time counterpart of the paper's Automated Code Generation (Sec. 3.1):
+the coefficient tensors U, V, W of a scheme are turned into straight-line code, so zero
+coefficients cost nothing and no coefficient is read at run time.  The scheme-agnostic
+part (tile staging, MFMA loop, stores) is csrc/lcma_device.hpp; what is emitted here is
+
+  * per chunk of products: which raw blocks A_{i,l}, B_{l,j} to stage, and the signed sums
+    of Eq. 3 / Eq. 4 on 16-byte register vectors;
+  * after each chunk: the signed accumulation of Eq. 6 into fp32 tiles of C, each tile
+    stored as soon as its last product has arrived (the "register reuse" reordering);
+  * on-chip resource planning: accumulator registers and LDS bytes of every variant are
+    computed and checked against the gfx950 budget before anything is written.
+
+Also emitted: builtin_schemes.inc (the scheme texts the library embeds) and registry.cc.
+"""
+from __future__ import annotations
+
+import os
+from dataclasses import dataclass, field
+
+import numpy as np
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+PKG = os.path.dirname(HERE)
+SCHEME_DIR = os.path.join(PKG, "schemes")
+
+SCHEME_IDS = {"plain": 0, "strassen": 1, "strassen2": 2, "laderman": 3}
+DTYPE_IDS = {"f32": 0, "bf16": 1, "f16": 2}
+ACC_REG_BUDGET = 400      # of 512 unified VGPR/AGPR per lane at one wave per SIMD
+LDS_BUDGET = 160 * 1024
+
+
+# ----------------------------------------------------------------------------- schemes
+@dataclass
+class Scheme:
+    name: str
+    m: int
+    k: int
+    n: int
+    R: int
+    U: np.ndarray
+    V: np.ndarray
+    W: np.ndarray
+
+    def text(self) -> str:
+        rows = [f"{self.m} {self.k} {self.n} {self.R}"]
+        for T in (self.U, self.V, self.W):
+            rows += [" ".join(str(int(v)) for v in T[r].reshape(-1)) for r in range(self.R)]
+        return "\n".join(rows) + "\n"
+
+
+def parse_scheme(name: str, text: str) -> Scheme:
+    nums = []
+    for line in text.splitlines():
+        nums += [int(t) for t in line.split("#", 1)[0].replace(",", " ").split()]
+    m, k, n, R = nums[:4]
+    body = np.array(nums[4:], dtype=np.int64)
+    assert body.size == R * (m * k + k * n + m * n), f"{name}: wrong number of coefficients"
+    a, b = R * m * k, R * m * k + R * k * n
+    return Scheme(name, m, k, n, R, body[:a].reshape(R, m, k), body[a:b].reshape(R, k, n),
+                  body[b:].reshape(R, m, n))
+
+
+def compose(outer: Scheme, inner: Scheme, name: str) -> Scheme:
+    """Scheme of applying `inner` to each block product of `outer` (flat Kronecker form)."""
+    def kron(X, Y):
+        R1, p1, q1 = X.shape
+        R2, p2, q2 = Y.shape
+        Z = np.zeros((R1 * R2, p1 * p2, q1 * q2), np.int64)
+        for r1 in range(R1):
+            for r2 in range(R2):
+                Z[r1 * R2 + r2] = np.kron(X[r1], Y[r2])
+        return Z
+    return Scheme(name, outer.m * inner.m, outer.k * inner.k, outer.n * inner.n, outer.R * inner.R,
+                  kron(outer.U, inner.U), kron(outer.V, inner.V), kron(outer.W, inner.W))
+
+
+def multiplies_matrices(s: Scheme) -> bool:
+    """Brent identity, exact (checked again by the library when a scheme is loaded)."""
+    for i in range(s.m):
+        for a in range(s.k):
+            for b in range(s.k):
+                for j in range(s.n):
+                    got = np.tensordot(s.U[:, i, a] * s.V[:, b, j], s.W, axes=(0, 0))
+                    want = np.zeros((s.m, s.n), np.int64)
+                    if a == b:
+                        want[i, j] = 1
+                    if not np.array_equal(got, want):
+                        return False
+    return True
+
+
+def load_schemes() -> dict[str, Scheme]:
+    out = {}
+    for name in ("strassen", "laderman"):
+        with open(os.path.join(SCHEME_DIR, name + ".txt")) as f:
+            out[name] = parse_scheme(name, f.read())
+    out["strassen2"] = compose(out["strassen"], out["strassen"], "strassen2")
+    one = np.ones((1, 1, 1), np.int64)
+    out["plain"] = Scheme("plain", 1, 1, 1, 1, one, one, one)
+    for s in out.values():
+        assert multiplies_matrices(s), f"scheme {s.name} violates the Brent equations"
+    return out
+
+
+# ----------------------------------------------------------------------------- variants
+@dataclass
+class Variant:
+    scheme: str
+    dtype: str
+    TM: int
+    TN: int
+    TK: int
+    wgm: int = 2
+    wgn: int = 2
+    chunk: int = 1            # products per chunk (consecutive in the chunk order)
+    stages: int = 2
+    rank: int = 0
+    group_by: int = 0         # >0: chunks are runs of this many consecutive products (two-level: outer r1)
+    name: str = field(default="")
+
+    def finish(self):
+        if not self.name:
+            self.name = f"{self.scheme}_{self.dtype}_t{self.TM}x{self.TN}x{self.TK}_c{self.chunk}"
+        return self
+
+
+def chunks_of(s: Scheme, v: Variant) -> list[list[int]]:
+    order = list(range(s.R))
+    if v.chunk >= s.R:
+        return [order]
+    return [order[i:i + v.chunk] for i in range(0, s.R, v.chunk)]
+
+
+def plan(s: Scheme, v: Variant):
+    """On-chip resource planning: (accumulator registers per lane, LDS bytes, peak live C tiles)."""
+    es = 4 if v.dtype == "f32" else 2
+    tile_regs = (v.TM // v.wgm // 32) * (v.TN // v.wgn // 32) * 16
+    chunks = chunks_of(s, v)
+    nslot = max(len(c) for c in chunks)
+    if len(chunks) == 1:
+        live_c = 0
+    else:
+        first, last = {}, {}
+        for ci, ch in enumerate(chunks):
+            for r in ch:
+                for i in range(s.m):
+                    for j in range(s.n):
+                        if s.W[r, i, j]:
+                            first.setdefault((i, j), ci)
+                            last[(i, j)] = ci
+        live_c = max(sum(1 for key in first if first[key] <= ci <= last[key]) for ci in range(len(chunks)))
+    regs = (live_c + nslot) * tile_regs
+    lds = v.stages * nslot * (v.TM * v.TK + v.TK * v.TN) * es
+    return regs, lds, live_c, nslot
+
+
+# ----------------------------------------------------------------------------- code emission
+CPP_TYPES = {"f32": ("F32", "F32"), "f16": ("F16", "F16"), "bf16": ("BF16", "F16")}
+
+
+def signed_sum(terms: list[tuple[int, str]], wide: bool = False) -> str:
+    """[(coef, expr)] -> C++ expression; +-1 become additions, anything else a multiply.
+    wide: form the sum in fp32 and round once (used for fp16 sums of three or more terms)."""
+    if wide and len(terms) >= 3:
+        return "Wide<V>::down(" + signed_sum([(c, f"Wide<V>::up({e})") for c, e in terms]) + ")"
+    terms = sorted(terms, key=lambda t: t[0] < 0)  # a positive term first when there is one
+    out = ""
+    for idx, (c, e) in enumerate(terms):
+        mag = e if abs(c) == 1 else f"{e} * {abs(c)}"
+        if idx == 0:
+            out = mag if c > 0 else f"-{mag}"
+        else:
+            out += (" + " if c > 0 else " - ") + mag
+    return out
+
+
+def emit_kernel(s: Scheme, v: Variant) -> str:
+    in_t, ct_t = CPP_TYPES[v.dtype]
+    if s.name == "plain":
+        ct_t = in_t  # nothing is added: multiply in the storage type
+    regs, lds, live_c, nslot = plan(s, v)
+    chunks = chunks_of(s, v)
+    single = len(chunks) == 1
+    # bf16 inputs carry 8 significant bits, so their sums are (nearly) exact in packed fp16 adds;
+    # fp16 inputs need the fp32 detour to be rounded only once.
+    wide = v.dtype == "f16"
+    L = []
+    w = L.append
+    w(f"// GENERATED by gen/generate.py - do not edit.  Scheme {s.name} <{s.m},{s.k},{s.n};{s.R}>, dtype {v.dtype},")
+    w(f"// tile {v.TM}x{v.TN}x{v.TK}, {len(chunks)} chunk(s) of up to {nslot} products; planned accumulator registers")
+    w(f"// per lane {regs}, LDS {lds} bytes, peak live C tiles {live_c}.")
+    w('#include "lcma_device.hpp"')
+    w("namespace {")
+    w("using namespace lcma;")
+    w(f"using T = Tile<{in_t}, {ct_t}, {v.TM}, {v.TN}, {v.TK}, {v.wgm}, {v.wgn}, {nslot}, {v.stages}>;")
+    for ci, ch in enumerate(chunks):
+        a_blocks = sorted({(i, l) for r in ch for i in range(s.m) for l in range(s.k) if s.U[r, i, l]})
+        b_blocks = sorted({(l, j) for r in ch for l in range(s.k) for j in range(s.n) if s.V[r, l, j]})
+        w(f"struct Chunk{ci} {{  // products {', '.join(str(r + 1) for r in ch)}")
+        w(f"    static constexpr int NA = {len(a_blocks)}, NB = {len(b_blocks)}, NP = {len(ch)};")
+        for fn, vals in (("a_i", [b[0] for b in a_blocks]), ("a_l", [b[1] for b in a_blocks]),
+                         ("b_l", [b[0] for b in b_blocks]), ("b_j", [b[1] for b in b_blocks])):
+            w(f"    static LCMA_DEV constexpr int {fn}(int t) {{ constexpr int v[] = {{{', '.join(map(str, vals))}}}; return v[t]; }}")
+        w("    template <class V> static LCMA_DEV void comb_a(const V (&in)[NA], V (&out)[NP]) {")
+        for si, r in enumerate(ch):
+            terms = [(int(s.U[r, i, l]), f"in[{a_blocks.index((i, l))}]") for (i, l) in a_blocks if s.U[r, i, l]]
+            w(f"        out[{si}] = {signed_sum(terms, wide)};")
+        w("    }")
+        w("    template <class V> static LCMA_DEV void comb_b(const V (&in)[NB], V (&out)[NP]) {")
+        for si, r in enumerate(ch):
+            terms = [(int(s.V[r, l, j]), f"in[{b_blocks.index((l, j))}]") for (l, j) in b_blocks if s.V[r, l, j]]
+            w(f"        out[{si}] = {signed_sum(terms, wide)};")
+        w("    }")
+        w("};")
+    w("")
+    w(f"__global__ __launch_bounds__(256) void kern(const Params p) {{")
+    w("    __shared__ __attribute__((aligned(16))) char smem[T::LDS_BYTES];")
+    w("    const Ctx<T> cx(p, (LCMA_LDS char *)smem);")
+    if single:
+        ch = chunks[0]
+        w(f"    T::Acc h[{len(ch)}];")
+        w(f"    for (auto &t : h) zero_acc(t);")
+        w("    run_chunk<T, Chunk0>(cx, h);")
+        for i in range(s.m):
+            for j in range(s.n):
+                terms = [(int(s.W[r, i, j]), f"h[{si}].v[mi][ni]") for si, r in enumerate(ch) if s.W[r, i, j]]
+                w(f"    cx.store_c({i}, {j}, [&](int mi, int ni) {{ return {signed_sum(terms)}; }});")
+    else:
+        first, last = {}, {}
+        for ci, ch in enumerate(chunks):
+            for r in ch:
+                for i in range(s.m):
+                    for j in range(s.n):
+                        if s.W[r, i, j]:
+                            first.setdefault((i, j), (ci, r))
+                            last[(i, j)] = (ci, r)
+        w(f"    T::Acc c[{s.m * s.n}];")
+        for ci, ch in enumerate(chunks):
+            w("    {")
+            w(f"        T::Acc h[{len(ch)}];")
+            w("        for (auto &t : h) zero_acc(t);")
+            w(f"        run_chunk<T, Chunk{ci}>(cx, h);")
+            for si, r in enumerate(ch):
+                for i in range(s.m):
+                    for j in range(s.n):
+                        coef = int(s.W[r, i, j])
+                        if not coef:
+                            continue
+                        op = "set" if first[(i, j)] == (ci, r) else "add"
+                        w(f"        acc_{op}(c[{i * s.n + j}], h[{si}], {float(coef)}f);")
+                        if last[(i, j)] == (ci, r):
+                            w(f"        cx.store_c({i}, {j}, [&](int mi, int ni) {{ return c[{i * s.n + j}].v[mi][ni]; }});")
+            w("    }")
+    w("}")
+    w("} // namespace")
+    w("")
+    w(f'extern "C" int lcma_launch_{v.name}(const lcma::Params *p, int grid, void *stream) {{')
+    w("    kern<<<dim3(grid), dim3(256), 0, (hipStream_t)stream>>>(*p);")
+    w("    return (int)hipGetLastError();")
+    w("}")
+    return "\n".join(L) + "\n"
+
+
+def emit_registry(schemes: dict[str, Scheme], variants: list[Variant]) -> str:
+    L = ["// GENERATED by gen/generate.py - do not edit.", '#include "host_common.h"', ""]
+    for v in variants:
+        L.append(f'extern "C" int lcma_launch_{v.name}(const lcma::Params *p, int grid, void *stream);')
+    L += ["", "namespace lcma {", "const Variant kVariants[] = {"]
+    for v in variants:
+        s = schemes[v.scheme]
+        hash_expr = "0" if s.name == "plain" else f"0x{scheme_hash(s):016x}ull"
+        L.append(f'    {{"{v.name}", {SCHEME_IDS[v.scheme]}, {DTYPE_IDS[v.dtype]}, {s.m}, {s.k}, {s.n}, {s.R}, '
+                 f"{hash_expr}, {v.TM}, {v.TN}, {v.TK}, {min(v.chunk, s.R)}, {v.rank}, lcma_launch_{v.name}}},")
+    L += ["};", f"const int kVariantCount = {len(variants)};", "} // namespace lcma", ""]
+    return "\n".join(L)
+
+
+def scheme_hash(s: Scheme) -> int:
+    """FNV-1a over (m,k,n,R) as int32 and the int8 coefficients, matching the library's."""
+    h = 0xCBF29CE484222325
+    data = np.array([s.m, s.k, s.n, s.R], np.int32).tobytes()
+    for T in (s.U, s.V, s.W):
+        data += T.astype(np.int8).tobytes()
+    for byte in data:
+        h = ((h ^ byte) * 0x100000001B3) & 0xFFFFFFFFFFFFFFFF
+    return h
+
+
+def emit_builtin_inc(schemes: dict[str, Scheme]) -> str:
+    names = [n for n in ("strassen", "strassen2", "laderman")]
+    L = ["// GENERATED by gen/generate.py from schemes/*.txt - do not edit."]
+    L.append("static const char *const kBuiltinNames[] = {" + ", ".join(f'"{n}"' for n in names) + "};")
+    L.append("static const char *const kBuiltinTexts[] = {")
+    for n in names:
+        body = "".join(f'    "{line}\\n"\n' for line in schemes[n].text().splitlines())
+        L.append(body.rstrip("\n") + ",")
+    L.append("};")
+    L.append(f"static const int kBuiltinCount = {len(names)};")
+    return "\n".join(L) + "\n"
+
+
+# ----------------------------------------------------------------------------- manifest
+def manifest() -> list[Variant]:
+    V = []
+    for dt in ("bf16", "f16"):
+        V += [
+            Variant("plain", dt, 256, 256, 64, rank=0),
+            Variant("plain", dt, 256, 128, 64, rank=1),
+            Variant("plain", dt, 128, 128, 64, rank=2),
+            Variant("plain", dt, 64, 64, 32, rank=9),
+            Variant("strassen", dt, 128, 64, 16, chunk=7, rank=0),
+            Variant("strassen", dt, 64, 64, 32, chunk=7, rank=5),
+            Variant("strassen", dt, 128, 128, 32, chunk=1, rank=7),
+            Variant("laderman", dt, 128, 64, 32, chunk=1, rank=0),
+            Variant("laderman", dt, 64, 64, 32, chunk=1, rank=5),
+            Variant("strassen2", dt, 64, 64, 32, chunk=7, rank=0),
+            Variant("strassen2", dt, 64, 64, 32, chunk=1, rank=5),
+        ]
+    V += [
+        Variant("plain", "f32", 128, 128, 16, rank=0),
+        Variant("plain", "f32", 64, 64, 16, rank=9),
+        Variant("strassen", "f32", 64, 64, 16, chunk=7, rank=0),
+        Variant("strassen", "f32", 128, 64, 16, chunk=1, rank=5),
+        Variant("laderman", "f32", 64, 64, 16, chunk=1, rank=0),
+        Variant("strassen2", "f32", 64, 64, 16, chunk=7, rank=0),
+    ]
+    return [v.finish() for v in V]
+
+
+def generate(out_dir: str) -> list[str]:
+    """Writes the generated sources into out_dir; returns the .hip files to compile."""
+    os.makedirs(out_dir, exist_ok=True)
+    schemes = load_schemes()
+    variants = manifest()
+    hips = []
+
+    def put(name, text):
+        path = os.path.join(out_dir, name)
+        old = None
+        if os.path.exists(path):
+            with open(path) as f:
+                old = f.read()
+        if old != text:
+            with open(path, "w") as f:
+                f.write(text)
+        return path
+
+    for v in variants:
+        s = schemes[v.scheme]
+        regs, lds, _, _ = plan(s, v)
+        assert regs <= ACC_REG_BUDGET, f"{v.name}: {regs} accumulator registers exceed the budget"
+        assert lds <= LDS_BUDGET, f"{v.name}: {lds} bytes of LDS exceed the budget"
+        hips.append(put(f"k_{v.name}.hip", emit_kernel(s, v)))
+    put("registry.cc", emit_registry(schemes, variants))
+    put("builtin_schemes.inc", emit_builtin_inc(schemes))
+    keep = {os.path.basename(h) for h in hips} | {"registry.cc", "builtin_schemes.inc"}
+    for f in os.listdir(out_dir):
+        if f not in keep and (f.endswith(".hip") or f.endswith(".o")) and f[:-len(os.path.splitext(f)[1])] + ".hip" not in keep:
+            os.remove(os.path.join(out_dir, f))
+    return hips
+
+
+if __name__ == "__main__":
+    import sys
+    for path in generate(sys.argv[1] if len(sys.argv) > 1 else os.path.join(PKG, "csrc", "generated")):
+        print(path)

@@ -1,0 +1,131 @@
+"""GPU parity: every generated kernel, through the C ABI, against the CPU oracle.
+
+Integer-valued inputs make every intermediate exact (entries in [-3,3], sums of at most 16
+terms, fp32 accumulation below 2^24), so the GPU result must equal the oracle's exact product
+rounded once to the storage type, bit for bit.  Seeded float inputs are held to the relative
+Frobenius bounds of the task: 1e-5 (fp32), 2e-2 (bf16/fp16), and at most 4x the error of the
+plain MFMA GEMM of this library on the same inputs.
+"""
+import numpy as np
+import pytest
+
+import lcma_inputs as inp
+import oracle
+from oracle import schemes as S
+
+pytestmark = pytest.mark.gpu
+
+DT = {0: "f32", 1: "bf16", 2: "f16"}
+REL_BOUND = {"f32": 1e-5, "bf16": 2e-2, "f16": 2e-2}
+
+
+@pytest.fixture(scope="module")
+def B():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    from paper_2605_06057_amd import binding
+    binding.lib()
+    return binding
+
+
+def variants():
+    from paper_2605_06057_amd import binding
+    return binding.lcma_variants()
+
+
+def small_shape(v):
+    """Several tiles in every direction, different counts per direction."""
+    return 3 * v["mult_M"], 2 * v["mult_N"], 2 * v["mult_K"]
+
+
+@pytest.mark.parametrize("v", variants(), ids=lambda v: v["name"])
+def test_integer_inputs_bit_exact(B, v):
+    import gpu_util as G
+    dt = DT[v["dtype"]]
+    M, N, K = small_shape(v)
+    print(f"variant {v['name']} shape {M}x{N}x{K}", flush=True)
+    Ai, Bi = inp.integers(101, 1, (M, K)), inp.integers(101, 2, (K, N))
+    want = inp.store(oracle.gemm(Ai, Bi).astype(np.float64), dt)
+    if v["scheme_id"]:
+        s = S.by_name(B.SCHEME_NAMES[v["scheme_id"]])
+        assert np.array_equal(oracle.lcma(s, Ai, Bi), oracle.gemm(Ai, Bi))
+    a, b = G.to_device(inp.store(Ai, dt), dt), G.to_device(inp.store(Bi, dt), dt)
+    c = G.empty_like_c(M, N, dt, fill=float("nan"))
+    B.lcma_gemm_variant(v["name"], a, b, c)
+    got = G.to_host_stored(c, dt)
+    assert np.array_equal(got.view(np.uint8), want.view(np.uint8))
+    c2 = G.empty_like_c(M, N, dt, fill=1.0)
+    B.lcma_gemm_variant(v["name"], a, b, c2)
+    assert np.array_equal(G.to_host_stored(c2, dt).view(np.uint8), got.view(np.uint8))  # run-to-run identical
+
+
+@pytest.mark.parametrize("v", variants(), ids=lambda v: v["name"])
+def test_float_inputs_within_bounds(B, v):
+    import gpu_util as G
+    dt = DT[v["dtype"]]
+    M, N, K = small_shape(v)
+    kinds = ("uniform", "uniform") if dt != "bf16" else ("normal", "weights")
+    As, Bs = inp.matrices(kinds[0], kinds[1], M, N, K, dt, seed=7)
+    ref = oracle.gemm(inp.widen(As, dt), inp.widen(Bs, dt))
+    a, b = G.to_device(As, dt), G.to_device(Bs, dt)
+    c = G.empty_like_c(M, N, dt, fill=float("nan"))
+    B.lcma_gemm_variant(v["name"], a, b, c)
+    err = oracle.rel_frobenius(G.to_host_f64(c, dt), ref)
+    cp = G.empty_like_c(M, N, dt)
+    B.lcma_gemm(a, b, cp, None)
+    err_plain = oracle.rel_frobenius(G.to_host_f64(cp, dt), ref)
+    print(f"{v['name']}: relF {err:.3e}, plain {err_plain:.3e}, ratio {err / err_plain:.2f}", flush=True)
+    assert err <= REL_BOUND[dt]
+    assert err_plain <= REL_BOUND[dt]
+    assert err <= 4.0 * err_plain
+
+
+def test_strided_views_and_dispatch(B):
+    """lda/ldb/ldc larger than the rows, scheme handles through lcma_gemm."""
+    import torch
+    import gpu_util as G
+    dt = "f16"
+    M, N, K = 768, 768, 768
+    Ai, Bi = inp.integers(5, 1, (M, K)), inp.integers(5, 2, (K, N))
+    big_a = torch.zeros((M, K + 64), dtype=torch.float16, device="cuda")
+    big_b = torch.zeros((K, N + 128), dtype=torch.float16, device="cuda")
+    big_c = torch.full((M, N + 8), 7.0, dtype=torch.float16, device="cuda")
+    big_a[:, 32:32 + K] = G.to_device(inp.store(Ai, dt), dt)
+    big_b[:, 64:64 + N] = G.to_device(inp.store(Bi, dt), dt)
+    want = inp.store(oracle.gemm(Ai, Bi).astype(np.float64), dt)
+    for spec in (None, "builtin:strassen", "builtin:laderman", "builtin:strassen2"):
+        s = B.lcma_scheme_load(spec) if spec else None
+        big_c.fill_(7.0)
+        B.lcma_gemm(big_a[:, 32:32 + K], big_b[:, 64:64 + N], big_c[:, :N], s)
+        out = big_c.cpu().numpy()
+        assert np.array_equal(out[:, :N], want), spec
+        assert np.all(out[:, N:] == 7.0), f"{spec}: wrote outside C"
+
+
+def test_error_paths_launch_nothing(B, tmp_path):
+    import torch
+    a = torch.ones((256, 256), dtype=torch.float16, device="cuda")
+    c = torch.full((256, 256), 3.0, dtype=torch.float16, device="cuda")
+    s = B.lcma_scheme_load("builtin:strassen")
+    with pytest.raises(B.LcmaError) as e:
+        B.lcma_gemm(a[:200], a, c[:200], s)  # 200 rows: not a multiple of the tile
+    assert e.value.status == B.LCMA_ERR_SHAPE
+    with pytest.raises(B.LcmaError) as e:
+        B.lcma_gemm(a[:, 1:249], a[:248], c[:, :256], None)  # misaligned A pointer
+    assert e.value.status in (B.LCMA_ERR_ARG, B.LCMA_ERR_SHAPE)
+    bad = S.strassen()
+    W = bad.W.copy(); W[0, 0, 0] = -1
+    path = tmp_path / "bad.txt"
+    path.write_text(S.to_text(S.Scheme(2, 2, 2, 7, bad.U, bad.V, W)))
+    with pytest.raises(B.LcmaError) as e:
+        B.lcma_gemm(a, a, c, B.lcma_scheme_load(str(path)))
+    assert e.value.status == B.LCMA_ERR_BRENT
+    classical = tmp_path / "classical.txt"
+    classical.write_text(S.to_text(S.classical(2, 2, 2)))
+    with pytest.raises(B.LcmaError) as e:
+        B.lcma_gemm(a, a, c, B.lcma_scheme_load(str(classical)))  # valid scheme, no generated kernel
+    assert e.value.status == B.LCMA_ERR_NOKERNEL
+    torch.cuda.synchronize()
+    assert torch.all(c == 3.0)
+    empty = torch.empty((0, 256), dtype=torch.float16, device="cuda")
+    B.lcma_gemm(empty, a, torch.empty((0, 256), dtype=torch.float16, device="cuda"), s)  # M = 0: nothing to do
