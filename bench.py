@@ -1,0 +1,194 @@
+#!/usr/bin/env python3
+"""Benchmark of the LCMA GEMM hot path on one MI355X.
+
+One "step" is one lcma_gemm call: the whole fused path (block split, operand combinations
+in LDS, grouped MFMA sub-GEMMs, W epilogue) over one pair of synthetic matrices that already
+sit in HBM.  The default workload is Strassen <2,2,2;7>, one level, bf16 inputs with fp32
+accumulation, M = N = K = 4096, A, B ~ N(0,1).
+
+Prints ONE JSON line.  `value` is effective TFLOP/s = 2MNK / time (standard-GEMM flop count,
+paper Sec. 4.1 "Measurement"), so it can exceed what the MFMA units did.  Beside it: the same-build
+plain MFMA GEMM timed the same way, the fraction of the dense MFMA peak, a roofline object
+for the dominant kernel and the CPU oracle timed on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_TFLOPS = {"bf16": 2500.0, "f16": 2500.0, "f32": 157.3}  # MI355X dense MFMA, published
+
+WORKLOADS = {
+    # name: (scheme, dtype, M, N, K, kind of A, kind of B, seed)
+    "strassen_bf16_4096": ("strassen", "bf16", 4096, 4096, 4096, "normal", "normal", 0x5EED0002),
+    "strassen_f32_256": ("strassen", "f32", 256, 256, 256, "uniform", "uniform", 0x5EED0001),
+    "strassen_bf16_ffn": ("strassen", "bf16", 8192, 14336, 4096, "normal", "weights", 0x5EED0003),
+    "strassen2_bf16_ffn": ("strassen2", "bf16", 8192, 14336, 4096, "normal", "weights", 0x5EED0003),
+    "laderman_f16_6144": ("laderman", "f16", 6144, 6144, 6144, "uniform", "uniform", 0x5EED0004),
+    "strassen_f32_4096": ("strassen", "f32", 4096, 4096, 4096, "uniform", "uniform", 0x5EED0005),
+    "strassen2_f32_4096": ("strassen2", "f32", 4096, 4096, 4096, "uniform", "uniform", 0x5EED0005),
+}
+
+
+def read_traffic(workload: str):
+    """HBM bytes per launch from the committed rocprofv3 counter summary, or None."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.txt")
+    if not os.path.exists(path):
+        return None
+    with open(path) as f:
+        for line in f:
+            tok = line.split("#", 1)[0].split()
+            if len(tok) >= 2 and tok[0] == workload:
+                return float(tok[1])
+    return None
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="strassen_bf16_4096", choices=sorted(WORKLOADS))
+    ap.add_argument("--variant", default=None, help="time this generated kernel instead of the default choice")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
+    ap.add_argument("--with-copy", action="store_true",
+                    help="also run a plain device copy of A's bytes (a known-size kernel that calibrates HBM counters)")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU (the path shards over M with no exchange; "
+                 "see DESIGN.md). Re-run with --gpus 1.")
+
+    import numpy as np
+    import torch
+
+    import lcma_inputs as inp
+    from paper_2605_06057_amd import binding as B
+
+    assert torch.cuda.is_available(), "bench.py needs the MI355X"
+    B.lib()
+    scheme_name, dt, M, N, K, kind_a, kind_b, seed = WORKLOADS[args.workload]
+    As, Bs = inp.matrices(kind_a, kind_b, M, N, K, dt, seed)
+
+    def dev(x):
+        if dt == "bf16":
+            return torch.from_numpy(x.view(np.int16)).cuda().view(torch.bfloat16)
+        return torch.from_numpy(x).cuda()
+
+    # three buffer sets, rotated, so that a step never finds its inputs left in cache by the step before
+    sets = []
+    for i in range(3):
+        a, b = dev(As), dev(Bs)
+        c = torch.empty((M, N), dtype=a.dtype, device="cuda")
+        sets.append((a, b, c))
+    scheme = B.lcma_scheme_load("builtin:" + scheme_name)
+    B.lcma_scheme_verify(scheme)
+    info = B.lcma_scheme_info(scheme)
+
+    def lcma_step(i):
+        a, b, c = sets[i % 3]
+        if args.variant:
+            B.lcma_gemm_variant(args.variant, a, b, c)
+        else:
+            B.lcma_gemm(a, b, c, scheme)
+
+    def plain_step(i):
+        a, b, c = sets[i % 3]
+        B.lcma_gemm(a, b, c, None)
+
+    def vendor_step(i):
+        a, b, c = sets[i % 3]
+        torch.mm(a, b, out=c)
+
+    def timed(step, steps, warmup):
+        for i in range(warmup):
+            step(i)
+        torch.cuda.synchronize()
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+        t0 = time.perf_counter()
+        ev[0].record()
+        for i in range(steps):
+            step(i)
+            ev[i + 1].record()
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+        per = [ev[i].elapsed_time(ev[i + 1]) for i in range(steps)]  # ms, on the launch stream
+        return wall / steps * 1e3, sum(per) / steps, sorted(per)[steps // 2]
+
+    if args.with_copy:
+        dst = torch.empty_like(sets[0][0])
+        for _ in range(5):
+            dst.copy_(sets[0][0])
+        torch.cuda.synchronize()
+
+    flops = 2.0 * M * N * K
+    wall_ms, ev_ms, med_ms = timed(lcma_step, args.steps, args.warmup)
+    p_wall_ms, p_ev_ms, p_med_ms = timed(plain_step, args.steps, args.warmup)
+    v_wall_ms, v_ev_ms, v_med_ms = timed(vendor_step, max(10, args.steps // 2), 3)
+    value = flops / (wall_ms * 1e-3) / 1e12
+    plain_tf = flops / (p_wall_ms * 1e-3) / 1e12
+    peak = PEAK_TFLOPS[dt]
+
+    # parity on sampled rows (one row range inside every block row of the scheme grid)
+    lcma_step(0)
+    plain_step(1)
+    torch.cuda.synchronize()
+    rows_per_block = 4
+    rows = np.concatenate([np.arange(rows_per_block) * 37 % (M // info["m"]) + i * (M // info["m"])
+                           for i in range(info["m"])])
+    cpu = None
+    err = err_plain = None
+    if not args.no_cpu:
+        import oracle
+        Aw, Bw = inp.widen(As, dt), inp.widen(Bs, dt)
+        t0 = time.perf_counter()
+        ref = oracle.gemm_rows(Aw, Bw, rows)
+        t_small = time.perf_counter() - t0
+
+        def host(t):
+            t = t[torch.from_numpy(rows).cuda()]
+            if dt == "bf16":
+                return inp.widen(t.contiguous().view(torch.int16).cpu().numpy().view(np.uint16), dt)
+            return t.cpu().numpy().astype(np.float64)
+        err = oracle.rel_frobenius(host(sets[0][2]), ref)
+        err_plain = oracle.rel_frobenius(host(sets[1][2]), ref)
+        # timed sample: as many leading rows as fit the CPU budget, judged from the small run
+        rate = 2.0 * len(rows) * N * K / max(t_small, 1e-6)
+        nrows = int(min(M, max(len(rows), args.cpu_seconds * rate / (2.0 * N * K))))
+        t0 = time.perf_counter()
+        oracle.gemm_rows(Aw, Bw, np.arange(nrows))
+        t_cpu = time.perf_counter() - t0
+        cpu = {"value": 2.0 * nrows * N * K / t_cpu / 1e12, "unit": "TFLOP/s", "cores": oracle.num_threads(),
+               "kind": "oracle", "sample": f"fp64 triple loop on the first {nrows} of {M} rows of C "
+               f"({t_cpu:.1f} s); whole problem extrapolated {t_cpu * M / nrows:.0f} s"}
+
+    mfma_flops = flops * info["R"] / (info["m"] * info["k"] * info["n"])
+    achieved = mfma_flops / (ev_ms * 1e-3) / 1e12
+    out = {
+        "metric": "effective TFLOP/s (2MNK/t) and fraction of MI355X dense MFMA peak",
+        "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": wall_ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f16" if dt == "bf16" else dt, "data": "synthetic",
+        "config": {"workload": f"{scheme_name} <{info['m']},{info['k']},{info['n']};{info['R']}> one launch, "
+                               f"{dt} storage, fp32 accumulate, M={M} N={N} K={K}, A {kind_a}, B {kind_b}",
+                   "variant": args.variant or "library default"},
+        "frac_of_dense_peak": value / peak,
+        "plain_mfma_gemm_tflops": plain_tf, "vs_plain": value / plain_tf,
+        "vendor_gemm_tflops": flops / (v_wall_ms * 1e-3) / 1e12,
+        "kernel_ms_events": {"lcma_mean": ev_ms, "lcma_median": med_ms, "plain_mean": p_ev_ms, "plain_median": p_med_ms},
+        "rel_frobenius_error": {"lcma": err, "plain": err_plain, "rows_checked": int(len(rows))},
+        "roofline": {"bound": "mfma", "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
+                     "frac": achieved / peak, "traffic": read_traffic(args.workload)},
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -91,8 +91,9 @@ template <> struct Round<BF16> {
 // TM x TN: tile of one block product owned by the work-group; TK: depth per y step;
 // WGM x WGN: wave grid (4 waves); NSLOT: products whose combinations are resident per stage;
 // STAGES: LDS stages.
-template <class IN_, class CT_, int TM_, int TN_, int TK_, int WGM_, int WGN_, int NSLOT_, int STAGES_>
+template <class IN_, class CT_, int TM_, int TN_, int TK_, int WGM_, int WGN_, int NSLOT_, int STAGES_, int PIPE_ = 0>
 struct Tile {
+    static constexpr int PIPE = PIPE_; // 0: double-buffered phases, 1: software-pipelined step
     using IN = IN_;
     using CT = CT_;
     static_assert(IN::ES == CT::ES, "conversion must keep the element size");
@@ -205,7 +206,6 @@ template <class T> struct Ctx {
     uint32_t a_group, b_group, c_group; // byte offsets of this group's tile inside a block
     uint32_t a_voff[T::QA], b_voff[T::QB];
     uint32_t a_lds[T::QA], b_lds[T::QB];
-    bool a_on[T::QA], b_on[T::QB];
     uint32_t a_frag[T::NKK], b_frag[T::NNI];
     uint32_t c_voff; // byte offset of this lane's first output element inside the tile
 
@@ -244,17 +244,17 @@ template <class T> struct Ctx {
 
 #pragma unroll
         for (int q = 0; q < T::QA; ++q) {
-            const int id2 = q * T::NT + tid;
+            // a tile smaller than the work-group is staged twice by threads that wrap around
+            // (same data to the same address), which keeps the pipeline free of branches
+            const int id2 = (q * T::NT + tid) % T::NCHK_A;
             const int row = id2 / T::CPR_A, c = id2 % T::CPR_A;
-            a_on[q] = (T::NCHK_A % T::NT == 0) || id2 < T::NCHK_A;
             a_voff[q] = (uint32_t)row * p.lda_b + c * 16;
             a_lds[q] = row * T::A_ROW + T::swz_a(row, c) * 16;
         }
 #pragma unroll
         for (int q = 0; q < T::QB; ++q) {
-            const int id2 = q * T::NT + tid;
+            const int id2 = (q * T::NT + tid) % T::NCHK_B;
             const int row = id2 / T::CPR_B, c = id2 % T::CPR_B;
-            b_on[q] = (T::NCHK_B % T::NT == 0) || id2 < T::NCHK_B;
             b_voff[q] = (uint32_t)row * p.ldb_b + c * 16;
             b_lds[q] = T::A_STAGE + row * T::B_ROW + T::swz_b(row, c) * 16;
         }
@@ -379,62 +379,101 @@ template <class T> struct Ctx {
 //   NA, NB, NP        raw A tiles, raw B tiles, products
 //   a_i(t), a_l(t)    block indices of raw A tile t; b_l(t), b_j(t) likewise for B
 //   comb_a(in, out)   out[s] = sum_t U * in[t]  (Eq. 3) on 16-byte vectors; comb_b likewise (Eq. 4)
-template <class T, class CH> LCMA_DEV void run_chunk(const Ctx<T> &cx, typename T::Acc (&acc)[CH::NP]) {
-    using V = typename T::CT::vec;
-    static_assert(CH::NP <= T::NSLOT, "chunk larger than the LDS slots");
-    u32x4 raw_a[CH::NA][T::QA], raw_b[CH::NB][T::QB];
+template <class T, class CH> struct RawSet {
+    u32x4 a[CH::NA][T::QA], b[CH::NB][T::QB];
+};
 
-    auto issue = [&](int y) {
+// Issue the buffer loads of step y into `r`.
+template <class T, class CH> LCMA_DEV void issue_loads(const Ctx<T> &cx, RawSet<T, CH> &r, int y) {
 #pragma unroll
-        for (int t = 0; t < CH::NA; ++t) {
-            const uint32_t so = cx.soff_a(CH::a_i(t), CH::a_l(t), y);
+    for (int t = 0; t < CH::NA; ++t) {
+        const uint32_t so = cx.soff_a(CH::a_i(t), CH::a_l(t), y);
 #pragma unroll
-            for (int q = 0; q < T::QA; ++q)
-                if (cx.a_on[q]) raw_a[t][q] = cx.load_a(q, so);
-        }
-#pragma unroll
-        for (int t = 0; t < CH::NB; ++t) {
-            const uint32_t so = cx.soff_b(CH::b_l(t), CH::b_j(t), y);
-#pragma unroll
-            for (int q = 0; q < T::QB; ++q)
-                if (cx.b_on[q]) raw_b[t][q] = cx.load_b(q, so);
-        }
-    };
-    auto combine_store = [&](int st) {
-        const uint32_t sb = st * T::STAGE;
-#pragma unroll
-        for (int q = 0; q < T::QA; ++q) {
-            if (!cx.a_on[q]) continue;
-            V in[CH::NA], out[CH::NP];
-#pragma unroll
-            for (int t = 0; t < CH::NA; ++t) in[t] = Convert<typename T::IN, typename T::CT>::run(raw_a[t][q]);
-            CH::comb_a(in, out);
-#pragma unroll
-            for (int s = 0; s < CH::NP; ++s) cx.lds_store(sb + s * T::A_SLOT + cx.a_lds[q], out[s]);
-        }
-#pragma unroll
-        for (int q = 0; q < T::QB; ++q) {
-            if (!cx.b_on[q]) continue;
-            V in[CH::NB], out[CH::NP];
-#pragma unroll
-            for (int t = 0; t < CH::NB; ++t) in[t] = Convert<typename T::IN, typename T::CT>::run(raw_b[t][q]);
-            CH::comb_b(in, out);
-#pragma unroll
-            for (int s = 0; s < CH::NP; ++s) cx.lds_store(sb + s * T::B_SLOT + cx.b_lds[q], out[s]);
-        }
-    };
-
-    const int ny = cx.p.ny;
-    issue(0);
-    for (int y = 0; y < ny; ++y) {
-        const int st = (T::STAGES == 1) ? 0 : (y % T::STAGES);
-        if constexpr (T::STAGES == 1) __syncthreads(); // readers of the previous step are done
-        combine_store(st);
-        if (y + 1 < ny) issue(y + 1);
-        __syncthreads();
-        cx.template mma_stage<CH::NP>(st, acc);
+        for (int q = 0; q < T::QA; ++q)
+            r.a[t][q] = cx.load_a(q, so);
     }
-    __syncthreads(); // the next chunk (or nothing) may overwrite the stages
+#pragma unroll
+    for (int t = 0; t < CH::NB; ++t) {
+        const uint32_t so = cx.soff_b(CH::b_l(t), CH::b_j(t), y);
+#pragma unroll
+        for (int q = 0; q < T::QB; ++q)
+            r.b[t][q] = cx.load_b(q, so);
+    }
+}
+
+// Convert the raw tiles in `r`, form the chunk's combinations (Eq. 3 / Eq. 4) and write them to LDS
+// stage `st`.
+template <class T, class CH> LCMA_DEV void combine_store(const Ctx<T> &cx, const RawSet<T, CH> &r, int st) {
+    using V = typename T::CT::vec;
+    using Cv = Convert<typename T::IN, typename T::CT>;
+    const uint32_t sb = st * T::STAGE;
+#pragma unroll
+    for (int q = 0; q < T::QA; ++q) {
+        V in[CH::NA], out[CH::NP];
+#pragma unroll
+        for (int t = 0; t < CH::NA; ++t) in[t] = Cv::run(r.a[t][q]);
+        CH::comb_a(in, out);
+#pragma unroll
+        for (int s = 0; s < CH::NP; ++s) cx.lds_store(sb + s * T::A_SLOT + cx.a_lds[q], out[s]);
+    }
+#pragma unroll
+    for (int q = 0; q < T::QB; ++q) {
+        V in[CH::NB], out[CH::NP];
+#pragma unroll
+        for (int t = 0; t < CH::NB; ++t) in[t] = Cv::run(r.b[t][q]);
+        CH::comb_b(in, out);
+#pragma unroll
+        for (int s = 0; s < CH::NP; ++s) cx.lds_store(sb + s * T::B_SLOT + cx.b_lds[q], out[s]);
+    }
+}
+
+// The y loop of Algorithm 2 for one chunk, software-pipelined over two LDS stages and two register
+// sets.  In the steady state one step (a single basic block, so that the scheduler may interleave
+// its parts) does: issue the loads of step y+2; multiply step y from LDS stage y%2; combine step
+// y+1 from registers into the other stage; barrier.  Loads therefore have a whole step of MFMA work
+// to arrive, and the additions, conversions and LDS writes share the step with the MFMAs.  Past the
+// end the last tile is loaded and combined again into the stage nobody reads, which keeps the
+// step branch-free.
+template <class T, class CH> LCMA_DEV void run_chunk(const Ctx<T> &cx, typename T::Acc (&acc)[CH::NP]) {
+    static_assert(CH::NP <= T::NSLOT, "chunk larger than the LDS slots");
+    static_assert(T::STAGES == 2, "two LDS stages");
+    const int ny = cx.p.ny, last = ny - 1;
+    if constexpr (T::PIPE == 0) {
+        // Plain double buffering: one register set, loads of step y+1 in flight during the MFMAs
+        // of step y.  Meant for two work-groups per CU, which overlap each other's phases.
+        RawSet<T, CH> r;
+        issue_loads<T, CH>(cx, r, 0);
+        for (int y = 0; y < ny; ++y) {
+            combine_store<T, CH>(cx, r, y & 1);
+            issue_loads<T, CH>(cx, r, y + 1 < ny ? y + 1 : last);
+            __syncthreads();
+            cx.template mma_stage<CH::NP>(y & 1, acc);
+        }
+        __syncthreads();
+    } else {
+        RawSet<T, CH> r0, r1;
+        issue_loads<T, CH>(cx, r0, 0);
+        issue_loads<T, CH>(cx, r1, ny > 1 ? 1 : 0);
+        combine_store<T, CH>(cx, r0, 0);
+        __syncthreads();
+        for (int y = 0; y < ny; y += 2) {
+            {   // even step: stage 0 holds y, r1 holds y+1, r0 is free
+                const int yn = y + 2 < ny ? y + 2 : last;
+                issue_loads<T, CH>(cx, r0, yn);
+                cx.template mma_stage<CH::NP>(0, acc);
+                combine_store<T, CH>(cx, r1, 1);
+                __syncthreads();
+            }
+            if (y + 1 >= ny) break;
+            {   // odd step: stage 1 holds y+1, r0 holds y+2, r1 is free
+                const int yn = y + 3 < ny ? y + 3 : last;
+                issue_loads<T, CH>(cx, r1, yn);
+                cx.template mma_stage<CH::NP>(1, acc);
+                combine_store<T, CH>(cx, r0, 0);
+                __syncthreads();
+            }
+        }
+    }
 }
 
 } // namespace lcma

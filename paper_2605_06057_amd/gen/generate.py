@@ -117,12 +117,14 @@ class Variant:
     chunk: int = 1            # products per chunk (consecutive in the chunk order)
     stages: int = 2
     rank: int = 0
-    group_by: int = 0         # >0: chunks are runs of this many consecutive products (two-level: outer r1)
+    pipe: int = 0             # 0: double-buffered phases, 1: software-pipelined step
+    occ: int = 1              # work-groups per CU the kernel is compiled for
     name: str = field(default="")
 
     def finish(self):
         if not self.name:
-            self.name = f"{self.scheme}_{self.dtype}_t{self.TM}x{self.TN}x{self.TK}_c{self.chunk}"
+            self.name = (f"{self.scheme}_{self.dtype}_t{self.TM}x{self.TN}x{self.TK}_c{self.chunk}"
+                         + ("p" if self.pipe else "") + (f"o{self.occ}" if self.occ > 1 else ""))
         return self
 
 
@@ -194,7 +196,7 @@ def emit_kernel(s: Scheme, v: Variant) -> str:
     w('#include "lcma_device.hpp"')
     w("namespace {")
     w("using namespace lcma;")
-    w(f"using T = Tile<{in_t}, {ct_t}, {v.TM}, {v.TN}, {v.TK}, {v.wgm}, {v.wgn}, {nslot}, {v.stages}>;")
+    w(f"using T = Tile<{in_t}, {ct_t}, {v.TM}, {v.TN}, {v.TK}, {v.wgm}, {v.wgn}, {nslot}, {v.stages}, {v.pipe}>;")
     for ci, ch in enumerate(chunks):
         a_blocks = sorted({(i, l) for r in ch for i in range(s.m) for l in range(s.k) if s.U[r, i, l]})
         b_blocks = sorted({(l, j) for r in ch for l in range(s.k) for j in range(s.n) if s.V[r, l, j]})
@@ -215,7 +217,7 @@ def emit_kernel(s: Scheme, v: Variant) -> str:
         w("    }")
         w("};")
     w("")
-    w(f"__global__ __launch_bounds__(256) void kern(const Params p) {{")
+    w(f"__global__ __launch_bounds__(256, {v.occ}) void kern(const Params p) {{")
     w("    __shared__ __attribute__((aligned(16))) char smem[T::LDS_BYTES];")
     w("    const Ctx<T> cx(p, (LCMA_LDS char *)smem);")
     if single:
@@ -307,11 +309,17 @@ def manifest() -> list[Variant]:
     for dt in ("bf16", "f16"):
         V += [
             Variant("plain", dt, 256, 256, 64, rank=0),
-            Variant("plain", dt, 256, 128, 64, rank=1),
-            Variant("plain", dt, 128, 128, 64, rank=2),
+            Variant("plain", dt, 256, 256, 32, rank=1, pipe=1),
+            Variant("plain", dt, 256, 128, 32, rank=2, occ=2),
+            Variant("plain", dt, 256, 128, 32, rank=3, occ=2, pipe=1),
+            Variant("plain", dt, 128, 128, 64, rank=4, occ=2),
+            Variant("plain", dt, 128, 128, 32, rank=5, occ=2, pipe=1),
             Variant("plain", dt, 64, 64, 32, rank=9),
             Variant("strassen", dt, 128, 64, 16, chunk=7, rank=0),
+            Variant("strassen", dt, 128, 64, 16, chunk=7, rank=1, pipe=1),
             Variant("strassen", dt, 64, 64, 32, chunk=7, rank=5),
+            Variant("strassen", dt, 64, 64, 32, chunk=7, rank=6, pipe=1),
+            Variant("strassen", dt, 64, 64, 16, chunk=7, rank=6, occ=2),
             Variant("strassen", dt, 128, 128, 32, chunk=1, rank=7),
             Variant("laderman", dt, 128, 64, 32, chunk=1, rank=0),
             Variant("laderman", dt, 64, 64, 32, chunk=1, rank=5),
