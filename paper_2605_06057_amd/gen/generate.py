@@ -217,7 +217,10 @@ def emit_kernel(s: Scheme, v: Variant) -> str:
         w("    }")
         w("};")
     w("")
-    w(f"__global__ __launch_bounds__(256, {v.occ}) void kern(const Params p) {{")
+    w("} // namespace")
+    w("")
+    w("// the kernel carries the variant's name so that profiles tell the variants apart")
+    w(f'extern "C" __global__ __launch_bounds__(256, {v.occ}) void lcma_k_{v.name}(const lcma::Params p) {{')
     w("    __shared__ __attribute__((aligned(16))) char smem[T::LDS_BYTES];")
     w("    const Ctx<T> cx(p, (LCMA_LDS char *)smem);")
     if single:
@@ -256,10 +259,9 @@ def emit_kernel(s: Scheme, v: Variant) -> str:
                             w(f"        cx.store_c({i}, {j}, [&](int mi, int ni) {{ return c[{i * s.n + j}].v[mi][ni]; }});")
             w("    }")
     w("}")
-    w("} // namespace")
     w("")
     w(f'extern "C" int lcma_launch_{v.name}(const lcma::Params *p, int grid, void *stream) {{')
-    w("    kern<<<dim3(grid), dim3(256), 0, (hipStream_t)stream>>>(*p);")
+    w(f"    lcma_k_{v.name}<<<dim3(grid), dim3(256), 0, (hipStream_t)stream>>>(*p);")
     w("    return (int)hipGetLastError();")
     w("}")
     return "\n".join(L) + "\n"
