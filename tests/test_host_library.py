@@ -1,0 +1,174 @@
+"""Host-side logic of liblcma.so, no GPU needed: exported symbols, scheme store and Brent
+verifier (against the oracle's independent tables), Table 2 / Eq. 8-10 closed forms, the
+Split-Group worked example, selector sanity."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import oracle
+from oracle import schemes as S
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2605_06057_amd import binding
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_2605_06057_amd import build
+        build.build()
+    binding.lib()
+    return binding
+
+
+def test_every_declared_symbol_is_exported(B):
+    header = open(os.path.join(ROOT, "include", "lcma.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(lcma_[a-z0-9_]+)\s*\(", header))
+    assert declared, "no declarations found"
+    assert declared == set(B.EXPORTS)
+    for name in declared:
+        assert hasattr(B.lib(), name), name
+
+
+@pytest.mark.parametrize("name", ["strassen", "strassen2", "laderman"])
+def test_builtin_schemes_equal_the_oracles(B, name):
+    s = B.lcma_scheme_load("builtin:" + name)
+    assert B.lcma_scheme_verify(s) == -1
+    U, V, W = B.lcma_scheme_coeffs(s)
+    ref = S.by_name(name)
+    assert np.array_equal(U, ref.U) and np.array_equal(V, ref.V) and np.array_equal(W, ref.W)
+    info = B.lcma_scheme_info(s)
+    assert (info["m"], info["k"], info["n"], info["R"]) == (ref.m, ref.k, ref.n, ref.R)
+    assert (info["nnzU"], info["nnzV"], info["nnzW"]) == ref.nnz()
+
+
+def test_paper_facts_from_the_library(B, golden):
+    g = golden("paper_facts.txt")
+    info = B.lcma_scheme_info(B.lcma_scheme_load("builtin:strassen"))
+    assert info["R"] == int(g["strassen_rank"][0]) and info["nnzU"] == int(g["strassen_nnzU"][0])
+    assert info["nnzU"] - info["R"] == int(g["strassen_addsA"][0])
+    _, _, W = B.lcma_scheme_coeffs(B.lcma_scheme_load("builtin:strassen"))
+    assert [r + 1 for r in range(7) if W[r, 0, 0]] == [int(x) for x in g["strassen_c11_products"]]
+    assert B.lcma_scheme_info(B.lcma_scheme_load("builtin:laderman"))["R"] == int(g["laderman_rank"][0])
+    assert B.lcma_scheme_info(B.lcma_scheme_load("builtin:strassen2"))["R"] == int(g["strassen2_rank"][0])
+
+
+def test_file_schemes_and_verifier_verdicts(B, tmp_path):
+    good = tmp_path / "classical.txt"
+    good.write_text("# classical 2x3x2\n" + S.to_text(S.classical(2, 3, 2)))
+    s = B.lcma_scheme_load(str(good))
+    assert B.lcma_scheme_verify(s) == -1
+    assert B.lcma_scheme_info(s)["R"] == 12
+    base = S.laderman()
+    for which, pos in [("U", (3, 1, 0)), ("V", (10, 2, 2)), ("W", (5, 0, 0))]:
+        T = {"U": base.U.copy(), "V": base.V.copy(), "W": base.W.copy()}
+        T[which][pos] = 0 if T[which][pos] else 1
+        bad = S.Scheme(3, 3, 3, 23, T["U"], T["V"], T["W"])
+        path = tmp_path / f"bad_{which}.txt"
+        path.write_text(S.to_text(bad))
+        with pytest.raises(B.LcmaError) as e:
+            B.lcma_scheme_verify(B.lcma_scheme_load(str(path)))
+        assert e.value.status == B.LCMA_ERR_BRENT
+        assert e.value.first_bad == oracle.brent(bad)[1]  # same first violated equation as the oracle finds
+    # a file with a built-in's coefficients is recognised as that built-in (kernels exist for it)
+    same = tmp_path / "strassen_copy.txt"
+    same.write_text(S.to_text(S.strassen()))
+    assert B.lcma_scheme_verify(B.lcma_scheme_load(str(same))) == -1
+
+
+def test_loader_error_paths(B, tmp_path):
+    for text, status in [("2 2 2\n", B.LCMA_ERR_PARSE), ("2 2 2 7\n1 0 0 1\n", B.LCMA_ERR_PARSE),
+                         ("2 2 2 1\n1 0 0 x\n", B.LCMA_ERR_PARSE), ("1 1 1 1\n300\n1\n1\n", B.LCMA_ERR_PARSE),
+                         ("0 1 1 1\n1\n1\n1\n", B.LCMA_ERR_PARSE)]:
+        p = tmp_path / "t.txt"
+        p.write_text(text)
+        with pytest.raises(B.LcmaError) as e:
+            B.lcma_scheme_load(str(p))
+        assert e.value.status == status, text
+    with pytest.raises(B.LcmaError) as e:
+        B.lcma_scheme_load(str(tmp_path / "missing.txt"))
+    assert e.value.status == B.LCMA_ERR_IO
+    with pytest.raises(B.LcmaError) as e:
+        B.lcma_scheme_load("builtin:nonesuch")
+    assert e.value.status == B.LCMA_ERR_IO
+    assert B.lib().lcma_status_str(B.LCMA_ERR_BRENT).decode().startswith("scheme violates")
+
+
+def test_split_group_worked_example(B, golden):
+    g = {k: v[0] for k, v in golden("split_group_example.txt").items()}
+    tile, R, units = int(g["tile"]), int(g["R"]), int(g["units"])
+    groups = (int(g["M"]) // 2 // tile) * (int(g["N"]) // 2 // tile)
+    assert groups == int(g["groups"]) and groups * R == int(g["h_tiles"])
+    tile_level, group_level = B.lcma_sched_waves(groups, R, units)
+    assert tile_level == int(g["waves_tile_level"]) and group_level == int(g["waves_group_level"])
+    assert round(100.0 * (group_level - tile_level) / tile_level, 1) == float(g["waste_percent"])
+    # Split-Group ranges: contiguous, cover every tile-product once, capacity ceil(total/units)
+    cap = -(-groups * R // units)
+    prev_end = 0
+    for u in range(units):
+        b, e = B.lcma_sched_range(groups, R, units, u)
+        assert b == prev_end and 0 <= e - b <= cap
+        prev_end = e
+    assert prev_end == groups * R
+    straddle = [sum(1 for u in range(units) if (lambda be: be[0] < (gi + 1) * R and be[1] > gi * R)(B.lcma_sched_range(groups, R, units, u)))
+                for gi in range(groups)]
+    assert max(straddle) <= 2  # a group is split across at most two units
+
+
+def test_table2_and_intensity_closed_forms(B):
+    M, N, K = 4096, 2048, 1024
+    s = B.lcma_scheme_load("builtin:strassen")
+    hw = B.lcma_hw()
+    hw.flops_mul, hw.flops_add, hw.beta = 148e12, 20e12, 2e12  # H20 bf16 figures of the roofline section: 4 TB/s = 2e12 elements/s
+    c = B.lcma_model_stages(s, M, N, K, hw)
+    # Table 2 with ||U||0 = ||V||0 = ||W||0 = 12, R = 7, m = k = n = 2
+    assert c.flops[0] == 5 * (M / 2) * (K / 2) and c.elems[0] == M * K * (1 + 7 / 4)
+    assert c.flops[1] == 5 * (N / 2) * (K / 2) and c.elems[1] == N * K * (1 + 7 / 4)
+    assert c.flops[2] == 2 * 7 * M * N * K / 8 and c.elems[2] == 7 * (M * K / 4 + N * K / 4 + M * N / 4)
+    assert c.flops[3] == (12 - 4) * (M / 2) * (N / 2) and c.elems[3] == M * N * (1 + 7 / 4)
+    for i in range(4):
+        rate = hw.flops_mul if i == 2 else hw.flops_add
+        assert c.seconds[i] == max(c.flops[i] / rate, c.elems[i] / hw.beta)
+    p = B.lcma_model_stages(None, M, N, K, hw)
+    assert p.flops[2] == 2 * M * N * K and p.elems[2] == M * K + N * K + M * N
+    eq8, eq9, eq10 = B.lcma_model_intensity(s, M, N, K)
+    assert eq8 == pytest.approx(2 * M * N * K / (M * K + N * K + M * N))
+    assert eq9 == pytest.approx(2 * M * N * K * (1 - 7 / 8) / (M * K * 2.75 + N * K * 2.75 + M * N * 2.75))
+    assert eq10 == pytest.approx(2 * M * N * K * (1 - 7 / 8) / (M * K * 2.75 + N * K * 2.75 + M * N))
+    assert eq10 > eq9  # fusing Combine H removes the R/mn term
+    # Eq. 9 is the simplification of "sum of stage times < plain time" when combines are memory-bound:
+    lhs = c.elems[0] / hw.beta + c.elems[1] / hw.beta + c.flops[2] / hw.flops_mul + c.elems[3] / hw.beta
+    assert (lhs < p.flops[2] / hw.flops_mul) == (eq9 > hw.flops_mul / hw.beta)
+
+
+def test_selector_sanity(B):
+    for dt in (B.LCMA_F32, B.LCMA_BF16, B.LCMA_F16):
+        assert B.lcma_select(64, 64, 64, dt) == B.LCMA_PLAIN        # memory/launch bound: Eq. 8 short-circuit
+        assert B.lcma_select(8, 4096, 4096, dt) == B.LCMA_PLAIN
+        pick = B.lcma_select(8192, 14336, 4096, dt)
+        assert pick in (B.LCMA_PLAIN, B.LCMA_STRASSEN, B.LCMA_STRASSEN2, B.LCMA_LADERMAN)
+        t_pick = B.lcma_predict_seconds(pick, 8192, 14336, 4096, dt)
+        for other in range(4):
+            t = B.lcma_predict_seconds(other, 8192, 14336, 4096, dt)
+            assert t < 0 or t_pick <= t  # the pick is the argmin of the model
+    assert B.lcma_select(0, 1, 1, B.LCMA_F32) < 0 and B.lcma_select(1, 1, 1, 9) < 0
+    hw = B.lcma_hw_mi355x(B.LCMA_BF16)
+    assert hw.flops_mul == pytest.approx(2516.6e12) and hw.beta == pytest.approx(4e12)
+    assert B.lcma_hw_mi355x(B.LCMA_F32).flops_mul == pytest.approx(157.3e12)
+
+
+def test_variant_registry(B):
+    vs = B.lcma_variants()
+    names = [v["name"] for v in vs]
+    assert len(set(names)) == len(names) > 0
+    for v in vs:
+        assert v["mult_M"] % v["TM"] == 0 and v["mult_N"] % v["TN"] == 0 and v["mult_K"] % v["TK"] == 0
+    # every BASELINE configuration has a kernel: (scheme id, dtype id, M, N, K)
+    for sid, dt, M, N, K in [(1, 0, 256, 256, 256), (1, 1, 4096, 4096, 4096), (1, 1, 8192, 14336, 4096),
+                             (2, 1, 8192, 14336, 4096), (3, 2, 6144, 6144, 6144), (0, 1, 2048, 4096, 14336)]:
+        assert any(v["scheme_id"] == sid and v["dtype"] == dt and M % v["mult_M"] == 0 and N % v["mult_N"] == 0
+                   and K % v["mult_K"] == 0 for v in vs), (sid, dt, M, N, K)
