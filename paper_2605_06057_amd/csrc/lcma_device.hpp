@@ -75,6 +75,19 @@ template <> struct Wide<f16x8> {
     static LCMA_DEV f16x8 down(const f32x8 &v) { return __builtin_convertvector(v, f16x8); }
 };
 
+// Element-wise add / subtract of the vectors the combinations are formed on.  A packed fp16
+// subtraction is written as fma(b, -1, a) with the -1 hidden from the optimiser: the compiler
+// otherwise splits a packed fp16 subtraction into two scalar subtractions and a pack per dword.
+// (No instruction is written by hand, so hazard handling stays with the compiler.)
+template <class V> LCMA_DEV V vadd(const V &a, const V &b) { return a + b; }
+template <class V> LCMA_DEV V vsub(const V &a, const V &b) { return a - b; }
+LCMA_DEV f16x8 vsub(const f16x8 &a, const f16x8 &b) {
+    uint32_t m = 0xBC00BC00u; // (-1.0h, -1.0h)
+    asm("" : "+v"(m)); // not volatile: identical copies merge into one
+    const u32x4 m4 = {m, m, m, m};
+    return __builtin_elementwise_fma(b, __builtin_bit_cast(f16x8, m4), a);
+}
+
 // fp32 accumulator -> storage element (one rounding, nearest-even), as raw bits.
 template <class IN> struct Round;
 template <> struct Round<F32> {
@@ -89,58 +102,60 @@ template <> struct Round<BF16> {
 
 // ---------------------------------------------------------------- tile configuration
 // TM x TN: tile of one block product owned by the work-group; TK: depth per y step;
-// WGM x WGN: wave grid (4 waves); NSLOT: products whose combinations are resident per stage;
-// STAGES: LDS stages.
-template <class IN_, class CT_, int TM_, int TN_, int TK_, int WGM_, int WGN_, int NSLOT_, int STAGES_, int PIPE_ = 0>
+// WGM x WGN: wave grid (4 waves); NSA / NSB: A-side / B-side tiles resident per LDS stage;
+// PIPE: 0 double-buffered phases, 1 software-pipelined step;
+// FC: 0 = combinations are formed while staging and LDS holds At_r, Bt_r;
+//     1 = LDS holds the raw (converted) blocks and every wave forms the combinations on the
+//         MFMA fragments it has read ("fragment combine").
+//
+// LDS layout of a stage: NSA tiles [TM rows][TK] then NSB tiles [TN rows][TK], both k-contiguous,
+// 16-byte chunks XOR-swizzled inside a row.  B arrives n-contiguous from memory and is transposed
+// in registers while it is staged, so that both MFMA operands are read with 16-byte LDS loads
+// (measured on MI355X: ds_read_b128 ~260 B/clk/CU, the transposing ds_read_b64_tr_b16 ~70).
+template <class IN_, class CT_, int TM_, int TN_, int TK_, int WGM_, int WGN_, int NSA_, int NSB_, int PIPE_ = 0,
+          int FC_ = 0>
 struct Tile {
-    static constexpr int PIPE = PIPE_; // 0: double-buffered phases, 1: software-pipelined step
+    static constexpr int PIPE = PIPE_, FC = FC_;
     using IN = IN_;
     using CT = CT_;
     static_assert(IN::ES == CT::ES, "conversion must keep the element size");
     static constexpr int TM = TM_, TN = TN_, TK = TK_, WGM = WGM_, WGN = WGN_;
-    static constexpr int NSLOT = NSLOT_, STAGES = STAGES_;
+    static constexpr int NSA = NSA_, NSB = NSB_, STAGES = 2;
     static constexpr int ES = CT::ES, CH = CT::CH;
     static constexpr int NT = 64 * WGM * WGN;
     static constexpr int WM = TM / WGM, WN = TN / WGN;
     static constexpr int NMI = WM / 32, NNI = WN / 32;
     static constexpr int KSTEP = (ES == 2) ? 16 : 8; // k covered by one fragment read
     static constexpr int NKK = TK / KSTEP;
-    static constexpr int CPR_A = TK / CH, CPR_B = TN / CH; // 16-byte chunks per LDS row
-    static constexpr int NCHK_A = TM * CPR_A, NCHK_B = TK * CPR_B;
-    static constexpr int QA = (NCHK_A + NT - 1) / NT, QB = (NCHK_B + NT - 1) / NT;
-    static constexpr int A_ROW = TK * ES, B_ROW = TN * ES; // LDS row pitch in bytes
-    static constexpr int A_SLOT = TM * A_ROW, B_SLOT = TK * B_ROW;
-    static constexpr int A_STAGE = NSLOT * A_SLOT, B_STAGE = NSLOT * B_SLOT;
+    static constexpr int CPR = TK / CH;        // 16-byte chunks per LDS row
+    static constexpr int ROW = TK * ES;        // LDS row pitch in bytes
+    static constexpr int NCHK_A = TM * CPR;    // A is staged one 16-byte chunk per thread and step
+    static constexpr int QA = (NCHK_A + NT - 1) / NT;
+    // B is staged in units: 16-bit: a column pair x 8 consecutive k (8 dword loads -> 2 chunks);
+    // fp32: one column x 4 consecutive k (4 dword loads -> 1 chunk).
+    static constexpr int BW = (ES == 2) ? 8 : 4;   // dword loads per unit
+    static constexpr int BH = BW / 4;              // 16-byte register vectors per unit
+    static constexpr int BCOLS = (ES == 2) ? TN / 2 : TN;
+    static constexpr int NU_B = BCOLS * CPR;
+    static constexpr int QB = (NU_B + NT - 1) / NT;
+    static constexpr int A_SLOT = TM * ROW, B_SLOT = TN * ROW;
+    static constexpr int A_STAGE = NSA * A_SLOT, B_STAGE = NSB * B_SLOT;
     static constexpr int STAGE = A_STAGE + B_STAGE;
     static constexpr int LDS_BYTES = STAGES * STAGE;
     static_assert(NT == 256, "four waves per work-group");
     static_assert(WM % 32 == 0 && WN % 32 == 0 && TK % KSTEP == 0, "MFMA 32x32 tiling");
-    static_assert(TK % CH == 0 && TN % CH == 0, "16-byte chunks");
     static_assert(LDS_BYTES <= 160 * 1024, "LDS budget of one CU");
 
     struct Acc {
         f32x16 v[NMI][NNI];
     };
 
-    // LDS swizzles: XOR on the 16-byte chunk index of a row.
-    // A rows are read 16 rows at a time (one chunk column): spread them over the 16 chunk
-    // positions of a 256-byte bank window.
-    static LCMA_DEV constexpr int swz_a(int row, int c) {
-        constexpr int rpw = (CPR_A >= 16) ? 1 : 16 / CPR_A; // rows per 256-byte window
-        constexpr int mask = (CPR_A >= 16) ? 15 : CPR_A - 1;
+    // XOR swizzle of the chunk index: a fragment read touches 16 consecutive rows at one chunk
+    // column; spread them over the 16 chunk positions of a 256-byte bank window.
+    static LCMA_DEV constexpr int swz(int row, int c) {
+        constexpr int rpw = (CPR >= 16) ? 1 : 16 / CPR; // rows per 256-byte window
+        constexpr int mask = (CPR >= 16) ? 15 : CPR - 1;
         return c ^ ((row / rpw) & mask);
-    }
-    // B rows are read four k-rows at a time, 64 bytes from each (16-bit types): move the four
-    // rows to four different 64-byte segments of the bank window.
-    static LCMA_DEV constexpr int swz_b(int row, int c) {
-        if constexpr (ES == 2) {
-            if constexpr (CPR_B >= 16) return c ^ ((row & 3) << 2);
-            else if constexpr (CPR_B == 8) return c ^ (((row >> 1) & 1) << 2);
-            else return c;
-        } else {
-            if constexpr (CPR_B >= 16) return c ^ (((row >> 2) & 1) << 3);
-            else return c;
-        }
     }
 };
 
@@ -205,8 +220,8 @@ template <class T> struct Ctx {
     int lane, wm, wn;
     uint32_t a_group, b_group, c_group; // byte offsets of this group's tile inside a block
     uint32_t a_voff[T::QA], b_voff[T::QB];
-    uint32_t a_lds[T::QA], b_lds[T::QB];
-    uint32_t a_frag[T::NKK], b_frag[T::NNI];
+    uint32_t a_lds[T::QA], b_lds[T::QB], b_lds1[T::QB]; // b_lds1: second LDS row of a 16-bit B unit
+    uint32_t a_frag[T::NKK], b_frag[T::NKK];
     uint32_t c_voff; // byte offset of this lane's first output element inside the tile
 
     LCMA_DEV Ctx(const Params &p_, LCMA_LDS char *lds_) : p(p_), lds(lds_) {
@@ -247,45 +262,28 @@ template <class T> struct Ctx {
             // a tile smaller than the work-group is staged twice by threads that wrap around
             // (same data to the same address), which keeps the pipeline free of branches
             const int id2 = (q * T::NT + tid) % T::NCHK_A;
-            const int row = id2 / T::CPR_A, c = id2 % T::CPR_A;
+            const int row = id2 / T::CPR, c = id2 % T::CPR;
             a_voff[q] = (uint32_t)row * p.lda_b + c * 16;
-            a_lds[q] = row * T::A_ROW + T::swz_a(row, c) * 16;
+            a_lds[q] = row * T::ROW + T::swz(row, c) * 16;
         }
 #pragma unroll
         for (int q = 0; q < T::QB; ++q) {
-            const int id2 = (q * T::NT + tid) % T::NCHK_B;
-            const int row = id2 / T::CPR_B, c = id2 % T::CPR_B;
-            b_voff[q] = (uint32_t)row * p.ldb_b + c * 16;
-            b_lds[q] = T::A_STAGE + row * T::B_ROW + T::swz_b(row, c) * 16;
+            // consecutive lanes take consecutive columns (coalesced dword loads along a row of B)
+            const int u = (q * T::NT + tid) % T::NU_B;
+            const int col = u % T::BCOLS, g = u / T::BCOLS; // g: group of CH consecutive k
+            const int row = (T::ES == 2) ? 2 * col : col;   // LDS row = column n of the tile
+            b_voff[q] = (uint32_t)(g * T::CH) * p.ldb_b + col * 4;
+            b_lds[q] = T::A_STAGE + row * T::ROW + T::swz(row, g) * 16;
+            b_lds1[q] = T::A_STAGE + (row + 1) * T::ROW + T::swz(row + 1, g) * 16;
         }
-        // Fragment addresses.  A operand of the 32x32 MFMA: lane holds row lane%32 and the
-        // (lane/32)-th group of consecutive k -> one 16-byte read.
+        // Fragment addresses.  Operand of the 32x32 MFMA: lane holds row lane%32 and the
+        // (lane/32)-th group of consecutive k -> one 16-byte read, for A (rows = m) and B (rows = n).
         const int l32 = lane & 31, lh = lane >> 5;
 #pragma unroll
         for (int kk = 0; kk < T::NKK; ++kk) {
-            const int row = wm * T::WM + l32;
-            a_frag[kk] = row * T::A_ROW + T::swz_a(row, kk * 2 + lh) * 16;
-        }
-        if constexpr (T::ES == 2) {
-            // B operand, 16-bit: column lane%32, 8 consecutive k.  The tile is stored
-            // n-contiguous, so it is read with the transposing 64-bit LDS load: 16 lanes
-            // fetch a 4(k) x 16(n) patch (lane i supplies row i/4, columns 4*(i%4)..+3) and
-            // lane j receives column j.
-            const int i16 = lane & 15, g = (lane >> 4) & 1;
-#pragma unroll
-            for (int ni = 0; ni < T::NNI; ++ni) {
-                const int row = 8 * lh + (i16 >> 2);
-                const int col = wn * T::WN + ni * 32 + 16 * g + 4 * (i16 & 3);
-                b_frag[ni] = T::A_STAGE + row * T::B_ROW + T::swz_b(row, col >> 3) * 16 + ((col >> 2) & 1) * 8;
-            }
-        } else {
-            // fp32: lane reads B[k][n = lane%32] for k = 4*(lane/32) + t, one dword each.
-#pragma unroll
-            for (int ni = 0; ni < T::NNI; ++ni) {
-                const int row = 4 * lh;
-                const int col = wn * T::WN + ni * 32 + l32;
-                b_frag[ni] = T::A_STAGE + row * T::B_ROW + T::swz_b(row, col >> 2) * 16 + (col & 3) * 4;
-            }
+            const int ra_ = wm * T::WM + l32, rb_ = wn * T::WN + l32;
+            a_frag[kk] = ra_ * T::ROW + T::swz(ra_, kk * 2 + lh) * 16;
+            b_frag[kk] = T::A_STAGE + rb_ * T::ROW + T::swz(rb_, kk * 2 + lh) * 16;
         }
         // Output: accumulator register v of MFMA tile (mi, ni) is row 8*(v/4) + 4*(lane/32) + v%4,
         // column lane%32 of that 32x32 tile.
@@ -295,8 +293,8 @@ template <class T> struct Ctx {
     LCMA_DEV u32x4 load_a(int q, uint32_t soff) const {
         return __builtin_amdgcn_raw_buffer_load_b128(ra, (int)a_voff[q], (int)soff, 0);
     }
-    LCMA_DEV u32x4 load_b(int q, uint32_t soff) const {
-        return __builtin_amdgcn_raw_buffer_load_b128(rb, (int)b_voff[q], (int)soff, 0);
+    LCMA_DEV uint32_t load_b(int q, uint32_t soff) const {
+        return __builtin_amdgcn_raw_buffer_load_b32(rb, (int)b_voff[q], (int)soff, 0);
     }
     // Scalar byte offset of tile y of block A_{i,l} / B_{l,j} for this group.
     LCMA_DEV uint32_t soff_a(int i, int l, int y) const {
@@ -306,11 +304,10 @@ template <class T> struct Ctx {
         return (uint32_t)l * p.b_brow + (uint32_t)j * p.b_bcol + b_group + (uint32_t)y * T::TK * p.ldb_b;
     }
 
-    LCMA_DEV void lds_store(uint32_t off, const V &v) const {
-        *(LCMA_LDS u32x4 *)(lds + off) = __builtin_bit_cast(u32x4, v);
-    }
+    LCMA_DEV void lds_store(uint32_t off, const u32x4 &v) const { *(LCMA_LDS u32x4 *)(lds + off) = v; }
+    LCMA_DEV Frag lds_frag(uint32_t off) const { return __builtin_bit_cast(Frag, *(LCMA_LDS u32x4 *)(lds + off)); }
 
-    // acc[s] += At_s x Bt_s for the NP products resident in LDS stage `st`.
+    // acc[s] += At_s x Bt_s for the NP products whose combinations sit in LDS stage `st`.
     template <int NP> LCMA_DEV void mma_stage(int st, typename T::Acc (&acc)[NP]) const {
         const uint32_t sb = st * T::STAGE;
 #pragma unroll
@@ -319,34 +316,61 @@ template <class T> struct Ctx {
             for (int kk = 0; kk < T::NKK; ++kk) {
                 Frag a[T::NMI], b[T::NNI];
 #pragma unroll
-                for (int mi = 0; mi < T::NMI; ++mi)
-                    a[mi] = __builtin_bit_cast(
-                        Frag, *(LCMA_LDS u32x4 *)(lds + sb + s * T::A_SLOT + a_frag[kk] + mi * 32 * T::A_ROW));
+                for (int mi = 0; mi < T::NMI; ++mi) a[mi] = lds_frag(sb + s * T::A_SLOT + a_frag[kk] + mi * 32 * T::ROW);
 #pragma unroll
-                for (int ni = 0; ni < T::NNI; ++ni) {
-                    const uint32_t base = sb + s * T::B_SLOT + b_frag[ni] + kk * T::KSTEP * T::B_ROW;
-                    if constexpr (T::ES == 2) {
-                        const i16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LCMA_LDS i16x4 *)(lds + base));
-                        const i16x4 hi =
-                            __builtin_amdgcn_ds_read_tr16_b64_v4i16((LCMA_LDS i16x4 *)(lds + base + 4 * T::B_ROW));
-                        i16x8 both;
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) {
-                            both[e] = lo[e];
-                            both[e + 4] = hi[e];
-                        }
-                        b[ni] = __builtin_bit_cast(Frag, both);
-                    } else {
-                        f32x4 t;
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) t[e] = *(LCMA_LDS float *)(lds + base + e * T::B_ROW);
-                        b[ni] = t;
-                    }
-                }
+                for (int ni = 0; ni < T::NNI; ++ni) b[ni] = lds_frag(sb + s * T::B_SLOT + b_frag[kk] + ni * 32 * T::ROW);
 #pragma unroll
                 for (int mi = 0; mi < T::NMI; ++mi)
 #pragma unroll
                     for (int ni = 0; ni < T::NNI; ++ni) Mma<CT>::run(a[mi], b[ni], acc[s].v[mi][ni]);
+            }
+        }
+    }
+
+    // Fragment-combine form: LDS stage `st` holds the raw blocks; read their fragments once, form the
+    // operand fragments of every product with CH::comb_a / comb_b (Eq. 3 / Eq. 4 on registers) and
+    // multiply.
+    template <class CH> LCMA_DEV void mma_stage_fc(int st, typename T::Acc (&acc)[CH::NP]) const {
+        const uint32_t sb = st * T::STAGE;
+        Frag ra_[2][T::NMI][CH::NA], rb_[2][T::NNI][CH::NB];
+        auto fetch = [&](int kk, int buf) {
+#pragma unroll
+            for (int mi = 0; mi < T::NMI; ++mi)
+#pragma unroll
+                for (int t = 0; t < CH::NA; ++t)
+                    ra_[buf][mi][t] = lds_frag(sb + t * T::A_SLOT + a_frag[kk] + mi * 32 * T::ROW);
+#pragma unroll
+            for (int ni = 0; ni < T::NNI; ++ni)
+#pragma unroll
+                for (int t = 0; t < CH::NB; ++t)
+                    rb_[buf][ni][t] = lds_frag(sb + t * T::B_SLOT + b_frag[kk] + ni * 32 * T::ROW);
+        };
+        fetch(0, 0);
+#pragma unroll
+        for (int kk = 0; kk < T::NKK; ++kk) {
+            const int cur = kk & 1;
+            if (kk + 1 < T::NKK) fetch(kk + 1, cur ^ 1); // next fragments arrive under this step's MFMAs
+#pragma unroll
+            for (int s = 0; s < CH::NP; ++s) {
+                // one product at a time keeps few combined fragments live; the unused outputs of the
+                // generated combination code are dead and vanish
+                Frag at[T::NMI], bt[T::NNI];
+#pragma unroll
+                for (int mi = 0; mi < T::NMI; ++mi) {
+                    Frag o[CH::NP];
+                    CH::comb_a(ra_[cur][mi], o);
+                    at[mi] = o[s];
+                }
+#pragma unroll
+                for (int ni = 0; ni < T::NNI; ++ni) {
+                    Frag o[CH::NP];
+                    CH::comb_b(rb_[cur][ni], o);
+                    bt[ni] = o[s];
+                }
+#pragma unroll
+                for (int mi = 0; mi < T::NMI; ++mi)
+#pragma unroll
+                    for (int ni = 0; ni < T::NNI; ++ni) Mma<CT>::run(at[mi], bt[ni], acc[s].v[mi][ni]);
             }
         }
     }
@@ -376,11 +400,11 @@ template <class T> struct Ctx {
 
 // ---------------------------------------------------------------- one chunk of products over all y
 // CH (generated) describes the chunk:
-//   NA, NB, NP        raw A tiles, raw B tiles, products
-//   a_i(t), a_l(t)    block indices of raw A tile t; b_l(t), b_j(t) likewise for B
+//   NA, NB, NP        raw A blocks, raw B blocks, products
+//   a_i(t), a_l(t)    block indices of raw A block t; b_l(t), b_j(t) likewise for B
 //   comb_a(in, out)   out[s] = sum_t U * in[t]  (Eq. 3) on 16-byte vectors; comb_b likewise (Eq. 4)
 template <class T, class CH> struct RawSet {
-    u32x4 a[CH::NA][T::QA], b[CH::NB][T::QB];
+    u32x4 a[CH::NA][T::QA], b[CH::NB][T::QB][T::BH];
 };
 
 // Issue the buffer loads of step y into `r`.
@@ -389,56 +413,193 @@ template <class T, class CH> LCMA_DEV void issue_loads(const Ctx<T> &cx, RawSet<
     for (int t = 0; t < CH::NA; ++t) {
         const uint32_t so = cx.soff_a(CH::a_i(t), CH::a_l(t), y);
 #pragma unroll
-        for (int q = 0; q < T::QA; ++q)
-            r.a[t][q] = cx.load_a(q, so);
+        for (int q = 0; q < T::QA; ++q) r.a[t][q] = cx.load_a(q, so);
     }
 #pragma unroll
     for (int t = 0; t < CH::NB; ++t) {
         const uint32_t so = cx.soff_b(CH::b_l(t), CH::b_j(t), y);
 #pragma unroll
         for (int q = 0; q < T::QB; ++q)
-            r.b[t][q] = cx.load_b(q, so);
+#pragma unroll
+            for (int e = 0; e < T::BW; ++e) r.b[t][q][e / 4][e % 4] = cx.load_b(q, so + (uint32_t)e * cx.p.ldb_b);
     }
 }
 
-// Convert the raw tiles in `r`, form the chunk's combinations (Eq. 3 / Eq. 4) and write them to LDS
-// stage `st`.
+// Convert the raw blocks in `r`, form the combinations (Eq. 3 / Eq. 4) unless the kernel combines
+// fragments later, transpose B to k-contiguous chunks and write everything to LDS stage `st`.
 template <class T, class CH> LCMA_DEV void combine_store(const Ctx<T> &cx, const RawSet<T, CH> &r, int st) {
     using V = typename T::CT::vec;
     using Cv = Convert<typename T::IN, typename T::CT>;
+    constexpr int NOA = T::FC ? CH::NA : CH::NP, NOB = T::FC ? CH::NB : CH::NP;
+    static_assert(NOA <= T::NSA && NOB <= T::NSB, "chunk larger than the LDS slots");
     const uint32_t sb = st * T::STAGE;
 #pragma unroll
     for (int q = 0; q < T::QA; ++q) {
-        V in[CH::NA], out[CH::NP];
+        V in[CH::NA], out[NOA];
 #pragma unroll
         for (int t = 0; t < CH::NA; ++t) in[t] = Cv::run(r.a[t][q]);
-        CH::comb_a(in, out);
+        if constexpr (T::FC) {
 #pragma unroll
-        for (int s = 0; s < CH::NP; ++s) cx.lds_store(sb + s * T::A_SLOT + cx.a_lds[q], out[s]);
+            for (int t = 0; t < CH::NA; ++t) out[t] = in[t];
+        } else {
+            CH::comb_a(in, out);
+        }
+#pragma unroll
+        for (int s = 0; s < NOA; ++s) cx.lds_store(sb + s * T::A_SLOT + cx.a_lds[q], __builtin_bit_cast(u32x4, out[s]));
     }
 #pragma unroll
     for (int q = 0; q < T::QB; ++q) {
-        V in[CH::NB], out[CH::NP];
+        V out[T::BH][NOB];
 #pragma unroll
-        for (int t = 0; t < CH::NB; ++t) in[t] = Cv::run(r.b[t][q]);
-        CH::comb_b(in, out);
+        for (int h = 0; h < T::BH; ++h) {
+            V in[CH::NB];
 #pragma unroll
-        for (int s = 0; s < CH::NP; ++s) cx.lds_store(sb + s * T::B_SLOT + cx.b_lds[q], out[s]);
+            for (int t = 0; t < CH::NB; ++t) in[t] = Cv::run(r.b[t][q][h]);
+            if constexpr (T::FC) {
+#pragma unroll
+                for (int t = 0; t < CH::NB; ++t) out[h][t] = in[t];
+            } else {
+                CH::comb_b(in, out[h]);
+            }
+        }
+#pragma unroll
+        for (int s = 0; s < NOB; ++s) {
+            if constexpr (T::ES == 2) {
+                // dword e of the unit holds columns (2c, 2c+1) at k = k0 + e; gather the low halves
+                // into the chunk of column 2c and the high halves into the chunk of column 2c+1
+                const u32x4 lo = __builtin_bit_cast(u32x4, out[0][s]), hi = __builtin_bit_cast(u32x4, out[1][s]);
+                u32x4 c0, c1;
+                c0[0] = __builtin_amdgcn_perm(lo[1], lo[0], 0x05040100u);
+                c0[1] = __builtin_amdgcn_perm(lo[3], lo[2], 0x05040100u);
+                c0[2] = __builtin_amdgcn_perm(hi[1], hi[0], 0x05040100u);
+                c0[3] = __builtin_amdgcn_perm(hi[3], hi[2], 0x05040100u);
+                c1[0] = __builtin_amdgcn_perm(lo[1], lo[0], 0x07060302u);
+                c1[1] = __builtin_amdgcn_perm(lo[3], lo[2], 0x07060302u);
+                c1[2] = __builtin_amdgcn_perm(hi[1], hi[0], 0x07060302u);
+                c1[3] = __builtin_amdgcn_perm(hi[3], hi[2], 0x07060302u);
+                cx.lds_store(sb + s * T::B_SLOT + cx.b_lds[q], c0);
+                cx.lds_store(sb + s * T::B_SLOT + cx.b_lds1[q], c1);
+            } else {
+                cx.lds_store(sb + s * T::B_SLOT + cx.b_lds[q], __builtin_bit_cast(u32x4, out[0][s]));
+            }
+        }
     }
 }
 
-// The y loop of Algorithm 2 for one chunk, software-pipelined over two LDS stages and two register
-// sets.  In the steady state one step (a single basic block, so that the scheduler may interleave
-// its parts) does: issue the loads of step y+2; multiply step y from LDS stage y%2; combine step
-// y+1 from registers into the other stage; barrier.  Loads therefore have a whole step of MFMA work
-// to arrive, and the additions, conversions and LDS writes share the step with the MFMAs.  Past the
-// end the last tile is loaded and combined again into the stage nobody reads, which keeps the
-// step branch-free.
+// Fragment-combine kernels stage the raw blocks only, so which block a thread stages need not be the
+// same for every thread: all chunks (A) and units (B) of all blocks form one pool that is dealt to
+// the threads, which avoids idle or duplicated staging work when a single block is small.
+template <class T, class CH> struct FlatStage {
+    static constexpr int NCA = CH::NA * T::NCHK_A, NUB = CH::NB * T::NU_B;
+    static constexpr int QA = (NCA + T::NT - 1) / T::NT, QB = (NUB + T::NT - 1) / T::NT;
+    uint32_t a_voff[QA], a_lds[QA], b_voff[QB], b_lds[QB], b_lds1[QB];
+    struct Raw {
+        u32x4 a[QA], b[QB][T::BH];
+    };
+
+    LCMA_DEV FlatStage(const Ctx<T> &cx) {
+        const int tid = threadIdx.x;
+#pragma unroll
+        for (int q = 0; q < QA; ++q) {
+            const int id = (q * T::NT + tid) % NCA;
+            const int t = id / T::NCHK_A, id2 = id % T::NCHK_A;
+            const int row = id2 / T::CPR, c = id2 % T::CPR;
+            a_voff[q] = (uint32_t)CH::a_i(t) * cx.p.a_brow + (uint32_t)CH::a_l(t) * cx.p.a_bcol +
+                        (uint32_t)row * cx.p.lda_b + c * 16;
+            a_lds[q] = t * T::A_SLOT + row * T::ROW + T::swz(row, c) * 16;
+        }
+#pragma unroll
+        for (int q = 0; q < QB; ++q) {
+            const int id = (q * T::NT + tid) % NUB;
+            const int t = id / T::NU_B, u = id % T::NU_B;
+            const int col = u % T::BCOLS, g = u / T::BCOLS;
+            const int row = (T::ES == 2) ? 2 * col : col;
+            b_voff[q] = (uint32_t)CH::b_l(t) * cx.p.b_brow + (uint32_t)CH::b_j(t) * cx.p.b_bcol +
+                        (uint32_t)(g * T::CH) * cx.p.ldb_b + col * 4;
+            b_lds[q] = T::A_STAGE + t * T::B_SLOT + row * T::ROW + T::swz(row, g) * 16;
+            b_lds1[q] = T::A_STAGE + t * T::B_SLOT + (row + 1) * T::ROW + T::swz(row + 1, g) * 16;
+        }
+    }
+    LCMA_DEV void issue(const Ctx<T> &cx, Raw &r, int y) const {
+        const uint32_t sa = cx.a_group + (uint32_t)y * (T::TK * T::ES);
+        const uint32_t sbo = cx.b_group + (uint32_t)y * T::TK * cx.p.ldb_b;
+#pragma unroll
+        for (int q = 0; q < QA; ++q) r.a[q] = __builtin_amdgcn_raw_buffer_load_b128(cx.ra, (int)a_voff[q], (int)sa, 0);
+#pragma unroll
+        for (int q = 0; q < QB; ++q)
+#pragma unroll
+            for (int e = 0; e < T::BW; ++e)
+                r.b[q][e / 4][e % 4] = __builtin_amdgcn_raw_buffer_load_b32(
+                    cx.rb, (int)b_voff[q], (int)(sbo + (uint32_t)e * cx.p.ldb_b), 0);
+    }
+    LCMA_DEV void store(const Ctx<T> &cx, const Raw &r, int st) const {
+        using Cv = Convert<typename T::IN, typename T::CT>;
+        const uint32_t sb = st * T::STAGE;
+#pragma unroll
+        for (int q = 0; q < QA; ++q) cx.lds_store(sb + a_lds[q], __builtin_bit_cast(u32x4, Cv::run(r.a[q])));
+#pragma unroll
+        for (int q = 0; q < QB; ++q) {
+            if constexpr (T::ES == 2) {
+                const u32x4 lo = __builtin_bit_cast(u32x4, Cv::run(r.b[q][0]));
+                const u32x4 hi = __builtin_bit_cast(u32x4, Cv::run(r.b[q][1]));
+                u32x4 c0, c1;
+                c0[0] = __builtin_amdgcn_perm(lo[1], lo[0], 0x05040100u);
+                c0[1] = __builtin_amdgcn_perm(lo[3], lo[2], 0x05040100u);
+                c0[2] = __builtin_amdgcn_perm(hi[1], hi[0], 0x05040100u);
+                c0[3] = __builtin_amdgcn_perm(hi[3], hi[2], 0x05040100u);
+                c1[0] = __builtin_amdgcn_perm(lo[1], lo[0], 0x07060302u);
+                c1[1] = __builtin_amdgcn_perm(lo[3], lo[2], 0x07060302u);
+                c1[2] = __builtin_amdgcn_perm(hi[1], hi[0], 0x07060302u);
+                c1[3] = __builtin_amdgcn_perm(hi[3], hi[2], 0x07060302u);
+                cx.lds_store(sb + b_lds[q], c0);
+                cx.lds_store(sb + b_lds1[q], c1);
+            } else {
+                cx.lds_store(sb + b_lds[q], __builtin_bit_cast(u32x4, Cv::run(r.b[q][0])));
+            }
+        }
+    }
+};
+
+template <class T, class CH> LCMA_DEV void mma_step(const Ctx<T> &cx, int st, typename T::Acc (&acc)[CH::NP]) {
+    if constexpr (T::FC) cx.template mma_stage_fc<CH>(st, acc);
+    else cx.template mma_stage<CH::NP>(st, acc);
+}
+
+// The y loop of Algorithm 2 for one chunk over two LDS stages.
 template <class T, class CH> LCMA_DEV void run_chunk(const Ctx<T> &cx, typename T::Acc (&acc)[CH::NP]) {
-    static_assert(CH::NP <= T::NSLOT, "chunk larger than the LDS slots");
-    static_assert(T::STAGES == 2, "two LDS stages");
     const int ny = cx.p.ny, last = ny - 1;
-    if constexpr (T::PIPE == 0) {
+    if constexpr (T::FC) {
+        static_assert(CH::NA <= T::NSA && CH::NB <= T::NSB, "raw blocks exceed the LDS slots");
+        const FlatStage<T, CH> fs(cx);
+        if constexpr (T::PIPE == 0) {
+            typename FlatStage<T, CH>::Raw r;
+            fs.issue(cx, r, 0);
+            for (int y = 0; y < ny; ++y) {
+                fs.store(cx, r, y & 1);
+                fs.issue(cx, r, y + 1 < ny ? y + 1 : last);
+                __syncthreads();
+                cx.template mma_stage_fc<CH>(y & 1, acc);
+            }
+            __syncthreads();
+        } else {
+            typename FlatStage<T, CH>::Raw r0, r1;
+            fs.issue(cx, r0, 0);
+            fs.issue(cx, r1, ny > 1 ? 1 : 0);
+            fs.store(cx, r0, 0);
+            __syncthreads();
+            for (int y = 0; y < ny; y += 2) {
+                fs.issue(cx, r0, y + 2 < ny ? y + 2 : last);
+                cx.template mma_stage_fc<CH>(0, acc);
+                fs.store(cx, r1, 1);
+                __syncthreads();
+                if (y + 1 >= ny) break;
+                fs.issue(cx, r1, y + 3 < ny ? y + 3 : last);
+                cx.template mma_stage_fc<CH>(1, acc);
+                fs.store(cx, r0, 0);
+                __syncthreads();
+            }
+        }
+    } else if constexpr (T::PIPE == 0) {
         // Plain double buffering: one register set, loads of step y+1 in flight during the MFMAs
         // of step y.  Meant for two work-groups per CU, which overlap each other's phases.
         RawSet<T, CH> r;
@@ -447,10 +608,14 @@ template <class T, class CH> LCMA_DEV void run_chunk(const Ctx<T> &cx, typename 
             combine_store<T, CH>(cx, r, y & 1);
             issue_loads<T, CH>(cx, r, y + 1 < ny ? y + 1 : last);
             __syncthreads();
-            cx.template mma_stage<CH::NP>(y & 1, acc);
+            mma_step<T, CH>(cx, y & 1, acc);
         }
         __syncthreads();
     } else {
+        // Software-pipelined: in the steady state one step (a single basic block, so that the
+        // scheduler may interleave its parts) issues the loads of step y+2, multiplies step y from
+        // one LDS stage and combines step y+1 from registers into the other.  Past the end the last
+        // tile is loaded and combined again into the stage nobody reads (keeps the step branch-free).
         RawSet<T, CH> r0, r1;
         issue_loads<T, CH>(cx, r0, 0);
         issue_loads<T, CH>(cx, r1, ny > 1 ? 1 : 0);
@@ -458,17 +623,15 @@ template <class T, class CH> LCMA_DEV void run_chunk(const Ctx<T> &cx, typename 
         __syncthreads();
         for (int y = 0; y < ny; y += 2) {
             {   // even step: stage 0 holds y, r1 holds y+1, r0 is free
-                const int yn = y + 2 < ny ? y + 2 : last;
-                issue_loads<T, CH>(cx, r0, yn);
-                cx.template mma_stage<CH::NP>(0, acc);
+                issue_loads<T, CH>(cx, r0, y + 2 < ny ? y + 2 : last);
+                mma_step<T, CH>(cx, 0, acc);
                 combine_store<T, CH>(cx, r1, 1);
                 __syncthreads();
             }
             if (y + 1 >= ny) break;
             {   // odd step: stage 1 holds y+1, r0 holds y+2, r1 is free
-                const int yn = y + 3 < ny ? y + 3 : last;
-                issue_loads<T, CH>(cx, r1, yn);
-                cx.template mma_stage<CH::NP>(1, acc);
+                issue_loads<T, CH>(cx, r1, y + 3 < ny ? y + 3 : last);
+                mma_step<T, CH>(cx, 1, acc);
                 combine_store<T, CH>(cx, r0, 0);
                 __syncthreads();
             }

@@ -119,12 +119,13 @@ class Variant:
     rank: int = 0
     pipe: int = 0             # 0: double-buffered phases, 1: software-pipelined step
     occ: int = 1              # work-groups per CU the kernel is compiled for
+    fc: int = 0               # 1: LDS holds raw blocks, waves combine MFMA fragments (needs chunk >= R)
     name: str = field(default="")
 
     def finish(self):
         if not self.name:
             self.name = (f"{self.scheme}_{self.dtype}_t{self.TM}x{self.TN}x{self.TK}_c{self.chunk}"
-                         + ("p" if self.pipe else "") + (f"o{self.occ}" if self.occ > 1 else ""))
+                         + ("f" if self.fc else "") + ("p" if self.pipe else "") + (f"o{self.occ}" if self.occ > 1 else ""))
         return self
 
 
@@ -154,15 +155,21 @@ def plan(s: Scheme, v: Variant):
                             last[(i, j)] = ci
         live_c = max(sum(1 for key in first if first[key] <= ci <= last[key]) for ci in range(len(chunks)))
     regs = (live_c + nslot) * tile_regs
-    lds = v.stages * nslot * (v.TM * v.TK + v.TK * v.TN) * es
-    return regs, lds, live_c, nslot
+    if v.fc:
+        assert len(chunks) == 1, "fragment combine keeps every product's accumulator live"
+        nsa = len({(i, l) for r in chunks[0] for i in range(s.m) for l in range(s.k) if s.U[r, i, l]})
+        nsb = len({(l, j) for r in chunks[0] for l in range(s.k) for j in range(s.n) if s.V[r, l, j]})
+    else:
+        nsa = nsb = nslot
+    lds = v.stages * (nsa * v.TM * v.TK + nsb * v.TK * v.TN) * es
+    return regs, lds, live_c, nslot, nsa, nsb
 
 
 # ----------------------------------------------------------------------------- code emission
 CPP_TYPES = {"f32": ("F32", "F32"), "f16": ("F16", "F16"), "bf16": ("BF16", "F16")}
 
 
-def signed_sum(terms: list[tuple[int, str]], wide: bool = False) -> str:
+def signed_sum(terms: list[tuple[int, str]], wide: bool = False, fn: bool = False) -> str:
     """[(coef, expr)] -> C++ expression; +-1 become additions, anything else a multiply.
     wide: form the sum in fp32 and round once (used for fp16 sums of three or more terms)."""
     if wide and len(terms) >= 3:
@@ -173,6 +180,8 @@ def signed_sum(terms: list[tuple[int, str]], wide: bool = False) -> str:
         mag = e if abs(c) == 1 else f"{e} * {abs(c)}"
         if idx == 0:
             out = mag if c > 0 else f"-{mag}"
+        elif fn:
+            out = f"{'vadd' if c > 0 else 'vsub'}({out}, {mag})"
         else:
             out += (" + " if c > 0 else " - ") + mag
     return out
@@ -182,7 +191,7 @@ def emit_kernel(s: Scheme, v: Variant) -> str:
     in_t, ct_t = CPP_TYPES[v.dtype]
     if s.name == "plain":
         ct_t = in_t  # nothing is added: multiply in the storage type
-    regs, lds, live_c, nslot = plan(s, v)
+    regs, lds, live_c, nslot, nsa, nsb = plan(s, v)
     chunks = chunks_of(s, v)
     single = len(chunks) == 1
     # bf16 inputs carry 8 significant bits, so their sums are (nearly) exact in packed fp16 adds;
@@ -196,7 +205,7 @@ def emit_kernel(s: Scheme, v: Variant) -> str:
     w('#include "lcma_device.hpp"')
     w("namespace {")
     w("using namespace lcma;")
-    w(f"using T = Tile<{in_t}, {ct_t}, {v.TM}, {v.TN}, {v.TK}, {v.wgm}, {v.wgn}, {nslot}, {v.stages}, {v.pipe}>;")
+    w(f"using T = Tile<{in_t}, {ct_t}, {v.TM}, {v.TN}, {v.TK}, {v.wgm}, {v.wgn}, {nsa}, {nsb}, {v.pipe}, {v.fc}>;")
     for ci, ch in enumerate(chunks):
         a_blocks = sorted({(i, l) for r in ch for i in range(s.m) for l in range(s.k) if s.U[r, i, l]})
         b_blocks = sorted({(l, j) for r in ch for l in range(s.k) for j in range(s.n) if s.V[r, l, j]})
@@ -208,12 +217,12 @@ def emit_kernel(s: Scheme, v: Variant) -> str:
         w("    template <class V> static LCMA_DEV void comb_a(const V (&in)[NA], V (&out)[NP]) {")
         for si, r in enumerate(ch):
             terms = [(int(s.U[r, i, l]), f"in[{a_blocks.index((i, l))}]") for (i, l) in a_blocks if s.U[r, i, l]]
-            w(f"        out[{si}] = {signed_sum(terms, wide)};")
+            w(f"        out[{si}] = {signed_sum(terms, wide, True)};")
         w("    }")
         w("    template <class V> static LCMA_DEV void comb_b(const V (&in)[NB], V (&out)[NP]) {")
         for si, r in enumerate(ch):
             terms = [(int(s.V[r, l, j]), f"in[{b_blocks.index((l, j))}]") for (l, j) in b_blocks if s.V[r, l, j]]
-            w(f"        out[{si}] = {signed_sum(terms, wide)};")
+            w(f"        out[{si}] = {signed_sum(terms, wide, True)};")
         w("    }")
         w("};")
     w("")
@@ -317,8 +326,13 @@ def manifest() -> list[Variant]:
             Variant("plain", dt, 128, 128, 64, rank=4, occ=2),
             Variant("plain", dt, 128, 128, 32, rank=5, occ=2, pipe=1),
             Variant("plain", dt, 64, 64, 32, rank=9),
-            Variant("strassen", dt, 128, 64, 16, chunk=7, rank=0),
-            Variant("strassen", dt, 128, 64, 16, chunk=7, rank=1, pipe=1),
+            Variant("strassen", dt, 128, 64, 32, chunk=7, rank=0, fc=1),
+            Variant("strassen", dt, 128, 64, 32, chunk=7, rank=1, fc=1, pipe=1),
+            Variant("strassen", dt, 128, 64, 16, chunk=7, rank=2),
+            Variant("strassen", dt, 128, 64, 16, chunk=7, rank=3, pipe=1),
+            Variant("strassen", dt, 64, 64, 32, chunk=7, rank=4, fc=1, occ=2),
+            Variant("strassen", dt, 64, 64, 32, chunk=7, rank=4, fc=1, pipe=1),
+            Variant("strassen", dt, 128, 64, 16, chunk=7, rank=4, fc=1, pipe=1),
             Variant("strassen", dt, 64, 64, 32, chunk=7, rank=5),
             Variant("strassen", dt, 64, 64, 32, chunk=7, rank=6, pipe=1),
             Variant("strassen", dt, 64, 64, 16, chunk=7, rank=6, occ=2),
@@ -331,7 +345,10 @@ def manifest() -> list[Variant]:
     V += [
         Variant("plain", "f32", 128, 128, 16, rank=0),
         Variant("plain", "f32", 64, 64, 16, rank=9),
-        Variant("strassen", "f32", 64, 64, 16, chunk=7, rank=0),
+        Variant("plain", "f32", 256, 128, 16, rank=1),
+        Variant("strassen", "f32", 128, 64, 16, chunk=7, rank=0, fc=1),
+        Variant("strassen", "f32", 128, 64, 8, chunk=7, rank=1),
+        Variant("strassen", "f32", 64, 64, 16, chunk=7, rank=2),
         Variant("strassen", "f32", 128, 64, 16, chunk=1, rank=5),
         Variant("laderman", "f32", 64, 64, 16, chunk=1, rank=0),
         Variant("strassen2", "f32", 64, 64, 16, chunk=7, rank=0),
@@ -359,7 +376,7 @@ def generate(out_dir: str) -> list[str]:
 
     for v in variants:
         s = schemes[v.scheme]
-        regs, lds, _, _ = plan(s, v)
+        regs, lds = plan(s, v)[:2]
         assert regs <= ACC_REG_BUDGET, f"{v.name}: {regs} accumulator registers exceed the budget"
         assert lds <= LDS_BUDGET, f"{v.name}: {lds} bytes of LDS exceed the budget"
         hips.append(put(f"k_{v.name}.hip", emit_kernel(s, v)))
