@@ -142,7 +142,7 @@ struct Tile {
     static constexpr int A_STAGE = NSA * A_SLOT, B_STAGE = NSB * B_SLOT;
     static constexpr int STAGE = A_STAGE + B_STAGE;
     static constexpr int LDS_BYTES = STAGES * STAGE;
-    static_assert(NT == 256, "four waves per work-group");
+    static_assert(NT == 256 || NT == 512, "four or eight waves per work-group");
     static_assert(WM % 32 == 0 && WN % 32 == 0 && TK % KSTEP == 0, "MFMA 32x32 tiling");
     static_assert(LDS_BYTES <= 160 * 1024, "LDS budget of one CU");
 
@@ -189,18 +189,26 @@ template <class ACC> LCMA_DEV void acc_add(ACC &c, const ACC &h, float w) {
 template <class CT> struct Mma;
 template <> struct Mma<F16> {
     using frag = f16x8;
+    static constexpr int SUB = 1;
+    static LCMA_DEV void run_sub(const frag &a, const frag &b, f32x16 &c, int) { run(a, b, c); }
     static LCMA_DEV void run(const frag &a, const frag &b, f32x16 &c) {
         c = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0);
     }
 };
 template <> struct Mma<BF16> {
     using frag = bf16x8;
+    static constexpr int SUB = 1;
+    static LCMA_DEV void run_sub(const frag &a, const frag &b, f32x16 &c, int) { run(a, b, c); }
     static LCMA_DEV void run(const frag &a, const frag &b, f32x16 &c) {
         c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
     }
 };
 template <> struct Mma<F32> {
     using frag = f32x4;
+    static constexpr int SUB = 4; // instructions per fragment pair
+    static LCMA_DEV void run_sub(const frag &a, const frag &b, f32x16 &c, int t) {
+        c = __builtin_amdgcn_mfma_f32_32x32x2f32(a[t], b[t], c, 0, 0, 0);
+    }
     static LCMA_DEV void run(const frag &a, const frag &b, f32x16 &c) {
 #pragma unroll
         for (int t = 0; t < 4; ++t) c = __builtin_amdgcn_mfma_f32_32x32x2f32(a[t], b[t], c, 0, 0, 0);
@@ -350,27 +358,41 @@ template <class T> struct Ctx {
         for (int kk = 0; kk < T::NKK; ++kk) {
             const int cur = kk & 1;
             if (kk + 1 < T::NKK) fetch(kk + 1, cur ^ 1); // next fragments arrive under this step's MFMAs
+            // A few products at a time keeps few combined fragments live (the unused outputs of the
+            // generated combination code are dead and vanish).  With several MFMA instructions per
+            // fragment pair (fp32) two products advance together, so that back-to-back instructions
+            // never accumulate into the same tile.
+            constexpr int G = (Mma<CT>::SUB > 1 && T::NMI * T::NNI == 1) ? 2 : 1;
 #pragma unroll
-            for (int s = 0; s < CH::NP; ++s) {
-                // one product at a time keeps few combined fragments live; the unused outputs of the
-                // generated combination code are dead and vanish
-                Frag at[T::NMI], bt[T::NNI];
+            for (int s0 = 0; s0 < CH::NP; s0 += G) {
+                Frag at[G][T::NMI], bt[G][T::NNI];
 #pragma unroll
-                for (int mi = 0; mi < T::NMI; ++mi) {
-                    Frag o[CH::NP];
-                    CH::comb_a(ra_[cur][mi], o);
-                    at[mi] = o[s];
+                for (int g = 0; g < G; ++g) {
+                    if (s0 + g >= CH::NP) continue;
+#pragma unroll
+                    for (int mi = 0; mi < T::NMI; ++mi) {
+                        Frag o[CH::NP];
+                        CH::comb_a(ra_[cur][mi], o);
+                        at[g][mi] = o[s0 + g];
+                    }
+#pragma unroll
+                    for (int ni = 0; ni < T::NNI; ++ni) {
+                        Frag o[CH::NP];
+                        CH::comb_b(rb_[cur][ni], o);
+                        bt[g][ni] = o[s0 + g];
+                    }
                 }
 #pragma unroll
-                for (int ni = 0; ni < T::NNI; ++ni) {
-                    Frag o[CH::NP];
-                    CH::comb_b(rb_[cur][ni], o);
-                    bt[ni] = o[s];
-                }
+                for (int t = 0; t < Mma<CT>::SUB; ++t)
 #pragma unroll
-                for (int mi = 0; mi < T::NMI; ++mi)
+                    for (int g = 0; g < G; ++g) {
+                        if (s0 + g >= CH::NP) continue;
 #pragma unroll
-                    for (int ni = 0; ni < T::NNI; ++ni) Mma<CT>::run(at[mi], bt[ni], acc[s].v[mi][ni]);
+                        for (int mi = 0; mi < T::NMI; ++mi)
+#pragma unroll
+                            for (int ni = 0; ni < T::NNI; ++ni)
+                                Mma<CT>::run_sub(at[g][mi], bt[g][ni], acc[s0 + g].v[mi][ni], t);
+                    }
             }
         }
     }

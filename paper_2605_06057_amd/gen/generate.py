@@ -125,7 +125,7 @@ class Variant:
     def finish(self):
         if not self.name:
             self.name = (f"{self.scheme}_{self.dtype}_t{self.TM}x{self.TN}x{self.TK}_c{self.chunk}"
-                         + ("f" if self.fc else "") + ("p" if self.pipe else "") + (f"o{self.occ}" if self.occ > 1 else ""))
+                         + (f"w{self.wgm}x{self.wgn}" if (self.wgm, self.wgn) != (2, 2) else "") + ("f" if self.fc else "") + ("p" if self.pipe else "") + (f"o{self.occ}" if self.occ > 1 else ""))
         return self
 
 
@@ -229,7 +229,7 @@ def emit_kernel(s: Scheme, v: Variant) -> str:
     w("} // namespace")
     w("")
     w("// the kernel carries the variant's name so that profiles tell the variants apart")
-    w(f'extern "C" __global__ __launch_bounds__(256, {v.occ}) void lcma_k_{v.name}(const lcma::Params p) {{')
+    w(f'extern "C" __global__ __launch_bounds__({64 * v.wgm * v.wgn}, {v.occ}) void lcma_k_{v.name}(const lcma::Params p) {{')
     w("    __shared__ __attribute__((aligned(16))) char smem[T::LDS_BYTES];")
     w("    const Ctx<T> cx(p, (LCMA_LDS char *)smem);")
     if single:
@@ -270,7 +270,7 @@ def emit_kernel(s: Scheme, v: Variant) -> str:
     w("}")
     w("")
     w(f'extern "C" int lcma_launch_{v.name}(const lcma::Params *p, int grid, void *stream) {{')
-    w(f"    lcma_k_{v.name}<<<dim3(grid), dim3(256), 0, (hipStream_t)stream>>>(*p);")
+    w(f"    lcma_k_{v.name}<<<dim3(grid), dim3({64 * v.wgm * v.wgn}), 0, (hipStream_t)stream>>>(*p);")
     w("    return (int)hipGetLastError();")
     w("}")
     return "\n".join(L) + "\n"
@@ -320,6 +320,15 @@ def manifest() -> list[Variant]:
     for dt in ("bf16", "f16"):
         V += [
             Variant("plain", dt, 256, 256, 64, rank=0),
+            Variant("plain", dt, 256, 256, 32, rank=1, wgm=4, wgn=2),
+            Variant("plain", dt, 256, 256, 32, rank=1, wgm=2, wgn=4),
+            Variant("plain", dt, 256, 256, 64, rank=1, wgm=2, wgn=4),
+            Variant("strassen", dt, 128, 64, 32, chunk=7, rank=1, fc=1, wgm=4, wgn=2),
+            Variant("strassen", dt, 64, 128, 32, chunk=7, rank=1, fc=1, wgm=2, wgn=4),
+            Variant("strassen", dt, 64, 128, 32, chunk=7, rank=1, fc=1, wgm=2, wgn=4, pipe=1),
+            Variant("strassen", dt, 128, 64, 32, chunk=7, rank=1, fc=1, wgm=4, wgn=2, pipe=1),
+            Variant("plain", dt, 256, 256, 64, rank=1, wgm=2, wgn=4, pipe=1),
+            Variant("plain", dt, 256, 256, 32, rank=1, wgm=2, wgn=4, pipe=1),
             Variant("plain", dt, 256, 256, 32, rank=1, pipe=1),
             Variant("plain", dt, 256, 128, 32, rank=2, occ=2),
             Variant("plain", dt, 256, 128, 32, rank=3, occ=2, pipe=1),
@@ -347,6 +356,14 @@ def manifest() -> list[Variant]:
         Variant("plain", "f32", 64, 64, 16, rank=9),
         Variant("plain", "f32", 256, 128, 16, rank=1),
         Variant("strassen", "f32", 128, 64, 16, chunk=7, rank=0, fc=1),
+        Variant("strassen", "f32", 128, 64, 16, chunk=7, rank=0, fc=1, wgm=4, wgn=2),
+        Variant("strassen", "f32", 64, 128, 16, chunk=7, rank=0, fc=1, wgm=2, wgn=4),
+        Variant("strassen", "f32", 64, 64, 16, chunk=7, rank=0, fc=1, occ=2),
+        Variant("strassen", "f32", 64, 64, 16, chunk=7, rank=0, fc=1, occ=2, pipe=1),
+        Variant("strassen", "f32", 128, 64, 16, chunk=7, rank=0, fc=1, wgm=4, wgn=2, pipe=1),
+        Variant("plain", "f32", 128, 128, 16, rank=1, occ=2, pipe=1),
+        Variant("plain", "f32", 256, 128, 16, rank=1, wgm=2, wgn=4),
+        Variant("plain", "f32", 128, 128, 16, rank=1, occ=2),
         Variant("strassen", "f32", 128, 64, 8, chunk=7, rank=1),
         Variant("strassen", "f32", 64, 64, 16, chunk=7, rank=2),
         Variant("strassen", "f32", 128, 64, 16, chunk=1, rank=5),
