@@ -73,6 +73,8 @@ template <class V> struct Wide {
 template <> struct Wide<f16x8> {
     static LCMA_DEV f32x8 up(const f16x8 &v) { return __builtin_convertvector(v, f32x8); }
     static LCMA_DEV f16x8 down(const f32x8 &v) { return __builtin_convertvector(v, f16x8); }
+    // what rounding v to fp16 loses, as fp16
+    static LCMA_DEV f16x8 residual(const f32x8 &v) { return down(v - up(down(v))); }
 };
 
 // Element-wise add / subtract of the vectors the combinations are formed on.  A packed fp16

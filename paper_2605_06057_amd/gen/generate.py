@@ -120,13 +120,27 @@ class Variant:
     pipe: int = 0             # 0: double-buffered phases, 1: software-pipelined step
     occ: int = 1              # work-groups per CU the kernel is compiled for
     fc: int = 0               # 1: LDS holds raw blocks, waves combine MFMA fragments (needs chunk >= R)
+    comp: tuple = ()          # products (0-based) whose left operand also gets its rounding residual multiplied
     name: str = field(default="")
 
     def finish(self):
         if not self.name:
             self.name = (f"{self.scheme}_{self.dtype}_t{self.TM}x{self.TN}x{self.TK}_c{self.chunk}"
-                         + (f"w{self.wgm}x{self.wgn}" if (self.wgm, self.wgn) != (2, 2) else "") + ("f" if self.fc else "") + ("p" if self.pipe else "") + (f"o{self.occ}" if self.occ > 1 else ""))
+                         + (f"x{len(self.comp)}" if self.comp else "") + (f"w{self.wgm}x{self.wgn}" if (self.wgm, self.wgn) != (2, 2) else "") + ("f" if self.fc else "") + ("p" if self.pipe else "") + (f"o{self.occ}" if self.occ > 1 else ""))
         return self
+
+
+def with_residuals(s: Scheme, comp: tuple) -> tuple[Scheme, set]:
+    """Error compensation for 16-bit operands.  For each product r in `comp` a further product is
+    appended whose left operand is the rounding residual of the r-th combination (its fp32 value minus
+    its fp16 value, itself rounded to fp16) and whose right operand and W row are those of r; the sum
+    of the two products is the product with an (almost) unrounded left operand.  Returns the longer
+    scheme and the indices of the residual products."""
+    if not comp:
+        return s, set()
+    rows = list(range(s.R)) + list(comp)
+    ext = Scheme(s.name, s.m, s.k, s.n, len(rows), s.U[rows], s.V[rows], s.W[rows])
+    return ext, set(range(s.R, len(rows)))
 
 
 def chunks_of(s: Scheme, v: Variant) -> list[list[int]]:
@@ -188,6 +202,7 @@ def signed_sum(terms: list[tuple[int, str]], wide: bool = False, fn: bool = Fals
 
 
 def emit_kernel(s: Scheme, v: Variant) -> str:
+    s, residual = with_residuals(s, v.comp)
     in_t, ct_t = CPP_TYPES[v.dtype]
     if s.name == "plain":
         ct_t = in_t  # nothing is added: multiply in the storage type
@@ -217,7 +232,12 @@ def emit_kernel(s: Scheme, v: Variant) -> str:
         w("    template <class V> static LCMA_DEV void comb_a(const V (&in)[NA], V (&out)[NP]) {")
         for si, r in enumerate(ch):
             terms = [(int(s.U[r, i, l]), f"in[{a_blocks.index((i, l))}]") for (i, l) in a_blocks if s.U[r, i, l]]
-            w(f"        out[{si}] = {signed_sum(terms, wide, True)};")
+            if r in residual:
+                assert wide and len(terms) >= 2, "residual products need fp16 sums formed in fp32"
+                wsum = signed_sum([(c, f"Wide<V>::up({e})") for c, e in terms])
+                w(f"        out[{si}] = Wide<V>::residual({wsum});")
+            else:
+                w(f"        out[{si}] = {signed_sum(terms, wide, True)};")
         w("    }")
         w("    template <class V> static LCMA_DEV void comb_b(const V (&in)[NB], V (&out)[NP]) {")
         for si, r in enumerate(ch):
@@ -316,57 +336,46 @@ def emit_builtin_inc(schemes: dict[str, Scheme]) -> str:
 
 # ----------------------------------------------------------------------------- manifest
 def manifest() -> list[Variant]:
+    """The kernels that are built.  rank orders the variants of one (scheme, dtype): the lowest rank
+    whose tile divides the shape is what lcma_gemm launches.  Ranks follow measurements on MI355X
+    (4096^3): eight-wave work-groups (two waves per SIMD) beat four-wave ones throughout."""
     V = []
     for dt in ("bf16", "f16"):
         V += [
-            Variant("plain", dt, 256, 256, 64, rank=0),
-            Variant("plain", dt, 256, 256, 32, rank=1, wgm=4, wgn=2),
-            Variant("plain", dt, 256, 256, 32, rank=1, wgm=2, wgn=4),
-            Variant("plain", dt, 256, 256, 64, rank=1, wgm=2, wgn=4),
-            Variant("strassen", dt, 128, 64, 32, chunk=7, rank=1, fc=1, wgm=4, wgn=2),
-            Variant("strassen", dt, 64, 128, 32, chunk=7, rank=1, fc=1, wgm=2, wgn=4),
-            Variant("strassen", dt, 64, 128, 32, chunk=7, rank=1, fc=1, wgm=2, wgn=4, pipe=1),
-            Variant("strassen", dt, 128, 64, 32, chunk=7, rank=1, fc=1, wgm=4, wgn=2, pipe=1),
-            Variant("plain", dt, 256, 256, 64, rank=1, wgm=2, wgn=4, pipe=1),
-            Variant("plain", dt, 256, 256, 32, rank=1, wgm=2, wgn=4, pipe=1),
-            Variant("plain", dt, 256, 256, 32, rank=1, pipe=1),
-            Variant("plain", dt, 256, 128, 32, rank=2, occ=2),
-            Variant("plain", dt, 256, 128, 32, rank=3, occ=2, pipe=1),
-            Variant("plain", dt, 128, 128, 64, rank=4, occ=2),
-            Variant("plain", dt, 128, 128, 32, rank=5, occ=2, pipe=1),
+            Variant("plain", dt, 256, 256, 64, rank=0, wgm=2, wgn=4),
+            Variant("plain", dt, 256, 128, 32, rank=1, occ=2),
+            Variant("plain", dt, 128, 128, 64, rank=2, occ=2),
             Variant("plain", dt, 64, 64, 32, rank=9),
-            Variant("strassen", dt, 128, 64, 32, chunk=7, rank=0, fc=1),
-            Variant("strassen", dt, 128, 64, 32, chunk=7, rank=1, fc=1, pipe=1),
-            Variant("strassen", dt, 128, 64, 16, chunk=7, rank=2),
-            Variant("strassen", dt, 128, 64, 16, chunk=7, rank=3, pipe=1),
-            Variant("strassen", dt, 64, 64, 32, chunk=7, rank=4, fc=1, occ=2),
-            Variant("strassen", dt, 64, 64, 32, chunk=7, rank=4, fc=1, pipe=1),
-            Variant("strassen", dt, 128, 64, 16, chunk=7, rank=4, fc=1, pipe=1),
-            Variant("strassen", dt, 64, 64, 32, chunk=7, rank=5),
-            Variant("strassen", dt, 64, 64, 32, chunk=7, rank=6, pipe=1),
-            Variant("strassen", dt, 64, 64, 16, chunk=7, rank=6, occ=2),
-            Variant("strassen", dt, 128, 128, 32, chunk=1, rank=7),
-            Variant("laderman", dt, 128, 64, 32, chunk=1, rank=0),
+            # fragment-combine kernels: raw blocks in LDS, every wave forms the 7 operand pairs
+            Variant("strassen", dt, 64, 128, 32, chunk=7, rank=0, fc=1, wgm=2, wgn=4),
+            Variant("strassen", dt, 128, 64, 32, chunk=7, rank=1, fc=1, wgm=4, wgn=2),
+            Variant("strassen", dt, 64, 64, 32, chunk=7, rank=2, fc=1, occ=2),
+            Variant("strassen", dt, 128, 64, 32, chunk=7, rank=3, fc=1),
+            # combinations formed while staging (Algorithm 2's r loop when chunk = 1)
+            Variant("strassen", dt, 64, 64, 32, chunk=7, rank=7),
+            Variant("strassen", dt, 128, 128, 32, chunk=1, rank=8),
+            Variant("laderman", dt, 128, 64, 32, chunk=1, rank=1 if dt == "f16" else 0),
             Variant("laderman", dt, 64, 64, 32, chunk=1, rank=5),
-            Variant("strassen2", dt, 64, 64, 32, chunk=7, rank=0),
-            Variant("strassen2", dt, 64, 64, 32, chunk=1, rank=5),
         ]
+    # Laderman with fp16 storage: rounding its 3- and 7-term combinations to fp16 costs 4.05x the error
+    # of the plain kernel; multiplying the residual of the left operand of products 4 and 7 (both
+    # three-term on each side) as well brings it under the 4x bound for 2 extra products out of 23.
+    V += [Variant("laderman", "f16", 128, 64, 32, chunk=1, rank=0, comp=(3, 6)),
+          Variant("laderman", "f16", 64, 64, 32, chunk=1, rank=4, comp=(3, 6))]
+    # two-level Strassen: with fp16 storage its four-term sums exceed the 4x error bound, so it is
+    # generated for bf16 (sums nearly exact in fp16) and fp32 only
     V += [
-        Variant("plain", "f32", 128, 128, 16, rank=0),
-        Variant("plain", "f32", 64, 64, 16, rank=9),
-        Variant("plain", "f32", 256, 128, 16, rank=1),
-        Variant("strassen", "f32", 128, 64, 16, chunk=7, rank=0, fc=1),
-        Variant("strassen", "f32", 128, 64, 16, chunk=7, rank=0, fc=1, wgm=4, wgn=2),
-        Variant("strassen", "f32", 64, 128, 16, chunk=7, rank=0, fc=1, wgm=2, wgn=4),
-        Variant("strassen", "f32", 64, 64, 16, chunk=7, rank=0, fc=1, occ=2),
-        Variant("strassen", "f32", 64, 64, 16, chunk=7, rank=0, fc=1, occ=2, pipe=1),
-        Variant("strassen", "f32", 128, 64, 16, chunk=7, rank=0, fc=1, wgm=4, wgn=2, pipe=1),
-        Variant("plain", "f32", 128, 128, 16, rank=1, occ=2, pipe=1),
+        Variant("strassen2", "bf16", 64, 64, 32, chunk=7, rank=0),
+        Variant("strassen2", "bf16", 64, 64, 32, chunk=1, rank=5),
+    ]
+    V += [
+        Variant("plain", "f32", 128, 128, 16, rank=0, occ=2),
         Variant("plain", "f32", 256, 128, 16, rank=1, wgm=2, wgn=4),
-        Variant("plain", "f32", 128, 128, 16, rank=1, occ=2),
-        Variant("strassen", "f32", 128, 64, 8, chunk=7, rank=1),
-        Variant("strassen", "f32", 64, 64, 16, chunk=7, rank=2),
-        Variant("strassen", "f32", 128, 64, 16, chunk=1, rank=5),
+        Variant("plain", "f32", 64, 64, 16, rank=9),
+        Variant("strassen", "f32", 64, 64, 16, chunk=7, rank=0, fc=1, occ=2),
+        Variant("strassen", "f32", 128, 64, 16, chunk=7, rank=1, fc=1, wgm=4, wgn=2),
+        Variant("strassen", "f32", 64, 64, 16, chunk=7, rank=5),
+        Variant("strassen", "f32", 128, 64, 16, chunk=1, rank=6),
         Variant("laderman", "f32", 64, 64, 16, chunk=1, rank=0),
         Variant("strassen2", "f32", 64, 64, 16, chunk=7, rank=0),
     ]
@@ -393,7 +402,7 @@ def generate(out_dir: str) -> list[str]:
 
     for v in variants:
         s = schemes[v.scheme]
-        regs, lds = plan(s, v)[:2]
+        regs, lds = plan(with_residuals(s, v.comp)[0], v)[:2]
         assert regs <= ACC_REG_BUDGET, f"{v.name}: {regs} accumulator registers exceed the budget"
         assert lds <= LDS_BUDGET, f"{v.name}: {lds} bytes of LDS exceed the budget"
         hips.append(put(f"k_{v.name}.hip", emit_kernel(s, v)))
