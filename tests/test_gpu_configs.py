@@ -1,0 +1,77 @@
+"""The BASELINE configurations at full size, through lcma_gemm's default kernel choice (the launch
+configuration bench.py times), checked on sampled rows of C that the oracle computes one by one:
+a few rows inside every block row of the scheme grid, all N columns, so every C block, every tile
+column and every y step takes part."""
+import numpy as np
+import pytest
+
+import lcma_inputs as inp
+import oracle
+
+pytestmark = pytest.mark.gpu
+
+CONFIGS = [
+    # id, scheme, dtype, M, N, K, A kind, B kind, seed, relF bound
+    ("c1_strassen_f32_256", "strassen", "f32", 256, 256, 256, "uniform", "uniform", 0x5EED0001, 1e-5),
+    ("c2_strassen_bf16_4096", "strassen", "bf16", 4096, 4096, 4096, "normal", "normal", 0x5EED0002, 2e-2),
+    ("c3_strassen_bf16_ffn", "strassen", "bf16", 8192, 14336, 4096, "normal", "weights", 0x5EED0003, 2e-2),
+    ("c3_strassen2_bf16_ffn", "strassen2", "bf16", 8192, 14336, 4096, "normal", "weights", 0x5EED0003, 2e-2),
+    ("c4_laderman_f16_6144", "laderman", "f16", 6144, 6144, 6144, "uniform", "uniform", 0x5EED0004, 2e-2),
+    ("c5_plain_bf16_2048x4096x14336", None, "bf16", 2048, 4096, 14336, "normal", "weights", 0x5EED0005, 2e-2),
+]
+
+
+@pytest.mark.parametrize("cfg", CONFIGS, ids=lambda c: c[0])
+def test_full_size_config_on_sampled_rows(cfg):
+    import torch
+    import gpu_util as G
+    from paper_2605_06057_amd import binding as B
+    name, scheme, dt, M, N, K, ka, kb, seed, bound = cfg
+    print(f"config {name}: generating inputs", flush=True)
+    As, Bs = inp.matrices(ka, kb, M, N, K, dt, seed)
+    a, b = G.to_device(As, dt), G.to_device(Bs, dt)
+    c = G.empty_like_c(M, N, dt, fill=float("nan"))
+    cp = G.empty_like_c(M, N, dt, fill=float("nan"))
+    s = B.lcma_scheme_load("builtin:" + scheme) if scheme else None
+    grid_m = B.lcma_scheme_info(s)["m"] if s else 1
+    print(f"config {name}: launching", flush=True)
+    B.lcma_gemm(a, b, c, s)
+    B.lcma_gemm(a, b, cp, None)
+    torch.cuda.synchronize()
+    bm = M // grid_m
+    rows = np.unique(np.concatenate([(np.array([0, 1, 63, 64, 127, 128, bm // 2 + 5, bm - 1]) % bm) + i * bm
+                                     for i in range(grid_m)]))
+    ref = oracle.gemm_rows(inp.widen(As, dt), inp.widen(Bs, dt), rows)
+    idx = torch.from_numpy(rows).cuda()
+    got = G.to_host_f64(c[idx], dt)
+    got_plain = G.to_host_f64(cp[idx], dt)
+    assert not np.isnan(G.to_host_f64(c[:: max(1, M // 64)], dt)).any(), "part of C was never written"
+    err, err_plain = oracle.rel_frobenius(got, ref), oracle.rel_frobenius(got_plain, ref)
+    print(f"config {name}: relF {err:.3e} plain {err_plain:.3e} ratio {err / err_plain:.2f}", flush=True)
+    assert err <= bound and err_plain <= bound
+    assert err <= 4.0 * err_plain
+    c2 = G.empty_like_c(M, N, dt, fill=0.0)
+    B.lcma_gemm(a, b, c2, s)
+    assert torch.equal(c2.view(torch.uint8), c.view(torch.uint8)), "two runs differ"
+
+
+def test_selector_sweep_runs_its_pick():
+    """Shape sweep of the Decision Module (bf16): whatever lcma_select picks must run and be right."""
+    import torch
+    import gpu_util as G
+    from paper_2605_06057_amd import binding as B
+    dt = "bf16"
+    for M in (2048, 8192):
+        for N, K in ((4096, 4096), (4096, 14336)):
+            pick = B.lcma_select(M, N, K, B.LCMA_BF16)
+            assert pick in (0, 1, 2, 3)
+            As, Bs = inp.matrices("normal", "weights", M, N, K, dt, 0x5EED0100 + M + N)
+            a, b = G.to_device(As, dt), G.to_device(Bs, dt)
+            c = G.empty_like_c(M, N, dt, fill=float("nan"))
+            s = B.lcma_scheme_load("builtin:" + B.SCHEME_NAMES[pick]) if pick else None
+            B.lcma_gemm(a, b, c, s)
+            rows = np.array([0, M // 3, M - 1])
+            ref = oracle.gemm_rows(inp.widen(As, dt), inp.widen(Bs, dt), rows)
+            err = oracle.rel_frobenius(G.to_host_f64(c[torch.from_numpy(rows).cuda()], dt), ref)
+            print(f"sweep {M}x{N}x{K}: pick {B.SCHEME_NAMES[pick]} relF {err:.3e}", flush=True)
+            assert err <= 2e-2
