@@ -18,16 +18,22 @@ lcma_status fail(lcma_status st, const char *fmt, ...) {
     return st;
 }
 
-static bool fits(const Variant &v, int64_t M, int64_t N, int64_t K) {
+bool variant_fits(const Variant &v, int64_t M, int64_t N, int64_t K) {
     return M % ((int64_t)v.m * v.TM) == 0 && N % ((int64_t)v.n * v.TN) == 0 && K % ((int64_t)v.k * v.TK) == 0;
 }
+static bool fits(const Variant &v, int64_t M, int64_t N, int64_t K) { return variant_fits(v, M, N, K); }
 
 const Variant *pick_variant(int scheme_id, int dtype, int64_t M, int64_t N, int64_t K) {
     const Variant *best = nullptr;
+    double best_t = 0.0;
     for (int i = 0; i < kVariantCount; ++i) {
         const Variant &v = kVariants[i];
-        if (v.scheme_id != scheme_id || v.dtype != dtype || !fits(v, M, N, K)) continue;
-        if (!best || v.rank < best->rank) best = &v;
+        if (v.scheme_id != scheme_id || v.dtype != dtype || v.rank >= 90 || !fits(v, M, N, K)) continue;
+        const double t = predict_variant(v, M, N, K);
+        if (!best || t < best_t) {
+            best = &v;
+            best_t = t;
+        }
     }
     return best;
 }

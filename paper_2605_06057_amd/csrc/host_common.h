@@ -37,7 +37,10 @@ struct Variant {
     uint64_t hash;      // scheme_hash of its coefficients (0 for plain)
     int TM, TN, TK;     // tile of one block product
     int chunk;          // products resident per pass (R: all H_r live, 1: Algorithm 2's r loop)
-    int rank;           // preference among variants of the same scheme and dtype (lower first)
+    int rank;           // >= 90: ablation variant, reachable by name only
+    double eff;         // measured fraction of the dtype's MFMA peak its MFMA work sustains at large shapes
+    int occ;            // work-groups per compute unit it is compiled for
+    int products;       // block products it multiplies (R plus residual products)
     int (*launch)(const Params *p, int grid, void *stream); // returns a hipError_t
 };
 extern const Variant kVariants[];
@@ -45,7 +48,12 @@ extern const int kVariantCount;
 
 int dtype_size(int dtype); // bytes, or 0
 
-// Preferred variant of (scheme_id, dtype) whose tile divides the shape; nullptr if none.
+// Variant of (scheme_id, dtype) with the smallest predicted time among those whose tile divides the
+// shape; nullptr if none.
 const Variant *pick_variant(int scheme_id, int dtype, int64_t M, int64_t N, int64_t K);
+// Predicted seconds of one variant on MI355X (MFMA time at its measured efficiency, stretched by
+// wave quantisation on 256 compute units, bounded below by the compulsory HBM traffic, plus launch).
+double predict_variant(const Variant &v, int64_t M, int64_t N, int64_t K);
+bool variant_fits(const Variant &v, int64_t M, int64_t N, int64_t K);
 
 } // namespace lcma

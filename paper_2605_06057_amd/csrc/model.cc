@@ -3,9 +3,11 @@
 // Two models live here.  lcma_model_stages / lcma_model_intensity are the paper's own
 // formulas (Table 2, Eq. 8-10), kept so that they can be evaluated for any hardware tuple.
 // lcma_predict_seconds is the model lcma_select uses for THIS library's kernels, whose
-// combinations never travel through HBM: the cost of a scheme is then MFMA time (with wave
-// quantisation on 256 compute units), vector-ALU time of the conversions and additions that
-// are repeated by every work-group that stages a tile, and the compulsory HBM traffic.
+// combinations never travel through HBM, so the paper's memory terms do not apply.  What the
+// additions, conversions and LDS traffic of a fused kernel cost shows in the fraction of the
+// MFMA peak that kernel sustains; that fraction is measured once per generated kernel and kept
+// in the kernel table.  A prediction is then MFMA time at that efficiency, stretched by wave
+// quantisation on 256 compute units and bounded below by the compulsory HBM traffic.
 #include "host_common.h"
 
 #include <algorithm>
@@ -14,7 +16,6 @@
 namespace lcma {
 
 static const int kUnits = 256;           // compute units of MI355X
-static const double kClock = 2.4e9;      // Hz
 static const double kHbmBytes = 8.0e12;  // bytes/s
 static const double kLaunch = 4.0e-6;    // seconds per launch
 
@@ -35,14 +36,16 @@ static int nnz(const std::vector<int8_t> &v) {
     return c;
 }
 
-// Fraction of the MFMA peak that a kernel of this tile family sustains, and how much of the
-// vector-ALU time fails to hide under it.  Measured on MI355X with this library's bench.
-struct Calib {
-    double eta_plain, eta_lcma, valu_exposed;
-};
-static Calib calib(int dtype) {
-    if (dtype == LCMA_F32) return {0.60, 0.55, 0.5};
-    return {0.45, 0.40, 0.5};
+double predict_variant(const Variant &v, int64_t M, int64_t N, int64_t K) {
+    const int es = dtype_size(v.dtype);
+    const double dM = (double)M, dN = (double)N, dK = (double)K;
+    const double groups = (dM / (v.m * v.TM)) * (dN / (v.n * v.TN));
+    const double slots = (double)kUnits * v.occ;
+    const double quant = std::ceil(groups / slots) * slots / groups; // idle share of the last wave
+    const double mfma_flops = 2.0 * dM * dN * dK * v.products / ((double)v.m * v.n * v.k);
+    const double t_mfma = mfma_flops / (v.eff * mfma_peak(v.dtype)) * quant;
+    const double t_hbm = (dM * dK + dK * dN + dM * dN) * es / kHbmBytes;
+    return std::max(t_hbm, t_mfma) + kLaunch;
 }
 
 } // namespace lcma
@@ -109,35 +112,9 @@ extern "C" lcma_status lcma_model_intensity(const lcma_scheme *s, int64_t M, int
 }
 
 extern "C" double lcma_predict_seconds(int scheme_id, int64_t M, int64_t N, int64_t K, lcma_dtype dtype) {
-    const int es = dtype_size(dtype);
-    if (!es || M <= 0 || N <= 0 || K <= 0) return -1.0;
+    if (!dtype_size(dtype) || M <= 0 || N <= 0 || K <= 0) return -1.0;
     const Variant *v = pick_variant(scheme_id, dtype, M, N, K);
-    if (!v) return -1.0;
-    const Calib cal = calib(dtype);
-    const double dM = (double)M, dN = (double)N, dK = (double)K;
-    const double groups = (dM / (v->m * v->TM)) * (dN / (v->n * v->TN));
-    const double waves = std::ceil(groups / kUnits);
-    const double quant = waves * kUnits / groups; // idle share of the last wave
-    const double eta = scheme_id == LCMA_PLAIN ? cal.eta_plain : cal.eta_lcma;
-    const double t_mfma = 2.0 * dM * dN * dK * v->R / ((double)v->m * v->n * v->k) / (eta * mfma_peak(dtype)) * quant;
-    double t_valu = 0.0;
-    if (scheme_id != LCMA_PLAIN) {
-        const lcma_scheme *s = builtin_scheme(scheme_id);
-        if (!s) return -1.0;
-        // lane-operations per element position of a staged tile: conversion of every raw tile
-        // (bf16 only: 3 operations per packed pair) plus one addition per extra term.
-        const double conv = dtype == LCMA_BF16 ? 1.5 : 0.0, add = es == 2 ? 0.5 : 1.0;
-        // a chunked kernel re-stages raw tiles once per chunk that uses them
-        const double passes = (double)v->R / v->chunk;
-        const double rawA = std::min((double)nnz(s->U), passes * v->m * v->k);
-        const double rawB = std::min((double)nnz(s->V), passes * v->k * v->n);
-        const double a_ops = (conv * rawA + add * (nnz(s->U) - v->R)) * (dM / v->m) * (dK / v->k) * (dN / (v->n * v->TN));
-        const double b_ops = (conv * rawB + add * (nnz(s->V) - v->R)) * (dK / v->k) * (dN / v->n) * (dM / (v->m * v->TM));
-        const double c_ops = (double)nnz(s->W) * (dM / v->m) * (dN / v->n);
-        t_valu = (a_ops + b_ops + c_ops) / (kUnits * 64.0 * kClock) * quant;
-    }
-    const double t_hbm = (dM * dK + dK * dN + dM * dN) * es / kHbmBytes;
-    return std::max(t_hbm, t_mfma + cal.valu_exposed * t_valu) + kLaunch;
+    return v ? predict_variant(*v, M, N, K) : -1.0;
 }
 
 extern "C" int lcma_select(int64_t M, int64_t N, int64_t K, lcma_dtype dtype) {

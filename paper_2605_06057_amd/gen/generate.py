@@ -116,7 +116,8 @@ class Variant:
     wgn: int = 2
     chunk: int = 1            # products per chunk (consecutive in the chunk order)
     stages: int = 2
-    rank: int = 0
+    rank: int = 0             # >= 90: ablation variant, only reachable by name
+    eff: float = 0.1          # measured fraction of the dtype's MFMA peak its MFMA work sustains (large shapes)
     pipe: int = 0             # 0: double-buffered phases, 1: software-pipelined step
     occ: int = 1              # work-groups per CU the kernel is compiled for
     fc: int = 0               # 1: LDS holds raw blocks, waves combine MFMA fragments (needs chunk >= R)
@@ -305,7 +306,7 @@ def emit_registry(schemes: dict[str, Scheme], variants: list[Variant]) -> str:
         s = schemes[v.scheme]
         hash_expr = "0" if s.name == "plain" else f"0x{scheme_hash(s):016x}ull"
         L.append(f'    {{"{v.name}", {SCHEME_IDS[v.scheme]}, {DTYPE_IDS[v.dtype]}, {s.m}, {s.k}, {s.n}, {s.R}, '
-                 f"{hash_expr}, {v.TM}, {v.TN}, {v.TK}, {min(v.chunk, s.R)}, {v.rank}, lcma_launch_{v.name}}},")
+                 f"{hash_expr}, {v.TM}, {v.TN}, {v.TK}, {min(v.chunk, s.R)}, {v.rank}, {v.eff}, {v.occ}, {s.R + len(v.comp)}, lcma_launch_{v.name}}},")
     L += ["};", f"const int kVariantCount = {len(variants)};", "} // namespace lcma", ""]
     return "\n".join(L)
 
@@ -336,48 +337,51 @@ def emit_builtin_inc(schemes: dict[str, Scheme]) -> str:
 
 # ----------------------------------------------------------------------------- manifest
 def manifest() -> list[Variant]:
-    """The kernels that are built.  rank orders the variants of one (scheme, dtype): the lowest rank
-    whose tile divides the shape is what lcma_gemm launches.  Ranks follow measurements on MI355X
-    (4096^3): eight-wave work-groups (two waves per SIMD) beat four-wave ones throughout."""
+    """The kernels that are built.  `eff` is the fraction of the dtype's dense MFMA peak that the
+    variant's own MFMA work sustained on MI355X at large shapes (4096^3 and up, this library's
+    bench); the library launches, among the variants of a scheme whose tile divides the shape, the one
+    with the smallest predicted time (eff and wave quantisation).  Eight-wave work-groups (two waves
+    per SIMD) beat four-wave ones throughout."""
     V = []
     for dt in ("bf16", "f16"):
         V += [
-            Variant("plain", dt, 256, 256, 64, rank=0, wgm=2, wgn=4),
-            Variant("plain", dt, 256, 128, 32, rank=1, occ=2),
-            Variant("plain", dt, 128, 128, 64, rank=2, occ=2),
-            Variant("plain", dt, 64, 64, 32, rank=9),
+            Variant("plain", dt, 256, 256, 64, wgm=2, wgn=4, eff=0.42),
+            Variant("plain", dt, 256, 128, 32, occ=2, eff=0.36),
+            Variant("plain", dt, 128, 128, 64, occ=2, eff=0.32),
+            Variant("plain", dt, 64, 64, 32, eff=0.16),
             # fragment-combine kernels: raw blocks in LDS, every wave forms the 7 operand pairs
-            Variant("strassen", dt, 64, 128, 32, chunk=7, rank=0, fc=1, wgm=2, wgn=4),
-            Variant("strassen", dt, 128, 64, 32, chunk=7, rank=1, fc=1, wgm=4, wgn=2),
-            Variant("strassen", dt, 64, 64, 32, chunk=7, rank=2, fc=1, occ=2),
-            Variant("strassen", dt, 128, 64, 32, chunk=7, rank=3, fc=1),
+            Variant("strassen", dt, 64, 128, 32, chunk=7, fc=1, wgm=2, wgn=4, eff=0.233),
+            Variant("strassen", dt, 128, 64, 32, chunk=7, fc=1, wgm=4, wgn=2, eff=0.225),
+            Variant("strassen", dt, 64, 64, 32, chunk=7, fc=1, occ=2, eff=0.205),
+            Variant("strassen", dt, 128, 64, 32, chunk=7, fc=1, eff=0.185),
             # combinations formed while staging (Algorithm 2's r loop when chunk = 1)
-            Variant("strassen", dt, 64, 64, 32, chunk=7, rank=7),
-            Variant("strassen", dt, 128, 128, 32, chunk=1, rank=8),
-            Variant("laderman", dt, 128, 64, 32, chunk=1, rank=1 if dt == "f16" else 0),
-            Variant("laderman", dt, 64, 64, 32, chunk=1, rank=5),
+            Variant("strassen", dt, 64, 64, 32, chunk=7, eff=0.097),
+            Variant("strassen", dt, 128, 128, 32, chunk=1, eff=0.123),
+            Variant("laderman", dt, 128, 64, 32, chunk=1, eff=0.056, rank=90 if dt == "f16" else 0),
+            Variant("laderman", dt, 64, 64, 32, chunk=1, eff=0.045, rank=90 if dt == "f16" else 0),
         ]
     # Laderman with fp16 storage: rounding its 3- and 7-term combinations to fp16 costs 4.05x the error
     # of the plain kernel; multiplying the residual of the left operand of products 4 and 7 (both
     # three-term on each side) as well brings it under the 4x bound for 2 extra products out of 23.
-    V += [Variant("laderman", "f16", 128, 64, 32, chunk=1, rank=0, comp=(3, 6)),
-          Variant("laderman", "f16", 64, 64, 32, chunk=1, rank=4, comp=(3, 6))]
+    # The uncompensated kernels above stay as ablation variants (rank 90).
+    V += [Variant("laderman", "f16", 128, 64, 32, chunk=1, comp=(3, 6), eff=0.056),
+          Variant("laderman", "f16", 64, 64, 32, chunk=1, comp=(3, 6), eff=0.045)]
     # two-level Strassen: with fp16 storage its four-term sums exceed the 4x error bound, so it is
     # generated for bf16 (sums nearly exact in fp16) and fp32 only
     V += [
-        Variant("strassen2", "bf16", 64, 64, 32, chunk=7, rank=0),
-        Variant("strassen2", "bf16", 64, 64, 32, chunk=1, rank=5),
+        Variant("strassen2", "bf16", 64, 64, 32, chunk=7, eff=0.061),
+        Variant("strassen2", "bf16", 64, 64, 32, chunk=1, eff=0.03),
     ]
     V += [
-        Variant("plain", "f32", 128, 128, 16, rank=0, occ=2),
-        Variant("plain", "f32", 256, 128, 16, rank=1, wgm=2, wgn=4),
-        Variant("plain", "f32", 64, 64, 16, rank=9),
-        Variant("strassen", "f32", 64, 64, 16, chunk=7, rank=0, fc=1, occ=2),
-        Variant("strassen", "f32", 128, 64, 16, chunk=7, rank=1, fc=1, wgm=4, wgn=2),
-        Variant("strassen", "f32", 64, 64, 16, chunk=7, rank=5),
-        Variant("strassen", "f32", 128, 64, 16, chunk=1, rank=6),
-        Variant("laderman", "f32", 64, 64, 16, chunk=1, rank=0),
-        Variant("strassen2", "f32", 64, 64, 16, chunk=7, rank=0),
+        Variant("plain", "f32", 128, 128, 16, occ=2, eff=0.89),
+        Variant("plain", "f32", 256, 128, 16, wgm=2, wgn=4, eff=0.885),
+        Variant("plain", "f32", 64, 64, 16, eff=0.745),
+        Variant("strassen", "f32", 64, 64, 16, chunk=7, fc=1, occ=2, eff=0.773),
+        Variant("strassen", "f32", 128, 64, 16, chunk=7, fc=1, wgm=4, wgn=2, eff=0.73),
+        Variant("strassen", "f32", 64, 64, 16, chunk=7, eff=0.62),
+        Variant("strassen", "f32", 128, 64, 16, chunk=1, eff=0.58),
+        Variant("laderman", "f32", 64, 64, 16, chunk=1, eff=0.40),
+        Variant("strassen2", "f32", 64, 64, 16, chunk=7, eff=0.487),
     ]
     return [v.finish() for v in V]
 
