@@ -15,6 +15,7 @@ LIB = os.path.join(PKG, "liblcma.so")
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 DEVICE_FLAGS = ["--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 COMMON = ["-O3", "-std=c++17", "-fPIC", "-I", CSRC, "-I", GEN, "-Wno-unused-command-line-argument"]
+COMMON += os.environ.get("LCMA_EXTRA_FLAGS", "").split()  # e.g. -D switches of timing experiments
 
 
 def _newer(target: str, deps: list[str]) -> bool:
