@@ -27,6 +27,9 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 #define LCMA_LDS __attribute__((address_space(3)))
 #define LCMA_DEV __device__ __forceinline__
+#ifndef LCMA_FP32_GROUP
+#define LCMA_FP32_GROUP 2 // products whose fp32 MFMA chains are interleaved
+#endif
 
 // ---------------------------------------------------------------- element types
 // ES: bytes per element, CH: elements per 16-byte chunk, vec: what the combination code adds.
@@ -364,7 +367,7 @@ template <class T> struct Ctx {
             // generated combination code are dead and vanish).  With several MFMA instructions per
             // fragment pair (fp32) two products advance together, so that back-to-back instructions
             // never accumulate into the same tile.
-            constexpr int G = (Mma<CT>::SUB > 1 && T::NMI * T::NNI == 1) ? 2 : 1;
+            constexpr int G = (Mma<CT>::SUB > 1 && T::NMI * T::NNI == 1) ? LCMA_FP32_GROUP : 1;
 #pragma unroll
             for (int s0 = 0; s0 < CH::NP; s0 += G) {
                 Frag at[G][T::NMI], bt[G][T::NNI];
