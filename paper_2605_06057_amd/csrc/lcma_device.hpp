@@ -108,7 +108,7 @@ template <> struct Round<BF16> {
 // ---------------------------------------------------------------- tile configuration
 // TM x TN: tile of one block product owned by the work-group; TK: depth per y step;
 // WGM x WGN: wave grid (4 waves); NSA / NSB: A-side / B-side tiles resident per LDS stage;
-// PIPE: 0 double-buffered phases, 1 software-pipelined step;
+// PIPE: 0 double-buffered phases, 1 software-pipelined step, 2 staging spread over the MFMA phase;
 // FC: 0 = combinations are formed while staging and LDS holds At_r, Bt_r;
 //     1 = LDS holds the raw (converted) blocks and every wave forms the combinations on the
 //         MFMA fragments it has read ("fragment combine").
@@ -343,7 +343,13 @@ template <class T> struct Ctx {
     // Fragment-combine form: LDS stage `st` holds the raw blocks; read their fragments once, form the
     // operand fragments of every product with CH::comb_a / comb_b (Eq. 3 / Eq. 4 on registers) and
     // multiply.
+    // `hook(slot, slots)` runs after the MFMA instructions of product group `slot` (numbered through
+    // all k sub-steps); its instructions issue while those MFMAs execute.
     template <class CH> LCMA_DEV void mma_stage_fc(int st, typename T::Acc (&acc)[CH::NP]) const {
+        mma_stage_fc<CH>(st, acc, [](int, int) {});
+    }
+    template <class CH, class HOOK>
+    LCMA_DEV void mma_stage_fc(int st, typename T::Acc (&acc)[CH::NP], HOOK hook) const {
         const uint32_t sb = st * T::STAGE;
         Frag ra_[2][T::NMI][CH::NA], rb_[2][T::NNI][CH::NB];
         auto fetch = [&](int kk, int buf) {
@@ -398,6 +404,8 @@ template <class T> struct Ctx {
                             for (int ni = 0; ni < T::NNI; ++ni)
                                 Mma<CT>::run_sub(at[g][mi], bt[g][ni], acc[s0 + g].v[mi][ni], t);
                     }
+                constexpr int NG = (CH::NP + G - 1) / G;
+                hook(kk * NG + s0 / G, T::NKK * NG);
             }
         }
     }
@@ -559,13 +567,41 @@ template <class T, class CH> struct FlatStage {
                 r.b[q][e / 4][e % 4] = __builtin_amdgcn_raw_buffer_load_b32(
                     cx.rb, (int)b_voff[q], (int)(sbo + (uint32_t)e * cx.p.ldb_b), 0);
     }
+    // The staging work of one thread cut into NPIECE pieces (one 16-byte A chunk or one B unit each),
+    // so that it can be spread over the MFMA phase.
+    static constexpr int NPIECE = QA + QB;
+    LCMA_DEV void issue_piece(const Ctx<T> &cx, Raw &r, int pc, int y) const {
+        if (pc < QA) {
+            const uint32_t sa = cx.a_group + (uint32_t)y * (T::TK * T::ES);
+            r.a[pc] = __builtin_amdgcn_raw_buffer_load_b128(cx.ra, (int)a_voff[pc], (int)sa, 0);
+        } else {
+            const int q = pc - QA;
+            const uint32_t sbo = cx.b_group + (uint32_t)y * T::TK * cx.p.ldb_b;
+#pragma unroll
+            for (int e = 0; e < T::BW; ++e)
+                r.b[q][e / 4][e % 4] = __builtin_amdgcn_raw_buffer_load_b32(
+                    cx.rb, (int)b_voff[q], (int)(sbo + (uint32_t)e * cx.p.ldb_b), 0);
+        }
+    }
+    LCMA_DEV void store_piece(const Ctx<T> &cx, const Raw &r, int pc, int st) const {
+        const uint32_t sb = st * T::STAGE;
+        if (pc < QA) store_a(cx, r, pc, sb);
+        else store_b(cx, r, pc - QA, sb);
+    }
     LCMA_DEV void store(const Ctx<T> &cx, const Raw &r, int st) const {
-        using Cv = Convert<typename T::IN, typename T::CT>;
         const uint32_t sb = st * T::STAGE;
 #pragma unroll
-        for (int q = 0; q < QA; ++q) cx.lds_store(sb + a_lds[q], __builtin_bit_cast(u32x4, Cv::run(r.a[q])));
+        for (int q = 0; q < QA; ++q) store_a(cx, r, q, sb);
 #pragma unroll
-        for (int q = 0; q < QB; ++q) {
+        for (int q = 0; q < QB; ++q) store_b(cx, r, q, sb);
+    }
+    LCMA_DEV void store_a(const Ctx<T> &cx, const Raw &r, int q, uint32_t sb) const {
+        using Cv = Convert<typename T::IN, typename T::CT>;
+        cx.lds_store(sb + a_lds[q], __builtin_bit_cast(u32x4, Cv::run(r.a[q])));
+    }
+    LCMA_DEV void store_b(const Ctx<T> &cx, const Raw &r, int q, uint32_t sb) const {
+        using Cv = Convert<typename T::IN, typename T::CT>;
+        {
             if constexpr (T::ES == 2) {
                 const u32x4 lo = __builtin_bit_cast(u32x4, Cv::run(r.b[q][0]));
                 const u32x4 hi = __builtin_bit_cast(u32x4, Cv::run(r.b[q][1]));
@@ -592,6 +628,28 @@ template <class T, class CH> LCMA_DEV void mma_step(const Ctx<T> &cx, int st, ty
     else cx.template mma_stage<CH::NP>(st, acc);
 }
 
+// Runs step(y, y & 1) for y = 0 .. ny-1.  With LIT the loop is unrolled twice so that the stage is a
+// literal at both call sites and every LDS address becomes a register plus an immediate.  The address
+// arithmetic this saves is worth 5-10% in the 16-bit kernels (bound by vector instruction issue) and
+// in the fp32 ones (measured: no cycle in which a VALU and an fp32 MFMA instruction execute together,
+// so every vector instruction there takes MFMA time).
+#ifndef LCMA_LITERAL_STAGE
+#define LCMA_LITERAL_STAGE 1
+#endif
+template <class T> constexpr bool LITERAL_STAGE = LCMA_LITERAL_STAGE != 0;
+template <bool LIT, class F> LCMA_DEV void stage_loop(int ny, F step) {
+    if constexpr (LIT) {
+        int y = 0;
+        for (; y + 1 < ny; y += 2) {
+            step(y, 0);
+            step(y + 1, 1);
+        }
+        if (y < ny) step(y, 0);
+    } else {
+        for (int y = 0; y < ny; ++y) step(y, y & 1);
+    }
+}
+
 // The y loop of Algorithm 2 for one chunk over two LDS stages.
 template <class T, class CH> LCMA_DEV void run_chunk(const Ctx<T> &cx, typename T::Acc (&acc)[CH::NP]) {
     const int ny = cx.p.ny, last = ny - 1;
@@ -601,13 +659,41 @@ template <class T, class CH> LCMA_DEV void run_chunk(const Ctx<T> &cx, typename 
         if constexpr (T::PIPE == 0) {
             typename FlatStage<T, CH>::Raw r;
             fs.issue(cx, r, 0);
-            for (int y = 0; y < ny; ++y) {
-                fs.store(cx, r, y & 1);
+            auto step = [&](int y, int st) {
+                fs.store(cx, r, st);
                 fs.issue(cx, r, y + 1 < ny ? y + 1 : last);
                 __syncthreads();
-                cx.template mma_stage_fc<CH>(y & 1, acc);
-            }
+                cx.template mma_stage_fc<CH>(st, acc);
+            };
+            stage_loop<LITERAL_STAGE<T>>(ny, step);
             __syncthreads();
+        } else if constexpr (T::PIPE == 2) {
+            // Staging spread over the MFMA phase: while step y is multiplied out of one LDS stage, each
+            // thread writes its pieces of step y+1 to the other stage and reloads the piece's registers
+            // with step y+2, a piece at a time between product groups, so that the LDS writes and the
+            // buffer loads issue under executing MFMAs.  One barrier per step: the stage written during
+            // step y was last read in step y-1, before the previous barrier.
+            using FS = FlatStage<T, CH>;
+            typename FS::Raw r;
+            fs.issue(cx, r, 0);
+            fs.store(cx, r, 0);
+            fs.issue(cx, r, ny > 1 ? 1 : 0);
+            __syncthreads();
+            auto step = [&](int y, int st) {
+                const int nxt = y + 2 < ny ? y + 2 : last; // past the end: reload the last tile, unused
+                cx.template mma_stage_fc<CH>(st, acc, [&](int slot, int slots) {
+#pragma unroll
+                    for (int pc = 0; pc < FS::NPIECE; ++pc)
+                        if (pc * slots / FS::NPIECE == slot) {
+                            __builtin_amdgcn_sched_barrier(0);
+                            fs.store_piece(cx, r, pc, st ^ 1);
+                            fs.issue_piece(cx, r, pc, nxt);
+                            __builtin_amdgcn_sched_barrier(0);
+                        }
+                });
+                __syncthreads();
+            };
+            stage_loop<LITERAL_STAGE<T>>(ny, step);
         } else {
             typename FlatStage<T, CH>::Raw r0, r1;
             fs.issue(cx, r0, 0);
@@ -631,12 +717,13 @@ template <class T, class CH> LCMA_DEV void run_chunk(const Ctx<T> &cx, typename 
         // of step y.  Meant for two work-groups per CU, which overlap each other's phases.
         RawSet<T, CH> r;
         issue_loads<T, CH>(cx, r, 0);
-        for (int y = 0; y < ny; ++y) {
-            combine_store<T, CH>(cx, r, y & 1);
+        auto step = [&](int y, int st) {
+            combine_store<T, CH>(cx, r, st);
             issue_loads<T, CH>(cx, r, y + 1 < ny ? y + 1 : last);
             __syncthreads();
-            mma_step<T, CH>(cx, y & 1, acc);
-        }
+            mma_step<T, CH>(cx, st, acc);
+        };
+        stage_loop<LITERAL_STAGE<T>>(ny, step);
         __syncthreads();
     } else {
         // Software-pipelined: in the steady state one step (a single basic block, so that the

@@ -127,7 +127,7 @@ class Variant:
     def finish(self):
         if not self.name:
             self.name = (f"{self.scheme}_{self.dtype}_t{self.TM}x{self.TN}x{self.TK}_c{self.chunk}"
-                         + (f"x{len(self.comp)}" if self.comp else "") + (f"w{self.wgm}x{self.wgn}" if (self.wgm, self.wgn) != (2, 2) else "") + ("f" if self.fc else "") + ("p" if self.pipe else "") + (f"o{self.occ}" if self.occ > 1 else ""))
+                         + (f"x{len(self.comp)}" if self.comp else "") + (f"w{self.wgm}x{self.wgn}" if (self.wgm, self.wgn) != (2, 2) else "") + ("f" if self.fc else "") + ("p" if self.pipe == 1 else "i" if self.pipe == 2 else "") + (f"o{self.occ}" if self.occ > 1 else ""))
         return self
 
 
@@ -352,6 +352,11 @@ def manifest() -> list[Variant]:
             # fragment-combine kernels: raw blocks in LDS, every wave forms the 7 operand pairs
             Variant("strassen", dt, 64, 128, 32, chunk=7, fc=1, wgm=2, wgn=4, eff=0.233),
             Variant("strassen", dt, 128, 64, 32, chunk=7, fc=1, wgm=4, wgn=2, eff=0.225),
+            Variant("strassen", dt, 64, 128, 32, chunk=7, fc=1, wgm=2, wgn=4, pipe=2, eff=0.233),
+            Variant("strassen", dt, 128, 64, 32, chunk=7, fc=1, wgm=4, wgn=2, pipe=2, eff=0.225),
+            Variant("strassen", dt, 64, 64, 32, chunk=7, fc=1, occ=2, pipe=2, eff=0.205),
+            Variant("strassen", dt, 128, 64, 32, chunk=7, fc=1, pipe=2, eff=0.185),
+            Variant("strassen", dt, 64, 128, 32, chunk=7, fc=1, pipe=2, eff=0.185),
             Variant("strassen", dt, 64, 64, 32, chunk=7, fc=1, occ=2, eff=0.205),
             Variant("strassen", dt, 128, 64, 32, chunk=7, fc=1, eff=0.185),
             # combinations formed while staging (Algorithm 2's r loop when chunk = 1)
@@ -377,7 +382,9 @@ def manifest() -> list[Variant]:
         Variant("plain", "f32", 256, 128, 16, wgm=2, wgn=4, eff=0.885),
         Variant("plain", "f32", 64, 64, 16, eff=0.745),
         Variant("strassen", "f32", 64, 64, 16, chunk=7, fc=1, occ=2, eff=0.773),
+        Variant("strassen", "f32", 64, 64, 16, chunk=7, fc=1, occ=2, pipe=2, eff=0.773),
         Variant("strassen", "f32", 128, 64, 16, chunk=7, fc=1, wgm=4, wgn=2, eff=0.73),
+        Variant("strassen", "f32", 128, 64, 16, chunk=7, fc=1, wgm=4, wgn=2, pipe=2, eff=0.73),
         Variant("strassen", "f32", 64, 64, 16, chunk=7, eff=0.62),
         Variant("strassen", "f32", 128, 64, 16, chunk=1, eff=0.58),
         Variant("laderman", "f32", 64, 64, 16, chunk=1, eff=0.40),
