@@ -52,8 +52,10 @@ def read_traffic(workload: str):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--heat-seconds", type=float, default=0.3,
+                    help="untimed load before each timed leg, so that clocks are settled")
     ap.add_argument("--workload", default="strassen_bf16_4096", choices=sorted(WORKLOADS))
     ap.add_argument("--variant", default=None, help="time this generated kernel instead of the default choice")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
@@ -107,6 +109,14 @@ def main():
         torch.mm(a, b, out=c)
 
     def timed(step, steps, warmup):
+        # Untimed: keep the chip busy for a moment first, so that its clocks have settled where a
+        # long-running job holds them (a cold MI355X needs some milliseconds of load to get there),
+        # then the W warm-up steps.
+        t_heat = time.perf_counter()
+        while time.perf_counter() - t_heat < args.heat_seconds:
+            for i in range(10):
+                step(i)
+            torch.cuda.synchronize()
         for i in range(warmup):
             step(i)
         torch.cuda.synchronize()

@@ -111,21 +111,23 @@ template <> struct Round<BF16> {
 // PIPE: 0 double-buffered phases, 1 software-pipelined step, 2 staging spread over the MFMA phase;
 // FC: 0 = combinations are formed while staging and LDS holds At_r, Bt_r;
 //     1 = LDS holds the raw (converted) blocks and every wave forms the combinations on the
-//         MFMA fragments it has read ("fragment combine").
+//         MFMA fragments it has read ("fragment combine");
+// STAGES: LDS stages (2, or 3 with PIPE 2 and FC: the first fragments of the next step are then read
+//         before the barrier that ends the step).
 //
 // LDS layout of a stage: NSA tiles [TM rows][TK] then NSB tiles [TN rows][TK], both k-contiguous,
 // 16-byte chunks XOR-swizzled inside a row.  B arrives n-contiguous from memory and is transposed
 // in registers while it is staged, so that both MFMA operands are read with 16-byte LDS loads
 // (measured on MI355X: ds_read_b128 ~260 B/clk/CU, the transposing ds_read_b64_tr_b16 ~70).
 template <class IN_, class CT_, int TM_, int TN_, int TK_, int WGM_, int WGN_, int NSA_, int NSB_, int PIPE_ = 0,
-          int FC_ = 0>
+          int FC_ = 0, int STAGES_ = 2>
 struct Tile {
     static constexpr int PIPE = PIPE_, FC = FC_;
     using IN = IN_;
     using CT = CT_;
     static_assert(IN::ES == CT::ES, "conversion must keep the element size");
     static constexpr int TM = TM_, TN = TN_, TK = TK_, WGM = WGM_, WGN = WGN_;
-    static constexpr int NSA = NSA_, NSB = NSB_, STAGES = 2;
+    static constexpr int NSA = NSA_, NSB = NSB_, STAGES = STAGES_;
     static constexpr int ES = CT::ES, CH = CT::CH;
     static constexpr int NT = 64 * WGM * WGN;
     static constexpr int WM = TM / WGM, WN = TN / WGN;
@@ -345,30 +347,43 @@ template <class T> struct Ctx {
     // multiply.
     // `hook(slot, slots)` runs after the MFMA instructions of product group `slot` (numbered through
     // all k sub-steps); its instructions issue while those MFMAs execute.
+    // Fragments of the raw blocks of one k sub-step, double-buffered.
+    template <class CH> struct Frags {
+        Frag a[2][T::NMI][CH::NA], b[2][T::NNI][CH::NB];
+    };
+    template <class CH> LCMA_DEV void fetch_frags(Frags<CH> &f, int st, int kk, int buf) const {
+        const uint32_t sb = st * T::STAGE;
+#pragma unroll
+        for (int mi = 0; mi < T::NMI; ++mi)
+#pragma unroll
+            for (int t = 0; t < CH::NA; ++t) f.a[buf][mi][t] = lds_frag(sb + t * T::A_SLOT + a_frag[kk] + mi * 32 * T::ROW);
+#pragma unroll
+        for (int ni = 0; ni < T::NNI; ++ni)
+#pragma unroll
+            for (int t = 0; t < CH::NB; ++t) f.b[buf][ni][t] = lds_frag(sb + t * T::B_SLOT + b_frag[kk] + ni * 32 * T::ROW);
+    }
     template <class CH> LCMA_DEV void mma_stage_fc(int st, typename T::Acc (&acc)[CH::NP]) const {
         mma_stage_fc<CH>(st, acc, [](int, int) {});
     }
     template <class CH, class HOOK>
     LCMA_DEV void mma_stage_fc(int st, typename T::Acc (&acc)[CH::NP], HOOK hook) const {
-        const uint32_t sb = st * T::STAGE;
-        Frag ra_[2][T::NMI][CH::NA], rb_[2][T::NNI][CH::NB];
-        auto fetch = [&](int kk, int buf) {
-#pragma unroll
-            for (int mi = 0; mi < T::NMI; ++mi)
-#pragma unroll
-                for (int t = 0; t < CH::NA; ++t)
-                    ra_[buf][mi][t] = lds_frag(sb + t * T::A_SLOT + a_frag[kk] + mi * 32 * T::ROW);
-#pragma unroll
-            for (int ni = 0; ni < T::NNI; ++ni)
-#pragma unroll
-                for (int t = 0; t < CH::NB; ++t)
-                    rb_[buf][ni][t] = lds_frag(sb + t * T::B_SLOT + b_frag[kk] + ni * 32 * T::ROW);
-        };
-        fetch(0, 0);
+        Frags<CH> f;
+        fetch_frags<CH>(f, st, 0, 0);
+        mma_stage_fc<CH>(st, -1, f, acc, hook);
+    }
+    // `f` holds the fragments of k sub-step 0 of stage `st` in buffer 0 on entry.  With nst >= 0 the
+    // fragments of k sub-step 0 of stage `nst` are fetched into buffer 0 under the last sub-step's
+    // MFMAs (needs an even number of sub-steps).  `hook(slot, slots)` runs after the MFMA instructions
+    // of product group `slot` (numbered through all k sub-steps); its instructions issue while those
+    // MFMAs execute.
+    template <class CH, class HOOK>
+    LCMA_DEV void mma_stage_fc(int st, int nst, Frags<CH> &f, typename T::Acc (&acc)[CH::NP], HOOK hook) const {
 #pragma unroll
         for (int kk = 0; kk < T::NKK; ++kk) {
             const int cur = kk & 1;
-            if (kk + 1 < T::NKK) fetch(kk + 1, cur ^ 1); // next fragments arrive under this step's MFMAs
+            // next fragments arrive under this step's MFMAs
+            if (kk + 1 < T::NKK) fetch_frags<CH>(f, st, kk + 1, cur ^ 1);
+            else if (nst >= 0) fetch_frags<CH>(f, nst, 0, cur ^ 1);
             // A few products at a time keeps few combined fragments live (the unused outputs of the
             // generated combination code are dead and vanish).  With several MFMA instructions per
             // fragment pair (fp32) two products advance together, so that back-to-back instructions
@@ -383,13 +398,13 @@ template <class T> struct Ctx {
 #pragma unroll
                     for (int mi = 0; mi < T::NMI; ++mi) {
                         Frag o[CH::NP];
-                        CH::comb_a(ra_[cur][mi], o);
+                        CH::comb_a(f.a[cur][mi], o);
                         at[g][mi] = o[s0 + g];
                     }
 #pragma unroll
                     for (int ni = 0; ni < T::NNI; ++ni) {
                         Frag o[CH::NP];
-                        CH::comb_b(rb_[cur][ni], o);
+                        CH::comb_b(f.b[cur][ni], o);
                         bt[g][ni] = o[s0 + g];
                     }
                 }
@@ -667,6 +682,44 @@ template <class T, class CH> LCMA_DEV void run_chunk(const Ctx<T> &cx, typename 
             };
             stage_loop<LITERAL_STAGE<T>>(ny, step);
             __syncthreads();
+        } else if constexpr (T::PIPE == 2 && T::STAGES == 3) {
+            // As below, with a third LDS stage: step y multiplies stage y%3, writes tile y+2 into stage
+            // (y+2)%3 and reloads the registers with tile y+3.  The stage of step y+1 is complete one
+            // barrier earlier than it is needed, so its first fragments are read under the last MFMAs
+            // of step y and no wave starts a step by waiting for LDS.
+            static_assert(T::NKK % 2 == 0, "fragment buffers must return to buffer 0 at the end of a step");
+            using FS = FlatStage<T, CH>;
+            typename FS::Raw r;
+            fs.issue(cx, r, 0);
+            fs.store(cx, r, 0);
+            fs.issue(cx, r, ny > 1 ? 1 : last);
+            fs.store(cx, r, 1);
+            fs.issue(cx, r, ny > 2 ? 2 : last);
+            __syncthreads();
+            typename Ctx<T>::template Frags<CH> f;
+            cx.template fetch_frags<CH>(f, 0, 0, 0);
+            auto step = [&](int y, int st) { // st = y % 3, a literal at every call site
+                const int nxt = y + 3 < ny ? y + 3 : last; // past the end: reload the last tile, unused
+                cx.template mma_stage_fc<CH>(st, (st + 1) % 3, f, acc, [&](int slot, int slots) {
+#pragma unroll
+                    for (int pc = 0; pc < FS::NPIECE; ++pc)
+                        if (pc * slots / FS::NPIECE == slot) {
+                            __builtin_amdgcn_sched_barrier(0);
+                            fs.store_piece(cx, r, pc, (st + 2) % 3);
+                            fs.issue_piece(cx, r, pc, nxt);
+                            __builtin_amdgcn_sched_barrier(0);
+                        }
+                });
+                __syncthreads();
+            };
+            int y = 0;
+            for (; y + 2 < ny; y += 3) {
+                step(y, 0);
+                step(y + 1, 1);
+                step(y + 2, 2);
+            }
+            if (y < ny) step(y, 0);
+            if (y + 1 < ny) step(y + 1, 1);
         } else if constexpr (T::PIPE == 2) {
             // Staging spread over the MFMA phase: while step y is multiplied out of one LDS stage, each
             // thread writes its pieces of step y+1 to the other stage and reloads the piece's registers

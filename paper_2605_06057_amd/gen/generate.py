@@ -127,7 +127,7 @@ class Variant:
     def finish(self):
         if not self.name:
             self.name = (f"{self.scheme}_{self.dtype}_t{self.TM}x{self.TN}x{self.TK}_c{self.chunk}"
-                         + (f"x{len(self.comp)}" if self.comp else "") + (f"w{self.wgm}x{self.wgn}" if (self.wgm, self.wgn) != (2, 2) else "") + ("f" if self.fc else "") + ("p" if self.pipe == 1 else "i" if self.pipe == 2 else "") + (f"o{self.occ}" if self.occ > 1 else ""))
+                         + (f"x{len(self.comp)}" if self.comp else "") + (f"w{self.wgm}x{self.wgn}" if (self.wgm, self.wgn) != (2, 2) else "") + ("f" if self.fc else "") + ("p" if self.pipe == 1 else "i" if self.pipe == 2 else "") + ("s3" if self.stages == 3 else "") + (f"o{self.occ}" if self.occ > 1 else ""))
         return self
 
 
@@ -221,7 +221,7 @@ def emit_kernel(s: Scheme, v: Variant) -> str:
     w('#include "lcma_device.hpp"')
     w("namespace {")
     w("using namespace lcma;")
-    w(f"using T = Tile<{in_t}, {ct_t}, {v.TM}, {v.TN}, {v.TK}, {v.wgm}, {v.wgn}, {nsa}, {nsb}, {v.pipe}, {v.fc}>;")
+    w(f"using T = Tile<{in_t}, {ct_t}, {v.TM}, {v.TN}, {v.TK}, {v.wgm}, {v.wgn}, {nsa}, {nsb}, {v.pipe}, {v.fc}, {v.stages}>;")
     for ci, ch in enumerate(chunks):
         a_blocks = sorted({(i, l) for r in ch for i in range(s.m) for l in range(s.k) if s.U[r, i, l]})
         b_blocks = sorted({(l, j) for r in ch for l in range(s.k) for j in range(s.n) if s.V[r, l, j]})
@@ -344,24 +344,23 @@ def manifest() -> list[Variant]:
     per SIMD) beat four-wave ones throughout."""
     V = []
     for dt in ("bf16", "f16"):
+        e = (lambda bf, f: bf if dt == "bf16" else f)  # bf16 pays for its conversion to fp16
         V += [
-            Variant("plain", dt, 256, 256, 64, wgm=2, wgn=4, eff=0.42),
-            Variant("plain", dt, 256, 128, 32, occ=2, eff=0.36),
-            Variant("plain", dt, 128, 128, 64, occ=2, eff=0.32),
-            Variant("plain", dt, 64, 64, 32, eff=0.16),
-            # fragment-combine kernels: raw blocks in LDS, every wave forms the 7 operand pairs
-            Variant("strassen", dt, 64, 128, 32, chunk=7, fc=1, wgm=2, wgn=4, eff=0.233),
-            Variant("strassen", dt, 128, 64, 32, chunk=7, fc=1, wgm=4, wgn=2, eff=0.225),
-            Variant("strassen", dt, 64, 128, 32, chunk=7, fc=1, wgm=2, wgn=4, pipe=2, eff=0.233),
-            Variant("strassen", dt, 128, 64, 32, chunk=7, fc=1, wgm=4, wgn=2, pipe=2, eff=0.225),
-            Variant("strassen", dt, 64, 64, 32, chunk=7, fc=1, occ=2, pipe=2, eff=0.205),
-            Variant("strassen", dt, 128, 64, 32, chunk=7, fc=1, pipe=2, eff=0.185),
-            Variant("strassen", dt, 64, 128, 32, chunk=7, fc=1, pipe=2, eff=0.185),
-            Variant("strassen", dt, 64, 64, 32, chunk=7, fc=1, occ=2, eff=0.205),
-            Variant("strassen", dt, 128, 64, 32, chunk=7, fc=1, eff=0.185),
-            # combinations formed while staging (Algorithm 2's r loop when chunk = 1)
-            Variant("strassen", dt, 64, 64, 32, chunk=7, eff=0.097),
-            Variant("strassen", dt, 128, 128, 32, chunk=1, eff=0.123),
+            Variant("plain", dt, 256, 256, 64, wgm=2, wgn=4, eff=e(0.447, 0.426)),
+            Variant("plain", dt, 256, 128, 32, occ=2, eff=e(0.375, 0.363)),
+            Variant("plain", dt, 128, 128, 64, occ=2, eff=e(0.332, 0.317)),
+            Variant("plain", dt, 64, 64, 32, eff=e(0.172, 0.163)),
+            # fragment-combine kernels: raw blocks in LDS, every wave forms the 7 operand pairs;
+            # "i": staging spread over the MFMA phase
+            Variant("strassen", dt, 128, 64, 32, chunk=7, fc=1, wgm=4, wgn=2, pipe=2, eff=e(0.268, 0.291)),
+            Variant("strassen", dt, 64, 128, 32, chunk=7, fc=1, wgm=2, wgn=4, pipe=2, eff=e(0.265, 0.287)),
+            Variant("strassen", dt, 64, 64, 32, chunk=7, fc=1, occ=2, pipe=2, eff=e(0.241, 0.263)),
+            # ablation variants: staging in one phase; a third LDS stage; combinations formed while staging
+            Variant("strassen", dt, 128, 64, 32, chunk=7, fc=1, wgm=4, wgn=2, eff=e(0.261, 0.280), rank=90),
+            Variant("strassen", dt, 128, 64, 32, chunk=7, fc=1, wgm=4, wgn=2, pipe=2, stages=3, eff=e(0.268, 0.286), rank=90),
+            Variant("strassen", dt, 64, 64, 32, chunk=7, eff=e(0.099, 0.114), rank=90),
+            # Algorithm 2's r loop: one product at a time, combinations formed while staging
+            Variant("strassen", dt, 128, 128, 32, chunk=1, eff=e(0.149, 0.179)),
             Variant("laderman", dt, 128, 64, 32, chunk=1, eff=0.056, rank=90 if dt == "f16" else 0),
             Variant("laderman", dt, 64, 64, 32, chunk=1, eff=0.045, rank=90 if dt == "f16" else 0),
         ]
@@ -374,21 +373,20 @@ def manifest() -> list[Variant]:
     # two-level Strassen: with fp16 storage its four-term sums exceed the 4x error bound, so it is
     # generated for bf16 (sums nearly exact in fp16) and fp32 only
     V += [
-        Variant("strassen2", "bf16", 64, 64, 32, chunk=7, eff=0.061),
-        Variant("strassen2", "bf16", 64, 64, 32, chunk=1, eff=0.03),
+        Variant("strassen2", "bf16", 64, 64, 32, chunk=7, eff=0.065),
+        Variant("strassen2", "bf16", 64, 64, 32, chunk=1, eff=0.032),
     ]
     V += [
-        Variant("plain", "f32", 128, 128, 16, occ=2, eff=0.89),
-        Variant("plain", "f32", 256, 128, 16, wgm=2, wgn=4, eff=0.885),
-        Variant("plain", "f32", 64, 64, 16, eff=0.745),
-        Variant("strassen", "f32", 64, 64, 16, chunk=7, fc=1, occ=2, eff=0.773),
-        Variant("strassen", "f32", 64, 64, 16, chunk=7, fc=1, occ=2, pipe=2, eff=0.773),
-        Variant("strassen", "f32", 128, 64, 16, chunk=7, fc=1, wgm=4, wgn=2, eff=0.73),
-        Variant("strassen", "f32", 128, 64, 16, chunk=7, fc=1, wgm=4, wgn=2, pipe=2, eff=0.73),
-        Variant("strassen", "f32", 64, 64, 16, chunk=7, eff=0.62),
-        Variant("strassen", "f32", 128, 64, 16, chunk=1, eff=0.58),
+        Variant("plain", "f32", 256, 128, 16, wgm=2, wgn=4, eff=0.917),
+        Variant("plain", "f32", 128, 128, 16, occ=2, eff=0.916),
+        Variant("plain", "f32", 64, 64, 16, eff=0.856),
+        Variant("strassen", "f32", 64, 64, 16, chunk=7, fc=1, occ=2, pipe=2, eff=0.819),
+        Variant("strassen", "f32", 128, 64, 16, chunk=7, fc=1, wgm=4, wgn=2, pipe=2, eff=0.802),
+        Variant("strassen", "f32", 64, 64, 16, chunk=7, fc=1, occ=2, eff=0.795, rank=90),
+        Variant("strassen", "f32", 64, 64, 16, chunk=7, eff=0.656, rank=90),
+        Variant("strassen", "f32", 128, 64, 16, chunk=1, eff=0.613),
         Variant("laderman", "f32", 64, 64, 16, chunk=1, eff=0.40),
-        Variant("strassen2", "f32", 64, 64, 16, chunk=7, eff=0.487),
+        Variant("strassen2", "f32", 64, 64, 16, chunk=7, eff=0.528),
     ]
     return [v.finish() for v in V]
 
