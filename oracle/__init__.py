@@ -115,6 +115,58 @@ def lcma(s: Scheme, A: np.ndarray, B: np.ndarray) -> np.ndarray:
     return C
 
 
+def combine_b(s: Scheme, B: np.ndarray) -> np.ndarray:
+    """Combine B (paper Eq. 4; Algorithm 2 stage 2): Bt[r] = sum_{l,j} V[r,l,j] * B_{l,j}, r = 0..R-1.
+
+    Returns an array of shape (R, K/k, N/n) in fp64 (int64 for integer input): the exact right
+    operands of the R products.  The paper's end-to-end evaluation runs this stage once, offline,
+    for static weights."""
+    integer = B.dtype == np.int64
+    B = np.asarray(B, np.int64 if integer else np.float64)
+    K, N = B.shape
+    if K % s.k or N % s.n:
+        raise ValueError(f"shape ({K},{N}) is not divisible by the scheme grid ({s.k},{s.n})")
+    bk, bn = K // s.k, N // s.n
+    out = np.zeros((s.R, bk, bn), B.dtype)
+    for r in range(s.R):
+        for l in range(s.k):
+            for j in range(s.n):
+                v = int(s.V[r, l, j])
+                if v:
+                    out[r] += v * B[l * bk:(l + 1) * bk, j * bn:(j + 1) * bn]
+    return out
+
+
+def combine_b_stored(s: Scheme, B: np.ndarray, dtype: str) -> np.ndarray:
+    """Combine B as a 16-bit / fp32 library has to store it: the terms of Eq. 4 are added in fp32, in
+    ascending (l, j) order, and the sum is rounded once (nearest-even) to the type the products are
+    multiplied in: fp16 for bf16 and fp16 storage, fp32 for fp32 storage.  B holds values already
+    representable in the storage type.  Returns (R, K/k, N/n) in fp64 (the stored values, widened).
+    This fixes the precision in which the rounding decision is taken, so that an implementation can be
+    compared bit for bit."""
+    B = np.asarray(B, np.float64)
+    K, N = B.shape
+    if K % s.k or N % s.n:
+        raise ValueError(f"shape ({K},{N}) is not divisible by the scheme grid ({s.k},{s.n})")
+    bk, bn = K // s.k, N // s.n
+    B32 = B.astype(np.float32)
+    out = np.empty((s.R, bk, bn), np.float64)
+    with np.errstate(over="ignore"):
+        for r in range(s.R):
+            acc = None
+            for l in range(s.k):
+                for j in range(s.n):
+                    v = int(s.V[r, l, j])
+                    if not v:
+                        continue
+                    term = np.float32(v) * B32[l * bk:(l + 1) * bk, j * bn:(j + 1) * bn]
+                    acc = term if acc is None else (acc + term).astype(np.float32)
+            if acc is None:
+                acc = np.zeros((bk, bn), np.float32)
+            out[r] = acc.astype(np.float16).astype(np.float64) if dtype in ("bf16", "f16") else acc.astype(np.float64)
+    return out
+
+
 def brent(s: Scheme):
     """(number of violated Brent equations, flat index of the first or -1)."""
     U = np.ascontiguousarray(s.U, np.int32)

@@ -284,3 +284,60 @@ def test_storage_rounding():
     ints = inp.integers(2, 1, (50,)).astype(np.float64)
     for dt in inp.DTYPES:
         assert np.array_equal(inp.widen(inp.store(ints, dt), dt), ints)
+
+
+# ----------------------------------------------------------------------------- Combine B (Eq. 4)
+def test_combine_b_strassen_textbook_operands():
+    """Right operands of Strassen's seven products as every textbook prints them."""
+    B = inp.integers(9, 3, (6, 8))
+    b11, b12, b21, b22 = B[:3, :4], B[:3, 4:], B[3:, :4], B[3:, 4:]
+    want = [b11 + b22, b11, b12 - b22, b21 - b11, b22, b11 + b12, b21 + b22]
+    got = oracle.combine_b(S.strassen(), B)
+    assert got.shape == (7, 3, 4)
+    for r in range(7):
+        assert np.array_equal(got[r], want[r]), r
+
+
+@pytest.mark.parametrize("name", ALL)
+def test_combine_b_rebuilds_the_product(name):
+    """Eq. 3-6 with Combine B taken from the oracle and the other stages written as einsums here:
+    the result must be A @ B.  A wrong sign, index or transposition in combine_b breaks it."""
+    s = S.by_name(name)
+    M, N, K = 2 * s.m, 3 * s.n, 2 * s.k
+    A = inp.integers(7, 4, (M, K))
+    B = inp.integers(7, 5, (K, N))
+    Ab = A.reshape(s.m, M // s.m, s.k, K // s.k)           # [i, x, l, y]
+    At = np.einsum("ril,ixly->rxy", s.U.astype(np.int64), Ab)
+    Bt = oracle.combine_b(s, B)                             # [r, y, z]
+    H = np.einsum("rxy,ryz->rxz", At, Bt)
+    Cb = np.einsum("rij,rxz->ixjz", s.W.astype(np.int64), H)
+    assert np.array_equal(Cb.reshape(M, N), A @ B)
+
+
+def test_combine_b_single_entry():
+    """B = E_{bj} (one block set to ones): Bt[r] = V[r,b,j] * ones."""
+    s = S.laderman()
+    for b, j in itertools.product(range(s.k), range(s.n)):
+        B = np.zeros((2 * s.k, 3 * s.n), np.int64)
+        B[2 * b:2 * b + 2, 3 * j:3 * j + 3] = 1
+        got = oracle.combine_b(s, B)
+        for r in range(s.R):
+            assert np.array_equal(got[r], int(s.V[r, b, j]) * np.ones((2, 3), np.int64))
+
+
+def test_combine_b_stored_rounds_once_to_nearest_even():
+    s = S.strassen()
+    small = inp.integers(9, 6, (4, 4)).astype(np.float64)
+    for dt in ("bf16", "f16", "f32"):  # representable sums are stored exactly
+        assert np.array_equal(oracle.combine_b_stored(s, small, dt), oracle.combine_b(s, small))
+    # fp16 keeps 11 significant bits: 2048 + 1 -> 2048, 2048 + 3 -> 2052 (tie to even), 2048 + 5 -> 2052
+    B = np.zeros((2, 2))
+    for add, want in ((1.0, 2048.0), (3.0, 2052.0), (5.0, 2052.0)):
+        B[0, 0], B[1, 1] = 2048.0, add
+        assert oracle.combine_b_stored(s, B, "f16")[0, 0, 0] == want      # product 1: b11 + b22
+        assert oracle.combine_b_stored(s, B, "bf16")[0, 0, 0] == want
+        assert oracle.combine_b_stored(s, B, "f32")[0, 0, 0] == 2048.0 + add
+    B[0, 0], B[1, 1] = 2.0 ** 24, 1.0                                      # fp32 keeps 24 bits
+    assert oracle.combine_b_stored(s, B, "f32")[0, 0, 0] == 2.0 ** 24
+    B[0, 0], B[1, 1] = 60000.0, 60000.0                                    # beyond fp16's range
+    assert np.isinf(oracle.combine_b_stored(s, B, "f16")[0, 0, 0])
