@@ -62,6 +62,9 @@ def main():
     ap.add_argument("--with-copy", action="store_true",
                     help="also run a plain device copy of A's bytes (a known-size kernel that calibrates HBM counters)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
+    ap.add_argument("--prepared-b", action="store_true",
+                    help="also time the offline Combine-B path (lcma_prepare_b once, lcma_gemm_prepared per step); "
+                         "reported beside `value`, which stays the fully fused lcma_gemm")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU (the path shards over M with no exchange; "
@@ -143,6 +146,29 @@ def main():
     v_wall_ms, v_ev_ms, v_med_ms = timed(vendor_step, max(10, args.steps // 2), 3)
     value = flops / (wall_ms * 1e-3) / 1e12
     plain_tf = flops / (p_wall_ms * 1e-3) / 1e12
+    prepared = None
+    if args.prepared_b:
+        if scheme is None:
+            sys.exit("bench.py: --prepared-b needs a workload with a scheme")
+        bts = [B.lcma_prepare_b(b, scheme) for _, b, _ in sets]  # offline stage, once per weight matrix
+
+        def prepared_step(i):
+            B.lcma_gemm_prepared(sets[i % 3][0], bts[i % 3], sets[i % 3][2], scheme)
+
+        def prepare_step(i):
+            B.lcma_prepare_b(sets[i % 3][1], scheme, bts[i % 3])
+        b_wall_ms, b_ev_ms, _ = timed(prepared_step, args.steps, args.warmup)
+        o_wall_ms, o_ev_ms, _ = timed(prepare_step, max(10, args.steps // 4), 3)
+        es = 4 if dt == "f32" else 2
+        prep_bytes = K * N * es + bts[0].numel() * bts[0].element_size()
+        prepared = {"gemm_prepared_tflops": flops / (b_wall_ms * 1e-3) / 1e12, "gemm_prepared_kernel_ms": b_ev_ms,
+                    "prepare_b_ms": o_ev_ms, "prepare_b_bytes": prep_bytes,
+                    "prepare_b_roofline": {"bound": "hbm", "achieved": prep_bytes / (o_ev_ms * 1e-3) / 1e9,
+                                           "peak": 8000.0, "unit": "GB/s",
+                                           "frac": prep_bytes / (o_ev_ms * 1e-3) / 1e9 / 8000.0}}
+        prepared_step(0)
+        torch.cuda.synchronize()
+        prepared["_c"] = sets[0][2].clone()
     peak = PEAK_TFLOPS[dt]
 
     # parity on sampled rows (one row range inside every block row of the scheme grid)
@@ -168,6 +194,8 @@ def main():
             return t.cpu().numpy().astype(np.float64)
         err = oracle.rel_frobenius(host(sets[0][2]), ref)
         err_plain = oracle.rel_frobenius(host(sets[1][2]), ref)
+        if prepared:
+            prepared["rel_frobenius_error"] = oracle.rel_frobenius(host(prepared["_c"]), ref)
         # timed sample: as many leading rows as fit the CPU budget, judged from the small run
         rate = 2.0 * len(rows) * N * K / max(t_small, 1e-6)
         nrows = int(min(M, max(len(rows), args.cpu_seconds * rate / (2.0 * N * K))))
@@ -178,6 +206,8 @@ def main():
                "kind": "oracle", "sample": f"fp64 triple loop on the first {nrows} of {M} rows of C "
                f"({t_cpu:.1f} s); whole problem extrapolated {t_cpu * M / nrows:.0f} s"}
 
+    if prepared:
+        prepared.pop("_c")
     mfma_flops = flops * info["R"] / (info["m"] * info["k"] * info["n"])
     achieved = mfma_flops / (ev_ms * 1e-3) / 1e12
     out = {
@@ -197,6 +227,8 @@ def main():
                      "frac": achieved / peak, "traffic": read_traffic(args.workload)},
         "cpu_baseline": cpu,
     }
+    if prepared:
+        out["offline_combine_b"] = prepared
     print(json.dumps(out))
 
 

@@ -107,6 +107,36 @@ lcma_status lcma_variant_info(int index, int *scheme_id, int *dtype, int *TM, in
 lcma_status lcma_gemm_variant(const char *variant, int64_t M, int64_t N, int64_t K,
                               const void *A, int64_t lda, const void *B, int64_t ldb,
                               void *C, int64_t ldc, void *stream);
+/* 1 when variant `index` takes the output of lcma_prepare_b in place of B (its B argument in
+ * lcma_gemm_variant is then that buffer and ldb is ignored), 0 when it takes B, -1 when out of range. */
+int lcma_variant_prepared(int index);
+
+/* Offline Combine B (Eq. 4; Algorithm 2, stage 2).  The paper's end-to-end evaluation runs this stage
+ * once for static weights B; lcma_gemm_prepared then multiplies any number of A against the result.
+ *
+ * lcma_prepare_b writes Bt_r = sum_{l,j} V[r,l,j] B_{l,j}, r = 1..R, into Bt (device memory owned by
+ * the caller, lcma_prepared_b_bytes() bytes, 16-byte aligned): R planes, plane r holding Bt_r
+ * transposed, N/n rows of K/k elements, k-contiguous, in the type the products are multiplied in
+ * (fp16 for BF16 and F16 storage, fp32 for F32).  The terms of a sum are added in fp32 in ascending
+ * (l, j) order and the sum is rounded once, to nearest-even.  B: device, K x N row-major, ldb in
+ * elements (multiple of 16 bytes).  N must be a multiple of 64 n, K of 32 k (16 k for F32); both
+ * buffers stay below 2 GiB.  Asynchronous on `stream`.  Errors: ARG, BRENT, SHAPE, DTYPE, NOKERNEL
+ * (no prepared-B kernels were generated for this scheme and dtype), HIP.
+ *
+ * lcma_prepared_b_bytes returns R * (N/n) * (K/k) * element size, or -1 for a bad argument.
+ *
+ * lcma_gemm_prepared computes what lcma_gemm computes, C = A B, with Bt in place of B: Combine A
+ * (Eq. 3) on MFMA fragments, H_r (Eq. 5) and the W-combination (Eq. 6) in fp32, nothing written to
+ * device memory but C.  Same contract for A, C, sizes, alignment and errors as lcma_gemm; `scheme`
+ * must be the one Bt was prepared with (not checked) and is required.
+ */
+int64_t lcma_prepared_b_bytes(const lcma_scheme *scheme, int64_t N, int64_t K, lcma_dtype dtype);
+lcma_status lcma_prepare_b(int64_t N, int64_t K, const void *B, int64_t ldb, lcma_dtype dtype,
+                           const lcma_scheme *scheme, void *Bt, void *stream);
+lcma_status lcma_gemm_prepared(int64_t M, int64_t N, int64_t K, const void *A, int64_t lda,
+                               const void *Bt, void *C, int64_t ldc, lcma_dtype dtype,
+                               const lcma_scheme *scheme, void *stream);
+
 
 /* ------------------------------------------------------------------ Decision Module (Sec. 3.3)
  * lcma_select: predicted-fastest algorithm for the shape on MI355X among

@@ -27,6 +27,7 @@ EXPORTS = [
     "lcma_gemm", "lcma_variant_count", "lcma_variant_name", "lcma_variant_info", "lcma_gemm_variant",
     "lcma_select", "lcma_hw_mi355x", "lcma_model_stages", "lcma_model_intensity", "lcma_predict_seconds",
     "lcma_sched_waves", "lcma_sched_range", "lcma_status_str", "lcma_last_error",
+    "lcma_variant_prepared", "lcma_prepared_b_bytes", "lcma_prepare_b", "lcma_gemm_prepared",
 ]
 
 
@@ -71,6 +72,11 @@ def lib() -> ctypes.CDLL:
         L.lcma_variant_name.restype = cp
         L.lcma_variant_info.argtypes = [i32] + [pi32] * 8
         L.lcma_gemm_variant.argtypes = [cp, i64, i64, i64, vp, i64, vp, i64, vp, i64, vp]
+        L.lcma_variant_prepared.argtypes = [i32]
+        L.lcma_prepared_b_bytes.argtypes = [vp, i64, i64, i32]
+        L.lcma_prepared_b_bytes.restype = i64
+        L.lcma_prepare_b.argtypes = [i64, i64, vp, i64, i32, vp, vp, vp]
+        L.lcma_gemm_prepared.argtypes = [i64, i64, i64, vp, i64, vp, vp, i64, i32, vp, vp]
         L.lcma_select.argtypes = [i64, i64, i64, i32]
         L.lcma_hw_mi355x.argtypes = [i32, ctypes.POINTER(lcma_hw)]
         L.lcma_model_stages.argtypes = [vp, i64, i64, i64, ctypes.POINTER(lcma_hw), ctypes.POINTER(lcma_stage_costs)]
@@ -177,8 +183,59 @@ def lcma_variants() -> list[dict]:
         d = dict(zip(["scheme_id", "dtype", "TM", "TN", "TK", "mult_M", "mult_N", "mult_K"],
                      [int(x.value) for x in v]))
         d["name"] = lib().lcma_variant_name(i).decode()
+        d["prepared"] = int(lib().lcma_variant_prepared(i))
         out.append(d)
     return out
+
+
+def lcma_prepared_b_bytes(scheme: Scheme, N: int, K: int, dtype: int) -> int:
+    return int(lib().lcma_prepared_b_bytes(scheme.handle, N, K, dtype))
+
+
+def lcma_prepare_b(B, scheme: Scheme, Bt=None):
+    """Offline Combine B of the K x N device tensor B; returns the prepared operand, a device tensor of
+    shape (R, N/n, K/k) in the compute type (allocated here unless Bt is given)."""
+    import torch
+    assert B.is_cuda and B.dim() == 2 and B.stride(1) == 1
+    K, N = B.shape
+    dt = _dtype_of(B)
+    nbytes = lcma_prepared_b_bytes(scheme, N, K, dt)
+    if nbytes < 0:
+        raise LcmaError(f"lcma_prepared_b_bytes: bad arguments (N={N}, K={K})")
+    info = lcma_scheme_info(scheme)
+    ct = torch.float32 if B.dtype == torch.float32 else torch.float16
+    if Bt is None:
+        Bt = torch.empty((info["R"], N // info["n"], K // info["k"]), device=B.device, dtype=ct)
+    assert Bt.is_cuda and Bt.is_contiguous() and Bt.dtype == ct and Bt.numel() * Bt.element_size() == nbytes
+    stream = torch.cuda.current_stream(B.device).cuda_stream
+    _check(lib().lcma_prepare_b(N, K, B.data_ptr(), B.stride(0), dt, scheme.handle, Bt.data_ptr(), stream))
+    return Bt
+
+
+def _marshal_prepared(A, Bt, C):
+    import torch
+    assert A.is_cuda and Bt.is_cuda and C.is_cuda, "matrices must live on the GPU"
+    assert A.dim() == C.dim() == 2 and A.stride(1) == C.stride(1) == 1 and Bt.is_contiguous()
+    assert A.dtype == C.dtype
+    M, K = A.shape
+    M2, N = C.shape
+    assert M == M2
+    stream = torch.cuda.current_stream(A.device).cuda_stream
+    return M, N, K, A.data_ptr(), A.stride(0), Bt.data_ptr(), C.data_ptr(), C.stride(0), stream
+
+
+def lcma_gemm_prepared(A, Bt, C, scheme: Scheme):
+    """C = A x B with the prepared operand Bt = lcma_prepare_b(B, scheme), on the current stream."""
+    M, N, K, pa, lda, pbt, pc, ldc, stream = _marshal_prepared(A, Bt, C)
+    _check(lib().lcma_gemm_prepared(M, N, K, pa, lda, pbt, pc, ldc, _dtype_of(A), scheme.handle, stream))
+    return C
+
+
+def lcma_gemm_variant_prepared(variant: str, A, Bt, C):
+    """lcma_gemm_variant for a variant that takes the prepared operand."""
+    M, N, K, pa, lda, pbt, pc, ldc, stream = _marshal_prepared(A, Bt, C)
+    _check(lib().lcma_gemm_variant(variant.encode(), M, N, K, pa, lda, pbt, N, pc, ldc, stream))
+    return C
 
 
 def lcma_select(M: int, N: int, K: int, dtype: int) -> int:

@@ -42,7 +42,7 @@ def build(force: bool = False, jobs: int | None = None, verbose: bool = True) ->
     from .gen.generate import generate
 
     hips = generate(GEN)
-    headers = [os.path.join(CSRC, h) for h in ("lcma_device.hpp", "lcma_params.h", "host_common.h")]
+    headers = [os.path.join(CSRC, h) for h in ("lcma_device.hpp", "lcma_prepare_b.hpp", "lcma_params.h", "host_common.h")]
     headers.append(os.path.join(PKG, "..", "include", "lcma.h"))
     headers.append(os.path.join(GEN, "builtin_schemes.inc"))
     units = [(h, h[:-4] + ".o") for h in hips]

@@ -23,12 +23,13 @@ bool variant_fits(const Variant &v, int64_t M, int64_t N, int64_t K) {
 }
 static bool fits(const Variant &v, int64_t M, int64_t N, int64_t K) { return variant_fits(v, M, N, K); }
 
-const Variant *pick_variant(int scheme_id, int dtype, int64_t M, int64_t N, int64_t K) {
+const Variant *pick_variant(int scheme_id, int dtype, int64_t M, int64_t N, int64_t K, int prepared) {
     const Variant *best = nullptr;
     double best_t = 0.0;
     for (int i = 0; i < kVariantCount; ++i) {
         const Variant &v = kVariants[i];
-        if (v.scheme_id != scheme_id || v.dtype != dtype || v.rank >= 90 || !fits(v, M, N, K)) continue;
+        if (v.scheme_id != scheme_id || v.dtype != dtype || v.prepared != prepared || v.rank >= 90 || !fits(v, M, N, K))
+            continue;
         const double t = predict_variant(v, M, N, K);
         if (!best || t < best_t) {
             best = &v;
@@ -44,6 +45,8 @@ static const Variant *find_variant(const char *name) {
     return nullptr;
 }
 
+// B and ldb describe the K x N matrix, or, for a prepared-B variant, the planes written by
+// lcma_prepare_b (ldb is then ignored).
 static lcma_status run(const Variant &v, int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const void *B,
                        int64_t ldb, void *C, int64_t ldc, void *stream) {
     const int es = dtype_size(v.dtype);
@@ -51,6 +54,7 @@ static lcma_status run(const Variant &v, int64_t M, int64_t N, int64_t K, const 
     if (M == 0 || N == 0) return LCMA_OK; // nothing to write
     if (K == 0) return fail(LCMA_ERR_SHAPE, "lcma_gemm: K = 0 is not supported");
     if (!A || !B || !C) return fail(LCMA_ERR_ARG, "lcma_gemm: null matrix pointer");
+    if (v.prepared) ldb = N;
     if (lda < K || ldb < N || ldc < N) return fail(LCMA_ERR_ARG, "lcma_gemm: leading dimension smaller than the row");
     if (((uintptr_t)A | (uintptr_t)B | (uintptr_t)C) & 15)
         return fail(LCMA_ERR_ARG, "lcma_gemm: matrix pointers must be 16-byte aligned");
@@ -59,7 +63,8 @@ static lcma_status run(const Variant &v, int64_t M, int64_t N, int64_t K, const 
     if (!fits(v, M, N, K))
         return fail(LCMA_ERR_SHAPE, "lcma_gemm: (%lld,%lld,%lld) is not a multiple of (%d,%d,%d) needed by %s",
                     (long long)M, (long long)N, (long long)K, v.m * v.TM, v.n * v.TN, v.k * v.TK, v.name);
-    const int64_t a_bytes = ((M - 1) * lda + K) * es, b_bytes = ((K - 1) * ldb + N) * es,
+    const int64_t a_bytes = ((M - 1) * lda + K) * es,
+                  b_bytes = v.prepared ? (int64_t)v.products * (N / v.n) * (K / v.k) * es : ((K - 1) * ldb + N) * es,
                   c_bytes = ((M - 1) * ldc + N) * es;
     const int64_t lim = (int64_t)1 << 31;
     if (a_bytes >= lim || b_bytes >= lim || c_bytes >= lim)
@@ -79,6 +84,11 @@ static lcma_status run(const Variant &v, int64_t M, int64_t N, int64_t K, const 
     p.a_bcol = (uint32_t)(bk * es);
     p.b_brow = (uint32_t)(bk * ldb * es);
     p.b_bcol = (uint32_t)(bn * es);
+    if (v.prepared) { // plane r: bn rows of bk elements
+        p.ldb_b = (uint32_t)(bk * es);
+        p.b_brow = (uint32_t)(bn * bk * es);
+        p.b_bcol = 0;
+    }
     p.c_brow = (uint32_t)(bm * ldc * es);
     p.c_bcol = (uint32_t)(bn * es);
     p.nx = (int32_t)(bm / v.TM);
@@ -138,6 +148,97 @@ extern "C" lcma_status lcma_gemm_variant(const char *variant, int64_t M, int64_t
     return run(*v, M, N, K, A, lda, B, ldb, C, ldc, stream);
 }
 
+static const PrepKernel *find_prep(int scheme_id, int dtype) {
+    for (int i = 0; i < kPrepKernelCount; ++i)
+        if (kPrepKernels[i].scheme_id == scheme_id && kPrepKernels[i].dtype == dtype) return &kPrepKernels[i];
+    return nullptr;
+}
+
+// The prepared-B entry points need a verified scheme that kernels were generated for.
+static lcma_status prepared_scheme(const lcma_scheme *scheme, const char *who, int *id) {
+    if (!scheme) return fail(LCMA_ERR_ARG, "%s: a scheme is required", who);
+    const lcma_status st = lcma_scheme_verify(scheme, nullptr);
+    if (st != LCMA_OK) return st;
+    if (!scheme->builtin)
+        return fail(LCMA_ERR_NOKERNEL, "%s: no kernel was generated for scheme <%d,%d,%d;%d> (hash %016llx)", who,
+                    scheme->m, scheme->k, scheme->n, scheme->R, (unsigned long long)scheme->hash);
+    *id = scheme->builtin;
+    return LCMA_OK;
+}
+
+extern "C" int64_t lcma_prepared_b_bytes(const lcma_scheme *scheme, int64_t N, int64_t K, lcma_dtype dtype) {
+    const int es = dtype_size(dtype);
+    if (!scheme || !es || N <= 0 || K <= 0 || N % scheme->n || K % scheme->k) return -1;
+    return (int64_t)scheme->R * (N / scheme->n) * (K / scheme->k) * es;
+}
+
+extern "C" lcma_status lcma_prepare_b(int64_t N, int64_t K, const void *B, int64_t ldb, lcma_dtype dtype,
+                                      const lcma_scheme *scheme, void *Bt, void *stream) {
+    const int es = dtype_size(dtype);
+    if (!es) return fail(LCMA_ERR_DTYPE, "lcma_prepare_b: unknown dtype %d", (int)dtype);
+    int id = 0;
+    if (const lcma_status st = prepared_scheme(scheme, "lcma_prepare_b", &id)) return st;
+    const PrepKernel *pk = find_prep(id, dtype);
+    if (!pk) return fail(LCMA_ERR_NOKERNEL, "lcma_prepare_b: no Combine-B kernel for scheme id %d with dtype %d", id, (int)dtype);
+    if (N < 0 || K < 0) return fail(LCMA_ERR_ARG, "lcma_prepare_b: negative size");
+    if (N == 0 || K == 0) return LCMA_OK;
+    if (!B || !Bt) return fail(LCMA_ERR_ARG, "lcma_prepare_b: null pointer");
+    if (ldb < N) return fail(LCMA_ERR_ARG, "lcma_prepare_b: leading dimension smaller than the row");
+    if ((((uintptr_t)B | (uintptr_t)Bt) & 15) || ((ldb * es) & 15))
+        return fail(LCMA_ERR_ARG, "lcma_prepare_b: pointers and the leading dimension must be multiples of 16 bytes");
+    const int kt = 64 / es; // k rows one work-group transposes
+    if (N % ((int64_t)scheme->n * 64) || K % ((int64_t)scheme->k * kt))
+        return fail(LCMA_ERR_SHAPE, "lcma_prepare_b: (N,K) = (%lld,%lld) is not a multiple of (%d,%d)", (long long)N,
+                    (long long)K, scheme->n * 64, scheme->k * kt);
+    const int64_t bn = N / scheme->n, bk = K / scheme->k;
+    const int64_t b_bytes = ((K - 1) * ldb + N) * es, bt_bytes = (int64_t)scheme->R * bn * bk * es;
+    const int64_t lim = (int64_t)1 << 31;
+    if (b_bytes >= lim || bt_bytes >= lim) return fail(LCMA_ERR_SHAPE, "lcma_prepare_b: a buffer spans 2 GiB or more");
+    if (bk / kt > 65535) return fail(LCMA_ERR_SHAPE, "lcma_prepare_b: K is too large");
+    PrepParams p;
+    p.B = B;
+    p.Bt = Bt;
+    p.b_bytes = (uint32_t)b_bytes;
+    p.bt_bytes = (uint32_t)bt_bytes;
+    p.ldb_b = (uint32_t)(ldb * es);
+    p.b_brow = (uint32_t)(bk * ldb * es);
+    p.b_bcol = (uint32_t)(bn * es);
+    p.bt_ld_b = (uint32_t)(bk * es);
+    p.bt_plane_b = (uint32_t)(bn * bk * es);
+    p.bk = (int32_t)bk;
+    p.bn = (int32_t)bn;
+    const int err = pk->launch(&p, (int)(bn / 64), (int)(bk / kt), stream);
+    if (err) return fail(LCMA_ERR_HIP, "lcma_prepare_b: launch failed with HIP error %d", err);
+    return LCMA_OK;
+}
+
+extern "C" lcma_status lcma_gemm_prepared(int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const void *Bt,
+                                          void *C, int64_t ldc, lcma_dtype dtype, const lcma_scheme *scheme,
+                                          void *stream) {
+    if (!dtype_size(dtype)) return fail(LCMA_ERR_DTYPE, "lcma_gemm_prepared: unknown dtype %d", (int)dtype);
+    int id = 0;
+    if (const lcma_status st = prepared_scheme(scheme, "lcma_gemm_prepared", &id)) return st;
+    if (M < 0 || N < 0 || K < 0) return fail(LCMA_ERR_ARG, "lcma_gemm_prepared: negative size");
+    if (M == 0 || N == 0) return LCMA_OK;
+    const Variant *v = nullptr;
+    if (const char *force = std::getenv("LCMA_VARIANT")) { // ablation override
+        v = find_variant(force);
+        if (v && (v->scheme_id != id || v->dtype != (int)dtype || !v->prepared)) v = nullptr;
+    }
+    if (!v) v = pick_variant(id, dtype, M, N, K, 1);
+    if (!v) {
+        bool any = false;
+        for (int i = 0; i < kVariantCount; ++i)
+            any |= kVariants[i].scheme_id == id && kVariants[i].dtype == (int)dtype && kVariants[i].prepared;
+        if (!any)
+            return fail(LCMA_ERR_NOKERNEL, "lcma_gemm_prepared: no prepared-B kernel for scheme id %d with dtype %d", id,
+                        (int)dtype);
+        return fail(LCMA_ERR_SHAPE, "lcma_gemm_prepared: no tile of scheme id %d divides (%lld,%lld,%lld)", id,
+                    (long long)M, (long long)N, (long long)K);
+    }
+    return run(*v, M, N, K, A, lda, Bt, N, C, ldc, stream);
+}
+
 extern "C" int lcma_variant_count(void) { return kVariantCount; }
 
 extern "C" const char *lcma_variant_name(int index) {
@@ -157,6 +258,10 @@ extern "C" lcma_status lcma_variant_info(int index, int *scheme_id, int *dtype, 
     if (mult_N) *mult_N = v.n * v.TN;
     if (mult_K) *mult_K = v.k * v.TK;
     return LCMA_OK;
+}
+
+extern "C" int lcma_variant_prepared(int index) {
+    return (index >= 0 && index < kVariantCount) ? kVariants[index].prepared : -1;
 }
 
 extern "C" const char *lcma_status_str(lcma_status st) {

@@ -41,16 +41,25 @@ struct Variant {
     double eff;         // measured fraction of the dtype's MFMA peak its MFMA work sustains at large shapes
     int occ;            // work-groups per compute unit it is compiled for
     int products;       // block products it multiplies (R plus residual products)
+    int prepared;       // 1: takes the output of the offline Combine-B kernel instead of B
     int (*launch)(const Params *p, int grid, void *stream); // returns a hipError_t
 };
 extern const Variant kVariants[];
 extern const int kVariantCount;
 
+// One generated offline Combine-B kernel (scheme x dtype).
+struct PrepKernel {
+    int scheme_id, dtype;
+    int (*launch)(const PrepParams *p, int grid_x, int grid_y, void *stream); // returns a hipError_t
+};
+extern const PrepKernel kPrepKernels[];
+extern const int kPrepKernelCount;
+
 int dtype_size(int dtype); // bytes, or 0
 
 // Variant of (scheme_id, dtype) with the smallest predicted time among those whose tile divides the
 // shape; nullptr if none.
-const Variant *pick_variant(int scheme_id, int dtype, int64_t M, int64_t N, int64_t K);
+const Variant *pick_variant(int scheme_id, int dtype, int64_t M, int64_t N, int64_t K, int prepared = 0);
 // Predicted seconds of one variant on MI355X (MFMA time at its measured efficiency, stretched by
 // wave quantisation on 256 compute units, bounded below by the compulsory HBM traffic, plus launch).
 double predict_variant(const Variant &v, int64_t M, int64_t N, int64_t K);

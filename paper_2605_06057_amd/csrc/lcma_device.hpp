@@ -113,16 +113,21 @@ template <> struct Round<BF16> {
 //     1 = LDS holds the raw (converted) blocks and every wave forms the combinations on the
 //         MFMA fragments it has read ("fragment combine");
 // STAGES: LDS stages (2, or 3 with PIPE 2 and FC: the first fragments of the next step are then read
-//         before the barrier that ends the step).
+//         before the barrier that ends the step);
+// PB: 1 = the B operand is the output of the offline Combine-B stage (Eq. 4 done once for static
+//         weights): R planes of (N/n) x (K/k) elements of the compute type, k-contiguous.  Tiles of the
+//         right operands Bt_r go to LDS as they are (no conversion, transposition or addition) and
+//         only the A side is combined on fragments.
 //
 // LDS layout of a stage: NSA tiles [TM rows][TK] then NSB tiles [TN rows][TK], both k-contiguous,
 // 16-byte chunks XOR-swizzled inside a row.  B arrives n-contiguous from memory and is transposed
 // in registers while it is staged, so that both MFMA operands are read with 16-byte LDS loads
 // (measured on MI355X: ds_read_b128 ~260 B/clk/CU, the transposing ds_read_b64_tr_b16 ~70).
 template <class IN_, class CT_, int TM_, int TN_, int TK_, int WGM_, int WGN_, int NSA_, int NSB_, int PIPE_ = 0,
-          int FC_ = 0, int STAGES_ = 2>
+          int FC_ = 0, int STAGES_ = 2, int PB_ = 0>
 struct Tile {
-    static constexpr int PIPE = PIPE_, FC = FC_;
+    static constexpr int PIPE = PIPE_, FC = FC_, PB = PB_;
+    static_assert(!PB_ || (FC_ && PIPE_ == 2 && STAGES_ == 2), "prepared B needs the interleaved fragment-combine loop");
     using IN = IN_;
     using CT = CT_;
     static_assert(IN::ES == CT::ES, "conversion must keep the element size");
@@ -269,7 +274,7 @@ template <class T> struct Ctx {
             z = (p.nz / pw) * pw + rem % w2;
         }
         a_group = (uint32_t)x * T::TM * p.lda_b;
-        b_group = (uint32_t)z * T::TN * T::ES;
+        b_group = T::PB ? (uint32_t)z * T::TN * p.ldb_b : (uint32_t)z * T::TN * T::ES;
         c_group = (uint32_t)x * T::TM * p.ldc_b + (uint32_t)z * T::TN * T::ES;
 
 #pragma unroll
@@ -425,6 +430,70 @@ template <class T> struct Ctx {
         }
     }
 
+    // Prepared-B form: LDS stage `st` holds the raw A blocks and the tile of Bt_s in B slot s.  The A
+    // fragments are read once per k sub-step and combined per product (Eq. 3 on registers); the
+    // fragments of Bt_s are used by product s alone, so they stream through two small buffers, each
+    // read while the previous product group multiplies.
+    template <class CH, class HOOK>
+    LCMA_DEV void mma_stage_pb(int st, typename T::Acc (&acc)[CH::NP], HOOK hook) const {
+        const uint32_t sb = st * T::STAGE;
+        constexpr int G = (Mma<CT>::SUB > 1 && T::NMI * T::NNI == 1) ? LCMA_FP32_GROUP : 1;
+        constexpr int NG = (CH::NP + G - 1) / G;
+        Frag fa[2][T::NMI][CH::NA], fb[2][G][T::NNI];
+        auto fetch_a = [&](int kk, int buf) {
+#pragma unroll
+            for (int mi = 0; mi < T::NMI; ++mi)
+#pragma unroll
+                for (int t = 0; t < CH::NA; ++t)
+                    fa[buf][mi][t] = lds_frag(sb + t * T::A_SLOT + a_frag[kk] + mi * 32 * T::ROW);
+        };
+        auto fetch_b = [&](int kk, int gi, int buf) {
+#pragma unroll
+            for (int g = 0; g < G; ++g) {
+                if (gi * G + g >= CH::NP) continue;
+#pragma unroll
+                for (int ni = 0; ni < T::NNI; ++ni)
+                    fb[buf][g][ni] = lds_frag(sb + (gi * G + g) * T::B_SLOT + b_frag[kk] + ni * 32 * T::ROW);
+            }
+        };
+        fetch_a(0, 0);
+        fetch_b(0, 0, 0);
+#pragma unroll
+        for (int kk = 0; kk < T::NKK; ++kk) {
+            const int cur = kk & 1;
+            if (kk + 1 < T::NKK) fetch_a(kk + 1, cur ^ 1);
+#pragma unroll
+            for (int gi = 0; gi < NG; ++gi) {
+                const int flat = kk * NG + gi, bcur = flat & 1;
+                if (gi + 1 < NG) fetch_b(kk, gi + 1, bcur ^ 1);
+                else if (kk + 1 < T::NKK) fetch_b(kk + 1, 0, bcur ^ 1);
+                Frag at[G][T::NMI];
+#pragma unroll
+                for (int g = 0; g < G; ++g) {
+                    if (gi * G + g >= CH::NP) continue;
+#pragma unroll
+                    for (int mi = 0; mi < T::NMI; ++mi) {
+                        Frag o[CH::NP];
+                        CH::comb_a(fa[cur][mi], o);
+                        at[g][mi] = o[gi * G + g];
+                    }
+                }
+#pragma unroll
+                for (int t = 0; t < Mma<CT>::SUB; ++t)
+#pragma unroll
+                    for (int g = 0; g < G; ++g) {
+                        if (gi * G + g >= CH::NP) continue;
+#pragma unroll
+                        for (int mi = 0; mi < T::NMI; ++mi)
+#pragma unroll
+                            for (int ni = 0; ni < T::NNI; ++ni)
+                                Mma<CT>::run_sub(at[g][mi], fb[bcur][g][ni], acc[gi * G + g].v[mi][ni], t);
+                    }
+                hook(flat, T::NKK * NG);
+            }
+        }
+    }
+
     // Round and store one fp32 tile into block C_{i,j}.  f(mi, ni) returns the f32x16 of MFMA
     // tile (mi, ni).
     template <class F> LCMA_DEV void store_c(int i, int j, F f) const {
@@ -540,11 +609,12 @@ template <class T, class CH> LCMA_DEV void combine_store(const Ctx<T> &cx, const
 // same for every thread: all chunks (A) and units (B) of all blocks form one pool that is dealt to
 // the threads, which avoids idle or duplicated staging work when a single block is small.
 template <class T, class CH> struct FlatStage {
-    static constexpr int NCA = CH::NA * T::NCHK_A, NUB = CH::NB * T::NU_B;
+    static constexpr int NCHK_B = T::TN * T::CPR; // 16-byte chunks of one prepared-B tile
+    static constexpr int NCA = CH::NA * T::NCHK_A, NUB = T::PB ? CH::NP * NCHK_B : CH::NB * T::NU_B;
     static constexpr int QA = (NCA + T::NT - 1) / T::NT, QB = (NUB + T::NT - 1) / T::NT;
     uint32_t a_voff[QA], a_lds[QA], b_voff[QB], b_lds[QB], b_lds1[QB];
     struct Raw {
-        u32x4 a[QA], b[QB][T::BH];
+        u32x4 a[QA], b[QB][T::PB ? 1 : T::BH];
     };
 
     LCMA_DEV FlatStage(const Ctx<T> &cx) {
@@ -561,26 +631,42 @@ template <class T, class CH> struct FlatStage {
 #pragma unroll
         for (int q = 0; q < QB; ++q) {
             const int id = (q * T::NT + tid) % NUB;
-            const int t = id / T::NU_B, u = id % T::NU_B;
-            const int col = u % T::BCOLS, g = u / T::BCOLS;
-            const int row = (T::ES == 2) ? 2 * col : col;
-            b_voff[q] = (uint32_t)CH::b_l(t) * cx.p.b_brow + (uint32_t)CH::b_j(t) * cx.p.b_bcol +
-                        (uint32_t)(g * T::CH) * cx.p.ldb_b + col * 4;
-            b_lds[q] = T::A_STAGE + t * T::B_SLOT + row * T::ROW + T::swz(row, g) * 16;
-            b_lds1[q] = T::A_STAGE + t * T::B_SLOT + (row + 1) * T::ROW + T::swz(row + 1, g) * 16;
+            if constexpr (T::PB) {
+                // plane s of the prepared operand: rows n of this group's tile, k-contiguous
+                const int sl = id / NCHK_B, id2 = id % NCHK_B;
+                const int row = id2 / T::CPR, c = id2 % T::CPR;
+                b_voff[q] = (uint32_t)sl * cx.p.b_brow + (uint32_t)row * cx.p.ldb_b + c * 16;
+                b_lds[q] = T::A_STAGE + sl * T::B_SLOT + row * T::ROW + T::swz(row, c) * 16;
+                b_lds1[q] = 0;
+            } else {
+                const int t = id / T::NU_B, u = id % T::NU_B;
+                const int col = u % T::BCOLS, g = u / T::BCOLS;
+                const int row = (T::ES == 2) ? 2 * col : col;
+                b_voff[q] = (uint32_t)CH::b_l(t) * cx.p.b_brow + (uint32_t)CH::b_j(t) * cx.p.b_bcol +
+                            (uint32_t)(g * T::CH) * cx.p.ldb_b + col * 4;
+                b_lds[q] = T::A_STAGE + t * T::B_SLOT + row * T::ROW + T::swz(row, g) * 16;
+                b_lds1[q] = T::A_STAGE + t * T::B_SLOT + (row + 1) * T::ROW + T::swz(row + 1, g) * 16;
+            }
         }
     }
-    LCMA_DEV void issue(const Ctx<T> &cx, Raw &r, int y) const {
-        const uint32_t sa = cx.a_group + (uint32_t)y * (T::TK * T::ES);
-        const uint32_t sbo = cx.b_group + (uint32_t)y * T::TK * cx.p.ldb_b;
-#pragma unroll
-        for (int q = 0; q < QA; ++q) r.a[q] = __builtin_amdgcn_raw_buffer_load_b128(cx.ra, (int)a_voff[q], (int)sa, 0);
-#pragma unroll
-        for (int q = 0; q < QB; ++q)
+    LCMA_DEV void load_b(const Ctx<T> &cx, Raw &r, int q, int y) const {
+        if constexpr (T::PB) {
+            const uint32_t sbo = cx.b_group + (uint32_t)y * (T::TK * T::ES);
+            r.b[q][0] = __builtin_amdgcn_raw_buffer_load_b128(cx.rb, (int)b_voff[q], (int)sbo, 0);
+        } else {
+            const uint32_t sbo = cx.b_group + (uint32_t)y * T::TK * cx.p.ldb_b;
 #pragma unroll
             for (int e = 0; e < T::BW; ++e)
                 r.b[q][e / 4][e % 4] = __builtin_amdgcn_raw_buffer_load_b32(
                     cx.rb, (int)b_voff[q], (int)(sbo + (uint32_t)e * cx.p.ldb_b), 0);
+        }
+    }
+    LCMA_DEV void issue(const Ctx<T> &cx, Raw &r, int y) const {
+        const uint32_t sa = cx.a_group + (uint32_t)y * (T::TK * T::ES);
+#pragma unroll
+        for (int q = 0; q < QA; ++q) r.a[q] = __builtin_amdgcn_raw_buffer_load_b128(cx.ra, (int)a_voff[q], (int)sa, 0);
+#pragma unroll
+        for (int q = 0; q < QB; ++q) load_b(cx, r, q, y);
     }
     // The staging work of one thread cut into NPIECE pieces (one 16-byte A chunk or one B unit each),
     // so that it can be spread over the MFMA phase.
@@ -590,12 +676,7 @@ template <class T, class CH> struct FlatStage {
             const uint32_t sa = cx.a_group + (uint32_t)y * (T::TK * T::ES);
             r.a[pc] = __builtin_amdgcn_raw_buffer_load_b128(cx.ra, (int)a_voff[pc], (int)sa, 0);
         } else {
-            const int q = pc - QA;
-            const uint32_t sbo = cx.b_group + (uint32_t)y * T::TK * cx.p.ldb_b;
-#pragma unroll
-            for (int e = 0; e < T::BW; ++e)
-                r.b[q][e / 4][e % 4] = __builtin_amdgcn_raw_buffer_load_b32(
-                    cx.rb, (int)b_voff[q], (int)(sbo + (uint32_t)e * cx.p.ldb_b), 0);
+            load_b(cx, r, pc - QA, y);
         }
     }
     LCMA_DEV void store_piece(const Ctx<T> &cx, const Raw &r, int pc, int st) const {
@@ -616,7 +697,9 @@ template <class T, class CH> struct FlatStage {
     }
     LCMA_DEV void store_b(const Ctx<T> &cx, const Raw &r, int q, uint32_t sb) const {
         using Cv = Convert<typename T::IN, typename T::CT>;
-        {
+        if constexpr (T::PB) {
+            cx.lds_store(sb + b_lds[q], r.b[q][0]); // already in the compute type and k-contiguous
+        } else {
             if constexpr (T::ES == 2) {
                 const u32x4 lo = __builtin_bit_cast(u32x4, Cv::run(r.b[q][0]));
                 const u32x4 hi = __builtin_bit_cast(u32x4, Cv::run(r.b[q][1]));
@@ -669,7 +752,7 @@ template <bool LIT, class F> LCMA_DEV void stage_loop(int ny, F step) {
 template <class T, class CH> LCMA_DEV void run_chunk(const Ctx<T> &cx, typename T::Acc (&acc)[CH::NP]) {
     const int ny = cx.p.ny, last = ny - 1;
     if constexpr (T::FC) {
-        static_assert(CH::NA <= T::NSA && CH::NB <= T::NSB, "raw blocks exceed the LDS slots");
+        static_assert(CH::NA <= T::NSA && (T::PB ? CH::NP : CH::NB) <= T::NSB, "blocks exceed the LDS slots");
         const FlatStage<T, CH> fs(cx);
         if constexpr (T::PIPE == 0) {
             typename FlatStage<T, CH>::Raw r;
@@ -734,7 +817,7 @@ template <class T, class CH> LCMA_DEV void run_chunk(const Ctx<T> &cx, typename 
             __syncthreads();
             auto step = [&](int y, int st) {
                 const int nxt = y + 2 < ny ? y + 2 : last; // past the end: reload the last tile, unused
-                cx.template mma_stage_fc<CH>(st, acc, [&](int slot, int slots) {
+                auto hook = [&](int slot, int slots) {
 #pragma unroll
                     for (int pc = 0; pc < FS::NPIECE; ++pc)
                         if (pc * slots / FS::NPIECE == slot) {
@@ -743,7 +826,9 @@ template <class T, class CH> LCMA_DEV void run_chunk(const Ctx<T> &cx, typename 
                             fs.issue_piece(cx, r, pc, nxt);
                             __builtin_amdgcn_sched_barrier(0);
                         }
-                });
+                };
+                if constexpr (T::PB) cx.template mma_stage_pb<CH>(st, acc, hook);
+                else cx.template mma_stage_fc<CH>(st, acc, hook);
                 __syncthreads();
             };
             stage_loop<LITERAL_STAGE<T>>(ny, step);

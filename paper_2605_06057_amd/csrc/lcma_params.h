@@ -6,15 +6,28 @@ namespace lcma {
 
 struct Params {
     const void *A;
-    const void *B;
+    const void *B;                      // prepared-B kernels: the R planes written by the Combine-B kernel
     void *C;
     uint32_t a_bytes, b_bytes, c_bytes; // byte extents of the three matrices (< 2 GiB each)
     uint32_t lda_b, ldb_b, ldc_b;       // leading dimensions in BYTES
     uint32_t a_brow, a_bcol;            // byte step from block A_{i,l} to A_{i+1,l} / A_{i,l+1}
     uint32_t b_brow, b_bcol;            // byte step from block B_{l,j} to B_{l+1,j} / B_{l,j+1}
+                                        // (prepared B: ldb_b = row pitch of a plane, b_brow = plane stride)
     uint32_t c_brow, c_bcol;            // byte step from block C_{i,j} to C_{i+1,j} / C_{i,j+1}
     int32_t nx, nz, ny;                 // tiles per block along M/m, N/n and K/k (Algorithm 2's x, z, y ranges in tiles)
     int32_t panel;                      // width (in z tiles) of a column panel in the tile order
+};
+
+// Argument block of the offline Combine-B kernels.
+struct PrepParams {
+    const void *B;
+    void *Bt;
+    uint32_t b_bytes, bt_bytes; // byte extents (< 2 GiB each)
+    uint32_t ldb_b;             // leading dimension of B in bytes
+    uint32_t b_brow, b_bcol;    // byte step from block B_{l,j} to B_{l+1,j} / B_{l,j+1}
+    uint32_t bt_ld_b;           // row pitch of a plane in bytes = (K/k) * ES
+    uint32_t bt_plane_b;        // plane stride in bytes = (N/n) * (K/k) * ES
+    int32_t bk, bn;             // K/k, N/n
 };
 
 } // namespace lcma

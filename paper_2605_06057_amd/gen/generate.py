@@ -122,12 +122,13 @@ class Variant:
     occ: int = 1              # work-groups per CU the kernel is compiled for
     fc: int = 0               # 1: LDS holds raw blocks, waves combine MFMA fragments (needs chunk >= R)
     comp: tuple = ()          # products (0-based) whose left operand also gets its rounding residual multiplied
+    pb: int = 0               # 1: B side comes from the offline Combine-B kernel (needs fc, pipe 2)
     name: str = field(default="")
 
     def finish(self):
         if not self.name:
             self.name = (f"{self.scheme}_{self.dtype}_t{self.TM}x{self.TN}x{self.TK}_c{self.chunk}"
-                         + (f"x{len(self.comp)}" if self.comp else "") + (f"w{self.wgm}x{self.wgn}" if (self.wgm, self.wgn) != (2, 2) else "") + ("f" if self.fc else "") + ("p" if self.pipe == 1 else "i" if self.pipe == 2 else "") + ("s3" if self.stages == 3 else "") + (f"o{self.occ}" if self.occ > 1 else ""))
+                         + (f"x{len(self.comp)}" if self.comp else "") + (f"w{self.wgm}x{self.wgn}" if (self.wgm, self.wgn) != (2, 2) else "") + ("f" if self.fc else "") + ("p" if self.pipe == 1 else "i" if self.pipe == 2 else "") + ("s3" if self.stages == 3 else "") + ("b" if self.pb else "") + (f"o{self.occ}" if self.occ > 1 else ""))
         return self
 
 
@@ -174,6 +175,8 @@ def plan(s: Scheme, v: Variant):
         assert len(chunks) == 1, "fragment combine keeps every product's accumulator live"
         nsa = len({(i, l) for r in chunks[0] for i in range(s.m) for l in range(s.k) if s.U[r, i, l]})
         nsb = len({(l, j) for r in chunks[0] for l in range(s.k) for j in range(s.n) if s.V[r, l, j]})
+        if v.pb:
+            nsb = len(chunks[0])  # one LDS slot per product's right operand
     else:
         nsa = nsb = nslot
     lds = v.stages * (nsa * v.TM * v.TK + nsb * v.TK * v.TN) * es
@@ -221,14 +224,18 @@ def emit_kernel(s: Scheme, v: Variant) -> str:
     w('#include "lcma_device.hpp"')
     w("namespace {")
     w("using namespace lcma;")
-    w(f"using T = Tile<{in_t}, {ct_t}, {v.TM}, {v.TN}, {v.TK}, {v.wgm}, {v.wgn}, {nsa}, {nsb}, {v.pipe}, {v.fc}, {v.stages}>;")
+    w(f"using T = Tile<{in_t}, {ct_t}, {v.TM}, {v.TN}, {v.TK}, {v.wgm}, {v.wgn}, {nsa}, {nsb}, {v.pipe}, {v.fc}, {v.stages}, {v.pb}>;")
     for ci, ch in enumerate(chunks):
         a_blocks = sorted({(i, l) for r in ch for i in range(s.m) for l in range(s.k) if s.U[r, i, l]})
         b_blocks = sorted({(l, j) for r in ch for l in range(s.k) for j in range(s.n) if s.V[r, l, j]})
         w(f"struct Chunk{ci} {{  // products {', '.join(str(r + 1) for r in ch)}")
+        if v.pb:
+            b_blocks = []
         w(f"    static constexpr int NA = {len(a_blocks)}, NB = {len(b_blocks)}, NP = {len(ch)};")
         for fn, vals in (("a_i", [b[0] for b in a_blocks]), ("a_l", [b[1] for b in a_blocks]),
                          ("b_l", [b[0] for b in b_blocks]), ("b_j", [b[1] for b in b_blocks])):
+            if not vals:
+                continue
             w(f"    static LCMA_DEV constexpr int {fn}(int t) {{ constexpr int v[] = {{{', '.join(map(str, vals))}}}; return v[t]; }}")
         w("    template <class V> static LCMA_DEV void comb_a(const V (&in)[NA], V (&out)[NP]) {")
         for si, r in enumerate(ch):
@@ -240,11 +247,12 @@ def emit_kernel(s: Scheme, v: Variant) -> str:
             else:
                 w(f"        out[{si}] = {signed_sum(terms, wide, True)};")
         w("    }")
-        w("    template <class V> static LCMA_DEV void comb_b(const V (&in)[NB], V (&out)[NP]) {")
-        for si, r in enumerate(ch):
-            terms = [(int(s.V[r, l, j]), f"in[{b_blocks.index((l, j))}]") for (l, j) in b_blocks if s.V[r, l, j]]
-            w(f"        out[{si}] = {signed_sum(terms, wide, True)};")
-        w("    }")
+        if not v.pb:
+            w("    template <class V> static LCMA_DEV void comb_b(const V (&in)[NB], V (&out)[NP]) {")
+            for si, r in enumerate(ch):
+                terms = [(int(s.V[r, l, j]), f"in[{b_blocks.index((l, j))}]") for (l, j) in b_blocks if s.V[r, l, j]]
+                w(f"        out[{si}] = {signed_sum(terms, wide, True)};")
+            w("    }")
         w("};")
     w("")
     w("} // namespace")
@@ -306,9 +314,67 @@ def emit_registry(schemes: dict[str, Scheme], variants: list[Variant]) -> str:
         s = schemes[v.scheme]
         hash_expr = "0" if s.name == "plain" else f"0x{scheme_hash(s):016x}ull"
         L.append(f'    {{"{v.name}", {SCHEME_IDS[v.scheme]}, {DTYPE_IDS[v.dtype]}, {s.m}, {s.k}, {s.n}, {s.R}, '
-                 f"{hash_expr}, {v.TM}, {v.TN}, {v.TK}, {min(v.chunk, s.R)}, {v.rank}, {v.eff}, {v.occ}, {s.R + len(v.comp)}, lcma_launch_{v.name}}},")
-    L += ["};", f"const int kVariantCount = {len(variants)};", "} // namespace lcma", ""]
+                 f"{hash_expr}, {v.TM}, {v.TN}, {v.TK}, {min(v.chunk, s.R)}, {v.rank}, {v.eff}, {v.occ}, {s.R + len(v.comp)}, {v.pb}, lcma_launch_{v.name}}},")
+    L += ["};", f"const int kVariantCount = {len(variants)};"]
+    preps = prep_kernels(variants)
+    L.append("const PrepKernel kPrepKernels[] = {")
+    for sch, dt in preps:
+        L.append(f"    {{{SCHEME_IDS[sch]}, {DTYPE_IDS[dt]}, lcma_launch_prep_b_{sch}_{dt}}},")
+    if not preps:
+        L.append("    {0, 0, nullptr},")
+    L += ["};", f"const int kPrepKernelCount = {len(preps)};", "} // namespace lcma", ""]
+    for sch, dt in preps:
+        L.insert(3, f'extern "C" int lcma_launch_prep_b_{sch}_{dt}(const lcma::PrepParams *p, int gx, int gy, void *stream);')
     return "\n".join(L)
+
+
+def prep_kernels(variants: list[Variant]) -> list[tuple[str, str]]:
+    """(scheme, dtype) pairs that need an offline Combine-B kernel: those with a prepared-B GEMM kernel."""
+    return sorted({(v.scheme, v.dtype) for v in variants if v.pb})
+
+
+def emit_prep_b(s: Scheme, dtype: str) -> str:
+    """Offline Combine B (Eq. 4) for one scheme and storage type; sums in fp32, ascending (l, j)."""
+    in_t, ct_t = CPP_TYPES[dtype]
+    b_blocks = sorted({(l, j) for r in range(s.R) for l in range(s.k) for j in range(s.n) if s.V[r, l, j]})
+    L = []
+    w = L.append
+    w(f"// GENERATED by gen/generate.py - do not edit.  Offline Combine B of scheme {s.name} <{s.m},{s.k},{s.n};{s.R}>, dtype {dtype}.")
+    w('#include "lcma_prepare_b.hpp"')
+    w("namespace {")
+    w("using namespace lcma;")
+    w("struct Comb {")
+    w(f"    static constexpr int NB = {len(b_blocks)}, NP = {s.R};")
+    for fn, vals in (("b_l", [b[0] for b in b_blocks]), ("b_j", [b[1] for b in b_blocks])):
+        w(f"    static LCMA_DEV constexpr int {fn}(int t) {{ constexpr int v[] = {{{', '.join(map(str, vals))}}}; return v[t]; }}")
+    w("    static LCMA_DEV void comb(const float (&in)[NB], float (&out)[NP]) {")
+    w("#pragma clang fp contract(off)")
+    for r in range(s.R):
+        # ascending (l, j), left to right: the order the stored result is defined in
+        expr = ""
+        for (l, j) in b_blocks:
+            c = int(s.V[r, l, j])
+            if not c:
+                continue
+            mag = f"in[{b_blocks.index((l, j))}]" if abs(c) == 1 else f"{float(abs(c))}f * in[{b_blocks.index((l, j))}]"
+            if not expr:
+                expr = mag if c > 0 else f"-{mag}"
+            else:
+                expr = f"({expr} {'+' if c > 0 else '-'} {mag})"
+        w(f"        out[{r}] = {expr or '0.f'};")
+    w("    }")
+    w("};")
+    w("} // namespace")
+    w("")
+    w(f'extern "C" __global__ __launch_bounds__(256) void lcma_k_prep_b_{s.name}_{dtype}(const lcma::PrepParams p) {{')
+    w(f"    prepare_b_tile<{in_t}, {ct_t}, Comb>(p);")
+    w("}")
+    w("")
+    w(f'extern "C" int lcma_launch_prep_b_{s.name}_{dtype}(const lcma::PrepParams *p, int gx, int gy, void *stream) {{')
+    w(f"    lcma_k_prep_b_{s.name}_{dtype}<<<dim3(gx, gy), dim3(256), 0, (hipStream_t)stream>>>(*p);")
+    w("    return (int)hipGetLastError();")
+    w("}")
+    return "\n".join(L) + "\n"
 
 
 def scheme_hash(s: Scheme) -> int:
@@ -355,6 +421,9 @@ def manifest() -> list[Variant]:
             Variant("strassen", dt, 128, 64, 32, chunk=7, fc=1, wgm=4, wgn=2, pipe=2, eff=e(0.268, 0.291)),
             Variant("strassen", dt, 64, 128, 32, chunk=7, fc=1, wgm=2, wgn=4, pipe=2, eff=e(0.265, 0.287)),
             Variant("strassen", dt, 64, 64, 32, chunk=7, fc=1, occ=2, pipe=2, eff=e(0.241, 0.263)),
+            # B from the offline Combine-B kernel (static weights): only the A side is combined on fragments
+            Variant("strassen", dt, 128, 64, 32, chunk=7, fc=1, wgm=4, wgn=2, pipe=2, pb=1, eff=e(0.264, 0.252)),
+            Variant("strassen", dt, 64, 64, 32, chunk=7, fc=1, pipe=2, pb=1, eff=e(0.202, 0.194)),
             # ablation variants: staging in one phase; a third LDS stage; combinations formed while staging
             Variant("strassen", dt, 128, 64, 32, chunk=7, fc=1, wgm=4, wgn=2, eff=e(0.261, 0.280), rank=90),
             Variant("strassen", dt, 128, 64, 32, chunk=7, fc=1, wgm=4, wgn=2, pipe=2, stages=3, eff=e(0.268, 0.286), rank=90),
@@ -382,6 +451,8 @@ def manifest() -> list[Variant]:
         Variant("plain", "f32", 64, 64, 16, eff=0.856),
         Variant("strassen", "f32", 64, 64, 16, chunk=7, fc=1, occ=2, pipe=2, eff=0.819),
         Variant("strassen", "f32", 128, 64, 16, chunk=7, fc=1, wgm=4, wgn=2, pipe=2, eff=0.802),
+        Variant("strassen", "f32", 128, 64, 16, chunk=7, fc=1, wgm=4, wgn=2, pipe=2, pb=1, eff=0.844),
+        Variant("strassen", "f32", 64, 64, 16, chunk=7, fc=1, pipe=2, pb=1, eff=0.74),
         Variant("strassen", "f32", 64, 64, 16, chunk=7, fc=1, occ=2, eff=0.795, rank=90),
         Variant("strassen", "f32", 64, 64, 16, chunk=7, eff=0.656, rank=90),
         Variant("strassen", "f32", 128, 64, 16, chunk=1, eff=0.613),
@@ -415,6 +486,8 @@ def generate(out_dir: str) -> list[str]:
         assert regs <= ACC_REG_BUDGET, f"{v.name}: {regs} accumulator registers exceed the budget"
         assert lds <= LDS_BUDGET, f"{v.name}: {lds} bytes of LDS exceed the budget"
         hips.append(put(f"k_{v.name}.hip", emit_kernel(s, v)))
+    for sch, dt in prep_kernels(variants):
+        hips.append(put(f"k_prep_b_{sch}_{dt}.hip", emit_prep_b(schemes[sch], dt)))
     put("registry.cc", emit_registry(schemes, variants))
     put("builtin_schemes.inc", emit_builtin_inc(schemes))
     keep = {os.path.basename(h) for h in hips} | {"registry.cc", "builtin_schemes.inc"}

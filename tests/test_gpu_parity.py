@@ -38,6 +38,15 @@ def small_shape(v):
     return 3 * v["mult_M"], 2 * v["mult_N"], 2 * v["mult_K"]
 
 
+def run_variant(B, v, a, b, c):
+    """Runs the named kernel; a prepared-B kernel gets the output of the offline Combine-B call."""
+    if v["prepared"]:
+        s = B.lcma_scheme_load("builtin:" + B.SCHEME_NAMES[v["scheme_id"]])
+        B.lcma_gemm_variant_prepared(v["name"], a, B.lcma_prepare_b(b, s), c)
+    else:
+        B.lcma_gemm_variant(v["name"], a, b, c)
+
+
 @pytest.mark.parametrize("v", variants(), ids=lambda v: v["name"])
 def test_integer_inputs_bit_exact(B, v):
     import gpu_util as G
@@ -51,11 +60,11 @@ def test_integer_inputs_bit_exact(B, v):
         assert np.array_equal(oracle.lcma(s, Ai, Bi), oracle.gemm(Ai, Bi))
     a, b = G.to_device(inp.store(Ai, dt), dt), G.to_device(inp.store(Bi, dt), dt)
     c = G.empty_like_c(M, N, dt, fill=float("nan"))
-    B.lcma_gemm_variant(v["name"], a, b, c)
+    run_variant(B, v, a, b, c)
     got = G.to_host_stored(c, dt)
     assert np.array_equal(got.view(np.uint8), want.view(np.uint8))
     c2 = G.empty_like_c(M, N, dt, fill=1.0)
-    B.lcma_gemm_variant(v["name"], a, b, c2)
+    run_variant(B, v, a, b, c2)
     assert np.array_equal(G.to_host_stored(c2, dt).view(np.uint8), got.view(np.uint8))  # run-to-run identical
 
 
@@ -69,7 +78,7 @@ def test_float_inputs_within_bounds(B, v):
     ref = oracle.gemm(inp.widen(As, dt), inp.widen(Bs, dt))
     a, b = G.to_device(As, dt), G.to_device(Bs, dt)
     c = G.empty_like_c(M, N, dt, fill=float("nan"))
-    B.lcma_gemm_variant(v["name"], a, b, c)
+    run_variant(B, v, a, b, c)
     err = oracle.rel_frobenius(G.to_host_f64(c, dt), ref)
     cp = G.empty_like_c(M, N, dt)
     B.lcma_gemm(a, b, cp, None)

@@ -1,0 +1,113 @@
+"""GPU parity of the offline Combine-B path: lcma_prepare_b against the oracle's Combine B as stored
+(bit for bit: both add in fp32 in the same order and round once), and lcma_gemm_prepared against the
+oracle's product (integers bit-exact, floats within the bounds of the fused path)."""
+import numpy as np
+import pytest
+
+import lcma_inputs as inp
+import oracle
+from oracle import schemes as S
+
+pytestmark = pytest.mark.gpu
+
+REL_BOUND = {"f32": 1e-5, "bf16": 2e-2, "f16": 2e-2}
+
+
+@pytest.fixture(scope="module")
+def B():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    from paper_2605_06057_amd import binding
+    binding.lib()
+    return binding
+
+
+def prepared_to_host(bt) -> np.ndarray:
+    """(R, N/n, K/k) device tensor -> (R, K/k, N/n) fp64, the oracle's orientation."""
+    return bt.cpu().numpy().astype(np.float64).transpose(0, 2, 1)
+
+
+@pytest.mark.parametrize("dt", ["bf16", "f16", "f32"])
+@pytest.mark.parametrize("kind", ["uniform", "weights", "int"])
+def test_prepare_b_equals_oracle_bit_for_bit(B, dt, kind):
+    import torch
+    import gpu_util as G
+    s = S.strassen()
+    N, K = 3 * 128, 5 * 64  # 3 x 5 tiles of the Combine-B kernel per block (5 x 10 for fp32)
+    print(f"prepare_b {dt} {kind} N={N} K={K}", flush=True)
+    _, Bs = inp.matrices("uniform", kind, 64, N, K, dt, seed=11)
+    want = oracle.combine_b_stored(s, inp.widen(Bs, dt), dt)
+    # B as a strided view (ldb > N)
+    pad = 16 // (4 if dt == "f32" else 2)
+    big = torch.zeros((K, N + 3 * pad), dtype=G.empty_like_c(1, 1, dt).dtype, device="cuda")
+    big[:, pad:pad + N] = G.to_device(Bs, dt)
+    h = B.lcma_scheme_load("builtin:strassen")
+    bt = B.lcma_prepare_b(big[:, pad:pad + N], h)
+    assert tuple(bt.shape) == (7, N // 2, K // 2)
+    assert bt.dtype == (torch.float32 if dt == "f32" else torch.float16)
+    assert B.lcma_prepared_b_bytes(h, N, K, B.DTYPE_IDS[dt]) == bt.numel() * bt.element_size()
+    got = prepared_to_host(bt)
+    assert np.array_equal(got, want)
+    if kind == "int":  # and then the stored values are the exact sums
+        assert np.array_equal(got, oracle.combine_b(s, inp.widen(Bs, dt)))
+
+
+@pytest.mark.parametrize("dt", ["bf16", "f16", "f32"])
+def test_gemm_prepared_integer_bit_exact_and_float_bounds(B, dt):
+    import gpu_util as G
+    h = B.lcma_scheme_load("builtin:strassen")
+    M, N, K = 768, 512, 384
+    print(f"gemm_prepared {dt} {M}x{N}x{K}", flush=True)
+    Ai, Bi = inp.integers(101, 1, (M, K)), inp.integers(101, 2, (K, N))
+    want = inp.store(oracle.gemm(Ai, Bi).astype(np.float64), dt)
+    a, b = G.to_device(inp.store(Ai, dt), dt), G.to_device(inp.store(Bi, dt), dt)
+    bt = B.lcma_prepare_b(b, h)
+    c = G.empty_like_c(M, N, dt, fill=float("nan"))
+    B.lcma_gemm_prepared(a, bt, c, h)
+    assert np.array_equal(G.to_host_stored(c, dt).view(np.uint8), want.view(np.uint8))
+
+    kinds = ("uniform", "uniform") if dt != "bf16" else ("normal", "weights")
+    As, Bs = inp.matrices(kinds[0], kinds[1], M, N, K, dt, seed=13)
+    ref = oracle.gemm(inp.widen(As, dt), inp.widen(Bs, dt))
+    a, b = G.to_device(As, dt), G.to_device(Bs, dt)
+    bt = B.lcma_prepare_b(b, h)
+    c = G.empty_like_c(M, N, dt, fill=float("nan"))
+    B.lcma_gemm_prepared(a, bt, c, h)
+    err = oracle.rel_frobenius(G.to_host_f64(c, dt), ref)
+    cp = G.empty_like_c(M, N, dt)
+    B.lcma_gemm(a, b, cp, None)
+    err_plain = oracle.rel_frobenius(G.to_host_f64(cp, dt), ref)
+    cf = G.empty_like_c(M, N, dt)
+    B.lcma_gemm(a, b, cf, h)
+    err_fused = oracle.rel_frobenius(G.to_host_f64(cf, dt), ref)
+    print(f"relF prepared {err:.3e} fused {err_fused:.3e} plain {err_plain:.3e}", flush=True)
+    assert err <= REL_BOUND[dt] and err <= 4.0 * err_plain
+    # the prepared operand is rounded once from an fp32 sum: never worse than the fused kernel's packed adds
+    assert err <= 1.05 * err_fused
+
+
+def test_prepared_error_paths_launch_nothing(B):
+    import torch
+    h = B.lcma_scheme_load("builtin:strassen")
+    b = torch.ones((256, 256), dtype=torch.float16, device="cuda")
+    with pytest.raises(B.LcmaError) as e:
+        B.lcma_prepare_b(b[:, :192], h)                     # N/n = 96 is not a multiple of 64
+    assert e.value.status == B.LCMA_ERR_SHAPE
+    with pytest.raises(B.LcmaError) as e:
+        B.lcma_prepare_b(b[:, 1:129], h)                    # misaligned pointer
+    assert e.value.status == B.LCMA_ERR_ARG
+    h2 = B.lcma_scheme_load("builtin:laderman")
+    assert B.lcma_prepared_b_bytes(h2, 384, 384, B.LCMA_F16) == 23 * 128 * 128 * 2
+    assert B.lcma_prepared_b_bytes(h2, 256, 384, B.LCMA_F16) == -1   # N not a multiple of n
+    bt3 = torch.zeros((23, 128, 128), dtype=torch.float16, device="cuda")
+    with pytest.raises(B.LcmaError) as e:                   # no prepared-B kernels for Laderman
+        B.lcma_prepare_b(torch.ones((384, 384), dtype=torch.float16, device="cuda"), h2, bt3)
+    assert e.value.status == B.LCMA_ERR_NOKERNEL
+    bt = B.lcma_prepare_b(b, h)
+    c = torch.full((200, 256), 3.0, dtype=torch.float16, device="cuda")
+    with pytest.raises(B.LcmaError) as e:
+        B.lcma_gemm_prepared(b[:200], bt, c, h)             # M = 200: not a multiple of the tile
+    assert e.value.status == B.LCMA_ERR_SHAPE
+    torch.cuda.synchronize()
+    assert torch.all(c == 3.0) and torch.all(bt3 == 0)
+    B.lcma_gemm_prepared(b[:0], bt, torch.empty((0, 256), dtype=torch.float16, device="cuda"), h)  # M = 0

@@ -172,3 +172,24 @@ def test_variant_registry(B):
                              (2, 1, 8192, 14336, 4096), (3, 2, 6144, 6144, 6144), (0, 1, 2048, 4096, 14336)]:
         assert any(v["scheme_id"] == sid and v["dtype"] == dt and M % v["mult_M"] == 0 and N % v["mult_N"] == 0
                    and K % v["mult_K"] == 0 for v in vs), (sid, dt, M, N, K)
+
+
+def test_prepared_b_host_side(B):
+    """Sizes and argument checks of the offline Combine-B entry points (nothing here launches)."""
+    s = B.lcma_scheme_load("builtin:strassen")
+    assert B.lcma_prepared_b_bytes(s, 4096, 4096, B.LCMA_BF16) == 7 * 2048 * 2048 * 2
+    assert B.lcma_prepared_b_bytes(s, 4096, 4096, B.LCMA_F32) == 7 * 2048 * 2048 * 4
+    assert B.lcma_prepared_b_bytes(s, 4095, 4096, B.LCMA_BF16) == -1
+    assert B.lcma_prepared_b_bytes(s, 4096, 0, B.LCMA_BF16) == -1
+    assert B.lcma_prepared_b_bytes(s, 4096, 4096, 17) == -1
+    L = B.lib()
+    # null pointers, a missing scheme and an unknown dtype are refused before anything is launched
+    assert L.lcma_prepare_b(256, 256, None, 256, B.LCMA_F16, s.handle, None, None) == B.LCMA_ERR_ARG
+    assert L.lcma_prepare_b(256, 256, None, 256, B.LCMA_F16, None, None, None) == B.LCMA_ERR_ARG
+    assert L.lcma_prepare_b(256, 256, None, 256, 17, s.handle, None, None) == B.LCMA_ERR_DTYPE
+    assert L.lcma_gemm_prepared(256, 256, 256, None, 256, None, None, 256, B.LCMA_F16, None, None) == B.LCMA_ERR_ARG
+    assert L.lcma_gemm_prepared(256, 256, 256, None, 256, None, None, 256, B.LCMA_F16, s.handle, None) == B.LCMA_ERR_ARG
+    assert b"null" in L.lcma_last_error()
+    vs = B.lcma_variants()
+    assert any(v["prepared"] for v in vs) and any(not v["prepared"] for v in vs)
+    assert B.lib().lcma_variant_prepared(len(vs)) == -1
