@@ -108,7 +108,8 @@ template <> struct Round<BF16> {
 // ---------------------------------------------------------------- tile configuration
 // TM x TN: tile of one block product owned by the work-group; TK: depth per y step;
 // WGM x WGN: wave grid (4 waves); NSA / NSB: A-side / B-side tiles resident per LDS stage;
-// PIPE: 0 double-buffered phases, 1 software-pipelined step, 2 staging spread over the MFMA phase;
+// PIPE: 0 staging in one phase before the barrier, 2 staging spread over the MFMA phase
+//       (fragment-combine kernels only);
 // FC: 0 = combinations are formed while staging and LDS holds At_r, Bt_r;
 //     1 = LDS holds the raw (converted) blocks and every wave forms the combinations on the
 //         MFMA fragments it has read ("fragment combine");
@@ -117,16 +118,20 @@ template <> struct Round<BF16> {
 // PB: 1 = the B operand is the output of the offline Combine-B stage (Eq. 4 done once for static
 //         weights): R planes of (N/n) x (K/k) elements of the compute type, k-contiguous.  Tiles of the
 //         right operands Bt_r go to LDS as they are (no conversion, transposition or addition) and
-//         only the A side is combined on fragments.
+//         only the A side is combined on fragments;
+// DL: 1 (with PB) = tiles travel from memory straight into LDS (buffer loads with the LDS bit: no
+//         staging registers, no LDS write instructions); the raw A blocks then sit in LDS in the
+//         storage type and are converted on the fragments.
 //
 // LDS layout of a stage: NSA tiles [TM rows][TK] then NSB tiles [TN rows][TK], both k-contiguous,
 // 16-byte chunks XOR-swizzled inside a row.  B arrives n-contiguous from memory and is transposed
 // in registers while it is staged, so that both MFMA operands are read with 16-byte LDS loads
 // (measured on MI355X: ds_read_b128 ~260 B/clk/CU, the transposing ds_read_b64_tr_b16 ~70).
 template <class IN_, class CT_, int TM_, int TN_, int TK_, int WGM_, int WGN_, int NSA_, int NSB_, int PIPE_ = 0,
-          int FC_ = 0, int STAGES_ = 2, int PB_ = 0>
+          int FC_ = 0, int STAGES_ = 2, int PB_ = 0, int DL_ = 0>
 struct Tile {
-    static constexpr int PIPE = PIPE_, FC = FC_, PB = PB_;
+    static constexpr int PIPE = PIPE_, FC = FC_, PB = PB_, DL = DL_;
+    static_assert(!DL_ || PB_, "direct loads need an operand that goes to LDS untouched on both sides");
     static_assert(!PB_ || (FC_ && PIPE_ == 2 && STAGES_ == 2), "prepared B needs the interleaved fragment-combine loop");
     using IN = IN_;
     using CT = CT_;
@@ -439,13 +444,14 @@ template <class T> struct Ctx {
         const uint32_t sb = st * T::STAGE;
         constexpr int G = (Mma<CT>::SUB > 1 && T::NMI * T::NNI == 1) ? LCMA_FP32_GROUP : 1;
         constexpr int NG = (CH::NP + G - 1) / G;
-        Frag fa[2][T::NMI][CH::NA], fb[2][G][T::NNI];
+        u32x4 fa[2][T::NMI][CH::NA]; // as they sit in LDS: compute type, or storage type with direct loads
+        Frag fb[2][G][T::NNI];
         auto fetch_a = [&](int kk, int buf) {
 #pragma unroll
             for (int mi = 0; mi < T::NMI; ++mi)
 #pragma unroll
                 for (int t = 0; t < CH::NA; ++t)
-                    fa[buf][mi][t] = lds_frag(sb + t * T::A_SLOT + a_frag[kk] + mi * 32 * T::ROW);
+                    fa[buf][mi][t] = *(LCMA_LDS u32x4 *)(lds + sb + t * T::A_SLOT + a_frag[kk] + mi * 32 * T::ROW);
         };
         auto fetch_b = [&](int kk, int gi, int buf) {
 #pragma unroll
@@ -462,6 +468,14 @@ template <class T> struct Ctx {
         for (int kk = 0; kk < T::NKK; ++kk) {
             const int cur = kk & 1;
             if (kk + 1 < T::NKK) fetch_a(kk + 1, cur ^ 1);
+            Frag ca[T::NMI][CH::NA];
+#pragma unroll
+            for (int mi = 0; mi < T::NMI; ++mi)
+#pragma unroll
+                for (int t = 0; t < CH::NA; ++t) {
+                    if constexpr (T::DL) ca[mi][t] = __builtin_bit_cast(Frag, Convert<IN, CT>::run(fa[cur][mi][t]));
+                    else ca[mi][t] = __builtin_bit_cast(Frag, fa[cur][mi][t]);
+                }
 #pragma unroll
             for (int gi = 0; gi < NG; ++gi) {
                 const int flat = kk * NG + gi, bcur = flat & 1;
@@ -474,7 +488,7 @@ template <class T> struct Ctx {
 #pragma unroll
                     for (int mi = 0; mi < T::NMI; ++mi) {
                         Frag o[CH::NP];
-                        CH::comb_a(fa[cur][mi], o);
+                        CH::comb_a(ca[mi], o);
                         at[g][mi] = o[gi * G + g];
                     }
                 }
@@ -721,6 +735,62 @@ template <class T, class CH> struct FlatStage {
     }
 };
 
+// Direct loads: the LDS image of a stage is linear in 16-byte chunks, a wave instruction fills 64
+// consecutive chunks (lane l lands at base + 16 l), and the swizzle is applied by choosing which
+// chunk of memory each lane fetches.  Pieces are whole work-group instructions; in the last piece of
+// a side the waves past the end skip (wave-uniform).
+template <class T, class CH> struct DirectStage {
+    static constexpr int NCHK_B = T::TN * T::CPR;
+    static constexpr int NCA = CH::NA * T::NCHK_A, NCB = CH::NP * NCHK_B;
+    static_assert(NCA % 64 == 0 && NCB % 64 == 0, "a wave instruction must not straddle the end of a side");
+    static constexpr int QA = (NCA + T::NT - 1) / T::NT, QB = (NCB + T::NT - 1) / T::NT;
+    static constexpr int NPIECE = QA + QB;
+    uint32_t a_voff[QA], b_voff[QB];
+    int wave_chunk; // first chunk of this wave inside a piece (wave-uniform)
+
+    LCMA_DEV DirectStage(const Ctx<T> &cx) {
+        const int tid = threadIdx.x;
+        wave_chunk = __builtin_amdgcn_readfirstlane(tid & ~63);
+#pragma unroll
+        for (int q = 0; q < QA; ++q) {
+            const int pp = (q * T::NT + tid) % NCA;
+            const int t = pp / T::NCHK_A, id2 = pp % T::NCHK_A;
+            const int row = id2 / T::CPR, cs = id2 % T::CPR;
+            // LDS position cs of the row holds memory chunk swz(row, cs) (the XOR is its own inverse)
+            a_voff[q] = (uint32_t)CH::a_i(t) * cx.p.a_brow + (uint32_t)CH::a_l(t) * cx.p.a_bcol +
+                        (uint32_t)row * cx.p.lda_b + T::swz(row, cs) * 16;
+        }
+#pragma unroll
+        for (int q = 0; q < QB; ++q) {
+            const int pp = (q * T::NT + tid) % NCB;
+            const int sl = pp / NCHK_B, id2 = pp % NCHK_B;
+            const int row = id2 / T::CPR, cs = id2 % T::CPR;
+            b_voff[q] = (uint32_t)sl * cx.p.b_brow + (uint32_t)row * cx.p.ldb_b + T::swz(row, cs) * 16;
+        }
+    }
+    LCMA_DEV void issue_piece(const Ctx<T> &cx, int pc, int st, int y) const {
+        if (pc < QA) {
+            const int first = pc * T::NT + wave_chunk;
+            if (first < NCA)
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(cx.ra, (LCMA_LDS void *)(cx.lds + st * T::STAGE + first * 16), 16,
+                                                         (int)a_voff[pc], (int)(cx.a_group + (uint32_t)y * (T::TK * T::ES)),
+                                                         0, 0);
+        } else {
+            const int q = pc - QA, first = q * T::NT + wave_chunk;
+            if (first < NCB)
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(
+                    cx.rb, (LCMA_LDS void *)(cx.lds + st * T::STAGE + T::A_STAGE + first * 16), 16, (int)b_voff[q],
+                    (int)(cx.b_group + (uint32_t)y * (T::TK * T::ES)), 0, 0);
+        }
+    }
+    LCMA_DEV void issue(const Ctx<T> &cx, int st, int y) const {
+#pragma unroll
+        for (int pc = 0; pc < NPIECE; ++pc) issue_piece(cx, pc, st, y);
+    }
+    // every direct load of this wave has landed in LDS
+    static LCMA_DEV void landed() { __builtin_amdgcn_s_waitcnt(0x0F70); } // vmcnt(0)
+};
+
 template <class T, class CH> LCMA_DEV void mma_step(const Ctx<T> &cx, int st, typename T::Acc (&acc)[CH::NP]) {
     if constexpr (T::FC) cx.template mma_stage_fc<CH>(st, acc);
     else cx.template mma_stage<CH::NP>(st, acc);
@@ -765,6 +835,29 @@ template <class T, class CH> LCMA_DEV void run_chunk(const Ctx<T> &cx, typename 
             };
             stage_loop<LITERAL_STAGE<T>>(ny, step);
             __syncthreads();
+        } else if constexpr (T::DL) {
+            // Direct loads: the tiles of step y+1 travel into the other stage while step y is multiplied;
+            // a piece (one work-group load instruction) is issued after each product group.
+            const DirectStage<T, CH> dl(cx);
+            dl.issue(cx, 0, 0);
+            dl.landed();
+            __syncthreads();
+            auto step = [&](int y, int st) {
+                const int nxt = y + 1 < ny ? y + 1 : last; // past the end: the last tile again, unused
+                using DS = DirectStage<T, CH>;
+                cx.template mma_stage_pb<CH>(st, acc, [&](int slot, int slots) {
+#pragma unroll
+                    for (int pc = 0; pc < DS::NPIECE; ++pc)
+                        if (pc * slots / DS::NPIECE == slot) {
+                            __builtin_amdgcn_sched_barrier(0);
+                            dl.issue_piece(cx, pc, st ^ 1, nxt);
+                            __builtin_amdgcn_sched_barrier(0);
+                        }
+                });
+                dl.landed();
+                __syncthreads();
+            };
+            stage_loop<LITERAL_STAGE<T>>(ny, step);
         } else if constexpr (T::PIPE == 2 && T::STAGES == 3) {
             // As below, with a third LDS stage: step y multiplies stage y%3, writes tile y+2 into stage
             // (y+2)%3 and reloads the registers with tile y+3.  The stage of step y+1 is complete one
@@ -832,25 +925,9 @@ template <class T, class CH> LCMA_DEV void run_chunk(const Ctx<T> &cx, typename 
                 __syncthreads();
             };
             stage_loop<LITERAL_STAGE<T>>(ny, step);
-        } else {
-            typename FlatStage<T, CH>::Raw r0, r1;
-            fs.issue(cx, r0, 0);
-            fs.issue(cx, r1, ny > 1 ? 1 : 0);
-            fs.store(cx, r0, 0);
-            __syncthreads();
-            for (int y = 0; y < ny; y += 2) {
-                fs.issue(cx, r0, y + 2 < ny ? y + 2 : last);
-                cx.template mma_stage_fc<CH>(0, acc);
-                fs.store(cx, r1, 1);
-                __syncthreads();
-                if (y + 1 >= ny) break;
-                fs.issue(cx, r1, y + 3 < ny ? y + 3 : last);
-                cx.template mma_stage_fc<CH>(1, acc);
-                fs.store(cx, r0, 0);
-                __syncthreads();
-            }
         }
-    } else if constexpr (T::PIPE == 0) {
+    } else {
+        static_assert(T::PIPE == 0, "staged-combine kernels stage in one phase");
         // Plain double buffering: one register set, loads of step y+1 in flight during the MFMAs
         // of step y.  Meant for two work-groups per CU, which overlap each other's phases.
         RawSet<T, CH> r;
@@ -863,31 +940,6 @@ template <class T, class CH> LCMA_DEV void run_chunk(const Ctx<T> &cx, typename 
         };
         stage_loop<LITERAL_STAGE<T>>(ny, step);
         __syncthreads();
-    } else {
-        // Software-pipelined: in the steady state one step (a single basic block, so that the
-        // scheduler may interleave its parts) issues the loads of step y+2, multiplies step y from
-        // one LDS stage and combines step y+1 from registers into the other.  Past the end the last
-        // tile is loaded and combined again into the stage nobody reads (keeps the step branch-free).
-        RawSet<T, CH> r0, r1;
-        issue_loads<T, CH>(cx, r0, 0);
-        issue_loads<T, CH>(cx, r1, ny > 1 ? 1 : 0);
-        combine_store<T, CH>(cx, r0, 0);
-        __syncthreads();
-        for (int y = 0; y < ny; y += 2) {
-            {   // even step: stage 0 holds y, r1 holds y+1, r0 is free
-                issue_loads<T, CH>(cx, r0, y + 2 < ny ? y + 2 : last);
-                mma_step<T, CH>(cx, 0, acc);
-                combine_store<T, CH>(cx, r1, 1);
-                __syncthreads();
-            }
-            if (y + 1 >= ny) break;
-            {   // odd step: stage 1 holds y+1, r0 holds y+2, r1 is free
-                issue_loads<T, CH>(cx, r1, y + 3 < ny ? y + 3 : last);
-                mma_step<T, CH>(cx, 1, acc);
-                combine_store<T, CH>(cx, r0, 0);
-                __syncthreads();
-            }
-        }
     }
 }
 

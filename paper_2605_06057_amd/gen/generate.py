@@ -118,17 +118,18 @@ class Variant:
     stages: int = 2
     rank: int = 0             # >= 90: ablation variant, only reachable by name
     eff: float = 0.1          # measured fraction of the dtype's MFMA peak its MFMA work sustains (large shapes)
-    pipe: int = 0             # 0: double-buffered phases, 1: software-pipelined step
+    pipe: int = 0             # 0: staging in one phase, 2: staging spread over the MFMA phase (with fc)
     occ: int = 1              # work-groups per CU the kernel is compiled for
     fc: int = 0               # 1: LDS holds raw blocks, waves combine MFMA fragments (needs chunk >= R)
     comp: tuple = ()          # products (0-based) whose left operand also gets its rounding residual multiplied
     pb: int = 0               # 1: B side comes from the offline Combine-B kernel (needs fc, pipe 2)
+    dl: int = 0               # 1 (with pb): tiles are loaded from memory straight into LDS
     name: str = field(default="")
 
     def finish(self):
         if not self.name:
             self.name = (f"{self.scheme}_{self.dtype}_t{self.TM}x{self.TN}x{self.TK}_c{self.chunk}"
-                         + (f"x{len(self.comp)}" if self.comp else "") + (f"w{self.wgm}x{self.wgn}" if (self.wgm, self.wgn) != (2, 2) else "") + ("f" if self.fc else "") + ("p" if self.pipe == 1 else "i" if self.pipe == 2 else "") + ("s3" if self.stages == 3 else "") + ("b" if self.pb else "") + (f"o{self.occ}" if self.occ > 1 else ""))
+                         + (f"x{len(self.comp)}" if self.comp else "") + (f"w{self.wgm}x{self.wgn}" if (self.wgm, self.wgn) != (2, 2) else "") + ("f" if self.fc else "") + ("i" if self.pipe == 2 else "") + ("s3" if self.stages == 3 else "") + ("b" if self.pb else "") + ("d" if self.dl else "") + (f"o{self.occ}" if self.occ > 1 else ""))
         return self
 
 
@@ -224,7 +225,7 @@ def emit_kernel(s: Scheme, v: Variant) -> str:
     w('#include "lcma_device.hpp"')
     w("namespace {")
     w("using namespace lcma;")
-    w(f"using T = Tile<{in_t}, {ct_t}, {v.TM}, {v.TN}, {v.TK}, {v.wgm}, {v.wgn}, {nsa}, {nsb}, {v.pipe}, {v.fc}, {v.stages}, {v.pb}>;")
+    w(f"using T = Tile<{in_t}, {ct_t}, {v.TM}, {v.TN}, {v.TK}, {v.wgm}, {v.wgn}, {nsa}, {nsb}, {v.pipe}, {v.fc}, {v.stages}, {v.pb}, {v.dl}>;")
     for ci, ch in enumerate(chunks):
         a_blocks = sorted({(i, l) for r in ch for i in range(s.m) for l in range(s.k) if s.U[r, i, l]})
         b_blocks = sorted({(l, j) for r in ch for l in range(s.k) for j in range(s.n) if s.V[r, l, j]})
@@ -424,6 +425,7 @@ def manifest() -> list[Variant]:
             # B from the offline Combine-B kernel (static weights): only the A side is combined on fragments
             Variant("strassen", dt, 128, 64, 32, chunk=7, fc=1, wgm=4, wgn=2, pipe=2, pb=1, eff=e(0.264, 0.252)),
             Variant("strassen", dt, 64, 64, 32, chunk=7, fc=1, pipe=2, pb=1, eff=e(0.202, 0.194)),
+            Variant("strassen", dt, 128, 64, 32, chunk=7, fc=1, wgm=4, wgn=2, pipe=2, pb=1, dl=1, eff=e(0.233, 0.243), rank=90),
             # ablation variants: staging in one phase; a third LDS stage; combinations formed while staging
             Variant("strassen", dt, 128, 64, 32, chunk=7, fc=1, wgm=4, wgn=2, eff=e(0.261, 0.280), rank=90),
             Variant("strassen", dt, 128, 64, 32, chunk=7, fc=1, wgm=4, wgn=2, pipe=2, stages=3, eff=e(0.268, 0.286), rank=90),
@@ -451,8 +453,9 @@ def manifest() -> list[Variant]:
         Variant("plain", "f32", 64, 64, 16, eff=0.856),
         Variant("strassen", "f32", 64, 64, 16, chunk=7, fc=1, occ=2, pipe=2, eff=0.819),
         Variant("strassen", "f32", 128, 64, 16, chunk=7, fc=1, wgm=4, wgn=2, pipe=2, eff=0.802),
-        Variant("strassen", "f32", 128, 64, 16, chunk=7, fc=1, wgm=4, wgn=2, pipe=2, pb=1, eff=0.844),
+        Variant("strassen", "f32", 128, 64, 16, chunk=7, fc=1, wgm=4, wgn=2, pipe=2, pb=1, eff=0.875),
         Variant("strassen", "f32", 64, 64, 16, chunk=7, fc=1, pipe=2, pb=1, eff=0.74),
+        Variant("strassen", "f32", 128, 64, 16, chunk=7, fc=1, wgm=4, wgn=2, pipe=2, pb=1, dl=1, eff=0.852, rank=90),
         Variant("strassen", "f32", 64, 64, 16, chunk=7, fc=1, occ=2, eff=0.795, rank=90),
         Variant("strassen", "f32", 64, 64, 16, chunk=7, eff=0.656, rank=90),
         Variant("strassen", "f32", 128, 64, 16, chunk=1, eff=0.613),

@@ -193,3 +193,40 @@ def test_prepared_b_host_side(B):
     vs = B.lcma_variants()
     assert any(v["prepared"] for v in vs) and any(not v["prepared"] for v in vs)
     assert B.lib().lcma_variant_prepared(len(vs)) == -1
+
+
+def test_gemm_argument_checks_before_any_launch(B):
+    """Every refusal below is decided on the host from sizes, strides and pointer values alone:
+    the fake (never dereferenced) pointers prove that nothing is launched or read."""
+    L = B.lib()
+    s = B.lcma_scheme_load("builtin:strassen")
+    P = 0x100000  # 16-byte aligned, not a real allocation
+    ok_shape = (256, 256, 256)
+
+    def gemm(M, N, K, a=P, lda=None, b=P, ldb=None, c=P, ldc=None, dt=B.LCMA_F16, sch=s.handle):
+        return L.lcma_gemm(M, N, K, a, K if lda is None else lda, b, N if ldb is None else ldb,
+                           c, N if ldc is None else ldc, dt, sch, None)
+
+    assert gemm(*ok_shape, a=None) == B.LCMA_ERR_ARG                    # null matrix
+    assert gemm(*ok_shape, lda=255) == B.LCMA_ERR_ARG                   # leading dimension below the row
+    assert gemm(*ok_shape, a=P + 2) == B.LCMA_ERR_ARG                   # pointer not 16-byte aligned
+    assert gemm(*ok_shape, ldc=260) == B.LCMA_ERR_ARG                   # ldc * 2 bytes not a multiple of 16
+    assert gemm(-1, 256, 256) == B.LCMA_ERR_ARG
+    assert gemm(256, 256, 0) == B.LCMA_ERR_SHAPE                        # K = 0
+    assert gemm(256, 250, 256) == B.LCMA_ERR_SHAPE                      # no tile divides N
+    assert gemm(*ok_shape, dt=9) == B.LCMA_ERR_DTYPE
+    assert gemm(0, 256, 256, a=None, b=None, c=None) == B.LCMA_OK       # M = 0: nothing to do
+    # a matrix whose rows span 2 GiB or more: 256 rows with a leading dimension of 2^23 fp16 elements
+    assert gemm(*ok_shape, lda=1 << 23) == B.LCMA_ERR_SHAPE
+    assert b"2 GiB" in L.lcma_last_error()
+    assert gemm(*ok_shape, ldc=1 << 23) == B.LCMA_ERR_SHAPE
+    # the largest accepted extent is just below 2 GiB
+    lda_max = ((1 << 31) // 2 - 256) // 255 // 8 * 8
+    assert (255 * lda_max + 256) * 2 < (1 << 31)
+    # (accepted arguments would launch: not tried here without a GPU)
+    # two-level Strassen has no fp16 kernel
+    s2 = B.lcma_scheme_load("builtin:strassen2")
+    assert gemm(*ok_shape, sch=s2.handle) == B.LCMA_ERR_NOKERNEL
+    # lcma_gemm_variant: unknown name, null name
+    assert L.lcma_gemm_variant(b"no_such_kernel", 256, 256, 256, P, 256, P, 256, P, 256, None) == B.LCMA_ERR_NOKERNEL
+    assert L.lcma_gemm_variant(None, 256, 256, 256, P, 256, P, 256, P, 256, None) == B.LCMA_ERR_ARG
