@@ -204,8 +204,9 @@ def lcma_prepare_b(B, scheme: Scheme, Bt=None):
         raise LcmaError(f"lcma_prepared_b_bytes: bad arguments (N={N}, K={K})")
     info = lcma_scheme_info(scheme)
     ct = torch.float32 if B.dtype == torch.float32 else torch.float16
-    if Bt is None:
-        Bt = torch.empty((info["R"], N // info["n"], K // info["k"]), device=B.device, dtype=ct)
+    if Bt is None:  # N/n rows per plane, padded to whole tiles
+        rows = nbytes // (info["R"] * (K // info["k"]) * B.element_size())
+        Bt = torch.empty((info["R"], rows, K // info["k"]), device=B.device, dtype=ct)
     assert Bt.is_cuda and Bt.is_contiguous() and Bt.dtype == ct and Bt.numel() * Bt.element_size() == nbytes
     stream = torch.cuda.current_stream(B.device).cuda_stream
     _check(lib().lcma_prepare_b(N, K, B.data_ptr(), B.stride(0), dt, scheme.handle, Bt.data_ptr(), stream))

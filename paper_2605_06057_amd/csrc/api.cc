@@ -18,10 +18,15 @@ lcma_status fail(lcma_status st, const char *fmt, ...) {
     return st;
 }
 
+// M is free (rows past M are padding the kernels never touch), N must keep rows 16-byte granular,
+// K must be whole tiles of every block.
 bool variant_fits(const Variant &v, int64_t M, int64_t N, int64_t K) {
-    return M % ((int64_t)v.m * v.TM) == 0 && N % ((int64_t)v.n * v.TN) == 0 && K % ((int64_t)v.k * v.TK) == 0;
+    (void)M;
+    const int vec = 16 / dtype_size(v.dtype);
+    return N % vec == 0 && K % ((int64_t)v.k * v.TK) == 0;
 }
 static bool fits(const Variant &v, int64_t M, int64_t N, int64_t K) { return variant_fits(v, M, N, K); }
+static int64_t round_up(int64_t x, int64_t g) { return (x + g - 1) / g * g; }
 
 const Variant *pick_variant(int scheme_id, int dtype, int64_t M, int64_t N, int64_t K, int prepared) {
     const Variant *best = nullptr;
@@ -61,15 +66,19 @@ static lcma_status run(const Variant &v, int64_t M, int64_t N, int64_t K, const 
     if (((lda * es) | (ldb * es) | (ldc * es)) & 15)
         return fail(LCMA_ERR_ARG, "lcma_gemm: leading dimensions must be multiples of 16 bytes");
     if (!fits(v, M, N, K))
-        return fail(LCMA_ERR_SHAPE, "lcma_gemm: (%lld,%lld,%lld) is not a multiple of (%d,%d,%d) needed by %s",
-                    (long long)M, (long long)N, (long long)K, v.m * v.TM, v.n * v.TN, v.k * v.TK, v.name);
+        return fail(LCMA_ERR_SHAPE, "lcma_gemm: %s needs K = %lld to be a multiple of %d and N = %lld of %d",
+                    v.name, (long long)K, v.k * v.TK, (long long)N, 16 / es);
+    // blocks are cut from the matrices padded to whole tiles; the extents stay the true ones
+    const int64_t Mp = round_up(M, (int64_t)v.m * v.TM), Np = round_up(N, (int64_t)v.n * v.TN);
+    const int64_t bm = Mp / v.m, bn = Np / v.n, bk = K / v.k;
     const int64_t a_bytes = ((M - 1) * lda + K) * es,
-                  b_bytes = v.prepared ? (int64_t)v.products * (N / v.n) * (K / v.k) * es : ((K - 1) * ldb + N) * es,
+                  b_bytes = v.prepared ? (int64_t)v.products * bn * bk * es : ((K - 1) * ldb + N) * es,
                   c_bytes = ((M - 1) * ldc + N) * es;
     const int64_t lim = (int64_t)1 << 31;
-    if (a_bytes >= lim || b_bytes >= lim || c_bytes >= lim)
+    // offsets of padded rows and columns are formed in 32 bits before the range check drops them
+    if (((Mp - 1) * lda + K) * es >= lim || ((K - 1) * ldb + Np) * es >= lim || ((Mp - 1) * ldc + Np) * es >= lim ||
+        b_bytes >= lim)
         return fail(LCMA_ERR_SHAPE, "lcma_gemm: a matrix spans 2 GiB or more");
-    const int64_t bm = M / v.m, bn = N / v.n, bk = K / v.k;
     Params p;
     p.A = A;
     p.B = B;
@@ -94,6 +103,7 @@ static lcma_status run(const Variant &v, int64_t M, int64_t N, int64_t K, const 
     p.nx = (int32_t)(bm / v.TM);
     p.nz = (int32_t)(bn / v.TN);
     p.ny = (int32_t)(bk / v.TK);
+    p.n_row_b = (uint32_t)(N * es);
     const int64_t grid = (int64_t)p.nx * p.nz;
     if (grid >= lim) return fail(LCMA_ERR_SHAPE, "lcma_gemm: too many tiles");
     int panel = 8;
@@ -134,8 +144,8 @@ extern "C" lcma_status lcma_gemm(int64_t M, int64_t N, int64_t K, const void *A,
         bool any = false;
         for (int i = 0; i < kVariantCount; ++i) any |= kVariants[i].scheme_id == id && kVariants[i].dtype == (int)dtype;
         if (!any) return fail(LCMA_ERR_NOKERNEL, "lcma_gemm: no kernel for scheme id %d with dtype %d", id, (int)dtype);
-        return fail(LCMA_ERR_SHAPE, "lcma_gemm: no tile of scheme id %d divides (%lld,%lld,%lld)", id, (long long)M,
-                    (long long)N, (long long)K);
+        return fail(LCMA_ERR_SHAPE, "lcma_gemm: no kernel of scheme id %d takes N = %lld (whole 16-byte vectors) and K = %lld (whole tiles)",
+                    id, (long long)N, (long long)K);
     }
     return run(*v, M, N, K, A, lda, B, ldb, C, ldc, stream);
 }
@@ -168,8 +178,8 @@ static lcma_status prepared_scheme(const lcma_scheme *scheme, const char *who, i
 
 extern "C" int64_t lcma_prepared_b_bytes(const lcma_scheme *scheme, int64_t N, int64_t K, lcma_dtype dtype) {
     const int es = dtype_size(dtype);
-    if (!scheme || !es || N <= 0 || K <= 0 || N % scheme->n || K % scheme->k) return -1;
-    return (int64_t)scheme->R * (N / scheme->n) * (K / scheme->k) * es;
+    if (!scheme || !es || N <= 0 || K <= 0 || N % (16 / es) || K % scheme->k) return -1;
+    return (int64_t)scheme->R * (round_up(N, (int64_t)scheme->n * 64) / scheme->n) * (K / scheme->k) * es;
 }
 
 extern "C" lcma_status lcma_prepare_b(int64_t N, int64_t K, const void *B, int64_t ldb, lcma_dtype dtype,
@@ -187,13 +197,14 @@ extern "C" lcma_status lcma_prepare_b(int64_t N, int64_t K, const void *B, int64
     if ((((uintptr_t)B | (uintptr_t)Bt) & 15) || ((ldb * es) & 15))
         return fail(LCMA_ERR_ARG, "lcma_prepare_b: pointers and the leading dimension must be multiples of 16 bytes");
     const int kt = 64 / es; // k rows one work-group transposes
-    if (N % ((int64_t)scheme->n * 64) || K % ((int64_t)scheme->k * kt))
-        return fail(LCMA_ERR_SHAPE, "lcma_prepare_b: (N,K) = (%lld,%lld) is not a multiple of (%d,%d)", (long long)N,
-                    (long long)K, scheme->n * 64, scheme->k * kt);
-    const int64_t bn = N / scheme->n, bk = K / scheme->k;
+    if (N % (16 / es) || K % ((int64_t)scheme->k * kt))
+        return fail(LCMA_ERR_SHAPE, "lcma_prepare_b: N = %lld must be a multiple of %d and K = %lld of %d", (long long)N,
+                    16 / es, (long long)K, scheme->k * kt);
+    const int64_t bn = round_up(N, (int64_t)scheme->n * 64) / scheme->n, bk = K / scheme->k; // planes hold padded rows
     const int64_t b_bytes = ((K - 1) * ldb + N) * es, bt_bytes = (int64_t)scheme->R * bn * bk * es;
     const int64_t lim = (int64_t)1 << 31;
-    if (b_bytes >= lim || bt_bytes >= lim) return fail(LCMA_ERR_SHAPE, "lcma_prepare_b: a buffer spans 2 GiB or more");
+    if (((K - 1) * ldb + bn * scheme->n) * es >= lim || bt_bytes >= lim)
+        return fail(LCMA_ERR_SHAPE, "lcma_prepare_b: a buffer spans 2 GiB or more");
     if (bk / kt > 65535) return fail(LCMA_ERR_SHAPE, "lcma_prepare_b: K is too large");
     PrepParams p;
     p.B = B;
@@ -207,6 +218,7 @@ extern "C" lcma_status lcma_prepare_b(int64_t N, int64_t K, const void *B, int64
     p.bt_plane_b = (uint32_t)(bn * bk * es);
     p.bk = (int32_t)bk;
     p.bn = (int32_t)bn;
+    p.n_row_b = (uint32_t)(N * es);
     const int err = pk->launch(&p, (int)(bn / 64), (int)(bk / kt), stream);
     if (err) return fail(LCMA_ERR_HIP, "lcma_prepare_b: launch failed with HIP error %d", err);
     return LCMA_OK;
@@ -233,8 +245,8 @@ extern "C" lcma_status lcma_gemm_prepared(int64_t M, int64_t N, int64_t K, const
         if (!any)
             return fail(LCMA_ERR_NOKERNEL, "lcma_gemm_prepared: no prepared-B kernel for scheme id %d with dtype %d", id,
                         (int)dtype);
-        return fail(LCMA_ERR_SHAPE, "lcma_gemm_prepared: no tile of scheme id %d divides (%lld,%lld,%lld)", id,
-                    (long long)M, (long long)N, (long long)K);
+        return fail(LCMA_ERR_SHAPE, "lcma_gemm_prepared: no kernel of scheme id %d takes N = %lld (whole 16-byte vectors) and K = %lld (whole tiles)",
+                    id, (long long)N, (long long)K);
     }
     return run(*v, M, N, K, A, lda, Bt, N, C, ldc, stream);
 }

@@ -248,6 +248,8 @@ template <class T> struct Ctx {
     uint32_t a_lds[T::QA], b_lds[T::QB], b_lds1[T::QB]; // b_lds1: second LDS row of a 16-bit B unit
     uint32_t a_frag[T::NKK], b_frag[T::NKK];
     uint32_t c_voff; // byte offset of this lane's first output element inside the tile
+    uint32_t c_colb; // byte column of that element inside a block of C (for the N bound)
+    uint32_t b_colb[T::QB]; // byte column inside a block of B of the unit staged by this thread
 
     LCMA_DEV Ctx(const Params &p_, LCMA_LDS char *lds_) : p(p_), lds(lds_) {
         ra = __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(p.A), 0, (int)p.a_bytes, 0x00020000);
@@ -298,6 +300,7 @@ template <class T> struct Ctx {
             const int col = u % T::BCOLS, g = u / T::BCOLS; // g: group of CH consecutive k
             const int row = (T::ES == 2) ? 2 * col : col;   // LDS row = column n of the tile
             b_voff[q] = (uint32_t)(g * T::CH) * p.ldb_b + col * 4;
+            b_colb[q] = (uint32_t)z * T::TN * T::ES + col * 4;
             b_lds[q] = T::A_STAGE + row * T::ROW + T::swz(row, g) * 16;
             b_lds1[q] = T::A_STAGE + (row + 1) * T::ROW + T::swz(row + 1, g) * 16;
         }
@@ -313,13 +316,18 @@ template <class T> struct Ctx {
         // Output: accumulator register v of MFMA tile (mi, ni) is row 8*(v/4) + 4*(lane/32) + v%4,
         // column lane%32 of that 32x32 tile.
         c_voff = (uint32_t)(wm * T::WM + 4 * lh) * p.ldc_b + (uint32_t)(wn * T::WN + l32) * T::ES;
+        c_colb = (uint32_t)z * T::TN * T::ES + (uint32_t)(wn * T::WN + l32) * T::ES;
     }
 
     LCMA_DEV u32x4 load_a(int q, uint32_t soff) const {
         return __builtin_amdgcn_raw_buffer_load_b128(ra, (int)a_voff[q], (int)soff, 0);
     }
-    LCMA_DEV uint32_t load_b(int q, uint32_t soff) const {
-        return __builtin_amdgcn_raw_buffer_load_b32(rb, (int)b_voff[q], (int)soff, 0);
+    // Offset of B unit q in block column j: past N the lane reads from the end of the extent (zero).
+    LCMA_DEV uint32_t b_voff_in(int q, int j) const {
+        return ((uint32_t)j * p.b_bcol + b_colb[q] < p.n_row_b) ? b_voff[q] : p.b_bytes;
+    }
+    LCMA_DEV uint32_t load_b(uint32_t voff, uint32_t soff) const {
+        return __builtin_amdgcn_raw_buffer_load_b32(rb, (int)voff, (int)soff, 0);
     }
     // Scalar byte offset of tile y of block A_{i,l} / B_{l,j} for this group.
     LCMA_DEV uint32_t soff_a(int i, int l, int y) const {
@@ -517,10 +525,12 @@ template <class T> struct Ctx {
 #pragma unroll
             for (int ni = 0; ni < T::NNI; ++ni) {
                 const f32x16 t = f(mi, ni);
+                // a lane whose column lies past N stores to the end of the extent: dropped
+                const uint32_t base = ((uint32_t)j * p.c_bcol + c_colb + ni * 32 * T::ES < p.n_row_b) ? c_voff : p.c_bytes;
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
                     const uint32_t off =
-                        c_voff + (uint32_t)(mi * 32 + (v >> 2) * 8 + (v & 3)) * p.ldc_b + ni * 32 * T::ES;
+                        base + (uint32_t)(mi * 32 + (v >> 2) * 8 + (v & 3)) * p.ldc_b + ni * 32 * T::ES;
                     const uint32_t bits = Round<IN>::run(t[v]);
                     if constexpr (T::ES == 2)
                         __builtin_amdgcn_raw_buffer_store_b16((short)bits, rc, (int)off, (int)soff, 0);
@@ -552,9 +562,11 @@ template <class T, class CH> LCMA_DEV void issue_loads(const Ctx<T> &cx, RawSet<
     for (int t = 0; t < CH::NB; ++t) {
         const uint32_t so = cx.soff_b(CH::b_l(t), CH::b_j(t), y);
 #pragma unroll
-        for (int q = 0; q < T::QB; ++q)
+        for (int q = 0; q < T::QB; ++q) {
+            const uint32_t vo = cx.b_voff_in(q, CH::b_j(t));
 #pragma unroll
-            for (int e = 0; e < T::BW; ++e) r.b[t][q][e / 4][e % 4] = cx.load_b(q, so + (uint32_t)e * cx.p.ldb_b);
+            for (int e = 0; e < T::BW; ++e) r.b[t][q][e / 4][e % 4] = cx.load_b(vo, so + (uint32_t)e * cx.p.ldb_b);
+        }
     }
 }
 
@@ -658,6 +670,8 @@ template <class T, class CH> struct FlatStage {
                 const int row = (T::ES == 2) ? 2 * col : col;
                 b_voff[q] = (uint32_t)CH::b_l(t) * cx.p.b_brow + (uint32_t)CH::b_j(t) * cx.p.b_bcol +
                             (uint32_t)(g * T::CH) * cx.p.ldb_b + col * 4;
+                // columns past N: read from the end of the extent (zero) for the whole run
+                if ((uint32_t)CH::b_j(t) * cx.p.b_bcol + cx.b_group + col * 4 >= cx.p.n_row_b) b_voff[q] = cx.p.b_bytes;
                 b_lds[q] = T::A_STAGE + t * T::B_SLOT + row * T::ROW + T::swz(row, g) * 16;
                 b_lds1[q] = T::A_STAGE + t * T::B_SLOT + (row + 1) * T::ROW + T::swz(row + 1, g) * 16;
             }

@@ -1,4 +1,10 @@
 // Kernel argument block shared by the host launcher and the generated gfx950 kernels.
+//
+// Ragged M and N.  The blocks of the scheme are cut from the matrices padded (virtually, with zeros)
+// to whole tiles: the block steps below are those of the padded sizes, the byte extents are the true
+// ones.  Rows past M fall outside the extents: gfx950 range-checks voffset + soffset per lane against
+// the descriptor, returns 0 for such loads and drops such stores (measured).  Columns past N would
+// alias the next row, so lanes that own them get an offset at the end of the extent instead.
 #pragma once
 #include <stdint.h>
 
@@ -16,6 +22,7 @@ struct Params {
     uint32_t c_brow, c_bcol;            // byte step from block C_{i,j} to C_{i+1,j} / C_{i,j+1}
     int32_t nx, nz, ny;                 // tiles per block along M/m, N/n and K/k (Algorithm 2's x, z, y ranges in tiles)
     int32_t panel;                      // width (in z tiles) of a column panel in the tile order
+    uint32_t n_row_b;                   // N * element size: columns at or beyond it are padding (read as 0, never written)
 };
 
 // Argument block of the offline Combine-B kernels.
@@ -27,7 +34,8 @@ struct PrepParams {
     uint32_t b_brow, b_bcol;    // byte step from block B_{l,j} to B_{l+1,j} / B_{l,j+1}
     uint32_t bt_ld_b;           // row pitch of a plane in bytes = (K/k) * ES
     uint32_t bt_plane_b;        // plane stride in bytes = (N/n) * (K/k) * ES
-    int32_t bk, bn;             // K/k, N/n
+    int32_t bk, bn;             // K/k, padded N/n
+    uint32_t n_row_b;           // N * element size of B: columns at or beyond it are read as 0
 };
 
 } // namespace lcma

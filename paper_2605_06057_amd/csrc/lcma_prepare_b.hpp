@@ -64,8 +64,10 @@ template <class IN, class CT, class CH> LCMA_DEV void prepare_b_tile(const PrepP
     float in[CH::NB][EPT];
 #pragma unroll
     for (int t = 0; t < CH::NB; ++t) {
-        const uint32_t off = (uint32_t)CH::b_l(t) * p.b_brow + (uint32_t)CH::b_j(t) * p.b_bcol +
-                             (uint32_t)(y0 + ky) * p.ldb_b + (uint32_t)(z0 + tx * EPT) * ES;
+        const uint32_t colb = (uint32_t)CH::b_j(t) * p.b_bcol + (uint32_t)(z0 + tx * EPT) * ES;
+        // columns past N are padding: read from the end of the extent, which returns zero
+        const uint32_t off = colb < p.n_row_b ? (uint32_t)CH::b_l(t) * p.b_brow + (uint32_t)(y0 + ky) * p.ldb_b + colb
+                                              : p.b_bytes;
         Widen<IN>::run(__builtin_amdgcn_raw_buffer_load_b128(rb, (int)off, 0, 0), in[t]);
     }
     // read-back assignment: 4 threads per output row, 16 bytes each

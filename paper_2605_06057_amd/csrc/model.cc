@@ -38,7 +38,9 @@ static int nnz(const std::vector<int8_t> &v) {
 
 double predict_variant(const Variant &v, int64_t M, int64_t N, int64_t K) {
     const int es = dtype_size(v.dtype);
-    const double dM = (double)M, dN = (double)N, dK = (double)K;
+    // padded to whole tiles, as the kernels run them
+    const double dM = std::ceil((double)M / (v.m * v.TM)) * (v.m * v.TM),
+                 dN = std::ceil((double)N / (v.n * v.TN)) * (v.n * v.TN), dK = (double)K;
     const double groups = (dM / (v.m * v.TM)) * (dN / (v.n * v.TN));
     const double slots = (double)kUnits * v.occ;
     const double quant = std::ceil(groups / slots) * slots / groups; // idle share of the last wave

@@ -94,6 +94,30 @@ def test_float_inputs_within_bounds(B, v):
     assert err <= ratio_bound * err_plain
 
 
+@pytest.mark.parametrize("v", variants(), ids=lambda v: v["name"])
+def test_ragged_m_and_n_bit_exact(B, v):
+    """M and N that are not whole tiles (rows and columns past the end count as zero and must never be
+    written): integer inputs, exact result, guard rows and columns around C untouched."""
+    import torch
+    import gpu_util as G
+    dt = DT[v["dtype"]]
+    vec = 4 if dt == "f32" else 8
+    for M, N in ((v["mult_M"] + 37, v["mult_N"] + 3 * vec), (5, vec), (2 * v["mult_M"] - 1, 2 * v["mult_N"] - vec)):
+        K = 2 * v["mult_K"]
+        print(f"variant {v['name']} ragged shape {M}x{N}x{K}", flush=True)
+        Ai, Bi = inp.integers(101, 3, (M, K)), inp.integers(101, 4, (K, N))
+        want = inp.store(oracle.gemm(Ai, Bi).astype(np.float64), dt)
+        a, b = G.to_device(inp.store(Ai, dt), dt), G.to_device(inp.store(Bi, dt), dt)
+        big = G.empty_like_c(M + 2, N + 2 * vec, dt, fill=7.0)
+        c = big[1:M + 1, vec:vec + N]
+        run_variant(B, v, a, b, c)
+        got = G.to_host_stored(c, dt)
+        assert np.array_equal(got.view(np.uint8), want.view(np.uint8)), (M, N)
+        guard = big.clone()
+        guard[1:M + 1, vec:vec + N] = 7.0
+        assert torch.all(guard == 7.0).item(), f"{v['name']} {M}x{N}: wrote outside C"
+
+
 def test_strided_views_and_dispatch(B):
     """lda/ldb/ldc larger than the rows, scheme handles through lcma_gemm (default variant choice)."""
     import torch
@@ -124,7 +148,7 @@ def test_error_paths_launch_nothing(B, tmp_path):
     c = torch.full((256, 256), 3.0, dtype=torch.float16, device="cuda")
     s = B.lcma_scheme_load("builtin:strassen")
     with pytest.raises(B.LcmaError) as e:
-        B.lcma_gemm(a[:200], a, c[:200], s)  # 200 rows: not a multiple of the tile
+        B.lcma_gemm(a[:, :200], a[:200], c, s)  # K = 200: not a multiple of the tile depth
     assert e.value.status == B.LCMA_ERR_SHAPE
     with pytest.raises(B.LcmaError) as e:
         B.lcma_gemm(a[:, 1:249], a[:248], c[:, :256], None)  # misaligned A pointer

@@ -86,19 +86,40 @@ def test_gemm_prepared_integer_bit_exact_and_float_bounds(B, dt):
     assert err <= 1.05 * err_fused
 
 
+@pytest.mark.parametrize("dt", ["bf16", "f16", "f32"])
+def test_prepare_b_ragged_n(B, dt):
+    """N that is not a whole number of tiles: the planes hold the padded rows, filled with zeros."""
+    import gpu_util as G
+    s = S.strassen()
+    h = B.lcma_scheme_load("builtin:strassen")
+    vec = 4 if dt == "f32" else 8
+    N, K = 128 + 5 * vec, 128
+    _, Bs = inp.matrices("uniform", "uniform", 64, N, K, dt, seed=17)
+    bt = B.lcma_prepare_b(G.to_device(Bs, dt), h)
+    assert tuple(bt.shape) == (7, 128, K // 2)          # N/n padded from 64 + 2.5 vec to 128
+    got = prepared_to_host(bt)
+    padded = np.zeros((K, 256))
+    Bw = inp.widen(Bs, dt)
+    # blocks are cut from the padded matrix: block column j starts at j * 128
+    padded[:, :N] = Bw
+    want = oracle.combine_b_stored(s, padded, dt)
+    assert np.array_equal(got, want)
+
+
 def test_prepared_error_paths_launch_nothing(B):
     import torch
     h = B.lcma_scheme_load("builtin:strassen")
     b = torch.ones((256, 256), dtype=torch.float16, device="cuda")
     with pytest.raises(B.LcmaError) as e:
-        B.lcma_prepare_b(b[:, :192], h)                     # N/n = 96 is not a multiple of 64
+        B.lcma_prepare_b(b[:200], h)                        # K/k = 100 is not a multiple of 32
     assert e.value.status == B.LCMA_ERR_SHAPE
     with pytest.raises(B.LcmaError) as e:
         B.lcma_prepare_b(b[:, 1:129], h)                    # misaligned pointer
     assert e.value.status == B.LCMA_ERR_ARG
     h2 = B.lcma_scheme_load("builtin:laderman")
     assert B.lcma_prepared_b_bytes(h2, 384, 384, B.LCMA_F16) == 23 * 128 * 128 * 2
-    assert B.lcma_prepared_b_bytes(h2, 256, 384, B.LCMA_F16) == -1   # N not a multiple of n
+    assert B.lcma_prepared_b_bytes(h2, 256, 384, B.LCMA_F16) == 23 * 128 * 128 * 2   # N padded to 3 * 128
+    assert B.lcma_prepared_b_bytes(h2, 250, 384, B.LCMA_F16) == -1   # rows of B must stay 16-byte granular
     bt3 = torch.zeros((23, 128, 128), dtype=torch.float16, device="cuda")
     with pytest.raises(B.LcmaError) as e:                   # no prepared-B kernels for Laderman
         B.lcma_prepare_b(torch.ones((384, 384), dtype=torch.float16, device="cuda"), h2, bt3)
@@ -106,7 +127,7 @@ def test_prepared_error_paths_launch_nothing(B):
     bt = B.lcma_prepare_b(b, h)
     c = torch.full((200, 256), 3.0, dtype=torch.float16, device="cuda")
     with pytest.raises(B.LcmaError) as e:
-        B.lcma_gemm_prepared(b[:200], bt, c, h)             # M = 200: not a multiple of the tile
+        B.lcma_gemm_prepared(b[:200, :200], bt, c, h)       # K = 200: not a multiple of the tile depth
     assert e.value.status == B.LCMA_ERR_SHAPE
     torch.cuda.synchronize()
     assert torch.all(c == 3.0) and torch.all(bt3 == 0)
