@@ -451,7 +451,7 @@ def manifest() -> list[Variant]:
         Variant("plain", "f32", 256, 128, 16, wgm=2, wgn=4, eff=0.917),
         Variant("plain", "f32", 128, 128, 16, occ=2, eff=0.916),
         Variant("plain", "f32", 64, 64, 16, eff=0.856),
-        Variant("strassen", "f32", 64, 64, 16, chunk=7, fc=1, occ=2, pipe=2, eff=0.819),
+        Variant("strassen", "f32", 64, 64, 16, chunk=7, fc=1, occ=2, pipe=2, eff=0.87),
         Variant("strassen", "f32", 128, 64, 16, chunk=7, fc=1, wgm=4, wgn=2, pipe=2, eff=0.802),
         Variant("strassen", "f32", 128, 64, 16, chunk=7, fc=1, wgm=4, wgn=2, pipe=2, pb=1, eff=0.875),
         Variant("strassen", "f32", 64, 64, 16, chunk=7, fc=1, pipe=2, pb=1, eff=0.74),
