@@ -42,10 +42,15 @@ double predict_variant(const Variant &v, int64_t M, int64_t N, int64_t K) {
     const double dM = std::ceil((double)M / (v.m * v.TM)) * (v.m * v.TM),
                  dN = std::ceil((double)N / (v.n * v.TN)) * (v.n * v.TN), dK = (double)K;
     const double groups = (dM / (v.m * v.TM)) * (dN / (v.n * v.TN));
+    // Work-groups run in rounds of 256 * occ.  A round that leaves every CU with a single work-group
+    // of a kernel built for two per CU is shorter than a full one: alone, a work-group takes ~0.63 of
+    // the time it takes beside a neighbour (measured on the plain and Strassen kernels).
     const double slots = (double)kUnits * v.occ;
-    const double quant = std::ceil(groups / slots) * slots / groups; // idle share of the last wave
-    const double mfma_flops = 2.0 * dM * dN * dK * v.products / ((double)v.m * v.n * v.k);
-    const double t_mfma = mfma_flops / (v.eff * mfma_peak(v.dtype)) * quant;
+    const double t_round = slots * (2.0 * v.TM * v.TN * dK * v.products / v.k) / (v.eff * mfma_peak(v.dtype));
+    const double full = std::floor(groups / slots), rest = groups - full * slots;
+    double rounds = full;
+    if (rest > 0) rounds += (v.occ > 1 && rest <= kUnits) ? 0.63 : 1.0;
+    const double t_mfma = rounds * t_round;
     const double t_hbm = (dM * dK + dK * dN + dM * dN) * es / kHbmBytes;
     return std::max(t_hbm, t_mfma) + kLaunch;
 }

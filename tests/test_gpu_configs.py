@@ -75,3 +75,46 @@ def test_selector_sweep_runs_its_pick():
             err = oracle.rel_frobenius(G.to_host_f64(c[torch.from_numpy(rows).cuda()], dt), ref)
             print(f"sweep {M}x{N}x{K}: pick {B.SCHEME_NAMES[pick]} relF {err:.3e}", flush=True)
             assert err <= 2e-2
+
+
+def test_selector_pick_is_close_to_the_measured_best():
+    """Decision Module (Sec. 3.3) against the clock: on a few shapes, time every scheme that has a kernel
+    and require lcma_select's pick to be within 12 % of the fastest (all timings from this one run)."""
+    import torch
+    from paper_2605_06057_amd import binding as B
+
+    def seconds(fn, iters=12, warm=4):
+        for _ in range(warm):
+            fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(iters):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / iters * 1e-3
+
+    schemes = {i: (B.lcma_scheme_load("builtin:" + n) if i else None) for i, n in B.SCHEME_NAMES.items()}
+    cases = [("bf16", 4096, 4096, 4096), ("bf16", 2048, 14336, 4096), ("bf16", 1000, 4096, 4096),
+             ("f16", 3072, 3072, 3072), ("f32", 4096, 4096, 4096), ("f32", 1024, 1024, 1024), ("f32", 3000, 4096, 2048)]
+    heat = torch.randn(4096, 4096, device="cuda", dtype=torch.bfloat16)
+    for _ in range(300):  # settle the clocks
+        torch.mm(heat, heat)
+    for dt, M, N, K in cases:
+        td = {"bf16": torch.bfloat16, "f16": torch.float16, "f32": torch.float32}[dt]
+        a = torch.randn(M, K, device="cuda").to(td)
+        b = (torch.randn(K, N, device="cuda") * 0.05).to(td)
+        c = torch.empty(M, N, device="cuda", dtype=td)
+        times = {}
+        for i, s in schemes.items():
+            try:
+                times[i] = seconds(lambda: B.lcma_gemm(a, b, c, s))
+            except B.LcmaError:
+                pass  # no kernel of this scheme for the dtype or shape
+        pick = B.lcma_select(M, N, K, B.DTYPE_IDS[dt])
+        best = min(times, key=times.get)
+        tf = {B.SCHEME_NAMES[i]: round(2.0 * M * N * K / t / 1e12, 1) for i, t in times.items()}
+        print(f"{dt} {M}x{N}x{K}: pick {B.SCHEME_NAMES[pick]}, measured TFLOP/s {tf}", flush=True)
+        assert pick in times
+        assert times[pick] <= 1.12 * times[best], (dt, M, N, K, B.SCHEME_NAMES[pick], B.SCHEME_NAMES[best])
