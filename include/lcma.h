@@ -80,11 +80,10 @@ lcma_status lcma_scheme_coeffs(const lcma_scheme *s, int8_t *U, int8_t *V, int8_
  * `stream` (a hipStream_t; NULL = the default stream).  `dtype` is the storage type of
  * all three matrices.  scheme == NULL runs the plain MFMA GEMM; otherwise the scheme
  * must pass lcma_scheme_verify (run and cached on first use) and have a generated
- * kernel.  Shapes: M is free; N must be a multiple of 16 bytes of elements (8 for the
- * 16-bit types, 4 for F32); K must be a multiple of k*TK of some kernel of the scheme
- * (64 for the 16-bit Strassen kernels, 32 for F32).  The blocks of the scheme (the paper
- * takes ceil(M/m) x ceil(K/k) etc., Sec. 2.1) are cut from the matrices padded with zero
- * rows and columns to whole tiles; the padding is never read from or written to memory.
+ * kernel.  Shapes: M is free; N and K must be multiples of 16 bytes of elements (8 for the
+ * 16-bit types, 4 for F32).  The blocks of the scheme (the paper takes ceil(M/m) x
+ * ceil(K/k) etc., Sec. 2.1) are cut from the matrices padded with zero rows and columns
+ * to whole tiles; the padding is never read from or written to memory.
  * Pointers must be 16-byte aligned and lda, ldb, ldc multiples of 16 bytes; each
  * matrix, padded to whole tiles, must span less than 2 GiB.  With 16-bit inputs the combinations of Eq. 3/4 are
  * formed and multiplied in fp16 (bf16 inputs are converted exactly for |x| in
@@ -105,8 +104,8 @@ lcma_status lcma_gemm(int64_t M, int64_t N, int64_t K,
 int lcma_variant_count(void);
 const char *lcma_variant_name(int index); /* NULL when out of range */
 /* Describes variant `index`: builtin scheme id, dtype, tile sizes and the granules m*TM, n*TN,
- * k*TK in which it works through M, N, K (any pointer may be NULL).  K must be a multiple of its
- * granule; M and N are padded up to theirs (full tiles cost the same whether padded or not). */
+ * k*TK in which it works through M, N, K (any pointer may be NULL).  Sizes are padded up to the
+ * granules (a tile costs the same whether it is full or mostly padding). */
 lcma_status lcma_variant_info(int index, int *scheme_id, int *dtype, int *TM, int *TN, int *TK,
                               int *mult_M, int *mult_N, int *mult_K);
 lcma_status lcma_gemm_variant(const char *variant, int64_t M, int64_t N, int64_t K,
@@ -124,12 +123,13 @@ int lcma_variant_prepared(int index);
  * transposed, N/n rows of K/k elements, k-contiguous, in the type the products are multiplied in
  * (fp16 for BF16 and F16 storage, fp32 for F32).  The terms of a sum are added in fp32 in ascending
  * (l, j) order and the sum is rounded once, to nearest-even.  B: device, K x N row-major, ldb in
- * elements (multiple of 16 bytes).  N must be a multiple of 16 bytes of elements and is padded with
- * zero columns to a multiple of 64 n (the planes hold the padded N/n rows); K must be a multiple of
- * 32 k (16 k for F32); both buffers stay below 2 GiB.  Asynchronous on `stream`.  Errors: ARG, BRENT, SHAPE, DTYPE, NOKERNEL
+ * elements (multiple of 16 bytes).  N and K must be multiples of 16 bytes of elements; the planes
+ * hold N/n rows and K/k columns padded with zeros to multiples of 64 and of 32 (16 for F32); both
+ * buffers stay below 2 GiB.  Asynchronous on `stream`.  Errors: ARG, BRENT, SHAPE, DTYPE, NOKERNEL
  * (no prepared-B kernels were generated for this scheme and dtype), HIP.
  *
- * lcma_prepared_b_bytes returns R * (padded N/n) * (K/k) * element size, or -1 for a bad argument.
+ * lcma_prepared_b_bytes returns R * (padded N/n) * (padded K/k) * element size, or -1 for a bad
+ * argument.
  *
  * lcma_gemm_prepared computes what lcma_gemm computes, C = A B, with Bt in place of B: Combine A
  * (Eq. 3) on MFMA fragments, H_r (Eq. 5) and the W-combination (Eq. 6) in fp32, nothing written to

@@ -201,12 +201,14 @@ def lcma_prepare_b(B, scheme: Scheme, Bt=None):
     dt = _dtype_of(B)
     nbytes = lcma_prepared_b_bytes(scheme, N, K, dt)
     if nbytes < 0:
-        raise LcmaError(f"lcma_prepared_b_bytes: bad arguments (N={N}, K={K})")
+        raise LcmaError(LCMA_ERR_SHAPE, f"lcma_prepare_b: N = {N} and K = {K} must be whole 16-byte vectors of elements")
     info = lcma_scheme_info(scheme)
     ct = torch.float32 if B.dtype == torch.float32 else torch.float16
-    if Bt is None:  # N/n rows per plane, padded to whole tiles
-        rows = nbytes // (info["R"] * (K // info["k"]) * B.element_size())
-        Bt = torch.empty((info["R"], rows, K // info["k"]), device=B.device, dtype=ct)
+    if Bt is None:  # planes of N/n rows and K/k columns, both padded to whole tiles of the Combine-B kernel
+        kt = 64 // B.element_size()
+        cols = -(-K // (info["k"] * kt)) * kt
+        rows = nbytes // (info["R"] * cols * B.element_size())
+        Bt = torch.empty((info["R"], rows, cols), device=B.device, dtype=ct)
     assert Bt.is_cuda and Bt.is_contiguous() and Bt.dtype == ct and Bt.numel() * Bt.element_size() == nbytes
     stream = torch.cuda.current_stream(B.device).cuda_stream
     _check(lib().lcma_prepare_b(N, K, B.data_ptr(), B.stride(0), dt, scheme.handle, Bt.data_ptr(), stream))

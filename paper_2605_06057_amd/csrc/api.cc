@@ -18,12 +18,13 @@ lcma_status fail(lcma_status st, const char *fmt, ...) {
     return st;
 }
 
-// M is free (rows past M are padding the kernels never touch), N must keep rows 16-byte granular,
-// K must be whole tiles of every block.
+// M is free (rows past M are padding the kernels never touch); N and K must keep rows 16-byte
+// granular.
 bool variant_fits(const Variant &v, int64_t M, int64_t N, int64_t K) {
     (void)M;
+    (void)v;
     const int vec = 16 / dtype_size(v.dtype);
-    return N % vec == 0 && K % ((int64_t)v.k * v.TK) == 0;
+    return N % vec == 0 && K % vec == 0;
 }
 static bool fits(const Variant &v, int64_t M, int64_t N, int64_t K) { return variant_fits(v, M, N, K); }
 static int64_t round_up(int64_t x, int64_t g) { return (x + g - 1) / g * g; }
@@ -66,17 +67,18 @@ static lcma_status run(const Variant &v, int64_t M, int64_t N, int64_t K, const 
     if (((lda * es) | (ldb * es) | (ldc * es)) & 15)
         return fail(LCMA_ERR_ARG, "lcma_gemm: leading dimensions must be multiples of 16 bytes");
     if (!fits(v, M, N, K))
-        return fail(LCMA_ERR_SHAPE, "lcma_gemm: %s needs K = %lld to be a multiple of %d and N = %lld of %d",
-                    v.name, (long long)K, v.k * v.TK, (long long)N, 16 / es);
+        return fail(LCMA_ERR_SHAPE, "lcma_gemm: N = %lld and K = %lld must be multiples of %d (16 bytes of elements)",
+                    (long long)N, (long long)K, 16 / es);
     // blocks are cut from the matrices padded to whole tiles; the extents stay the true ones
-    const int64_t Mp = round_up(M, (int64_t)v.m * v.TM), Np = round_up(N, (int64_t)v.n * v.TN);
-    const int64_t bm = Mp / v.m, bn = Np / v.n, bk = K / v.k;
+    const int64_t Mp = round_up(M, (int64_t)v.m * v.TM), Np = round_up(N, (int64_t)v.n * v.TN),
+                  Kp = round_up(K, (int64_t)v.k * v.TK);
+    const int64_t bm = Mp / v.m, bn = Np / v.n, bk = Kp / v.k;
     const int64_t a_bytes = ((M - 1) * lda + K) * es,
                   b_bytes = v.prepared ? (int64_t)v.products * bn * bk * es : ((K - 1) * ldb + N) * es,
                   c_bytes = ((M - 1) * ldc + N) * es;
     const int64_t lim = (int64_t)1 << 31;
     // offsets of padded rows and columns are formed in 32 bits before the range check drops them
-    if (((Mp - 1) * lda + K) * es >= lim || ((K - 1) * ldb + Np) * es >= lim || ((Mp - 1) * ldc + Np) * es >= lim ||
+    if (((Mp - 1) * lda + Kp) * es >= lim || ((Kp - 1) * ldb + Np) * es >= lim || ((Mp - 1) * ldc + Np) * es >= lim ||
         b_bytes >= lim)
         return fail(LCMA_ERR_SHAPE, "lcma_gemm: a matrix spans 2 GiB or more");
     Params p;
@@ -104,6 +106,12 @@ static lcma_status run(const Variant &v, int64_t M, int64_t N, int64_t K, const 
     p.nz = (int32_t)(bn / v.TN);
     p.ny = (int32_t)(bk / v.TK);
     p.n_row_b = (uint32_t)(N * es);
+    p.k_row_b = (uint32_t)(K * es);
+    {   // first byte column inside the last block column of A whose tile reaches past K
+        const int64_t valid = K - (int64_t)(v.k - 1) * bk; // columns of the last block inside K (may be <= 0)
+        const int64_t whole = valid <= 0 ? 0 : valid / v.TK * v.TK;
+        p.k_tail_b = (uint32_t)(whole * es);
+    }
     const int64_t grid = (int64_t)p.nx * p.nz;
     if (grid >= lim) return fail(LCMA_ERR_SHAPE, "lcma_gemm: too many tiles");
     int panel = 8;
@@ -178,8 +186,9 @@ static lcma_status prepared_scheme(const lcma_scheme *scheme, const char *who, i
 
 extern "C" int64_t lcma_prepared_b_bytes(const lcma_scheme *scheme, int64_t N, int64_t K, lcma_dtype dtype) {
     const int es = dtype_size(dtype);
-    if (!scheme || !es || N <= 0 || K <= 0 || N % (16 / es) || K % scheme->k) return -1;
-    return (int64_t)scheme->R * (round_up(N, (int64_t)scheme->n * 64) / scheme->n) * (K / scheme->k) * es;
+    if (!scheme || !es || N <= 0 || K <= 0 || N % (16 / es) || K % (16 / es)) return -1;
+    return (int64_t)scheme->R * (round_up(N, (int64_t)scheme->n * 64) / scheme->n) *
+           (round_up(K, (int64_t)scheme->k * (64 / es)) / scheme->k) * es;
 }
 
 extern "C" lcma_status lcma_prepare_b(int64_t N, int64_t K, const void *B, int64_t ldb, lcma_dtype dtype,
@@ -197,13 +206,15 @@ extern "C" lcma_status lcma_prepare_b(int64_t N, int64_t K, const void *B, int64
     if ((((uintptr_t)B | (uintptr_t)Bt) & 15) || ((ldb * es) & 15))
         return fail(LCMA_ERR_ARG, "lcma_prepare_b: pointers and the leading dimension must be multiples of 16 bytes");
     const int kt = 64 / es; // k rows one work-group transposes
-    if (N % (16 / es) || K % ((int64_t)scheme->k * kt))
-        return fail(LCMA_ERR_SHAPE, "lcma_prepare_b: N = %lld must be a multiple of %d and K = %lld of %d", (long long)N,
-                    16 / es, (long long)K, scheme->k * kt);
-    const int64_t bn = round_up(N, (int64_t)scheme->n * 64) / scheme->n, bk = K / scheme->k; // planes hold padded rows
+    if (N % (16 / es) || K % (16 / es))
+        return fail(LCMA_ERR_SHAPE, "lcma_prepare_b: N = %lld and K = %lld must be multiples of %d", (long long)N,
+                    (long long)K, 16 / es);
+    // the planes hold the padded rows and columns (zeros)
+    const int64_t bn = round_up(N, (int64_t)scheme->n * 64) / scheme->n,
+                  bk = round_up(K, (int64_t)scheme->k * kt) / scheme->k;
     const int64_t b_bytes = ((K - 1) * ldb + N) * es, bt_bytes = (int64_t)scheme->R * bn * bk * es;
     const int64_t lim = (int64_t)1 << 31;
-    if (((K - 1) * ldb + bn * scheme->n) * es >= lim || bt_bytes >= lim)
+    if (((bk * scheme->k - 1) * ldb + bn * scheme->n) * es >= lim || bt_bytes >= lim)
         return fail(LCMA_ERR_SHAPE, "lcma_prepare_b: a buffer spans 2 GiB or more");
     if (bk / kt > 65535) return fail(LCMA_ERR_SHAPE, "lcma_prepare_b: K is too large");
     PrepParams p;

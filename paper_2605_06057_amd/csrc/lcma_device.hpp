@@ -334,8 +334,19 @@ template <class T> struct Ctx {
         c_colb = (uint32_t)z * T::TN * T::ES + (uint32_t)(wn * T::WN + l32) * T::ES;
     }
 
-    LCMA_DEV u32x4 load_a(int q, uint32_t soff) const {
-        return __builtin_amdgcn_raw_buffer_load_b128(ra, (int)a_voff[q], (int)soff, 0);
+    // Ragged K.  True (uniformly) in the y steps in which the last block column of A reaches past K.
+    LCMA_DEV bool k_tail(int y) const { return (uint32_t)(y + 1) * (T::TK * T::ES) > p.k_tail_b; }
+    // In such a step: `voff` if the 16-byte chunk at byte column `colb` of the matrix lies inside K,
+    // else the end of the extent (the load returns zero).  The column of a thread's chunk is worked
+    // out again from its thread index there rather than kept in a register through the whole loop.
+    LCMA_DEV uint32_t a_inside(uint32_t voff, uint32_t colb) const { return colb < p.k_row_b ? voff : p.a_bytes; }
+    LCMA_DEV u32x4 load_a(int q, uint32_t soff, int l, int y) const {
+        uint32_t vo = a_voff[q];
+        if (k_tail(y)) {
+            const int c = ((q * T::NT + (int)threadIdx.x) % T::NCHK_A) % T::CPR;
+            vo = a_inside(vo, (uint32_t)l * p.a_bcol + (uint32_t)y * (T::TK * T::ES) + c * 16);
+        }
+        return __builtin_amdgcn_raw_buffer_load_b128(ra, (int)vo, (int)soff, 0);
     }
     // Offset of B unit q in block column j: past N the lane reads from the end of the extent (zero).
     LCMA_DEV uint32_t b_voff_in(int q, int j) const {
@@ -578,7 +589,7 @@ template <class T, class CH> LCMA_DEV void issue_loads(const Ctx<T> &cx, RawSet<
     for (int t = 0; t < CH::NA; ++t) {
         const uint32_t so = cx.soff_a(CH::a_i(t), CH::a_l(t), y);
 #pragma unroll
-        for (int q = 0; q < T::QA; ++q) r.a[t][q] = cx.load_a(q, so);
+        for (int q = 0; q < T::QA; ++q) r.a[t][q] = cx.load_a(q, so, CH::a_l(t), y);
     }
 #pragma unroll
     for (int t = 0; t < CH::NB; ++t) {
@@ -699,6 +710,16 @@ template <class T, class CH> struct FlatStage {
             }
         }
     }
+    // offset of A chunk q in step y (ragged K: the end of the extent when the chunk lies past K)
+    LCMA_DEV uint32_t a_off(const Ctx<T> &cx, int q, int y) const {
+        uint32_t vo = a_voff[q];
+        if (cx.k_tail(y)) {
+            const int id = (q * T::NT + (int)threadIdx.x) % NCA;
+            const int t = id / T::NCHK_A, c = (id % T::NCHK_A) % T::CPR;
+            vo = cx.a_inside(vo, (uint32_t)CH::a_l(t) * cx.p.a_bcol + (uint32_t)y * (T::TK * T::ES) + c * 16);
+        }
+        return vo;
+    }
     LCMA_DEV void load_b(const Ctx<T> &cx, Raw &r, int q, int y) const {
         if constexpr (T::PB) {
             const uint32_t sbo = cx.b_group + (uint32_t)y * (T::TK * T::ES);
@@ -714,7 +735,7 @@ template <class T, class CH> struct FlatStage {
     LCMA_DEV void issue(const Ctx<T> &cx, Raw &r, int y) const {
         const uint32_t sa = cx.a_group + (uint32_t)y * (T::TK * T::ES);
 #pragma unroll
-        for (int q = 0; q < QA; ++q) r.a[q] = __builtin_amdgcn_raw_buffer_load_b128(cx.ra, (int)a_voff[q], (int)sa, 0);
+        for (int q = 0; q < QA; ++q) r.a[q] = __builtin_amdgcn_raw_buffer_load_b128(cx.ra, (int)a_off(cx, q, y), (int)sa, 0);
 #pragma unroll
         for (int q = 0; q < QB; ++q) load_b(cx, r, q, y);
     }
@@ -724,7 +745,7 @@ template <class T, class CH> struct FlatStage {
     LCMA_DEV void issue_piece(const Ctx<T> &cx, Raw &r, int pc, int y) const {
         if (pc < QA) {
             const uint32_t sa = cx.a_group + (uint32_t)y * (T::TK * T::ES);
-            r.a[pc] = __builtin_amdgcn_raw_buffer_load_b128(cx.ra, (int)a_voff[pc], (int)sa, 0);
+            r.a[pc] = __builtin_amdgcn_raw_buffer_load_b128(cx.ra, (int)a_off(cx, pc, y), (int)sa, 0);
         } else {
             load_b(cx, r, pc - QA, y);
         }
@@ -807,10 +828,15 @@ template <class T, class CH> struct DirectStage {
     LCMA_DEV void issue_piece(const Ctx<T> &cx, int pc, int st, int y) const {
         if (pc < QA) {
             const int first = pc * T::NT + wave_chunk;
+            uint32_t vo = a_voff[pc];
+            if (cx.k_tail(y)) {
+                const int pp = (pc * T::NT + (int)threadIdx.x) % NCA;
+                const int t = pp / T::NCHK_A, row = (pp % T::NCHK_A) / T::CPR, cs = (pp % T::NCHK_A) % T::CPR;
+                vo = cx.a_inside(vo, (uint32_t)CH::a_l(t) * cx.p.a_bcol + (uint32_t)y * (T::TK * T::ES) + T::swz(row, cs) * 16);
+            }
             if (first < NCA)
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(cx.ra, (LCMA_LDS void *)(cx.lds + st * T::STAGE + first * 16), 16,
-                                                         (int)a_voff[pc], (int)(cx.a_group + (uint32_t)y * (T::TK * T::ES)),
-                                                         0, 0);
+                                                         (int)vo, (int)(cx.a_group + (uint32_t)y * (T::TK * T::ES)), 0, 0);
         } else {
             const int q = pc - QA, first = q * T::NT + wave_chunk;
             if (first < NCB)

@@ -5,6 +5,9 @@
 // ones.  Rows past M fall outside the extents: gfx950 range-checks voffset + soffset per lane against
 // the descriptor, returns 0 for such loads and drops such stores (measured).  Columns past N would
 // alias the next row, so lanes that own them get an offset at the end of the extent instead.
+// Ragged K: rows of B past K fall outside the extent as well; columns of A past K (only in the last
+// block column, only in its last y steps) get the offset at the end of the extent, decided in those
+// steps alone.
 #pragma once
 #include <stdint.h>
 
@@ -23,6 +26,9 @@ struct Params {
     int32_t nx, nz, ny;                 // tiles per block along M/m, N/n and K/k (Algorithm 2's x, z, y ranges in tiles)
     int32_t panel;                      // width (in z tiles) of a column panel in the tile order
     uint32_t n_row_b;                   // N * element size: columns at or beyond it are padding (read as 0, never written)
+    uint32_t k_row_b;                   // K * element size: columns of A at or beyond it are padding (read as 0)
+    uint32_t k_tail_b;                  // byte column inside a block from which the LAST block column of A may
+                                        // run past K: K*ES - (k-1)*a_bcol, rounded down to whole tiles
 };
 
 // Argument block of the offline Combine-B kernels.

@@ -95,15 +95,17 @@ def test_float_inputs_within_bounds(B, v):
 
 
 @pytest.mark.parametrize("v", variants(), ids=lambda v: v["name"])
-def test_ragged_m_and_n_bit_exact(B, v):
-    """M and N that are not whole tiles (rows and columns past the end count as zero and must never be
-    written): integer inputs, exact result, guard rows and columns around C untouched."""
+def test_ragged_shapes_bit_exact(B, v):
+    """M, N and K that are not whole tiles (rows and columns past the end count as zero and must never
+    be written): integer inputs, exact result, guard rows and columns around C untouched."""
     import torch
     import gpu_util as G
     dt = DT[v["dtype"]]
     vec = 4 if dt == "f32" else 8
-    for M, N in ((v["mult_M"] + 37, v["mult_N"] + 3 * vec), (5, vec), (2 * v["mult_M"] - 1, 2 * v["mult_N"] - vec)):
-        K = 2 * v["mult_K"]
+    for M, N, K in ((v["mult_M"] + 37, v["mult_N"] + 3 * vec, 2 * v["mult_K"]),
+                    (5, vec, v["mult_K"] + vec),
+                    (2 * v["mult_M"] - 1, 2 * v["mult_N"] - vec, 3 * v["mult_K"] - 2 * vec),
+                    (v["mult_M"], v["mult_N"], vec)):
         print(f"variant {v['name']} ragged shape {M}x{N}x{K}", flush=True)
         Ai, Bi = inp.integers(101, 3, (M, K)), inp.integers(101, 4, (K, N))
         want = inp.store(oracle.gemm(Ai, Bi).astype(np.float64), dt)
@@ -148,7 +150,7 @@ def test_error_paths_launch_nothing(B, tmp_path):
     c = torch.full((256, 256), 3.0, dtype=torch.float16, device="cuda")
     s = B.lcma_scheme_load("builtin:strassen")
     with pytest.raises(B.LcmaError) as e:
-        B.lcma_gemm(a[:, :200], a[:200], c, s)  # K = 200: not a multiple of the tile depth
+        B.lcma_gemm(a[:, :100], a[:100], c, s)  # K = 100: rows of A are not whole 16-byte vectors
     assert e.value.status == B.LCMA_ERR_SHAPE
     with pytest.raises(B.LcmaError) as e:
         B.lcma_gemm(a[:, 1:249], a[:248], c[:, :256], None)  # misaligned A pointer

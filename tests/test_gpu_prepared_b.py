@@ -93,17 +93,26 @@ def test_prepare_b_ragged_n(B, dt):
     s = S.strassen()
     h = B.lcma_scheme_load("builtin:strassen")
     vec = 4 if dt == "f32" else 8
-    N, K = 128 + 5 * vec, 128
+    N, K = 128 + 5 * vec, 128 + 3 * vec
     _, Bs = inp.matrices("uniform", "uniform", 64, N, K, dt, seed=17)
     bt = B.lcma_prepare_b(G.to_device(Bs, dt), h)
-    assert tuple(bt.shape) == (7, 128, K // 2)          # N/n padded from 64 + 2.5 vec to 128
+    kt = 16 if dt == "f32" else 32                       # K/k is padded to whole tiles of the Combine-B kernel
+    Kp = -(-K // (2 * kt)) * 2 * kt
+    assert tuple(bt.shape) == (7, 128, Kp // 2)          # N/n padded from 64 + 2.5 vec to 128
     got = prepared_to_host(bt)
-    padded = np.zeros((K, 256))
-    Bw = inp.widen(Bs, dt)
-    # blocks are cut from the padded matrix: block column j starts at j * 128
-    padded[:, :N] = Bw
+    padded = np.zeros((Kp, 256))
+    # blocks are cut from the padded matrix: block row l starts at l * Kp/2, block column j at j * 128
+    padded[:K, :N] = inp.widen(Bs, dt)
     want = oracle.combine_b_stored(s, padded, dt)
     assert np.array_equal(got, want)
+    # and the product against it, ragged in all three directions
+    M = 200 + 3
+    Ai, Bi = inp.integers(9, 5, (M, K)), inp.integers(9, 6, (K, N))
+    a, b = G.to_device(inp.store(Ai, dt), dt), G.to_device(inp.store(Bi, dt), dt)
+    c = G.empty_like_c(M, N, dt, fill=float("nan"))
+    B.lcma_gemm_prepared(a, B.lcma_prepare_b(b, h), c, h)
+    want = inp.store(oracle.gemm(Ai, Bi).astype(np.float64), dt)
+    assert np.array_equal(G.to_host_stored(c, dt).view(np.uint8), want.view(np.uint8))
 
 
 def test_prepared_error_paths_launch_nothing(B):
@@ -111,7 +120,7 @@ def test_prepared_error_paths_launch_nothing(B):
     h = B.lcma_scheme_load("builtin:strassen")
     b = torch.ones((256, 256), dtype=torch.float16, device="cuda")
     with pytest.raises(B.LcmaError) as e:
-        B.lcma_prepare_b(b[:200], h)                        # K/k = 100 is not a multiple of 32
+        B.lcma_prepare_b(b[:100, :252], h)                  # N = 252: rows are not whole 16-byte vectors
     assert e.value.status == B.LCMA_ERR_SHAPE
     with pytest.raises(B.LcmaError) as e:
         B.lcma_prepare_b(b[:, 1:129], h)                    # misaligned pointer
@@ -127,7 +136,7 @@ def test_prepared_error_paths_launch_nothing(B):
     bt = B.lcma_prepare_b(b, h)
     c = torch.full((200, 256), 3.0, dtype=torch.float16, device="cuda")
     with pytest.raises(B.LcmaError) as e:
-        B.lcma_gemm_prepared(b[:200, :200], bt, c, h)       # K = 200: not a multiple of the tile depth
+        B.lcma_gemm_prepared(b[:200, :100], bt, c, h)       # K = 100: rows of A are not whole 16-byte vectors
     assert e.value.status == B.LCMA_ERR_SHAPE
     torch.cuda.synchronize()
     assert torch.all(c == 3.0) and torch.all(bt3 == 0)

@@ -213,7 +213,7 @@ def test_gemm_argument_checks_before_any_launch(B):
     assert gemm(*ok_shape, ldc=260) == B.LCMA_ERR_ARG                   # ldc * 2 bytes not a multiple of 16
     assert gemm(-1, 256, 256) == B.LCMA_ERR_ARG
     assert gemm(256, 256, 0) == B.LCMA_ERR_SHAPE                        # K = 0
-    assert gemm(256, 256, 248) == B.LCMA_ERR_SHAPE                      # K is not a multiple of any tile depth
+    assert gemm(256, 256, 252, lda=256) == B.LCMA_ERR_SHAPE             # K = 252: rows of A not 16-byte granular
     assert gemm(256, 250, 256) == B.LCMA_ERR_SHAPE                      # N = 250: rows not 16-byte granular
     assert gemm(*ok_shape, dt=9) == B.LCMA_ERR_DTYPE
     assert gemm(0, 256, 256, a=None, b=None, c=None) == B.LCMA_OK       # M = 0: nothing to do
