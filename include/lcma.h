@@ -139,6 +139,10 @@ int lcma_variant_prepared(int index);
 int64_t lcma_prepared_b_bytes(const lcma_scheme *scheme, int64_t N, int64_t K, lcma_dtype dtype);
 lcma_status lcma_prepare_b(int64_t N, int64_t K, const void *B, int64_t ldb, lcma_dtype dtype,
                            const lcma_scheme *scheme, void *Bt, void *stream);
+/* lcma_prepare_b for weights stored N x K row-major (W[n][k] = B[k][n], the layout of a linear
+ * layer's weight; ldw in elements): same output, bit for bit, same contract and errors. */
+lcma_status lcma_prepare_bt(int64_t N, int64_t K, const void *W, int64_t ldw, lcma_dtype dtype,
+                            const lcma_scheme *scheme, void *Bt, void *stream);
 lcma_status lcma_gemm_prepared(int64_t M, int64_t N, int64_t K, const void *A, int64_t lda,
                                const void *Bt, void *C, int64_t ldc, lcma_dtype dtype,
                                const lcma_scheme *scheme, void *stream);

@@ -27,7 +27,7 @@ EXPORTS = [
     "lcma_gemm", "lcma_variant_count", "lcma_variant_name", "lcma_variant_info", "lcma_gemm_variant",
     "lcma_select", "lcma_hw_mi355x", "lcma_model_stages", "lcma_model_intensity", "lcma_predict_seconds",
     "lcma_sched_waves", "lcma_sched_range", "lcma_status_str", "lcma_last_error",
-    "lcma_variant_prepared", "lcma_prepared_b_bytes", "lcma_prepare_b", "lcma_gemm_prepared",
+    "lcma_variant_prepared", "lcma_prepared_b_bytes", "lcma_prepare_b", "lcma_prepare_bt", "lcma_gemm_prepared",
 ]
 
 
@@ -76,6 +76,7 @@ def lib() -> ctypes.CDLL:
         L.lcma_prepared_b_bytes.argtypes = [vp, i64, i64, i32]
         L.lcma_prepared_b_bytes.restype = i64
         L.lcma_prepare_b.argtypes = [i64, i64, vp, i64, i32, vp, vp, vp]
+        L.lcma_prepare_bt.argtypes = [i64, i64, vp, i64, i32, vp, vp, vp]
         L.lcma_gemm_prepared.argtypes = [i64, i64, i64, vp, i64, vp, vp, i64, i32, vp, vp]
         L.lcma_select.argtypes = [i64, i64, i64, i32]
         L.lcma_hw_mi355x.argtypes = [i32, ctypes.POINTER(lcma_hw)]
@@ -192,12 +193,13 @@ def lcma_prepared_b_bytes(scheme: Scheme, N: int, K: int, dtype: int) -> int:
     return int(lib().lcma_prepared_b_bytes(scheme.handle, N, K, dtype))
 
 
-def lcma_prepare_b(B, scheme: Scheme, Bt=None):
-    """Offline Combine B of the K x N device tensor B; returns the prepared operand, a device tensor of
-    shape (R, N/n, K/k) in the compute type (allocated here unless Bt is given)."""
+def lcma_prepare_b(B, scheme: Scheme, Bt=None, transposed: bool = False):
+    """Offline Combine B of the K x N device tensor B (or, with transposed=True, of the N x K weight
+    tensor W = B^T); returns the prepared operand, a device tensor of shape (R, N/n, K/k), padded to
+    whole tiles, in the compute type (allocated here unless Bt is given)."""
     import torch
     assert B.is_cuda and B.dim() == 2 and B.stride(1) == 1
-    K, N = B.shape
+    (N, K) = B.shape if transposed else B.shape[::-1]
     dt = _dtype_of(B)
     nbytes = lcma_prepared_b_bytes(scheme, N, K, dt)
     if nbytes < 0:
@@ -211,8 +213,14 @@ def lcma_prepare_b(B, scheme: Scheme, Bt=None):
         Bt = torch.empty((info["R"], rows, cols), device=B.device, dtype=ct)
     assert Bt.is_cuda and Bt.is_contiguous() and Bt.dtype == ct and Bt.numel() * Bt.element_size() == nbytes
     stream = torch.cuda.current_stream(B.device).cuda_stream
-    _check(lib().lcma_prepare_b(N, K, B.data_ptr(), B.stride(0), dt, scheme.handle, Bt.data_ptr(), stream))
+    fn = lib().lcma_prepare_bt if transposed else lib().lcma_prepare_b
+    _check(fn(N, K, B.data_ptr(), B.stride(0), dt, scheme.handle, Bt.data_ptr(), stream))
     return Bt
+
+
+def lcma_prepare_bt(W, scheme: Scheme, Bt=None):
+    """lcma_prepare_b for weights stored N x K (a linear layer's weight)."""
+    return lcma_prepare_b(W, scheme, Bt, transposed=True)
 
 
 def _marshal_prepared(A, Bt, C):

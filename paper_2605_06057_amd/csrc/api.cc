@@ -191,48 +191,75 @@ extern "C" int64_t lcma_prepared_b_bytes(const lcma_scheme *scheme, int64_t N, i
            (round_up(K, (int64_t)scheme->k * (64 / es)) / scheme->k) * es;
 }
 
-extern "C" lcma_status lcma_prepare_b(int64_t N, int64_t K, const void *B, int64_t ldb, lcma_dtype dtype,
-                                      const lcma_scheme *scheme, void *Bt, void *stream) {
+// transposed: the input is the N x K weight matrix W (W[n][k] = B[k][n]) with leading dimension ldb.
+static lcma_status prepare_b(bool transposed, int64_t N, int64_t K, const void *B, int64_t ldb, lcma_dtype dtype,
+                             const lcma_scheme *scheme, void *Bt, void *stream) {
+    const char *who = transposed ? "lcma_prepare_bt" : "lcma_prepare_b";
     const int es = dtype_size(dtype);
-    if (!es) return fail(LCMA_ERR_DTYPE, "lcma_prepare_b: unknown dtype %d", (int)dtype);
+    if (!es) return fail(LCMA_ERR_DTYPE, "%s: unknown dtype %d", who, (int)dtype);
     int id = 0;
-    if (const lcma_status st = prepared_scheme(scheme, "lcma_prepare_b", &id)) return st;
+    if (const lcma_status st = prepared_scheme(scheme, who, &id)) return st;
     const PrepKernel *pk = find_prep(id, dtype);
-    if (!pk) return fail(LCMA_ERR_NOKERNEL, "lcma_prepare_b: no Combine-B kernel for scheme id %d with dtype %d", id, (int)dtype);
-    if (N < 0 || K < 0) return fail(LCMA_ERR_ARG, "lcma_prepare_b: negative size");
+    if (!pk) return fail(LCMA_ERR_NOKERNEL, "%s: no Combine-B kernel for scheme id %d with dtype %d", who, id, (int)dtype);
+    if (N < 0 || K < 0) return fail(LCMA_ERR_ARG, "%s: negative size", who);
     if (N == 0 || K == 0) return LCMA_OK;
-    if (!B || !Bt) return fail(LCMA_ERR_ARG, "lcma_prepare_b: null pointer");
-    if (ldb < N) return fail(LCMA_ERR_ARG, "lcma_prepare_b: leading dimension smaller than the row");
+    if (!B || !Bt) return fail(LCMA_ERR_ARG, "%s: null pointer", who);
+    const int64_t rows = transposed ? N : K, cols = transposed ? K : N; // of the input as stored
+    if (ldb < cols) return fail(LCMA_ERR_ARG, "%s: leading dimension smaller than the row", who);
     if ((((uintptr_t)B | (uintptr_t)Bt) & 15) || ((ldb * es) & 15))
-        return fail(LCMA_ERR_ARG, "lcma_prepare_b: pointers and the leading dimension must be multiples of 16 bytes");
-    const int kt = 64 / es; // k rows one work-group transposes
+        return fail(LCMA_ERR_ARG, "%s: pointers and the leading dimension must be multiples of 16 bytes", who);
+    const int kt = 64 / es; // k granule of a plane
     if (N % (16 / es) || K % (16 / es))
-        return fail(LCMA_ERR_SHAPE, "lcma_prepare_b: N = %lld and K = %lld must be multiples of %d", (long long)N,
-                    (long long)K, 16 / es);
+        return fail(LCMA_ERR_SHAPE, "%s: N = %lld and K = %lld must be multiples of %d", who, (long long)N, (long long)K,
+                    16 / es);
     // the planes hold the padded rows and columns (zeros)
     const int64_t bn = round_up(N, (int64_t)scheme->n * 64) / scheme->n,
                   bk = round_up(K, (int64_t)scheme->k * kt) / scheme->k;
-    const int64_t b_bytes = ((K - 1) * ldb + N) * es, bt_bytes = (int64_t)scheme->R * bn * bk * es;
+    const int64_t b_bytes = ((rows - 1) * ldb + cols) * es, bt_bytes = (int64_t)scheme->R * bn * bk * es;
     const int64_t lim = (int64_t)1 << 31;
-    if (((bk * scheme->k - 1) * ldb + bn * scheme->n) * es >= lim || bt_bytes >= lim)
-        return fail(LCMA_ERR_SHAPE, "lcma_prepare_b: a buffer spans 2 GiB or more");
-    if (bk / kt > 65535) return fail(LCMA_ERR_SHAPE, "lcma_prepare_b: K is too large");
+    const int64_t prow = transposed ? bn * scheme->n : bk * scheme->k, pcol = transposed ? bk * scheme->k : bn * scheme->n;
+    if (((prow - 1) * ldb + pcol) * es >= lim || bt_bytes >= lim)
+        return fail(LCMA_ERR_SHAPE, "%s: a buffer spans 2 GiB or more", who);
     PrepParams p;
     p.B = B;
     p.Bt = Bt;
     p.b_bytes = (uint32_t)b_bytes;
     p.bt_bytes = (uint32_t)bt_bytes;
     p.ldb_b = (uint32_t)(ldb * es);
-    p.b_brow = (uint32_t)(bk * ldb * es);
-    p.b_bcol = (uint32_t)(bn * es);
     p.bt_ld_b = (uint32_t)(bk * es);
     p.bt_plane_b = (uint32_t)(bn * bk * es);
     p.bk = (int32_t)bk;
     p.bn = (int32_t)bn;
-    p.n_row_b = (uint32_t)(N * es);
-    const int err = pk->launch(&p, (int)(bn / 64), (int)(bk / kt), stream);
-    if (err) return fail(LCMA_ERR_HIP, "lcma_prepare_b: launch failed with HIP error %d", err);
+    int gx, gy, err;
+    if (transposed) {
+        p.b_brow = (uint32_t)(bn * ldb * es); // from block row j of W to j + 1
+        p.b_bcol = (uint32_t)(bk * es);       // from block column l of W to l + 1
+        p.n_row_b = (uint32_t)(K * es);       // row length of W
+        gx = (int)(bn / 16);
+        gy = (int)((bk * es + 255) / 256);
+        if (gy > 65535) return fail(LCMA_ERR_SHAPE, "%s: K is too large", who);
+        err = pk->launch_t(&p, gx, gy, stream);
+    } else {
+        p.b_brow = (uint32_t)(bk * ldb * es);
+        p.b_bcol = (uint32_t)(bn * es);
+        p.n_row_b = (uint32_t)(N * es);
+        gx = (int)(bn / 64);
+        gy = (int)(bk / kt);
+        if (gy > 65535) return fail(LCMA_ERR_SHAPE, "%s: K is too large", who);
+        err = pk->launch(&p, gx, gy, stream);
+    }
+    if (err) return fail(LCMA_ERR_HIP, "%s: launch failed with HIP error %d", who, err);
     return LCMA_OK;
+}
+
+extern "C" lcma_status lcma_prepare_b(int64_t N, int64_t K, const void *B, int64_t ldb, lcma_dtype dtype,
+                                      const lcma_scheme *scheme, void *Bt, void *stream) {
+    return prepare_b(false, N, K, B, ldb, dtype, scheme, Bt, stream);
+}
+
+extern "C" lcma_status lcma_prepare_bt(int64_t N, int64_t K, const void *W, int64_t ldw, lcma_dtype dtype,
+                                       const lcma_scheme *scheme, void *Bt, void *stream) {
+    return prepare_b(true, N, K, W, ldw, dtype, scheme, Bt, stream);
 }
 
 extern "C" lcma_status lcma_gemm_prepared(int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const void *Bt,

@@ -50,7 +50,8 @@ extern const int kVariantCount;
 // One generated offline Combine-B kernel (scheme x dtype).
 struct PrepKernel {
     int scheme_id, dtype;
-    int (*launch)(const PrepParams *p, int grid_x, int grid_y, void *stream); // returns a hipError_t
+    int (*launch)(const PrepParams *p, int grid_x, int grid_y, void *stream);   // B given K x N; returns a hipError_t
+    int (*launch_t)(const PrepParams *p, int grid_x, int grid_y, void *stream); // weights given N x K
 };
 extern const PrepKernel kPrepKernels[];
 extern const int kPrepKernelCount;

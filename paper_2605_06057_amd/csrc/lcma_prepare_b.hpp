@@ -93,4 +93,58 @@ template <class IN, class CT, class CH> LCMA_DEV void prepare_b_tile(const PrepP
     }
 }
 
+// The same stage for a weight matrix stored as N x K (row n holds the K inputs of output n, the layout
+// of a linear layer's weight): W[n][k] = B[k][n].  The rows are k-contiguous already, so there is nothing
+// to transpose: a thread reads one 16-byte vector per block, forms the sums and writes one 16-byte
+// vector per plane.  Here PrepParams describes W: ldb_b is its row pitch, b_brow the byte step between
+// block rows of W (n direction, (N/n) * ldb_b) and b_bcol between its block columns (k direction).
+template <class IN, class CT, class CH> LCMA_DEV void prepare_bt_tile(const PrepParams &p) {
+    constexpr int ES = IN::ES, EPT = 16 / ES;
+    static_assert(CT::ES == ES, "the output keeps the element size");
+    const auto rb = __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(p.B), 0, (int)p.b_bytes, 0x00020000);
+    const auto rt = __builtin_amdgcn_make_buffer_rsrc(p.Bt, 0, (int)p.bt_bytes, 0x00020000);
+    // 256 threads: 16 rows (n) x 16 vectors (k) of every block
+    const int rn = blockIdx.x * 16 + (int)threadIdx.x / 16;
+    const uint32_t kb = (uint32_t)(blockIdx.y * 16 + (int)threadIdx.x % 16) * 16; // byte column inside a block
+    if (kb >= p.bt_ld_b) return; // past the padded K/k (whole work-group columns only when K/k < 256 B)
+    float in[CH::NB][EPT];
+#pragma unroll
+    for (int t = 0; t < CH::NB; ++t) {
+        // block B_{l,j} of B is block (j, l) of W; rows past N lie outside the extent, columns past K
+        // would alias the next row
+        const uint32_t colb = (uint32_t)CH::b_l(t) * p.b_bcol + kb;
+        const uint32_t off = colb < p.n_row_b ? (uint32_t)CH::b_j(t) * p.b_brow + (uint32_t)rn * p.ldb_b + colb : p.b_bytes;
+        Widen<IN>::run(__builtin_amdgcn_raw_buffer_load_b128(rb, (int)off, 0, 0), in[t]);
+    }
+#pragma unroll
+    for (int r = 0; r < CH::NP; ++r) {
+        u32x4 v;
+        if constexpr (ES == 2) {
+            f16x8 h;
+#pragma unroll
+            for (int e = 0; e < EPT; ++e) {
+                float col[CH::NB], o[CH::NP];
+#pragma unroll
+                for (int t = 0; t < CH::NB; ++t) col[t] = in[t][e];
+                CH::comb(col, o);
+                h[e] = (_Float16)o[r]; // one rounding, nearest-even
+            }
+            v = __builtin_bit_cast(u32x4, h);
+        } else {
+            f32x4 f;
+#pragma unroll
+            for (int e = 0; e < EPT; ++e) {
+                float col[CH::NB], o[CH::NP];
+#pragma unroll
+                for (int t = 0; t < CH::NB; ++t) col[t] = in[t][e];
+                CH::comb(col, o);
+                f[e] = o[r];
+            }
+            v = __builtin_bit_cast(u32x4, f);
+        }
+        const uint32_t off = (uint32_t)r * p.bt_plane_b + (uint32_t)rn * p.bt_ld_b + kb;
+        __builtin_amdgcn_raw_buffer_store_b128(v, rt, (int)off, 0, 0);
+    }
+}
+
 } // namespace lcma

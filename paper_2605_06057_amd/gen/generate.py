@@ -320,12 +320,13 @@ def emit_registry(schemes: dict[str, Scheme], variants: list[Variant]) -> str:
     preps = prep_kernels(variants)
     L.append("const PrepKernel kPrepKernels[] = {")
     for sch, dt in preps:
-        L.append(f"    {{{SCHEME_IDS[sch]}, {DTYPE_IDS[dt]}, lcma_launch_prep_b_{sch}_{dt}}},")
+        L.append(f"    {{{SCHEME_IDS[sch]}, {DTYPE_IDS[dt]}, lcma_launch_prep_b_{sch}_{dt}, lcma_launch_prep_bt_{sch}_{dt}}},")
     if not preps:
-        L.append("    {0, 0, nullptr},")
+        L.append("    {0, 0, nullptr, nullptr},")
     L += ["};", f"const int kPrepKernelCount = {len(preps)};", "} // namespace lcma", ""]
     for sch, dt in preps:
         L.insert(3, f'extern "C" int lcma_launch_prep_b_{sch}_{dt}(const lcma::PrepParams *p, int gx, int gy, void *stream);')
+        L.insert(3, f'extern "C" int lcma_launch_prep_bt_{sch}_{dt}(const lcma::PrepParams *p, int gx, int gy, void *stream);')
     return "\n".join(L)
 
 
@@ -373,6 +374,16 @@ def emit_prep_b(s: Scheme, dtype: str) -> str:
     w("")
     w(f'extern "C" int lcma_launch_prep_b_{s.name}_{dtype}(const lcma::PrepParams *p, int gx, int gy, void *stream) {{')
     w(f"    lcma_k_prep_b_{s.name}_{dtype}<<<dim3(gx, gy), dim3(256), 0, (hipStream_t)stream>>>(*p);")
+    w("    return (int)hipGetLastError();")
+    w("}")
+    w("")
+    w("// the same for a weight matrix stored N x K")
+    w(f'extern "C" __global__ __launch_bounds__(256) void lcma_k_prep_bt_{s.name}_{dtype}(const lcma::PrepParams p) {{')
+    w(f"    prepare_bt_tile<{in_t}, {ct_t}, Comb>(p);")
+    w("}")
+    w("")
+    w(f'extern "C" int lcma_launch_prep_bt_{s.name}_{dtype}(const lcma::PrepParams *p, int gx, int gy, void *stream) {{')
+    w(f"    lcma_k_prep_bt_{s.name}_{dtype}<<<dim3(gx, gy), dim3(256), 0, (hipStream_t)stream>>>(*p);")
     w("    return (int)hipGetLastError();")
     w("}")
     return "\n".join(L) + "\n"

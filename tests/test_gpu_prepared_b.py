@@ -115,6 +115,32 @@ def test_prepare_b_ragged_n(B, dt):
     assert np.array_equal(G.to_host_stored(c, dt).view(np.uint8), want.view(np.uint8))
 
 
+@pytest.mark.parametrize("dt", ["bf16", "f16", "f32"])
+def test_prepare_bt_takes_the_weight_layout(B, dt):
+    """Weights stored N x K (W = B^T, strided view): same planes as lcma_prepare_b, bit for bit, and
+    equal to the oracle's stored Combine B, for a full and a ragged shape."""
+    import torch
+    import gpu_util as G
+    s = S.strassen()
+    h = B.lcma_scheme_load("builtin:strassen")
+    vec = 4 if dt == "f32" else 8
+    for N, K in ((256, 192), (128 + 5 * vec, 128 + 3 * vec)):
+        print(f"prepare_bt {dt} N={N} K={K}", flush=True)
+        _, Bs = inp.matrices("uniform", "weights", 64, N, K, dt, seed=23)
+        b = G.to_device(Bs, dt)
+        big = torch.zeros((N, K + 2 * vec), dtype=b.dtype, device="cuda")
+        big[:, vec:vec + K] = b.t()
+        bt_w = B.lcma_prepare_bt(big[:, vec:vec + K], h)
+        bt_b = B.lcma_prepare_b(b, h)
+        assert bt_w.shape == bt_b.shape
+        assert torch.equal(bt_w.view(torch.uint8), bt_b.view(torch.uint8))
+        kt = 16 if dt == "f32" else 32
+        Kp, Np = -(-K // (2 * kt)) * 2 * kt, -(-N // 128) * 128
+        padded = np.zeros((Kp, Np))
+        padded[:K, :N] = inp.widen(Bs, dt)
+        assert np.array_equal(prepared_to_host(bt_w), oracle.combine_b_stored(s, padded, dt))
+
+
 def test_prepared_error_paths_launch_nothing(B):
     import torch
     h = B.lcma_scheme_load("builtin:strassen")

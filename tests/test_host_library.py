@@ -187,6 +187,8 @@ def test_prepared_b_host_side(B):
     assert L.lcma_prepare_b(256, 256, None, 256, B.LCMA_F16, s.handle, None, None) == B.LCMA_ERR_ARG
     assert L.lcma_prepare_b(256, 256, None, 256, B.LCMA_F16, None, None, None) == B.LCMA_ERR_ARG
     assert L.lcma_prepare_b(256, 256, None, 256, 17, s.handle, None, None) == B.LCMA_ERR_DTYPE
+    assert L.lcma_prepare_bt(256, 256, None, 256, B.LCMA_F16, s.handle, None, None) == B.LCMA_ERR_ARG
+    assert L.lcma_prepare_bt(256, 512, 0x1000, 256, B.LCMA_F16, s.handle, 0x2000, None) == B.LCMA_ERR_ARG  # ldw < K
     assert L.lcma_gemm_prepared(256, 256, 256, None, 256, None, None, 256, B.LCMA_F16, None, None) == B.LCMA_ERR_ARG
     assert L.lcma_gemm_prepared(256, 256, 256, None, 256, None, None, 256, B.LCMA_F16, s.handle, None) == B.LCMA_ERR_ARG
     assert b"null" in L.lcma_last_error()
