@@ -132,7 +132,8 @@ template <class IN_, class CT_, int TM_, int TN_, int TK_, int WGM_, int WGN_, i
 struct Tile {
     static constexpr int PIPE = PIPE_, FC = FC_, PB = PB_, DL = DL_;
     static_assert(!DL_ || PB_, "direct loads need an operand that goes to LDS untouched on both sides");
-    static_assert(!PB_ || (FC_ && PIPE_ == 2 && STAGES_ == 2), "prepared B needs the interleaved fragment-combine loop");
+    static_assert(!PB_ || (FC_ && PIPE_ == 2 && STAGES_ == 2) || (!FC_ && PIPE_ == 0),
+                  "prepared B: the interleaved fragment-combine loop or the staged loop");
     using IN = IN_;
     using CT = CT_;
     static_assert(IN::ES == CT::ES, "conversion must keep the element size");
@@ -155,6 +156,8 @@ struct Tile {
     static constexpr int BCOLS = (ES == 2) ? TN / 2 : TN;
     static constexpr int NU_B = BCOLS * CPR;
     static constexpr int QB = (NU_B + NT - 1) / NT;
+    static constexpr int NCHK_BP = TN * CPR;   // 16-byte chunks of one tile of a prepared right operand
+    static constexpr int QBP = (NCHK_BP + NT - 1) / NT;
     static constexpr int A_SLOT = TM * ROW, B_SLOT = TN * ROW;
     static constexpr int A_STAGE = NSA * A_SLOT, B_STAGE = NSB * B_SLOT;
     static constexpr int STAGE = A_STAGE + B_STAGE;
@@ -265,6 +268,7 @@ template <class T> struct Ctx {
     uint32_t c_voff; // byte offset of this lane's first output element inside the tile
     uint32_t c_colb; // byte column of that element inside a block of C (for the N bound)
     uint32_t b_colb[T::QB]; // byte column inside a block of B of the unit staged by this thread
+    uint32_t bp_voff[T::QBP], bp_lds[T::QBP]; // staged kernels with prepared B: chunks of a Bt_r tile
 
     LCMA_DEV Ctx(const Params &p_, LCMA_LDS char *lds_) : p(p_), lds(lds_) {
         ra = __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(p.A), 0, (int)p.a_bytes, 0x00020000);
@@ -318,6 +322,13 @@ template <class T> struct Ctx {
             b_colb[q] = (uint32_t)z * T::TN * T::ES + col * 4;
             b_lds[q] = T::A_STAGE + row * T::ROW + T::swz(row, g) * 16;
             b_lds1[q] = T::A_STAGE + (row + 1) * T::ROW + T::swz(row + 1, g) * 16;
+        }
+#pragma unroll
+        for (int q = 0; q < T::QBP; ++q) {
+            const int id2 = (q * T::NT + tid) % T::NCHK_BP;
+            const int row = id2 / T::CPR, c = id2 % T::CPR;
+            bp_voff[q] = (uint32_t)row * p.ldb_b + c * 16;
+            bp_lds[q] = T::A_STAGE + row * T::ROW + T::swz(row, c) * 16;
         }
         // Fragment addresses.  Operand of the 32x32 MFMA: lane holds row lane%32 and the
         // (lane/32)-th group of consecutive k -> one 16-byte read, for A (rows = m) and B (rows = n).
@@ -580,7 +591,9 @@ template <class T> struct Ctx {
 //   a_i(t), a_l(t)    block indices of raw A block t; b_l(t), b_j(t) likewise for B
 //   comb_a(in, out)   out[s] = sum_t U * in[t]  (Eq. 3) on 16-byte vectors; comb_b likewise (Eq. 4)
 template <class T, class CH> struct RawSet {
-    u32x4 a[CH::NA][T::QA], b[CH::NB][T::QB][T::BH];
+    u32x4 a[CH::NA][T::QA];
+    // B side: raw blocks (units of BH vectors), or with prepared B one tile of Bt_r per product
+    u32x4 b[T::PB ? CH::NP : CH::NB][T::PB ? T::QBP : T::QB][T::PB ? 1 : T::BH];
 };
 
 // Issue the buffer loads of step y into `r`.
@@ -591,14 +604,24 @@ template <class T, class CH> LCMA_DEV void issue_loads(const Ctx<T> &cx, RawSet<
 #pragma unroll
         for (int q = 0; q < T::QA; ++q) r.a[t][q] = cx.load_a(q, so, CH::a_l(t), y);
     }
+    if constexpr (T::PB) {
 #pragma unroll
-    for (int t = 0; t < CH::NB; ++t) {
-        const uint32_t so = cx.soff_b(CH::b_l(t), CH::b_j(t), y);
+        for (int s = 0; s < CH::NP; ++s) {
+            const uint32_t so = (uint32_t)CH::b_plane(s) * cx.p.b_brow + cx.b_group + (uint32_t)y * (T::TK * T::ES);
 #pragma unroll
-        for (int q = 0; q < T::QB; ++q) {
-            const uint32_t vo = cx.b_voff_in(q, CH::b_j(t));
+            for (int q = 0; q < T::QBP; ++q)
+                r.b[s][q][0] = __builtin_amdgcn_raw_buffer_load_b128(cx.rb, (int)cx.bp_voff[q], (int)so, 0);
+        }
+    } else {
 #pragma unroll
-            for (int e = 0; e < T::BW; ++e) r.b[t][q][e / 4][e % 4] = cx.load_b(vo, so + (uint32_t)e * cx.p.ldb_b);
+        for (int t = 0; t < CH::NB; ++t) {
+            const uint32_t so = cx.soff_b(CH::b_l(t), CH::b_j(t), y);
+#pragma unroll
+            for (int q = 0; q < T::QB; ++q) {
+                const uint32_t vo = cx.b_voff_in(q, CH::b_j(t));
+#pragma unroll
+                for (int e = 0; e < T::BW; ++e) r.b[t][q][e / 4][e % 4] = cx.load_b(vo, so + (uint32_t)e * cx.p.ldb_b);
+            }
         }
     }
 }
@@ -625,6 +648,13 @@ template <class T, class CH> LCMA_DEV void combine_store(const Ctx<T> &cx, const
 #pragma unroll
         for (int s = 0; s < NOA; ++s) cx.lds_store(sb + s * T::A_SLOT + cx.a_lds[q], __builtin_bit_cast(u32x4, out[s]));
     }
+    if constexpr (T::PB) { // tiles of Bt_r go to LDS as they are
+#pragma unroll
+        for (int s = 0; s < CH::NP; ++s)
+#pragma unroll
+            for (int q = 0; q < T::QBP; ++q) cx.lds_store(sb + s * T::B_SLOT + cx.bp_lds[q], r.b[s][q][0]);
+        return;
+    } else {
 #pragma unroll
     for (int q = 0; q < T::QB; ++q) {
         V out[T::BH][NOB];
@@ -661,6 +691,7 @@ template <class T, class CH> LCMA_DEV void combine_store(const Ctx<T> &cx, const
                 cx.lds_store(sb + s * T::B_SLOT + cx.b_lds[q], __builtin_bit_cast(u32x4, out[0][s]));
             }
         }
+    }
     }
 }
 

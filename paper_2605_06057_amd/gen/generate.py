@@ -248,6 +248,10 @@ def emit_kernel(s: Scheme, v: Variant) -> str:
             else:
                 w(f"        out[{si}] = {signed_sum(terms, wide, True)};")
         w("    }")
+        if v.pb:
+            n_orig = s.R - len(v.comp)  # a residual product multiplies the same right operand as its source
+            planes = [r if r < n_orig else v.comp[r - n_orig] for r in ch]
+            w(f"    static LCMA_DEV constexpr int b_plane(int s) {{ constexpr int v[] = {{{', '.join(map(str, planes))}}}; return v[s]; }}")
         if not v.pb:
             w("    template <class V> static LCMA_DEV void comb_b(const V (&in)[NB], V (&out)[NP]) {")
             for si, r in enumerate(ch):
@@ -443,20 +447,25 @@ def manifest() -> list[Variant]:
             Variant("strassen", dt, 64, 64, 32, chunk=7, eff=e(0.099, 0.114), rank=90),
             # Algorithm 2's r loop: one product at a time, combinations formed while staging
             Variant("strassen", dt, 128, 128, 32, chunk=1, eff=e(0.149, 0.179)),
-            Variant("laderman", dt, 128, 64, 32, chunk=1, eff=0.056, rank=90 if dt == "f16" else 0),
-            Variant("laderman", dt, 64, 64, 32, chunk=1, eff=0.045, rank=90 if dt == "f16" else 0),
+            Variant("laderman", dt, 128, 64, 32, chunk=1, eff=e(0.060, 0.068), rank=90 if dt == "f16" else 0),
+            Variant("laderman", dt, 64, 64, 32, chunk=1, eff=e(0.039, 0.043), rank=90 if dt == "f16" else 0),
         ]
     # Laderman with fp16 storage: rounding its 3- and 7-term combinations to fp16 costs 4.05x the error
     # of the plain kernel; multiplying the residual of the left operand of products 4 and 7 (both
     # three-term on each side) as well brings it under the 4x bound for 2 extra products out of 23.
     # The uncompensated kernels above stay as ablation variants (rank 90).
-    V += [Variant("laderman", "f16", 128, 64, 32, chunk=1, comp=(3, 6), eff=0.056),
-          Variant("laderman", "f16", 64, 64, 32, chunk=1, comp=(3, 6), eff=0.045)]
+    V += [Variant("laderman", "bf16", 128, 64, 32, chunk=1, pb=1, eff=0.088),
+          Variant("laderman", "f16", 128, 64, 32, chunk=1, pb=1, comp=(3, 6), eff=0.09)]
+    V += [Variant("strassen2", "bf16", 64, 64, 32, chunk=7, pb=1, eff=0.104),
+          Variant("strassen2", "f32", 64, 64, 16, chunk=7, pb=1, eff=0.579),
+          Variant("laderman", "f32", 64, 64, 16, chunk=1, pb=1, eff=0.473)]
+    V += [Variant("laderman", "f16", 128, 64, 32, chunk=1, comp=(3, 6), eff=0.064),
+          Variant("laderman", "f16", 64, 64, 32, chunk=1, comp=(3, 6), eff=0.041)]
     # two-level Strassen: with fp16 storage its four-term sums exceed the 4x error bound, so it is
     # generated for bf16 (sums nearly exact in fp16) and fp32 only
     V += [
-        Variant("strassen2", "bf16", 64, 64, 32, chunk=7, eff=0.065),
-        Variant("strassen2", "bf16", 64, 64, 32, chunk=1, eff=0.032),
+        Variant("strassen2", "bf16", 64, 64, 32, chunk=7, eff=0.062),
+        Variant("strassen2", "bf16", 64, 64, 32, chunk=1, eff=0.030),
     ]
     V += [
         Variant("plain", "f32", 256, 128, 16, wgm=2, wgn=4, eff=0.917),
@@ -470,8 +479,8 @@ def manifest() -> list[Variant]:
         Variant("strassen", "f32", 64, 64, 16, chunk=7, fc=1, occ=2, eff=0.795, rank=90),
         Variant("strassen", "f32", 64, 64, 16, chunk=7, eff=0.656, rank=90),
         Variant("strassen", "f32", 128, 64, 16, chunk=1, eff=0.613),
-        Variant("laderman", "f32", 64, 64, 16, chunk=1, eff=0.40),
-        Variant("strassen2", "f32", 64, 64, 16, chunk=7, eff=0.528),
+        Variant("laderman", "f32", 64, 64, 16, chunk=1, eff=0.399),
+        Variant("strassen2", "f32", 64, 64, 16, chunk=7, eff=0.511),
     ]
     return [v.finish() for v in V]
 
