@@ -155,9 +155,10 @@ def test_prepared_error_paths_launch_nothing(B):
     assert B.lcma_prepared_b_bytes(h2, 384, 384, B.LCMA_F16) == 23 * 128 * 128 * 2
     assert B.lcma_prepared_b_bytes(h2, 256, 384, B.LCMA_F16) == 23 * 128 * 128 * 2   # N padded to 3 * 128
     assert B.lcma_prepared_b_bytes(h2, 250, 384, B.LCMA_F16) == -1   # rows of B must stay 16-byte granular
-    bt3 = torch.zeros((23, 128, 128), dtype=torch.float16, device="cuda")
-    with pytest.raises(B.LcmaError) as e:                   # no prepared-B kernels for Laderman
-        B.lcma_prepare_b(torch.ones((384, 384), dtype=torch.float16, device="cuda"), h2, bt3)
+    h3 = B.lcma_scheme_load("builtin:strassen2")
+    bt3 = torch.zeros((49, 64, 64), dtype=torch.float16, device="cuda")
+    with pytest.raises(B.LcmaError) as e:                   # two-level Strassen has no fp16 kernels
+        B.lcma_prepare_b(torch.ones((256, 256), dtype=torch.float16, device="cuda"), h3, bt3)
     assert e.value.status == B.LCMA_ERR_NOKERNEL
     bt = B.lcma_prepare_b(b, h)
     c = torch.full((200, 256), 3.0, dtype=torch.float16, device="cuda")
