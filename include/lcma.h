@@ -102,6 +102,12 @@ lcma_status lcma_gemm(int64_t M, int64_t N, int64_t K,
  * the variant was generated for).  Names look like "strassen_bf16_t128x64x16_c7".
  */
 int lcma_variant_count(void);
+/* Name of the scheme with id `scheme_id` as used in "builtin:<name>" ("plain" for LCMA_PLAIN), or NULL.
+ * Ids 1..3 are the paper's schemes (the enum above); every further scheme file that was present when
+ * the library was built (Sec. 3.1: kernels are generated per scheme) has an id from 4 up to
+ * lcma_scheme_id_max().  lcma_select chooses among the paper's schemes only. */
+const char *lcma_scheme_name(int scheme_id);
+int lcma_scheme_id_max(void);
 const char *lcma_variant_name(int index); /* NULL when out of range */
 /* Describes variant `index`: builtin scheme id, dtype, tile sizes and the granules m*TM, n*TN,
  * k*TK in which it works through M, N, K (any pointer may be NULL).  Sizes are padded up to the

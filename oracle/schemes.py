@@ -183,8 +183,15 @@ def strassen2() -> Scheme:
     return kronecker(s, s, "strassen2")
 
 
+def strassen_wide() -> Scheme:
+    """A rectangular scheme <2,2,4;14>: Strassen with every block column of B and C cut in two
+    (Strassen composed with the definition of a 1 x 1 by 1 x 2 block product)."""
+    return kronecker(strassen(), classical(1, 1, 2), "strassen_wide")
+
+
 def by_name(name: str) -> Scheme:
-    return {"strassen": strassen, "strassen2": strassen2, "laderman": laderman}[name]()
+    return {"strassen": strassen, "strassen2": strassen2, "laderman": laderman,
+            "strassen_wide": strassen_wide}[name]()
 
 
 def to_text(s: Scheme) -> str:

@@ -27,7 +27,7 @@ EXPORTS = [
     "lcma_gemm", "lcma_variant_count", "lcma_variant_name", "lcma_variant_info", "lcma_gemm_variant",
     "lcma_select", "lcma_hw_mi355x", "lcma_model_stages", "lcma_model_intensity", "lcma_predict_seconds",
     "lcma_sched_waves", "lcma_sched_range", "lcma_status_str", "lcma_last_error",
-    "lcma_variant_prepared", "lcma_prepared_b_bytes", "lcma_prepare_b", "lcma_prepare_bt", "lcma_gemm_prepared",
+    "lcma_scheme_name", "lcma_scheme_id_max", "lcma_variant_prepared", "lcma_prepared_b_bytes", "lcma_prepare_b", "lcma_prepare_bt", "lcma_gemm_prepared",
 ]
 
 
@@ -72,6 +72,9 @@ def lib() -> ctypes.CDLL:
         L.lcma_variant_name.restype = cp
         L.lcma_variant_info.argtypes = [i32] + [pi32] * 8
         L.lcma_gemm_variant.argtypes = [cp, i64, i64, i64, vp, i64, vp, i64, vp, i64, vp]
+        L.lcma_scheme_name.argtypes = [i32]
+        L.lcma_scheme_name.restype = cp
+        L.lcma_scheme_id_max.argtypes = []
         L.lcma_variant_prepared.argtypes = [i32]
         L.lcma_prepared_b_bytes.argtypes = [vp, i64, i64, i32]
         L.lcma_prepared_b_bytes.restype = i64
@@ -91,6 +94,11 @@ def lib() -> ctypes.CDLL:
         L.lcma_last_error.argtypes = []
         L.lcma_last_error.restype = cp
         _lib = L
+        # schemes that kernels were generated for beyond the paper's three
+        for sid in range(4, int(L.lcma_scheme_id_max()) + 1):
+            name = L.lcma_scheme_name(sid)
+            if name:
+                SCHEME_NAMES[sid] = name.decode()
     return _lib
 
 

@@ -310,6 +310,10 @@ extern "C" lcma_status lcma_variant_info(int index, int *scheme_id, int *dtype, 
     return LCMA_OK;
 }
 
+extern "C" const char *lcma_scheme_name(int scheme_id) { return builtin_name_of(scheme_id); }
+
+extern "C" int lcma_scheme_id_max(void) { return builtin_max_id(); }
+
 extern "C" int lcma_variant_prepared(int index) {
     return (index >= 0 && index < kVariantCount) ? kVariants[index].prepared : -1;
 }

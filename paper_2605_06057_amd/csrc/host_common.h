@@ -26,7 +26,9 @@ lcma_status fail(lcma_status st, const char *fmt, ...) __attribute__((format(pri
 
 uint64_t scheme_hash(int m, int k, int n, int R, const int8_t *U, const int8_t *V, const int8_t *W);
 const lcma_scheme *builtin_scheme(int id); // verified, cached; nullptr for LCMA_PLAIN / unknown
-int builtin_id_of(const char *name);
+int builtin_id_of(const char *name);        // -1 if unknown
+const char *builtin_name_of(int id);        // "plain" for LCMA_PLAIN; nullptr if unknown
+int builtin_max_id();
 
 // One generated kernel (scheme x dtype x tile x dataflow).
 struct Variant {

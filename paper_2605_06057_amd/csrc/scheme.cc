@@ -111,30 +111,49 @@ static bool brent_holds(const lcma_scheme *s, int64_t *first_bad) {
     return true;
 }
 
-int builtin_id_of(const char *name) {
-    if (!std::strcmp(name, "strassen")) return LCMA_STRASSEN;
-    if (!std::strcmp(name, "strassen2")) return LCMA_STRASSEN2;
-    if (!std::strcmp(name, "laderman")) return LCMA_LADERMAN;
+// Built-in schemes are the ones kernels were generated for: the paper's three and every further scheme
+// file that was present when the library was built (ids from 4 up).
+static int builtin_index_of_id(int id) {
+    for (int i = 0; i < kBuiltinCount; ++i)
+        if (kBuiltinIds[i] == id) return i;
     return -1;
 }
 
+int builtin_id_of(const char *name) {
+    for (int i = 0; i < kBuiltinCount; ++i)
+        if (!std::strcmp(kBuiltinNames[i], name)) return kBuiltinIds[i];
+    return -1;
+}
+
+const char *builtin_name_of(int id) {
+    if (id == LCMA_PLAIN) return "plain";
+    const int i = builtin_index_of_id(id);
+    return i < 0 ? nullptr : kBuiltinNames[i];
+}
+
+int builtin_max_id() {
+    int m = 0;
+    for (int i = 0; i < kBuiltinCount; ++i) m = kBuiltinIds[i] > m ? kBuiltinIds[i] : m;
+    return m;
+}
+
 const lcma_scheme *builtin_scheme(int id) {
-    static lcma_scheme *cache[4] = {nullptr, nullptr, nullptr, nullptr};
+    static std::vector<lcma_scheme *> cache(kBuiltinCount, nullptr);
     static std::mutex mu;
-    if (id < LCMA_STRASSEN || id > LCMA_LADERMAN) return nullptr;
+    const int i = builtin_index_of_id(id);
+    if (i < 0) return nullptr;
     std::lock_guard<std::mutex> lock(mu);
-    if (!cache[id]) {
-        const char *names[4] = {"", "strassen", "strassen2", "laderman"};
+    if (!cache[i]) {
         lcma_scheme *s = nullptr;
-        std::string spec = std::string("builtin:") + names[id];
+        std::string spec = std::string("builtin:") + kBuiltinNames[i];
         if (lcma_scheme_load(spec.c_str(), &s) != LCMA_OK) return nullptr;
         if (lcma_scheme_verify(s, nullptr) != LCMA_OK) {
             lcma_scheme_free(s);
             return nullptr;
         }
-        cache[id] = s;
+        cache[i] = s;
     }
-    return cache[id];
+    return cache[i];
 }
 
 } // namespace lcma
@@ -170,9 +189,9 @@ extern "C" lcma_status lcma_scheme_load(const char *spec, lcma_scheme **out) {
     }
     s->builtin = builtin > 0 ? builtin : 0;
     if (!s->builtin) { // a file holding the coefficients of a built-in scheme is that scheme
-        for (int id = LCMA_STRASSEN; id <= LCMA_LADERMAN; ++id) {
-            const lcma_scheme *b = builtin_scheme(id);
-            if (b && b->hash == s->hash && b->U == s->U && b->V == s->V && b->W == s->W) s->builtin = id;
+        for (int i = 0; i < kBuiltinCount; ++i) {
+            const lcma_scheme *b = builtin_scheme(kBuiltinIds[i]);
+            if (b && b->hash == s->hash && b->U == s->U && b->V == s->V && b->W == s->W) s->builtin = kBuiltinIds[i];
         }
     }
     *out = s;

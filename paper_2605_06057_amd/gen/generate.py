@@ -25,7 +25,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 PKG = os.path.dirname(HERE)
 SCHEME_DIR = os.path.join(PKG, "schemes")
 
-SCHEME_IDS = {"plain": 0, "strassen": 1, "strassen2": 2, "laderman": 3}
+SCHEME_IDS = {"plain": 0, "strassen": 1, "strassen2": 2, "laderman": 3}  # further scheme files: 4, 5, ... by name
 DTYPE_IDS = {"f32": 0, "bf16": 1, "f16": 2}
 ACC_REG_BUDGET = 400      # of 512 unified VGPR/AGPR per lane at one wave per SIMD
 LDS_BUDGET = 160 * 1024
@@ -92,6 +92,11 @@ def multiplies_matrices(s: Scheme) -> bool:
 
 
 def load_schemes() -> dict[str, Scheme]:
+    """The schemes kernels are generated for: Strassen and Laderman from their files, two-level
+    Strassen composed from Strassen, and every further scheme file: any other *.txt in schemes/ and the
+    paths listed (colon-separated) in the environment variable LCMA_EXTRA_SCHEMES.  A further scheme is
+    known to the library by its file name without the extension ("builtin:<name>") and gets ids from 4
+    up in name order."""
     out = {}
     for name in ("strassen", "laderman"):
         with open(os.path.join(SCHEME_DIR, name + ".txt")) as f:
@@ -99,9 +104,27 @@ def load_schemes() -> dict[str, Scheme]:
     out["strassen2"] = compose(out["strassen"], out["strassen"], "strassen2")
     one = np.ones((1, 1, 1), np.int64)
     out["plain"] = Scheme("plain", 1, 1, 1, 1, one, one, one)
+    extra = [os.path.join(SCHEME_DIR, f) for f in os.listdir(SCHEME_DIR) if f.endswith(".txt")]
+    extra += [p for p in os.environ.get("LCMA_EXTRA_SCHEMES", "").split(":") if p]
+    for path in sorted(extra, key=os.path.basename):
+        name = os.path.splitext(os.path.basename(path))[0]
+        if name in out:
+            continue
+        assert name.isidentifier(), f"{path}: the file name must be usable as an identifier"
+        with open(path) as f:
+            out[name] = parse_scheme(name, f.read())
     for s in out.values():
         assert multiplies_matrices(s), f"scheme {s.name} violates the Brent equations"
+    nxt = max(SCHEME_IDS.values()) + 1
+    for name in sorted(out):
+        if name not in SCHEME_IDS:
+            SCHEME_IDS[name] = nxt
+            nxt += 1
     return out
+
+
+def further_schemes(schemes: dict[str, Scheme]) -> list[str]:
+    return sorted(n for n in schemes if SCHEME_IDS[n] > 3)
 
 
 # ----------------------------------------------------------------------------- variants
@@ -405,9 +428,10 @@ def scheme_hash(s: Scheme) -> int:
 
 
 def emit_builtin_inc(schemes: dict[str, Scheme]) -> str:
-    names = [n for n in ("strassen", "strassen2", "laderman")]
+    names = ["strassen", "strassen2", "laderman"] + further_schemes(schemes)
     L = ["// GENERATED by gen/generate.py from schemes/*.txt - do not edit."]
     L.append("static const char *const kBuiltinNames[] = {" + ", ".join(f'"{n}"' for n in names) + "};")
+    L.append("static const int kBuiltinIds[] = {" + ", ".join(str(SCHEME_IDS[n]) for n in names) + "};")
     L.append("static const char *const kBuiltinTexts[] = {")
     for n in names:
         body = "".join(f'    "{line}\\n"\n' for line in schemes[n].text().splitlines())
@@ -417,8 +441,7 @@ def emit_builtin_inc(schemes: dict[str, Scheme]) -> str:
     return "\n".join(L) + "\n"
 
 
-# ----------------------------------------------------------------------------- manifest
-def manifest() -> list[Variant]:
+def manifest(schemes: dict[str, Scheme] | None = None) -> list[Variant]:
     """The kernels that are built.  `eff` is the fraction of the dtype's dense MFMA peak that the
     variant's own MFMA work sustained on MI355X at large shapes (4096^3 and up, this library's
     bench); the library launches, among the variants of a scheme whose tile divides the shape, the one
@@ -482,6 +505,14 @@ def manifest() -> list[Variant]:
         Variant("laderman", "f32", 64, 64, 16, chunk=1, eff=0.399),
         Variant("strassen2", "f32", 64, 64, 16, chunk=7, eff=0.511),
     ]
+    # Further scheme files get Algorithm 2's r loop (one product at a time, the m*n C tiles in registers)
+    # on a 64 x 64 tile, which fits any grid up to m*n = 24.
+    schemes = load_schemes() if schemes is None else schemes
+    for name in further_schemes(schemes):
+        sch = schemes[name]
+        assert (sch.m * sch.n + 1) * 16 <= ACC_REG_BUDGET, f"{name}: {sch.m}x{sch.n} C tiles do not fit the registers"
+        V += [Variant(name, "bf16", 64, 64, 32, chunk=1, eff=0.04), Variant(name, "f16", 64, 64, 32, chunk=1, eff=0.04),
+              Variant(name, "f32", 64, 64, 16, chunk=1, eff=0.4)]
     return [v.finish() for v in V]
 
 
@@ -489,7 +520,7 @@ def generate(out_dir: str) -> list[str]:
     """Writes the generated sources into out_dir; returns the .hip files to compile."""
     os.makedirs(out_dir, exist_ok=True)
     schemes = load_schemes()
-    variants = manifest()
+    variants = manifest(schemes)
     hips = []
 
     def put(name, text):

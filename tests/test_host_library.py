@@ -34,7 +34,7 @@ def test_every_declared_symbol_is_exported(B):
         assert hasattr(B.lib(), name), name
 
 
-@pytest.mark.parametrize("name", ["strassen", "strassen2", "laderman"])
+@pytest.mark.parametrize("name", ["strassen", "strassen2", "laderman", "strassen_wide"])
 def test_builtin_schemes_equal_the_oracles(B, name):
     s = B.lcma_scheme_load("builtin:" + name)
     assert B.lcma_scheme_verify(s) == -1
@@ -159,6 +159,23 @@ def test_selector_sanity(B):
     hw = B.lcma_hw_mi355x(B.LCMA_BF16)
     assert hw.flops_mul == pytest.approx(2516.6e12) and hw.beta == pytest.approx(4e12)
     assert B.lcma_hw_mi355x(B.LCMA_F32).flops_mul == pytest.approx(157.3e12)
+
+
+def test_further_scheme_files_get_ids_and_kernels(B):
+    """A scheme file present at build time (here the rectangular <2,2,4;14>) is known by name, gets an
+    id after the paper's three, and has kernels for every dtype; a copy of its text is recognised."""
+    L = B.lib()
+    assert L.lcma_scheme_name(0) == b"plain" and L.lcma_scheme_name(1) == b"strassen"
+    assert L.lcma_scheme_name(3) == b"laderman" and L.lcma_scheme_name(99) is None
+    ids = {L.lcma_scheme_name(i).decode(): i for i in range(L.lcma_scheme_id_max() + 1)}
+    assert ids["strassen_wide"] >= 4
+    vs = [v for v in B.lcma_variants() if v["scheme_id"] == ids["strassen_wide"]]
+    assert {v["dtype"] for v in vs} == {B.LCMA_F32, B.LCMA_BF16, B.LCMA_F16}
+    assert all(v["mult_N"] == 4 * v["TN"] and v["mult_M"] == 2 * v["TM"] for v in vs)
+    assert B.SCHEME_NAMES[ids["strassen_wide"]] == "strassen_wide"
+    s = B.lcma_scheme_load("builtin:strassen_wide")
+    info = B.lcma_scheme_info(s)
+    assert (info["m"], info["k"], info["n"], info["R"]) == (2, 2, 4, 14)
 
 
 def test_variant_registry(B):

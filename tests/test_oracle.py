@@ -16,7 +16,7 @@ import lcma_inputs as inp
 import oracle
 from oracle import schemes as S
 
-ALL = ["strassen", "laderman", "strassen2"]
+ALL = ["strassen", "laderman", "strassen2", "strassen_wide"]
 
 
 # ---------------------------------------------------------------- GEMM triple loop
