@@ -47,7 +47,7 @@ template <> struct Widen<F16> {
     }
 };
 
-// CH (generated): NB raw blocks with b_l(t), b_j(t); NP outputs; comb(in, out): out[r] = Eq. 4 on floats.
+// CH (generated): NB raw blocks with b_l(t), b_j(t); NP outputs; comb(in, r) = Eq. 4 for product r on floats.
 template <class IN, class CT, class CH> LCMA_DEV void prepare_b_tile(const PrepParams &p) {
     constexpr int ES = IN::ES, EPT = 16 / ES;       // elements per 16-byte vector
     constexpr int KT = 64 / ES;                     // k rows of the tile (32 or 16): 64-byte output rows
@@ -76,14 +76,13 @@ template <class IN, class CT, class CH> LCMA_DEV void prepare_b_tile(const PrepP
     for (int r = 0; r < CH::NP; ++r) {
 #pragma unroll
         for (int e = 0; e < EPT; ++e) {
-            // the generated code forms every output; r is a literal after unrolling, so the others are dead
-            float col[CH::NB], o[CH::NP];
+            float col[CH::NB];
 #pragma unroll
             for (int t = 0; t < CH::NB; ++t) col[t] = in[t][e];
-            CH::comb(col, o);
+            const float o = CH::comb(col, r);
             char *dst = tile + (tx * EPT + e) * PITCH + ky * ES;
-            if constexpr (ES == 2) *(_Float16 *)dst = (_Float16)o[r]; // one rounding, nearest-even
-            else *(float *)dst = o[r];
+            if constexpr (ES == 2) *(_Float16 *)dst = (_Float16)o; // one rounding, nearest-even
+            else *(float *)dst = o;
         }
         __syncthreads();
         const u32x4 v = *(const u32x4 *)(tile + rn * PITCH + rc * 16);
@@ -123,22 +122,20 @@ template <class IN, class CT, class CH> LCMA_DEV void prepare_bt_tile(const Prep
             f16x8 h;
 #pragma unroll
             for (int e = 0; e < EPT; ++e) {
-                float col[CH::NB], o[CH::NP];
+                float col[CH::NB];
 #pragma unroll
                 for (int t = 0; t < CH::NB; ++t) col[t] = in[t][e];
-                CH::comb(col, o);
-                h[e] = (_Float16)o[r]; // one rounding, nearest-even
+                h[e] = (_Float16)CH::comb(col, r); // one rounding, nearest-even
             }
             v = __builtin_bit_cast(u32x4, h);
         } else {
             f32x4 f;
 #pragma unroll
             for (int e = 0; e < EPT; ++e) {
-                float col[CH::NB], o[CH::NP];
+                float col[CH::NB];
 #pragma unroll
                 for (int t = 0; t < CH::NB; ++t) col[t] = in[t][e];
-                CH::comb(col, o);
-                f[e] = o[r];
+                f[e] = CH::comb(col, r);
             }
             v = __builtin_bit_cast(u32x4, f);
         }

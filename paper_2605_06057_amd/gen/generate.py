@@ -376,8 +376,10 @@ def emit_prep_b(s: Scheme, dtype: str) -> str:
     w(f"    static constexpr int NB = {len(b_blocks)}, NP = {s.R};")
     for fn, vals in (("b_l", [b[0] for b in b_blocks]), ("b_j", [b[1] for b in b_blocks])):
         w(f"    static LCMA_DEV constexpr int {fn}(int t) {{ constexpr int v[] = {{{', '.join(map(str, vals))}}}; return v[t]; }}")
-    w("    static LCMA_DEV void comb(const float (&in)[NB], float (&out)[NP]) {")
+    w("    // Bt_r at one element position; r is a literal at every call site, so the switch folds")
+    w("    static LCMA_DEV float comb(const float (&in)[NB], int r) {")
     w("#pragma clang fp contract(off)")
+    w("        switch (r) {")
     for r in range(s.R):
         # ascending (l, j), left to right: the order the stored result is defined in
         expr = ""
@@ -390,7 +392,9 @@ def emit_prep_b(s: Scheme, dtype: str) -> str:
                 expr = mag if c > 0 else f"-{mag}"
             else:
                 expr = f"({expr} {'+' if c > 0 else '-'} {mag})"
-        w(f"        out[{r}] = {expr or '0.f'};")
+        w(f"        case {r}: return {expr or '0.f'};")
+    w("        default: return 0.f;")
+    w("        }")
     w("    }")
     w("};")
     w("} // namespace")
