@@ -18,6 +18,9 @@ CONFIGS = [
     ("c3_strassen2_bf16_ffn", "strassen2", "bf16", 8192, 14336, 4096, "normal", "weights", 0x5EED0003, 2e-2),
     ("c4_laderman_f16_6144", "laderman", "f16", 6144, 6144, 6144, "uniform", "uniform", 0x5EED0004, 2e-2),
     ("c5_plain_bf16_2048x4096x14336", None, "bf16", 2048, 4096, 14336, "normal", "weights", 0x5EED0005, 2e-2),
+    # close to the largest C the 32-bit offsets allow (0.98 GB, padded 0.99 GB), ragged in all three directions
+    ("big_ragged_strassen_bf16", "strassen", "bf16", 30001, 16376, 2056, "normal", "weights", 0x5EED0006, 2e-2),
+    ("big_ragged_strassen_f32", "strassen", "f32", 15001, 16380, 1028, "uniform", "uniform", 0x5EED0007, 1e-5),
 ]
 
 
