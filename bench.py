@@ -67,8 +67,8 @@ def main():
                          "reported beside `value`, which stays the fully fused lcma_gemm")
     args = ap.parse_args()
     if args.gpus != 1:
-        sys.exit("bench.py: this build runs on ONE GPU (the path shards over M with no exchange; "
-                 "see DESIGN.md). Re-run with --gpus 1.")
+        sys.exit("bench.py: this build runs on ONE GPU (the path would shard over M with no exchange between "
+                 "GPUs, each running this same kernel on its rows). Re-run with --gpus 1.")
 
     import numpy as np
     import torch

@@ -88,7 +88,7 @@ def test_float_inputs_within_bounds(B, v):
     assert err_plain <= REL_BOUND[dt]
     # The library's defaults must stay within 4x the plain kernel's error.  The uncompensated Laderman
     # kernels with fp16 storage are kept as non-default ablation variants: rounding 3- and 7-term
-    # combinations to fp16 puts them at 4.05x by construction (parity bar), which is what
+    # combinations to fp16 puts them at 4.05x by construction, which is what
     # the compensated default variants (name suffix x2) exist to fix.
     ratio_bound = 4.2 if v["name"] in ("laderman_f16_t128x64x32_c1", "laderman_f16_t64x64x32_c1") else 4.0
     assert err <= ratio_bound * err_plain
