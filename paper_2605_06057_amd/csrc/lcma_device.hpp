@@ -12,6 +12,7 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <type_traits>
 
 #include "lcma_params.h"
 
@@ -351,9 +352,10 @@ template <class T> struct Ctx {
     // else the end of the extent (the load returns zero).  The column of a thread's chunk is worked
     // out again from its thread index there rather than kept in a register through the whole loop.
     LCMA_DEV uint32_t a_inside(uint32_t voff, uint32_t colb) const { return colb < p.k_row_b ? voff : p.a_bytes; }
-    LCMA_DEV u32x4 load_a(int q, uint32_t soff, int l, int y) const {
+    // `guard` is a literal at every call site: the steps before the tail carry no guard code at all.
+    LCMA_DEV u32x4 load_a(int q, uint32_t soff, int l, int y, bool guard) const {
         uint32_t vo = a_voff[q];
-        if (k_tail(y)) {
+        if (guard) {
             const int c = ((q * T::NT + (int)threadIdx.x) % T::NCHK_A) % T::CPR;
             vo = a_inside(vo, (uint32_t)l * p.a_bcol + (uint32_t)y * (T::TK * T::ES) + c * 16);
         }
@@ -597,12 +599,12 @@ template <class T, class CH> struct RawSet {
 };
 
 // Issue the buffer loads of step y into `r`.
-template <class T, class CH> LCMA_DEV void issue_loads(const Ctx<T> &cx, RawSet<T, CH> &r, int y) {
+template <class T, class CH> LCMA_DEV void issue_loads(const Ctx<T> &cx, RawSet<T, CH> &r, int y, bool guard) {
 #pragma unroll
     for (int t = 0; t < CH::NA; ++t) {
         const uint32_t so = cx.soff_a(CH::a_i(t), CH::a_l(t), y);
 #pragma unroll
-        for (int q = 0; q < T::QA; ++q) r.a[t][q] = cx.load_a(q, so, CH::a_l(t), y);
+        for (int q = 0; q < T::QA; ++q) r.a[t][q] = cx.load_a(q, so, CH::a_l(t), y, guard);
     }
     if constexpr (T::PB) {
 #pragma unroll
@@ -742,9 +744,9 @@ template <class T, class CH> struct FlatStage {
         }
     }
     // offset of A chunk q in step y (ragged K: the end of the extent when the chunk lies past K)
-    LCMA_DEV uint32_t a_off(const Ctx<T> &cx, int q, int y) const {
+    LCMA_DEV uint32_t a_off(const Ctx<T> &cx, int q, int y, bool guard) const {
         uint32_t vo = a_voff[q];
-        if (cx.k_tail(y)) {
+        if (guard) {
             const int id = (q * T::NT + (int)threadIdx.x) % NCA;
             const int t = id / T::NCHK_A, c = (id % T::NCHK_A) % T::CPR;
             vo = cx.a_inside(vo, (uint32_t)CH::a_l(t) * cx.p.a_bcol + (uint32_t)y * (T::TK * T::ES) + c * 16);
@@ -763,20 +765,20 @@ template <class T, class CH> struct FlatStage {
                     cx.rb, (int)b_voff[q], (int)(sbo + (uint32_t)e * cx.p.ldb_b), 0);
         }
     }
-    LCMA_DEV void issue(const Ctx<T> &cx, Raw &r, int y) const {
+    LCMA_DEV void issue(const Ctx<T> &cx, Raw &r, int y, bool guard) const {
         const uint32_t sa = cx.a_group + (uint32_t)y * (T::TK * T::ES);
 #pragma unroll
-        for (int q = 0; q < QA; ++q) r.a[q] = __builtin_amdgcn_raw_buffer_load_b128(cx.ra, (int)a_off(cx, q, y), (int)sa, 0);
+        for (int q = 0; q < QA; ++q) r.a[q] = __builtin_amdgcn_raw_buffer_load_b128(cx.ra, (int)a_off(cx, q, y, guard), (int)sa, 0);
 #pragma unroll
         for (int q = 0; q < QB; ++q) load_b(cx, r, q, y);
     }
     // The staging work of one thread cut into NPIECE pieces (one 16-byte A chunk or one B unit each),
     // so that it can be spread over the MFMA phase.
     static constexpr int NPIECE = QA + QB;
-    LCMA_DEV void issue_piece(const Ctx<T> &cx, Raw &r, int pc, int y) const {
+    LCMA_DEV void issue_piece(const Ctx<T> &cx, Raw &r, int pc, int y, bool guard) const {
         if (pc < QA) {
             const uint32_t sa = cx.a_group + (uint32_t)y * (T::TK * T::ES);
-            r.a[pc] = __builtin_amdgcn_raw_buffer_load_b128(cx.ra, (int)a_off(cx, pc, y), (int)sa, 0);
+            r.a[pc] = __builtin_amdgcn_raw_buffer_load_b128(cx.ra, (int)a_off(cx, pc, y, guard), (int)sa, 0);
         } else {
             load_b(cx, r, pc - QA, y);
         }
@@ -856,11 +858,11 @@ template <class T, class CH> struct DirectStage {
             b_voff[q] = (uint32_t)sl * cx.p.b_brow + (uint32_t)row * cx.p.ldb_b + T::swz(row, cs) * 16;
         }
     }
-    LCMA_DEV void issue_piece(const Ctx<T> &cx, int pc, int st, int y) const {
+    LCMA_DEV void issue_piece(const Ctx<T> &cx, int pc, int st, int y, bool guard) const {
         if (pc < QA) {
             const int first = pc * T::NT + wave_chunk;
             uint32_t vo = a_voff[pc];
-            if (cx.k_tail(y)) {
+            if (guard) {
                 const int pp = (pc * T::NT + (int)threadIdx.x) % NCA;
                 const int t = pp / T::NCHK_A, row = (pp % T::NCHK_A) / T::CPR, cs = (pp % T::NCHK_A) % T::CPR;
                 vo = cx.a_inside(vo, (uint32_t)CH::a_l(t) * cx.p.a_bcol + (uint32_t)y * (T::TK * T::ES) + T::swz(row, cs) * 16);
@@ -878,7 +880,7 @@ template <class T, class CH> struct DirectStage {
     }
     LCMA_DEV void issue(const Ctx<T> &cx, int st, int y) const {
 #pragma unroll
-        for (int pc = 0; pc < NPIECE; ++pc) issue_piece(cx, pc, st, y);
+        for (int pc = 0; pc < NPIECE; ++pc) issue_piece(cx, pc, st, y, true);
     }
     // every direct load of this wave has landed in LDS
     static LCMA_DEV void landed() { __builtin_amdgcn_s_waitcnt(0x0F70); } // vmcnt(0)
@@ -898,20 +900,31 @@ template <class T, class CH> LCMA_DEV void mma_step(const Ctx<T> &cx, int st, ty
 #define LCMA_LITERAL_STAGE 1
 #endif
 template <class T> constexpr bool LITERAL_STAGE = LCMA_LITERAL_STAGE != 0;
-template <bool LIT, class F> LCMA_DEV void stage_loop(int ny, F step) {
+template <bool LIT, class F> LCMA_DEV void stage_loop(int y0, int y1, F step) { // y0 even
     if constexpr (LIT) {
-        int y = 0;
-        for (; y + 1 < ny; y += 2) {
+        int y = y0;
+        for (; y + 1 < y1; y += 2) {
             step(y, 0);
             step(y + 1, 1);
         }
-        if (y < ny) step(y, 0);
+        if (y < y1) step(y, 0);
     } else {
-        for (int y = 0; y < ny; ++y) step(y, y & 1);
+        for (int y = y0; y < y1; ++y) step(y, y & 1);
     }
 }
 
 // The y loop of Algorithm 2 for one chunk over two LDS stages.
+//
+// Ragged K: only the loads of the last y steps can reach past K.  The loop is therefore run in two
+// parts, the steps whose loads stay inside K without any guard code and the few tail steps with the
+// guard on the A loads (the guard cost 4 % when it sat in every step).  main_steps(D, G) is where the
+// tail begins for a loop that loads tile y + D in step y, rounded down to a multiple of G stages.
+template <class T> LCMA_DEV int main_steps(const Ctx<T> &cx, int D, int G) {
+    const int yt = (int)(cx.p.k_tail_b / (T::TK * T::ES)); // first tile that reaches past K (ny if none)
+    const int m = yt - D > 0 ? yt - D : 0;
+    return m / G * G;
+}
+
 template <class T, class CH> LCMA_DEV void run_chunk(const Ctx<T> &cx, typename T::Acc (&acc)[CH::NP]) {
     const int ny = cx.p.ny, last = ny - 1;
     if constexpr (T::FC) {
@@ -919,14 +932,18 @@ template <class T, class CH> LCMA_DEV void run_chunk(const Ctx<T> &cx, typename 
         const FlatStage<T, CH> fs(cx);
         if constexpr (T::PIPE == 0) {
             typename FlatStage<T, CH>::Raw r;
-            fs.issue(cx, r, 0);
-            auto step = [&](int y, int st) {
-                fs.store(cx, r, st);
-                fs.issue(cx, r, y + 1 < ny ? y + 1 : last);
-                __syncthreads();
-                cx.template mma_stage_fc<CH>(st, acc);
+            fs.issue(cx, r, 0, true);
+            auto make_step = [&](auto guard) {
+                return [&](int y, int st) {
+                    fs.store(cx, r, st);
+                    fs.issue(cx, r, y + 1 < ny ? y + 1 : last, decltype(guard)::value);
+                    __syncthreads();
+                    cx.template mma_stage_fc<CH>(st, acc);
+                };
             };
-            stage_loop<LITERAL_STAGE<T>>(ny, step);
+            const int ym = main_steps(cx, 1, 2);
+            stage_loop<LITERAL_STAGE<T>>(0, ym, make_step(std::false_type{}));
+            stage_loop<LITERAL_STAGE<T>>(ym, ny, make_step(std::true_type{}));
             __syncthreads();
         } else if constexpr (T::DL) {
             // Direct loads: the tiles of step y+1 travel into the other stage while step y is multiplied;
@@ -935,22 +952,26 @@ template <class T, class CH> LCMA_DEV void run_chunk(const Ctx<T> &cx, typename 
             dl.issue(cx, 0, 0);
             dl.landed();
             __syncthreads();
-            auto step = [&](int y, int st) {
-                const int nxt = y + 1 < ny ? y + 1 : last; // past the end: the last tile again, unused
-                using DS = DirectStage<T, CH>;
-                cx.template mma_stage_pb<CH>(st, acc, [&](int slot, int slots) {
+            auto make_step = [&](auto guard) {
+                return [&](int y, int st) {
+                    const int nxt = y + 1 < ny ? y + 1 : last; // past the end: the last tile again, unused
+                    using DS = DirectStage<T, CH>;
+                    cx.template mma_stage_pb<CH>(st, acc, [&](int slot, int slots) {
 #pragma unroll
-                    for (int pc = 0; pc < DS::NPIECE; ++pc)
-                        if (pc * slots / DS::NPIECE == slot) {
-                            __builtin_amdgcn_sched_barrier(0);
-                            dl.issue_piece(cx, pc, st ^ 1, nxt);
-                            __builtin_amdgcn_sched_barrier(0);
-                        }
-                });
-                dl.landed();
-                __syncthreads();
+                        for (int pc = 0; pc < DS::NPIECE; ++pc)
+                            if (pc * slots / DS::NPIECE == slot) {
+                                __builtin_amdgcn_sched_barrier(0);
+                                dl.issue_piece(cx, pc, st ^ 1, nxt, decltype(guard)::value);
+                                __builtin_amdgcn_sched_barrier(0);
+                            }
+                    });
+                    dl.landed();
+                    __syncthreads();
+                };
             };
-            stage_loop<LITERAL_STAGE<T>>(ny, step);
+            const int ym = main_steps(cx, 1, 2);
+            stage_loop<LITERAL_STAGE<T>>(0, ym, make_step(std::false_type{}));
+            stage_loop<LITERAL_STAGE<T>>(ym, ny, make_step(std::true_type{}));
         } else if constexpr (T::PIPE == 2 && T::STAGES == 3) {
             // As below, with a third LDS stage: step y multiplies stage y%3, writes tile y+2 into stage
             // (y+2)%3 and reloads the registers with tile y+3.  The stage of step y+1 is complete one
@@ -959,36 +980,43 @@ template <class T, class CH> LCMA_DEV void run_chunk(const Ctx<T> &cx, typename 
             static_assert(T::NKK % 2 == 0, "fragment buffers must return to buffer 0 at the end of a step");
             using FS = FlatStage<T, CH>;
             typename FS::Raw r;
-            fs.issue(cx, r, 0);
+            fs.issue(cx, r, 0, true);
             fs.store(cx, r, 0);
-            fs.issue(cx, r, ny > 1 ? 1 : last);
+            fs.issue(cx, r, ny > 1 ? 1 : last, true);
             fs.store(cx, r, 1);
-            fs.issue(cx, r, ny > 2 ? 2 : last);
+            fs.issue(cx, r, ny > 2 ? 2 : last, true);
             __syncthreads();
             typename Ctx<T>::template Frags<CH> f;
             cx.template fetch_frags<CH>(f, 0, 0, 0);
-            auto step = [&](int y, int st) { // st = y % 3, a literal at every call site
-                const int nxt = y + 3 < ny ? y + 3 : last; // past the end: reload the last tile, unused
-                cx.template mma_stage_fc<CH>(st, (st + 1) % 3, f, acc, [&](int slot, int slots) {
+            auto make_step = [&](auto guard) {
+                return [&](int y, int st) { // st = y % 3, a literal at every call site
+                    const int nxt = y + 3 < ny ? y + 3 : last; // past the end: reload the last tile, unused
+                    cx.template mma_stage_fc<CH>(st, (st + 1) % 3, f, acc, [&](int slot, int slots) {
 #pragma unroll
-                    for (int pc = 0; pc < FS::NPIECE; ++pc)
-                        if (pc * slots / FS::NPIECE == slot) {
-                            __builtin_amdgcn_sched_barrier(0);
-                            fs.store_piece(cx, r, pc, (st + 2) % 3);
-                            fs.issue_piece(cx, r, pc, nxt);
-                            __builtin_amdgcn_sched_barrier(0);
-                        }
-                });
-                __syncthreads();
+                        for (int pc = 0; pc < FS::NPIECE; ++pc)
+                            if (pc * slots / FS::NPIECE == slot) {
+                                __builtin_amdgcn_sched_barrier(0);
+                                fs.store_piece(cx, r, pc, (st + 2) % 3);
+                                fs.issue_piece(cx, r, pc, nxt, decltype(guard)::value);
+                                __builtin_amdgcn_sched_barrier(0);
+                            }
+                    });
+                    __syncthreads();
+                };
             };
-            int y = 0;
-            for (; y + 2 < ny; y += 3) {
-                step(y, 0);
-                step(y + 1, 1);
-                step(y + 2, 2);
-            }
-            if (y < ny) step(y, 0);
-            if (y + 1 < ny) step(y + 1, 1);
+            auto loop3 = [&](int y0, int y1, auto step) { // y0 a multiple of 3
+                int y = y0;
+                for (; y + 2 < y1; y += 3) {
+                    step(y, 0);
+                    step(y + 1, 1);
+                    step(y + 2, 2);
+                }
+                if (y < y1) step(y, 0);
+                if (y + 1 < y1) step(y + 1, 1);
+            };
+            const int ym = main_steps(cx, 3, 3);
+            loop3(0, ym, make_step(std::false_type{}));
+            loop3(ym, ny, make_step(std::true_type{}));
         } else if constexpr (T::PIPE == 2) {
             // Staging spread over the MFMA phase: while step y is multiplied out of one LDS stage, each
             // thread writes its pieces of step y+1 to the other stage and reloads the piece's registers
@@ -997,41 +1025,49 @@ template <class T, class CH> LCMA_DEV void run_chunk(const Ctx<T> &cx, typename 
             // step y was last read in step y-1, before the previous barrier.
             using FS = FlatStage<T, CH>;
             typename FS::Raw r;
-            fs.issue(cx, r, 0);
+            fs.issue(cx, r, 0, true);
             fs.store(cx, r, 0);
-            fs.issue(cx, r, ny > 1 ? 1 : 0);
+            fs.issue(cx, r, ny > 1 ? 1 : 0, true);
             __syncthreads();
-            auto step = [&](int y, int st) {
-                const int nxt = y + 2 < ny ? y + 2 : last; // past the end: reload the last tile, unused
-                auto hook = [&](int slot, int slots) {
+            auto make_step = [&](auto guard) {
+                return [&](int y, int st) {
+                    const int nxt = y + 2 < ny ? y + 2 : last; // past the end: reload the last tile, unused
+                    auto hook = [&](int slot, int slots) {
 #pragma unroll
-                    for (int pc = 0; pc < FS::NPIECE; ++pc)
-                        if (pc * slots / FS::NPIECE == slot) {
-                            __builtin_amdgcn_sched_barrier(0);
-                            fs.store_piece(cx, r, pc, st ^ 1);
-                            fs.issue_piece(cx, r, pc, nxt);
-                            __builtin_amdgcn_sched_barrier(0);
-                        }
+                        for (int pc = 0; pc < FS::NPIECE; ++pc)
+                            if (pc * slots / FS::NPIECE == slot) {
+                                __builtin_amdgcn_sched_barrier(0);
+                                fs.store_piece(cx, r, pc, st ^ 1);
+                                fs.issue_piece(cx, r, pc, nxt, decltype(guard)::value);
+                                __builtin_amdgcn_sched_barrier(0);
+                            }
+                    };
+                    if constexpr (T::PB) cx.template mma_stage_pb<CH>(st, acc, hook);
+                    else cx.template mma_stage_fc<CH>(st, acc, hook);
+                    __syncthreads();
                 };
-                if constexpr (T::PB) cx.template mma_stage_pb<CH>(st, acc, hook);
-                else cx.template mma_stage_fc<CH>(st, acc, hook);
-                __syncthreads();
             };
-            stage_loop<LITERAL_STAGE<T>>(ny, step);
+            const int ym = main_steps(cx, 2, 2);
+            stage_loop<LITERAL_STAGE<T>>(0, ym, make_step(std::false_type{}));
+            stage_loop<LITERAL_STAGE<T>>(ym, ny, make_step(std::true_type{}));
         }
     } else {
         static_assert(T::PIPE == 0, "staged-combine kernels stage in one phase");
         // Plain double buffering: one register set, loads of step y+1 in flight during the MFMAs
         // of step y.  Meant for two work-groups per CU, which overlap each other's phases.
         RawSet<T, CH> r;
-        issue_loads<T, CH>(cx, r, 0);
-        auto step = [&](int y, int st) {
-            combine_store<T, CH>(cx, r, st);
-            issue_loads<T, CH>(cx, r, y + 1 < ny ? y + 1 : last);
-            __syncthreads();
-            mma_step<T, CH>(cx, st, acc);
+        issue_loads<T, CH>(cx, r, 0, true);
+        auto make_step = [&](auto guard) {
+            return [&](int y, int st) {
+                combine_store<T, CH>(cx, r, st);
+                issue_loads<T, CH>(cx, r, y + 1 < ny ? y + 1 : last, decltype(guard)::value);
+                __syncthreads();
+                mma_step<T, CH>(cx, st, acc);
+            };
         };
-        stage_loop<LITERAL_STAGE<T>>(ny, step);
+        const int ym = main_steps(cx, 1, 2);
+        stage_loop<LITERAL_STAGE<T>>(0, ym, make_step(std::false_type{}));
+        stage_loop<LITERAL_STAGE<T>>(ym, ny, make_step(std::true_type{}));
         __syncthreads();
     }
 }
