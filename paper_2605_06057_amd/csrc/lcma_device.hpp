@@ -1,14 +1,18 @@
 // Device-side building blocks of the fused LCMA kernel for gfx950 (CDNA4, 64-wide waves).
 //
-// One work-group (4 waves) owns one GROUP in the sense of the paper's Group-Parallel
+// One work-group (4 or 8 waves) owns one GROUP in the sense of the paper's Group-Parallel
 // Optimization (Sec. 3.2, Algorithm 2): the tile at coordinate (x, z) of every block of C.
 // The R products of the scheme are cut into CHUNKS.  For a chunk the work-group walks y
-// (the K/k direction): it loads the tiles A_{i,l}[x,y], B_{l,j}[y,z] that the chunk needs
-// (coalesced 16-byte buffer loads), forms the chunk's operand combinations of Eq. 3 / Eq. 4
-// in registers, writes them to LDS (never to HBM) and multiplies them with MFMA into one fp32
-// accumulator tile per product (Eq. 5).  After the chunk, the generated code applies W
-// (Eq. 6) in fp32 registers.  Everything that depends on U, V, W is straight-line generated
-// code (Sec. 3.1, coefficients as compile-time constants); this header is scheme-agnostic.
+// (the K/k direction) and multiplies with MFMA into one fp32 accumulator tile per product
+// (Eq. 5); after the chunk the generated code applies W (Eq. 6) in fp32 registers.  Nothing
+// but C is ever written to device memory.  Two dataflows form the operands of Eq. 3 / Eq. 4:
+//   staged combine    the tiles A_{i,l}[x,y], B_{l,j}[y,z] the chunk needs are loaded, combined
+//                     in registers and the combined tiles At_r, Bt_r written to LDS;
+//   fragment combine  the raw (converted) tiles are written to LDS and every wave combines the
+//                     MFMA fragments it reads (all R products advance together; the fast path).
+// With the offline Combine-B stage the right operands come from memory ready-made and go to
+// LDS untouched.  Everything that depends on U, V, W is straight-line generated code
+// (Sec. 3.1, coefficients as compile-time constants); this header is scheme-agnostic.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
