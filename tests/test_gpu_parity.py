@@ -120,6 +120,39 @@ def test_ragged_shapes_bit_exact(B, v):
         assert torch.all(guard == 7.0).item(), f"{v['name']} {M}x{N}: wrote outside C"
 
 
+def test_random_shapes_integer_exact(B):
+    """Seeded random (variant, M, N, K, leading dimensions): integer inputs, exact result, guard band
+    around C untouched.  Shapes run from a single row or vector up to a few tiles per direction."""
+    import torch
+    import gpu_util as G
+    vs = variants()
+    rng = np.random.default_rng(0x5EED0200)
+    for case in range(48):
+        v = vs[int(rng.integers(len(vs)))]
+        dt = DT[v["dtype"]]
+        vec = 4 if dt == "f32" else 8
+        M = int(rng.integers(1, 2 * v["mult_M"] + 2))
+        N = vec * int(rng.integers(1, 2 * v["mult_N"] // vec + 2))
+        K = vec * int(rng.integers(1, 3 * v["mult_K"] // vec + 2))
+        pa, pb, pc = (vec * int(rng.integers(0, 3)) for _ in range(3))
+        print(f"case {case}: {v['name']} {M}x{N}x{K} pads {pa},{pb},{pc}", flush=True)
+        Ai, Bi = inp.integers(1000 + case, 1, (M, K)), inp.integers(1000 + case, 2, (K, N))
+        want = inp.store(oracle.gemm(Ai, Bi).astype(np.float64), dt)
+        td = G.empty_like_c(1, 1, dt).dtype
+        big_a = torch.zeros((M, K + pa), dtype=td, device="cuda")
+        big_b = torch.zeros((K, N + pb), dtype=td, device="cuda")
+        big_a[:, :K] = G.to_device(inp.store(Ai, dt), dt)
+        big_b[:, :N] = G.to_device(inp.store(Bi, dt), dt)
+        big_c = G.empty_like_c(M + 2, N + pc + vec, dt, fill=7.0)
+        c = big_c[1:M + 1, vec:vec + N]
+        run_variant(B, v, big_a[:, :K], big_b[:, :N], c)
+        got = G.to_host_stored(c, dt)
+        assert np.array_equal(got.view(np.uint8), want.view(np.uint8)), (case, v["name"], M, N, K)
+        guard = big_c.clone()
+        guard[1:M + 1, vec:vec + N] = 7.0
+        assert torch.all(guard == 7.0).item(), f"case {case}: wrote outside C"
+
+
 def test_strided_views_and_dispatch(B):
     """lda/ldb/ldc larger than the rows, scheme handles through lcma_gemm (default variant choice)."""
     import torch
