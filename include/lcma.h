@@ -96,6 +96,16 @@ lcma_status lcma_gemm(int64_t M, int64_t N, int64_t K,
                       void *C, int64_t ldc, lcma_dtype dtype,
                       const lcma_scheme *scheme, void *stream);
 
+/* lcma_gemm with the right operand given the way a linear layer stores its weight (the operand the
+ * paper's end-to-end evaluation multiplies by): W is N x K row-major, ldw in elements, and
+ * C[M x N] = A[M x K] x W^T, that is B[k][n] = W[n][k] in Eq. 1.  Everything else (types, sizes,
+ * alignment, padding, arithmetic, errors) is lcma_gemm's; the result is the same bit for bit.
+ * NOKERNEL when no kernel taking this layout was generated for the scheme and dtype. */
+lcma_status lcma_gemm_nt(int64_t M, int64_t N, int64_t K,
+                         const void *A, int64_t lda, const void *W, int64_t ldw,
+                         void *C, int64_t ldc, lcma_dtype dtype,
+                         const lcma_scheme *scheme, void *stream);
+
 /* Generated kernels ("variants": one per scheme x dtype x tile shape x dataflow, Sec. 3.1
  * Automated Code Generation).  lcma_gemm picks the preferred variant that fits the shape;
  * lcma_gemm_variant runs the named one (same contract as lcma_gemm; the scheme is the one
@@ -120,6 +130,10 @@ lcma_status lcma_gemm_variant(const char *variant, int64_t M, int64_t N, int64_t
 /* 1 when variant `index` takes the output of lcma_prepare_b in place of B (its B argument in
  * lcma_gemm_variant is then that buffer and ldb is ignored), 0 when it takes B, -1 when out of range. */
 int lcma_variant_prepared(int index);
+/* What variant `index` takes as its B argument in lcma_gemm_variant: 0 the K x N matrix B, 1 the
+ * output of lcma_prepare_b, 2 the N x K matrix W of lcma_gemm_nt (ldb is then its leading
+ * dimension); -1 when out of range. */
+int lcma_variant_b_layout(int index);
 
 /* Offline Combine B (Eq. 4; Algorithm 2, stage 2).  The paper's end-to-end evaluation runs this stage
  * once for static weights B; lcma_gemm_prepared then multiplies any number of A against the result.

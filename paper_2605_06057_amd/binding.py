@@ -28,6 +28,7 @@ EXPORTS = [
     "lcma_select", "lcma_hw_mi355x", "lcma_model_stages", "lcma_model_intensity", "lcma_predict_seconds",
     "lcma_sched_waves", "lcma_sched_range", "lcma_status_str", "lcma_last_error",
     "lcma_scheme_name", "lcma_scheme_id_max", "lcma_variant_prepared", "lcma_prepared_b_bytes", "lcma_prepare_b", "lcma_prepare_bt", "lcma_gemm_prepared",
+    "lcma_gemm_nt", "lcma_variant_b_layout",
 ]
 
 
@@ -67,6 +68,8 @@ def lib() -> ctypes.CDLL:
         L.lcma_scheme_info.argtypes = [vp] + [pi32] * 7
         L.lcma_scheme_coeffs.argtypes = [vp, vp, vp, vp]
         L.lcma_gemm.argtypes = [i64, i64, i64, vp, i64, vp, i64, vp, i64, i32, vp, vp]
+        L.lcma_gemm_nt.argtypes = L.lcma_gemm.argtypes
+        L.lcma_variant_b_layout.argtypes = [i32]
         L.lcma_variant_count.argtypes = []
         L.lcma_variant_name.argtypes = [i32]
         L.lcma_variant_name.restype = cp
@@ -157,14 +160,15 @@ def _dtype_of(t) -> int:
     return {torch.float32: LCMA_F32, torch.bfloat16: LCMA_BF16, torch.float16: LCMA_F16}[t.dtype]
 
 
-def _marshal(A, B, C):
-    """(M, N, K, ptrs and leading dimensions, stream) of three row-major device tensors."""
+def _marshal(A, B, C, b_nk: bool = False):
+    """(M, N, K, ptrs and leading dimensions, stream) of three row-major device tensors; with b_nk the
+    second one is the N x K weight matrix."""
     import torch
     assert A.is_cuda and B.is_cuda and C.is_cuda, "matrices must live on the GPU"
     assert A.dim() == B.dim() == C.dim() == 2 and A.stride(1) == B.stride(1) == C.stride(1) == 1
     assert A.dtype == B.dtype == C.dtype
     M, K = A.shape
-    K2, N = B.shape
+    K2, N = B.shape[::-1] if b_nk else B.shape
     assert K == K2 and tuple(C.shape) == (M, N)
     stream = torch.cuda.current_stream(A.device).cuda_stream
     return M, N, K, A.data_ptr(), A.stride(0), B.data_ptr(), B.stride(0), C.data_ptr(), C.stride(0), stream
@@ -178,8 +182,17 @@ def lcma_gemm(A, B, C, scheme: Scheme | None = None):
     return C
 
 
-def lcma_gemm_variant(variant: str, A, B, C):
-    M, N, K, pa, lda, pb, ldb, pc, ldc, stream = _marshal(A, B, C)
+def lcma_gemm_nt(A, W, C, scheme: Scheme | None = None):
+    """C = A x W^T for the N x K weight tensor W, on the current stream."""
+    M, N, K, pa, lda, pw, ldw, pc, ldc, stream = _marshal(A, W, C, True)
+    _check(lib().lcma_gemm_nt(M, N, K, pa, lda, pw, ldw, pc, ldc, _dtype_of(A),
+                              scheme.handle if scheme is not None else None, stream))
+    return C
+
+
+def lcma_gemm_variant(variant: str, A, B, C, b_nk: bool = False):
+    """Runs the named kernel; b_nk: B is the N x K matrix (for variants whose b_layout is 2)."""
+    M, N, K, pa, lda, pb, ldb, pc, ldc, stream = _marshal(A, B, C, b_nk)
     _check(lib().lcma_gemm_variant(variant.encode(), M, N, K, pa, lda, pb, ldb, pc, ldc, stream))
     return C
 
@@ -193,6 +206,7 @@ def lcma_variants() -> list[dict]:
                      [int(x.value) for x in v]))
         d["name"] = lib().lcma_variant_name(i).decode()
         d["prepared"] = int(lib().lcma_variant_prepared(i))
+        d["b_layout"] = int(lib().lcma_variant_b_layout(i))  # 0: K x N, 1: prepared planes, 2: N x K
         out.append(d)
     return out
 

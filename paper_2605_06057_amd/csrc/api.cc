@@ -29,12 +29,12 @@ bool variant_fits(const Variant &v, int64_t M, int64_t N, int64_t K) {
 static bool fits(const Variant &v, int64_t M, int64_t N, int64_t K) { return variant_fits(v, M, N, K); }
 static int64_t round_up(int64_t x, int64_t g) { return (x + g - 1) / g * g; }
 
-const Variant *pick_variant(int scheme_id, int dtype, int64_t M, int64_t N, int64_t K, int prepared) {
+const Variant *pick_variant(int scheme_id, int dtype, int64_t M, int64_t N, int64_t K, int prepared, int b_nk) {
     const Variant *best = nullptr;
     double best_t = 0.0;
     for (int i = 0; i < kVariantCount; ++i) {
         const Variant &v = kVariants[i];
-        if (v.scheme_id != scheme_id || v.dtype != dtype || v.prepared != prepared || v.rank >= 90 || !fits(v, M, N, K))
+        if (v.scheme_id != scheme_id || v.dtype != dtype || v.prepared != prepared || v.b_nk != b_nk || v.rank >= 90 || !fits(v, M, N, K))
             continue;
         const double t = predict_variant(v, M, N, K);
         if (!best || t < best_t) {
@@ -51,8 +51,8 @@ static const Variant *find_variant(const char *name) {
     return nullptr;
 }
 
-// B and ldb describe the K x N matrix, or, for a prepared-B variant, the planes written by
-// lcma_prepare_b (ldb is then ignored).
+// B and ldb describe the K x N matrix; for a variant that takes the weight layout, the N x K matrix W;
+// for a prepared-B variant, the planes written by lcma_prepare_b (ldb is then ignored).
 static lcma_status run(const Variant &v, int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const void *B,
                        int64_t ldb, void *C, int64_t ldc, void *stream) {
     const int es = dtype_size(v.dtype);
@@ -61,7 +61,8 @@ static lcma_status run(const Variant &v, int64_t M, int64_t N, int64_t K, const 
     if (K == 0) return fail(LCMA_ERR_SHAPE, "lcma_gemm: K = 0 is not supported");
     if (!A || !B || !C) return fail(LCMA_ERR_ARG, "lcma_gemm: null matrix pointer");
     if (v.prepared) ldb = N;
-    if (lda < K || ldb < N || ldc < N) return fail(LCMA_ERR_ARG, "lcma_gemm: leading dimension smaller than the row");
+    if (lda < K || ldb < (v.b_nk ? K : N) || ldc < N)
+        return fail(LCMA_ERR_ARG, "lcma_gemm: leading dimension smaller than the row");
     if (((uintptr_t)A | (uintptr_t)B | (uintptr_t)C) & 15)
         return fail(LCMA_ERR_ARG, "lcma_gemm: matrix pointers must be 16-byte aligned");
     if (((lda * es) | (ldb * es) | (ldc * es)) & 15)
@@ -74,11 +75,14 @@ static lcma_status run(const Variant &v, int64_t M, int64_t N, int64_t K, const 
                   Kp = round_up(K, (int64_t)v.k * v.TK);
     const int64_t bm = Mp / v.m, bn = Np / v.n, bk = Kp / v.k;
     const int64_t a_bytes = ((M - 1) * lda + K) * es,
-                  b_bytes = v.prepared ? (int64_t)v.products * bn * bk * es : ((K - 1) * ldb + N) * es,
+                  b_bytes = v.prepared ? (int64_t)v.products * bn * bk * es
+                            : v.b_nk   ? ((N - 1) * ldb + K) * es
+                                       : ((K - 1) * ldb + N) * es,
                   c_bytes = ((M - 1) * ldc + N) * es;
     const int64_t lim = (int64_t)1 << 31;
     // offsets of padded rows and columns are formed in 32 bits before the range check drops them
-    if (((Mp - 1) * lda + Kp) * es >= lim || ((Kp - 1) * ldb + Np) * es >= lim || ((Mp - 1) * ldc + Np) * es >= lim ||
+    const int64_t b_span = v.b_nk ? (Np - 1) * ldb + Kp : (Kp - 1) * ldb + Np;
+    if (((Mp - 1) * lda + Kp) * es >= lim || b_span * es >= lim || ((Mp - 1) * ldc + Np) * es >= lim ||
         b_bytes >= lim)
         return fail(LCMA_ERR_SHAPE, "lcma_gemm: a matrix spans 2 GiB or more");
     Params p;
@@ -95,6 +99,10 @@ static lcma_status run(const Variant &v, int64_t M, int64_t N, int64_t K, const 
     p.a_bcol = (uint32_t)(bk * es);
     p.b_brow = (uint32_t)(bk * ldb * es);
     p.b_bcol = (uint32_t)(bn * es);
+    if (v.b_nk) { // block B_{l,j} is block (j, l) of W
+        p.b_brow = (uint32_t)(bk * es);
+        p.b_bcol = (uint32_t)(bn * ldb * es);
+    }
     if (v.prepared) { // plane r: bn rows of bk elements
         p.ldb_b = (uint32_t)(bk * es);
         p.b_brow = (uint32_t)(bn * bk * es);
@@ -127,9 +135,8 @@ static lcma_status run(const Variant &v, int64_t M, int64_t N, int64_t K, const 
 
 using namespace lcma;
 
-extern "C" lcma_status lcma_gemm(int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const void *B,
-                                 int64_t ldb, void *C, int64_t ldc, lcma_dtype dtype, const lcma_scheme *scheme,
-                                 void *stream) {
+static lcma_status gemm(int b_nk, int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const void *B, int64_t ldb,
+                        void *C, int64_t ldc, lcma_dtype dtype, const lcma_scheme *scheme, void *stream) {
     if (!dtype_size(dtype)) return fail(LCMA_ERR_DTYPE, "lcma_gemm: unknown dtype %d", (int)dtype);
     int id = LCMA_PLAIN;
     if (scheme) {
@@ -145,17 +152,33 @@ extern "C" lcma_status lcma_gemm(int64_t M, int64_t N, int64_t K, const void *A,
     const Variant *v = nullptr;
     if (const char *force = std::getenv("LCMA_VARIANT")) { // ablation override
         v = find_variant(force);
-        if (v && (v->scheme_id != id || v->dtype != (int)dtype)) v = nullptr;
+        if (v && (v->scheme_id != id || v->dtype != (int)dtype || v->prepared || v->b_nk != b_nk)) v = nullptr;
     }
-    if (!v) v = pick_variant(id, dtype, M, N, K);
+    if (!v) v = pick_variant(id, dtype, M, N, K, 0, b_nk);
     if (!v) {
         bool any = false;
-        for (int i = 0; i < kVariantCount; ++i) any |= kVariants[i].scheme_id == id && kVariants[i].dtype == (int)dtype;
-        if (!any) return fail(LCMA_ERR_NOKERNEL, "lcma_gemm: no kernel for scheme id %d with dtype %d", id, (int)dtype);
+        for (int i = 0; i < kVariantCount; ++i)
+            any |= kVariants[i].scheme_id == id && kVariants[i].dtype == (int)dtype && !kVariants[i].prepared &&
+                   kVariants[i].b_nk == b_nk;
+        if (!any)
+            return fail(LCMA_ERR_NOKERNEL, "lcma_gemm: no kernel for scheme id %d with dtype %d%s", id, (int)dtype,
+                        b_nk ? " that takes B as N x K" : "");
         return fail(LCMA_ERR_SHAPE, "lcma_gemm: no kernel of scheme id %d takes N = %lld (whole 16-byte vectors) and K = %lld (whole tiles)",
                     id, (long long)N, (long long)K);
     }
     return run(*v, M, N, K, A, lda, B, ldb, C, ldc, stream);
+}
+
+extern "C" lcma_status lcma_gemm(int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const void *B,
+                                 int64_t ldb, void *C, int64_t ldc, lcma_dtype dtype, const lcma_scheme *scheme,
+                                 void *stream) {
+    return gemm(0, M, N, K, A, lda, B, ldb, C, ldc, dtype, scheme, stream);
+}
+
+extern "C" lcma_status lcma_gemm_nt(int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const void *W,
+                                    int64_t ldw, void *C, int64_t ldc, lcma_dtype dtype, const lcma_scheme *scheme,
+                                    void *stream) {
+    return gemm(1, M, N, K, A, lda, W, ldw, C, ldc, dtype, scheme, stream);
 }
 
 extern "C" lcma_status lcma_gemm_variant(const char *variant, int64_t M, int64_t N, int64_t K, const void *A,
@@ -316,6 +339,11 @@ extern "C" int lcma_scheme_id_max(void) { return builtin_max_id(); }
 
 extern "C" int lcma_variant_prepared(int index) {
     return (index >= 0 && index < kVariantCount) ? kVariants[index].prepared : -1;
+}
+
+extern "C" int lcma_variant_b_layout(int index) {
+    if (index < 0 || index >= kVariantCount) return -1;
+    return kVariants[index].prepared ? 1 : kVariants[index].b_nk ? 2 : 0;
 }
 
 extern "C" const char *lcma_status_str(lcma_status st) {

@@ -44,6 +44,7 @@ struct Variant {
     int occ;            // work-groups per compute unit it is compiled for
     int products;       // block products it multiplies (R plus residual products)
     int prepared;       // 1: takes the output of the offline Combine-B kernel instead of B
+    int b_nk;           // 1: takes B as the N x K weight matrix W (W[n][k] = B[k][n])
     int (*launch)(const Params *p, int grid, void *stream); // returns a hipError_t
 };
 extern const Variant kVariants[];
@@ -62,7 +63,7 @@ int dtype_size(int dtype); // bytes, or 0
 
 // Variant of (scheme_id, dtype) with the smallest predicted time among those whose tile divides the
 // shape; nullptr if none.
-const Variant *pick_variant(int scheme_id, int dtype, int64_t M, int64_t N, int64_t K, int prepared = 0);
+const Variant *pick_variant(int scheme_id, int dtype, int64_t M, int64_t N, int64_t K, int prepared = 0, int b_nk = 0);
 // Predicted seconds of one variant on MI355X (MFMA time at its measured efficiency, stretched by
 // wave quantisation on 256 compute units, bounded below by the compulsory HBM traffic, plus launch).
 double predict_variant(const Variant &v, int64_t M, int64_t N, int64_t K);

@@ -126,16 +126,20 @@ template <> struct Round<BF16> {
 //         only the A side is combined on fragments;
 // DL: 1 (with PB) = tiles travel from memory straight into LDS (buffer loads with the LDS bit: no
 //         staging registers, no LDS write instructions); the raw A blocks then sit in LDS in the
-//         storage type and are converted on the fragments.
+//         storage type and are converted on the fragments;
+// TB: 1 = B is given as the N x K matrix W with W[n][k] = B[k][n] (the layout of a linear layer's
+//         weight): its rows are k-contiguous like those of A, so its tiles are staged exactly like
+//         A's (16-byte loads, no transposition).
 //
 // LDS layout of a stage: NSA tiles [TM rows][TK] then NSB tiles [TN rows][TK], both k-contiguous,
 // 16-byte chunks XOR-swizzled inside a row.  B arrives n-contiguous from memory and is transposed
 // in registers while it is staged, so that both MFMA operands are read with 16-byte LDS loads
 // (measured on MI355X: ds_read_b128 ~260 B/clk/CU, the transposing ds_read_b64_tr_b16 ~70).
 template <class IN_, class CT_, int TM_, int TN_, int TK_, int WGM_, int WGN_, int NSA_, int NSB_, int PIPE_ = 0,
-          int FC_ = 0, int STAGES_ = 2, int PB_ = 0, int DL_ = 0>
+          int FC_ = 0, int STAGES_ = 2, int PB_ = 0, int DL_ = 0, int TB_ = 0>
 struct Tile {
-    static constexpr int PIPE = PIPE_, FC = FC_, PB = PB_, DL = DL_;
+    static constexpr int PIPE = PIPE_, FC = FC_, PB = PB_, DL = DL_, TB = TB_;
+    static_assert(!TB_ || !PB_, "a prepared operand has one layout only");
     static_assert(!DL_ || PB_, "direct loads need an operand that goes to LDS untouched on both sides");
     static_assert(!PB_ || (FC_ && PIPE_ == 2 && STAGES_ == 2) || (!FC_ && PIPE_ == 0),
                   "prepared B: the interleaved fragment-combine loop or the staged loop");
@@ -154,12 +158,13 @@ struct Tile {
     static constexpr int ROW = TK * ES;        // LDS row pitch in bytes
     static constexpr int NCHK_A = TM * CPR;    // A is staged one 16-byte chunk per thread and step
     static constexpr int QA = (NCHK_A + NT - 1) / NT;
-    // B is staged in units: 16-bit: a column pair x 8 consecutive k (8 dword loads -> 2 chunks);
-    // fp32: one column x 4 consecutive k (4 dword loads -> 1 chunk).
+    // B (K x N) is staged in units: 16-bit: a column pair x 8 consecutive k (8 dword loads -> 2 chunks);
+    // fp32: one column x 4 consecutive k (4 dword loads -> 1 chunk).  Given as N x K a unit is one
+    // 16-byte chunk of a row, as for A.
     static constexpr int BW = (ES == 2) ? 8 : 4;   // dword loads per unit
-    static constexpr int BH = BW / 4;              // 16-byte register vectors per unit
+    static constexpr int BH = TB ? 1 : BW / 4;     // 16-byte register vectors per unit
     static constexpr int BCOLS = (ES == 2) ? TN / 2 : TN;
-    static constexpr int NU_B = BCOLS * CPR;
+    static constexpr int NU_B = TB ? TN * CPR : BCOLS * CPR;
     static constexpr int QB = (NU_B + NT - 1) / NT;
     static constexpr int NCHK_BP = TN * CPR;   // 16-byte chunks of one tile of a prepared right operand
     static constexpr int QBP = (NCHK_BP + NT - 1) / NT;
@@ -267,12 +272,13 @@ template <class T> struct Ctx {
     __amdgpu_buffer_rsrc_t ra, rb, rc;
     int lane, wm, wn;
     uint32_t a_group, b_group, c_group; // byte offsets of this group's tile inside a block
+    uint32_t n_group;                   // first column n of the tile inside a block, in bytes of a row of C
     uint32_t a_voff[T::QA], b_voff[T::QB];
     uint32_t a_lds[T::QA], b_lds[T::QB], b_lds1[T::QB]; // b_lds1: second LDS row of a 16-bit B unit
     uint32_t a_frag[T::NKK], b_frag[T::NKK];
     uint32_t c_voff; // byte offset of this lane's first output element inside the tile
     uint32_t c_colb; // byte column of that element inside a block of C (for the N bound)
-    uint32_t b_colb[T::QB]; // byte column inside a block of B of the unit staged by this thread
+    uint32_t b_colb[T::QB]; // position n (in bytes of a row of C) inside a block of the unit staged by this thread
     uint32_t bp_voff[T::QBP], bp_lds[T::QBP]; // staged kernels with prepared B: chunks of a Bt_r tile
 
     LCMA_DEV Ctx(const Params &p_, LCMA_LDS char *lds_) : p(p_), lds(lds_) {
@@ -305,8 +311,9 @@ template <class T> struct Ctx {
             z = (p.nz / pw) * pw + rem % w2;
         }
         a_group = (uint32_t)x * T::TM * p.lda_b;
-        b_group = T::PB ? (uint32_t)z * T::TN * p.ldb_b : (uint32_t)z * T::TN * T::ES;
+        b_group = (T::PB || T::TB) ? (uint32_t)z * T::TN * p.ldb_b : (uint32_t)z * T::TN * T::ES;
         c_group = (uint32_t)x * T::TM * p.ldc_b + (uint32_t)z * T::TN * T::ES;
+        n_group = (uint32_t)z * T::TN * T::ES;
 
 #pragma unroll
         for (int q = 0; q < T::QA; ++q) {
@@ -321,12 +328,20 @@ template <class T> struct Ctx {
         for (int q = 0; q < T::QB; ++q) {
             // consecutive lanes take consecutive columns (coalesced dword loads along a row of B)
             const int u = (q * T::NT + tid) % T::NU_B;
-            const int col = u % T::BCOLS, g = u / T::BCOLS; // g: group of CH consecutive k
-            const int row = (T::ES == 2) ? 2 * col : col;   // LDS row = column n of the tile
-            b_voff[q] = (uint32_t)(g * T::CH) * p.ldb_b + col * 4;
-            b_colb[q] = (uint32_t)z * T::TN * T::ES + col * 4;
-            b_lds[q] = T::A_STAGE + row * T::ROW + T::swz(row, g) * 16;
-            b_lds1[q] = T::A_STAGE + (row + 1) * T::ROW + T::swz(row + 1, g) * 16;
+            if constexpr (T::TB) { // rows n of the tile, k-contiguous: as for A
+                const int row = u / T::CPR, c = u % T::CPR;
+                b_voff[q] = (uint32_t)row * p.ldb_b + c * 16;
+                b_colb[q] = (uint32_t)(z * T::TN + row) * T::ES;
+                b_lds[q] = T::A_STAGE + row * T::ROW + T::swz(row, c) * 16;
+                b_lds1[q] = 0;
+            } else {
+                const int col = u % T::BCOLS, g = u / T::BCOLS; // g: group of CH consecutive k
+                const int row = (T::ES == 2) ? 2 * col : col;   // LDS row = column n of the tile
+                b_voff[q] = (uint32_t)(g * T::CH) * p.ldb_b + col * 4;
+                b_colb[q] = (uint32_t)z * T::TN * T::ES + col * 4;
+                b_lds[q] = T::A_STAGE + row * T::ROW + T::swz(row, g) * 16;
+                b_lds1[q] = T::A_STAGE + (row + 1) * T::ROW + T::swz(row + 1, g) * 16;
+            }
         }
 #pragma unroll
         for (int q = 0; q < T::QBP; ++q) {
@@ -366,8 +381,19 @@ template <class T> struct Ctx {
         return __builtin_amdgcn_raw_buffer_load_b128(ra, (int)vo, (int)soff, 0);
     }
     // Offset of B unit q in block column j: past N the lane reads from the end of the extent (zero).
+    // (c_bcol is the width of a block of B and C in bytes of n, whichever way B is stored.)
     LCMA_DEV uint32_t b_voff_in(int q, int j) const {
-        return ((uint32_t)j * p.b_bcol + b_colb[q] < p.n_row_b) ? b_voff[q] : p.b_bytes;
+        return ((uint32_t)j * p.c_bcol + b_colb[q] < p.n_row_b) ? b_voff[q] : p.b_bytes;
+    }
+    // B given N x K: chunk q of the tile of B_{l,j}; what lies past K must read as zero here too,
+    // because a row of W continues with padding or with the next row.
+    LCMA_DEV u32x4 load_bt(int q, uint32_t soff, int l, int j, int y, bool guard) const {
+        uint32_t vo = b_voff_in(q, j);
+        if (guard) {
+            const int c = ((q * T::NT + (int)threadIdx.x) % T::NU_B) % T::CPR;
+            if ((uint32_t)l * p.b_brow + (uint32_t)y * (T::TK * T::ES) + c * 16 >= p.k_row_b) vo = p.b_bytes;
+        }
+        return __builtin_amdgcn_raw_buffer_load_b128(rb, (int)vo, (int)soff, 0);
     }
     LCMA_DEV uint32_t load_b(uint32_t voff, uint32_t soff) const {
         return __builtin_amdgcn_raw_buffer_load_b32(rb, (int)voff, (int)soff, 0);
@@ -377,7 +403,8 @@ template <class T> struct Ctx {
         return (uint32_t)i * p.a_brow + (uint32_t)l * p.a_bcol + a_group + (uint32_t)y * (T::TK * T::ES);
     }
     LCMA_DEV uint32_t soff_b(int l, int j, int y) const {
-        return (uint32_t)l * p.b_brow + (uint32_t)j * p.b_bcol + b_group + (uint32_t)y * T::TK * p.ldb_b;
+        return (uint32_t)l * p.b_brow + (uint32_t)j * p.b_bcol + b_group +
+               (T::TB ? (uint32_t)y * (T::TK * T::ES) : (uint32_t)y * T::TK * p.ldb_b);
     }
 
     LCMA_DEV void lds_store(uint32_t off, const u32x4 &v) const { *(LCMA_LDS u32x4 *)(lds + off) = v; }
@@ -624,9 +651,13 @@ template <class T, class CH> LCMA_DEV void issue_loads(const Ctx<T> &cx, RawSet<
             const uint32_t so = cx.soff_b(CH::b_l(t), CH::b_j(t), y);
 #pragma unroll
             for (int q = 0; q < T::QB; ++q) {
-                const uint32_t vo = cx.b_voff_in(q, CH::b_j(t));
+                if constexpr (T::TB) {
+                    r.b[t][q][0] = cx.load_bt(q, so, CH::b_l(t), CH::b_j(t), y, guard);
+                } else {
+                    const uint32_t vo = cx.b_voff_in(q, CH::b_j(t));
 #pragma unroll
-                for (int e = 0; e < T::BW; ++e) r.b[t][q][e / 4][e % 4] = cx.load_b(vo, so + (uint32_t)e * cx.p.ldb_b);
+                    for (int e = 0; e < T::BW; ++e) r.b[t][q][e / 4][e % 4] = cx.load_b(vo, so + (uint32_t)e * cx.p.ldb_b);
+                }
             }
         }
     }
@@ -678,7 +709,9 @@ template <class T, class CH> LCMA_DEV void combine_store(const Ctx<T> &cx, const
         }
 #pragma unroll
         for (int s = 0; s < NOB; ++s) {
-            if constexpr (T::ES == 2) {
+            if constexpr (T::TB) { // a chunk of a row n: k-contiguous already
+                cx.lds_store(sb + s * T::B_SLOT + cx.b_lds[q], __builtin_bit_cast(u32x4, out[0][s]));
+            } else if constexpr (T::ES == 2) {
                 // dword e of the unit holds columns (2c, 2c+1) at k = k0 + e; gather the low halves
                 // into the chunk of column 2c and the high halves into the chunk of column 2c+1
                 const u32x4 lo = __builtin_bit_cast(u32x4, out[0][s]), hi = __builtin_bit_cast(u32x4, out[1][s]);
@@ -734,6 +767,17 @@ template <class T, class CH> struct FlatStage {
                 b_voff[q] = (uint32_t)sl * cx.p.b_brow + (uint32_t)row * cx.p.ldb_b + c * 16;
                 b_lds[q] = T::A_STAGE + sl * T::B_SLOT + row * T::ROW + T::swz(row, c) * 16;
                 b_lds1[q] = 0;
+            } else if constexpr (T::TB) {
+                // B given N x K: chunk c of row n of block B_{l,j}, handled like a chunk of A
+                const int t = id / T::NU_B, u = id % T::NU_B;
+                const int row = u / T::CPR, c = u % T::CPR;
+                b_voff[q] = (uint32_t)CH::b_l(t) * cx.p.b_brow + (uint32_t)CH::b_j(t) * cx.p.b_bcol +
+                            (uint32_t)row * cx.p.ldb_b + c * 16;
+                // rows past N: read from the end of the extent (zero) for the whole run
+                const uint32_t n_b = cx.n_group + (uint32_t)row * T::ES; // n inside the block, in bytes of a row of C
+                if ((uint32_t)CH::b_j(t) * cx.p.c_bcol + n_b >= cx.p.n_row_b) b_voff[q] = cx.p.b_bytes;
+                b_lds[q] = T::A_STAGE + t * T::B_SLOT + row * T::ROW + T::swz(row, c) * 16;
+                b_lds1[q] = 0;
             } else {
                 const int t = id / T::NU_B, u = id % T::NU_B;
                 const int col = u % T::BCOLS, g = u / T::BCOLS;
@@ -757,10 +801,19 @@ template <class T, class CH> struct FlatStage {
         }
         return vo;
     }
-    LCMA_DEV void load_b(const Ctx<T> &cx, Raw &r, int q, int y) const {
+    LCMA_DEV void load_b(const Ctx<T> &cx, Raw &r, int q, int y, bool guard) const {
         if constexpr (T::PB) {
             const uint32_t sbo = cx.b_group + (uint32_t)y * (T::TK * T::ES);
             r.b[q][0] = __builtin_amdgcn_raw_buffer_load_b128(cx.rb, (int)b_voff[q], (int)sbo, 0);
+        } else if constexpr (T::TB) {
+            const uint32_t sbo = cx.b_group + (uint32_t)y * (T::TK * T::ES);
+            uint32_t vo = b_voff[q];
+            if (guard) { // past K a row of W goes on with padding or the next row: read zero instead
+                const int id = (q * T::NT + (int)threadIdx.x) % NUB;
+                const int t = id / T::NU_B, c = (id % T::NU_B) % T::CPR;
+                if ((uint32_t)CH::b_l(t) * cx.p.b_brow + (uint32_t)y * (T::TK * T::ES) + c * 16 >= cx.p.k_row_b) vo = cx.p.b_bytes;
+            }
+            r.b[q][0] = __builtin_amdgcn_raw_buffer_load_b128(cx.rb, (int)vo, (int)sbo, 0);
         } else {
             const uint32_t sbo = cx.b_group + (uint32_t)y * T::TK * cx.p.ldb_b;
 #pragma unroll
@@ -774,7 +827,7 @@ template <class T, class CH> struct FlatStage {
 #pragma unroll
         for (int q = 0; q < QA; ++q) r.a[q] = __builtin_amdgcn_raw_buffer_load_b128(cx.ra, (int)a_off(cx, q, y, guard), (int)sa, 0);
 #pragma unroll
-        for (int q = 0; q < QB; ++q) load_b(cx, r, q, y);
+        for (int q = 0; q < QB; ++q) load_b(cx, r, q, y, guard);
     }
     // The staging work of one thread cut into NPIECE pieces (one 16-byte A chunk or one B unit each),
     // so that it can be spread over the MFMA phase.
@@ -784,7 +837,7 @@ template <class T, class CH> struct FlatStage {
             const uint32_t sa = cx.a_group + (uint32_t)y * (T::TK * T::ES);
             r.a[pc] = __builtin_amdgcn_raw_buffer_load_b128(cx.ra, (int)a_off(cx, pc, y, guard), (int)sa, 0);
         } else {
-            load_b(cx, r, pc - QA, y);
+            load_b(cx, r, pc - QA, y, guard);
         }
     }
     LCMA_DEV void store_piece(const Ctx<T> &cx, const Raw &r, int pc, int st) const {
@@ -807,6 +860,8 @@ template <class T, class CH> struct FlatStage {
         using Cv = Convert<typename T::IN, typename T::CT>;
         if constexpr (T::PB) {
             cx.lds_store(sb + b_lds[q], r.b[q][0]); // already in the compute type and k-contiguous
+        } else if constexpr (T::TB) {
+            cx.lds_store(sb + b_lds[q], __builtin_bit_cast(u32x4, Cv::run(r.b[q][0]))); // k-contiguous already
         } else {
             if constexpr (T::ES == 2) {
                 const u32x4 lo = __builtin_bit_cast(u32x4, Cv::run(r.b[q][0]));

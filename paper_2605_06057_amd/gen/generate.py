@@ -147,12 +147,13 @@ class Variant:
     comp: tuple = ()          # products (0-based) whose left operand also gets its rounding residual multiplied
     pb: int = 0               # 1: B side comes from the offline Combine-B kernel (needs fc, pipe 2)
     dl: int = 0               # 1 (with pb): tiles are loaded from memory straight into LDS
+    tb: int = 0               # 1: B is given as the N x K weight matrix (k-contiguous rows)
     name: str = field(default="")
 
     def finish(self):
         if not self.name:
             self.name = (f"{self.scheme}_{self.dtype}_t{self.TM}x{self.TN}x{self.TK}_c{self.chunk}"
-                         + (f"x{len(self.comp)}" if self.comp else "") + (f"w{self.wgm}x{self.wgn}" if (self.wgm, self.wgn) != (2, 2) else "") + ("f" if self.fc else "") + ("i" if self.pipe == 2 else "") + ("s3" if self.stages == 3 else "") + ("b" if self.pb else "") + ("d" if self.dl else "") + (f"o{self.occ}" if self.occ > 1 else ""))
+                         + (f"x{len(self.comp)}" if self.comp else "") + (f"w{self.wgm}x{self.wgn}" if (self.wgm, self.wgn) != (2, 2) else "") + ("f" if self.fc else "") + ("i" if self.pipe == 2 else "") + ("s3" if self.stages == 3 else "") + ("b" if self.pb else "") + ("d" if self.dl else "") + ("t" if self.tb else "") + (f"o{self.occ}" if self.occ > 1 else ""))
         return self
 
 
@@ -248,7 +249,7 @@ def emit_kernel(s: Scheme, v: Variant) -> str:
     w('#include "lcma_device.hpp"')
     w("namespace {")
     w("using namespace lcma;")
-    w(f"using T = Tile<{in_t}, {ct_t}, {v.TM}, {v.TN}, {v.TK}, {v.wgm}, {v.wgn}, {nsa}, {nsb}, {v.pipe}, {v.fc}, {v.stages}, {v.pb}, {v.dl}>;")
+    w(f"using T = Tile<{in_t}, {ct_t}, {v.TM}, {v.TN}, {v.TK}, {v.wgm}, {v.wgn}, {nsa}, {nsb}, {v.pipe}, {v.fc}, {v.stages}, {v.pb}, {v.dl}, {v.tb}>;")
     for ci, ch in enumerate(chunks):
         a_blocks = sorted({(i, l) for r in ch for i in range(s.m) for l in range(s.k) if s.U[r, i, l]})
         b_blocks = sorted({(l, j) for r in ch for l in range(s.k) for j in range(s.n) if s.V[r, l, j]})
@@ -342,7 +343,7 @@ def emit_registry(schemes: dict[str, Scheme], variants: list[Variant]) -> str:
         s = schemes[v.scheme]
         hash_expr = "0" if s.name == "plain" else f"0x{scheme_hash(s):016x}ull"
         L.append(f'    {{"{v.name}", {SCHEME_IDS[v.scheme]}, {DTYPE_IDS[v.dtype]}, {s.m}, {s.k}, {s.n}, {s.R}, '
-                 f"{hash_expr}, {v.TM}, {v.TN}, {v.TK}, {min(v.chunk, s.R)}, {v.rank}, {v.eff}, {v.occ}, {s.R + len(v.comp)}, {v.pb}, lcma_launch_{v.name}}},")
+                 f"{hash_expr}, {v.TM}, {v.TN}, {v.TK}, {min(v.chunk, s.R)}, {v.rank}, {v.eff}, {v.occ}, {s.R + len(v.comp)}, {v.pb}, {v.tb}, lcma_launch_{v.name}}},")
     L += ["};", f"const int kVariantCount = {len(variants)};"]
     preps = prep_kernels(variants)
     L.append("const PrepKernel kPrepKernels[] = {")
@@ -517,6 +518,10 @@ def manifest(schemes: dict[str, Scheme] | None = None) -> list[Variant]:
         assert (sch.m * sch.n + 1) * 16 <= ACC_REG_BUDGET, f"{name}: {sch.m}x{sch.n} C tiles do not fit the registers"
         V += [Variant(name, "bf16", 64, 64, 32, chunk=1, eff=0.04), Variant(name, "f16", 64, 64, 32, chunk=1, eff=0.04),
               Variant(name, "f32", 64, 64, 16, chunk=1, eff=0.4)]
+    # Every kernel that lcma_gemm can pick for the paper's schemes also exists for B given as the N x K
+    # weight matrix ("t"): its B tiles are staged like A's, with 16-byte loads and no transposition.
+    from dataclasses import replace
+    V += [replace(v, tb=1, name="") for v in V if not v.pb and v.rank < 90 and SCHEME_IDS[v.scheme] <= 3]
     return [v.finish() for v in V]
 
 

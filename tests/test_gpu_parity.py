@@ -39,10 +39,18 @@ def small_shape(v):
 
 
 def run_variant(B, v, a, b, c):
-    """Runs the named kernel; a prepared-B kernel gets the output of the offline Combine-B call."""
+    """Runs the named kernel; a prepared-B kernel gets the output of the offline Combine-B call, a
+    kernel for the weight layout gets W = B^T as a view of a wider matrix whose padding holds NaN."""
     if v["prepared"]:
         s = B.lcma_scheme_load("builtin:" + B.SCHEME_NAMES[v["scheme_id"]])
         B.lcma_gemm_variant_prepared(v["name"], a, B.lcma_prepare_b(b, s), c)
+    elif v["b_layout"] == 2:
+        import torch
+        K, N = b.shape
+        pad = 16 // b.element_size()
+        wide = torch.full((N, K + pad), float("nan"), dtype=b.dtype, device=b.device)
+        wide[:, :K] = b.t()
+        B.lcma_gemm_variant(v["name"], a, wide[:, :K], c, b_nk=True)
     else:
         B.lcma_gemm_variant(v["name"], a, b, c)
 
