@@ -65,6 +65,9 @@ def main():
     ap.add_argument("--prepared-b", action="store_true",
                     help="also time the offline Combine-B path (lcma_prepare_b once, lcma_gemm_prepared per step); "
                          "reported beside `value`, which stays the fully fused lcma_gemm")
+    ap.add_argument("--weight-layout", action="store_true",
+                    help="also time lcma_gemm_nt, which takes B as the N x K weight matrix of a linear layer "
+                         "(no transposition while staging); reported beside `value`, which stays lcma_gemm on K x N")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU (the path would shard over M with no exchange between "
@@ -169,6 +172,27 @@ def main():
         prepared_step(0)
         torch.cuda.synchronize()
         prepared["_c"] = sets[0][2].clone()
+    nk = None
+    if args.weight_layout:
+        ws = [b.t().contiguous() for _, b, _ in sets]
+
+        def nt_step(i):
+            B.lcma_gemm_nt(sets[i % 3][0], ws[i % 3], sets[i % 3][2], scheme)
+
+        def nt_plain_step(i):
+            B.lcma_gemm_nt(sets[i % 3][0], ws[i % 3], sets[i % 3][2], None)
+
+        def nt_vendor_step(i):
+            torch.mm(sets[i % 3][0], ws[i % 3].t(), out=sets[i % 3][2])
+        n_wall_ms, n_ev_ms, _ = timed(nt_step, args.steps, args.warmup)
+        np_wall_ms, _, _ = timed(nt_plain_step, args.steps, args.warmup)
+        nv_wall_ms, _, _ = timed(nt_vendor_step, max(10, args.steps // 2), 3)
+        nk = {"lcma_tflops": flops / (n_wall_ms * 1e-3) / 1e12, "lcma_kernel_ms": n_ev_ms,
+              "plain_mfma_gemm_tflops": flops / (np_wall_ms * 1e-3) / 1e12,
+              "vendor_gemm_tflops": flops / (nv_wall_ms * 1e-3) / 1e12}
+        nt_step(0)
+        torch.cuda.synchronize()
+        nk["_c"] = sets[0][2].clone()
     peak = PEAK_TFLOPS[dt]
 
     # parity on sampled rows (one row range inside every block row of the scheme grid)
@@ -196,6 +220,8 @@ def main():
         err_plain = oracle.rel_frobenius(host(sets[1][2]), ref)
         if prepared:
             prepared["rel_frobenius_error"] = oracle.rel_frobenius(host(prepared["_c"]), ref)
+        if nk:
+            nk["rel_frobenius_error"] = oracle.rel_frobenius(host(nk["_c"]), ref)
         # timed sample: as many leading rows as fit the CPU budget, judged from the small run
         rate = 2.0 * len(rows) * N * K / max(t_small, 1e-6)
         nrows = int(min(M, max(len(rows), args.cpu_seconds * rate / (2.0 * N * K))))
@@ -208,6 +234,8 @@ def main():
 
     if prepared:
         prepared.pop("_c")
+    if nk:
+        nk.pop("_c")
     mfma_flops = flops * info["R"] / (info["m"] * info["k"] * info["n"])
     achieved = mfma_flops / (ev_ms * 1e-3) / 1e12
     out = {
@@ -229,6 +257,8 @@ def main():
     }
     if prepared:
         out["offline_combine_b"] = prepared
+    if nk:
+        out["weight_layout_nk"] = nk
     print(json.dumps(out))
 
 
