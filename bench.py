@@ -68,6 +68,10 @@ def main():
     ap.add_argument("--weight-layout", action="store_true",
                     help="also time lcma_gemm_nt, which takes B as the N x K weight matrix of a linear layer "
                          "(no transposition while staging); reported beside `value`, which stays lcma_gemm on K x N")
+    ap.add_argument("--ablation", action="store_true",
+                    help="also time the dataflows the paper starts from (lcma_gemm_unfused): Algorithm 1 (four stages "
+                         "through device memory) and Algorithm 2 as printed (Combine A/B materialised, GEMM + Combine H "
+                         "fused), each with Combine B per call and with Combine B done once (static weights)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU (the path would shard over M with no exchange between "
@@ -193,6 +197,24 @@ def main():
         nt_step(0)
         torch.cuda.synchronize()
         nk["_c"] = sets[0][2].clone()
+    ablation = None
+    if args.ablation:
+        nbytes = B.lcma_unfused_workspace_bytes(scheme, M, N, K, B.DTYPE_IDS[dt])
+        ws = torch.empty((nbytes,), dtype=torch.uint8, device="cuda")
+        ablation = {"workspace_bytes": nbytes}
+        for level, key in ((1, "algorithm1"), (2, "algorithm2_as_printed")):
+            for reuse, tag in ((False, ""), (True, "_combine_b_offline")):
+                if reuse:  # the planes of B in the workspace belong to buffer set 0 from here on
+                    B.lcma_gemm_unfused(level, sets[0][0], sets[0][1], sets[0][2], scheme, ws)
+
+                def unfused_step(i, level=level, reuse=reuse):
+                    a, b, c = sets[0] if reuse else sets[i % 3]
+                    B.lcma_gemm_unfused(level, a, b, c, scheme, ws, reuse_bt=reuse)
+                u_wall_ms, u_ev_ms, _ = timed(unfused_step, max(10, args.steps // 2), 5)
+                ablation[key + tag + "_tflops"] = flops / (u_wall_ms * 1e-3) / 1e12
+            unfused_step(0)
+            torch.cuda.synchronize()
+            ablation["_c" + key] = sets[0][2].clone()
     peak = PEAK_TFLOPS[dt]
 
     # parity on sampled rows (one row range inside every block row of the scheme grid)
@@ -222,6 +244,9 @@ def main():
             prepared["rel_frobenius_error"] = oracle.rel_frobenius(host(prepared["_c"]), ref)
         if nk:
             nk["rel_frobenius_error"] = oracle.rel_frobenius(host(nk["_c"]), ref)
+        if ablation:
+            for key in ("algorithm1", "algorithm2_as_printed"):
+                ablation[key + "_rel_frobenius_error"] = oracle.rel_frobenius(host(ablation["_c" + key]), ref)
         # timed sample: as many leading rows as fit the CPU budget, judged from the small run
         rate = 2.0 * len(rows) * N * K / max(t_small, 1e-6)
         nrows = int(min(M, max(len(rows), args.cpu_seconds * rate / (2.0 * N * K))))
@@ -236,6 +261,8 @@ def main():
         prepared.pop("_c")
     if nk:
         nk.pop("_c")
+    if ablation:
+        ablation = {k: v for k, v in ablation.items() if not k.startswith("_c")}
     mfma_flops = flops * info["R"] / (info["m"] * info["k"] * info["n"])
     achieved = mfma_flops / (ev_ms * 1e-3) / 1e12
     out = {
@@ -259,6 +286,8 @@ def main():
         out["offline_combine_b"] = prepared
     if nk:
         out["weight_layout_nk"] = nk
+    if ablation:
+        out["ablation_unfused_dataflows"] = ablation
     print(json.dumps(out))
 
 

@@ -132,7 +132,8 @@ lcma_status lcma_gemm_variant(const char *variant, int64_t M, int64_t N, int64_t
 int lcma_variant_prepared(int index);
 /* What variant `index` takes as its B argument in lcma_gemm_variant: 0 the K x N matrix B, 1 the
  * output of lcma_prepare_b, 2 the N x K matrix W of lcma_gemm_nt (ldb is then its leading
- * dimension); -1 when out of range. */
+ * dimension); 3: a stage kernel of lcma_gemm_unfused, which lcma_gemm_variant refuses (ARG);
+ * -1 when out of range. */
 int lcma_variant_b_layout(int index);
 
 /* Offline Combine B (Eq. 4; Algorithm 2, stage 2).  The paper's end-to-end evaluation runs this stage
@@ -167,6 +168,32 @@ lcma_status lcma_gemm_prepared(int64_t M, int64_t N, int64_t K, const void *A, i
                                const void *Bt, void *C, int64_t ldc, lcma_dtype dtype,
                                const lcma_scheme *scheme, void *stream);
 
+
+/* ------------------------------------------------------------------ the unfused dataflows (Algorithm 1; Algorithm 2 as printed)
+ * Provided to be measured against lcma_gemm (the step-wise ablation of Sec. 4.5), not as a faster path.
+ *
+ * lcma_gemm_unfused computes C = A B like lcma_gemm, with intermediate results in device memory:
+ *   level 1  Algorithm 1: four stages, each through device memory: Combine A (Eq. 3) writes At_r,
+ *            Combine B (Eq. 4) writes Bt_r, one batched launch of the plain MFMA GEMM writes
+ *            H_r = At_r Bt_r (Eq. 5), Combine H (Eq. 6) reads the H_r and writes C;
+ *   level 2  Algorithm 2 as the paper runs it: Combine A and Combine B as above, then one kernel that
+ *            multiplies group by group and applies W to the fp32 accumulators (H_r stays on chip).
+ * At_r, Bt_r and H_r are stored in the type the products are multiplied in (fp16 for BF16 and F16
+ * storage, fp32 for F32): each is an fp32 sum (ascending block order, ascending r) or an fp32 MFMA
+ * accumulation rounded once, to nearest-even.  C is rounded once from fp32.
+ * A, B, C, sizes, alignment, padding and errors as for lcma_gemm; `scheme` is required and must be
+ * one of the paper's (NOKERNEL otherwise).  workspace: device memory, 256-byte aligned, at least
+ * lcma_unfused_workspace_bytes() bytes (-1 for bad arguments), owned by the caller, overwritten.
+ * reuse_bt != 0 skips Combine B: the Bt_r left in the workspace by an earlier call with the same B,
+ * scheme, dtype and sizes are used (the paper's offline Combine B for static weights).
+ * Asynchronous on `stream`; nothing is launched when an argument is rejected.
+ */
+int64_t lcma_unfused_workspace_bytes(int64_t M, int64_t N, int64_t K, lcma_dtype dtype,
+                                     const lcma_scheme *scheme);
+lcma_status lcma_gemm_unfused(int level, int64_t M, int64_t N, int64_t K,
+                              const void *A, int64_t lda, const void *B, int64_t ldb,
+                              void *C, int64_t ldc, lcma_dtype dtype, const lcma_scheme *scheme,
+                              void *workspace, int64_t workspace_bytes, int reuse_bt, void *stream);
 
 /* ------------------------------------------------------------------ Decision Module (Sec. 3.3)
  * lcma_select: predicted-fastest algorithm for the shape on MI355X among

@@ -167,6 +167,61 @@ def combine_b_stored(s: Scheme, B: np.ndarray, dtype: str) -> np.ndarray:
     return out
 
 
+def combine_a_stored(s: Scheme, A: np.ndarray, dtype: str) -> np.ndarray:
+    """Combine A (paper Eq. 3; Algorithm 1 stage 1) as a library that materialises At_r has to store it:
+    terms added in fp32 in ascending (i, l) order, the sum rounded once (nearest-even) to fp16 (bf16 and
+    fp16 storage) or kept in fp32.  A holds values representable in the storage type.  Returns
+    (R, M/m, K/k) in fp64 (the stored values, widened)."""
+    A = np.asarray(A, np.float64)
+    M, K = A.shape
+    if M % s.m or K % s.k:
+        raise ValueError(f"shape ({M},{K}) is not divisible by the scheme grid ({s.m},{s.k})")
+    bm, bk = M // s.m, K // s.k
+    A32 = A.astype(np.float32)
+    out = np.empty((s.R, bm, bk), np.float64)
+    with np.errstate(over="ignore"):
+        for r in range(s.R):
+            acc = None
+            for i in range(s.m):
+                for l in range(s.k):
+                    u = int(s.U[r, i, l])
+                    if not u:
+                        continue
+                    term = np.float32(u) * A32[i * bm:(i + 1) * bm, l * bk:(l + 1) * bk]
+                    acc = term if acc is None else (acc + term).astype(np.float32)
+            if acc is None:
+                acc = np.zeros((bm, bk), np.float32)
+            out[r] = acc.astype(np.float16).astype(np.float64) if dtype in ("bf16", "f16") else acc.astype(np.float64)
+    return out
+
+
+def lcma_unfused(s: Scheme, A: np.ndarray, B: np.ndarray, dtype: str, level: int) -> np.ndarray:
+    """C by the dataflows that keep intermediate results in memory, with the roundings that storing
+    them implies (values in fp64, before the final rounding of C to the storage type):
+      level 1  Algorithm 1: At_r and Bt_r stored (combine_a_stored, combine_b_stored), H_r = At_r Bt_r
+               (Eq. 5; exact product, rounded once to fp16 / fp32 when it is stored), C_{i,j} =
+               sum_r W[r,i,j] H_r (Eq. 6);
+      level 2  Algorithm 2 as printed: At_r and Bt_r stored, H_r kept unrounded on chip.
+    A and B hold values representable in the storage type; shapes divisible by the grid."""
+    if level not in (1, 2):
+        raise ValueError("level is 1 (Algorithm 1) or 2 (Algorithm 2)")
+    At = combine_a_stored(s, A, dtype)       # [r, x, y]
+    Bt = combine_b_stored(s, B, dtype)       # [r, y, z]
+    bm, bn = At.shape[1], Bt.shape[2]
+    C = np.zeros((s.m * bm, s.n * bn), np.float64)
+    with np.errstate(over="ignore"):
+        for r in range(s.R):
+            H = gemm(np.ascontiguousarray(At[r]), np.ascontiguousarray(Bt[r]))
+            if level == 1:
+                H = (H.astype(np.float16) if dtype in ("bf16", "f16") else H.astype(np.float32)).astype(np.float64)
+            for i in range(s.m):
+                for j in range(s.n):
+                    w = int(s.W[r, i, j])
+                    if w:
+                        C[i * bm:(i + 1) * bm, j * bn:(j + 1) * bn] += w * H
+    return C
+
+
 def brent(s: Scheme):
     """(number of violated Brent equations, flat index of the first or -1)."""
     U = np.ascontiguousarray(s.U, np.int32)

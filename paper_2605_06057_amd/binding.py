@@ -28,7 +28,7 @@ EXPORTS = [
     "lcma_select", "lcma_hw_mi355x", "lcma_model_stages", "lcma_model_intensity", "lcma_predict_seconds",
     "lcma_sched_waves", "lcma_sched_range", "lcma_status_str", "lcma_last_error",
     "lcma_scheme_name", "lcma_scheme_id_max", "lcma_variant_prepared", "lcma_prepared_b_bytes", "lcma_prepare_b", "lcma_prepare_bt", "lcma_gemm_prepared",
-    "lcma_gemm_nt", "lcma_variant_b_layout",
+    "lcma_gemm_nt", "lcma_variant_b_layout", "lcma_unfused_workspace_bytes", "lcma_gemm_unfused",
 ]
 
 
@@ -70,6 +70,9 @@ def lib() -> ctypes.CDLL:
         L.lcma_gemm.argtypes = [i64, i64, i64, vp, i64, vp, i64, vp, i64, i32, vp, vp]
         L.lcma_gemm_nt.argtypes = L.lcma_gemm.argtypes
         L.lcma_variant_b_layout.argtypes = [i32]
+        L.lcma_unfused_workspace_bytes.argtypes = [i64, i64, i64, i32, vp]
+        L.lcma_unfused_workspace_bytes.restype = i64
+        L.lcma_gemm_unfused.argtypes = [i32, i64, i64, i64, vp, i64, vp, i64, vp, i64, i32, vp, vp, i64, i32, vp]
         L.lcma_variant_count.argtypes = []
         L.lcma_variant_name.argtypes = [i32]
         L.lcma_variant_name.restype = cp
@@ -187,6 +190,21 @@ def lcma_gemm_nt(A, W, C, scheme: Scheme | None = None):
     M, N, K, pa, lda, pw, ldw, pc, ldc, stream = _marshal(A, W, C, True)
     _check(lib().lcma_gemm_nt(M, N, K, pa, lda, pw, ldw, pc, ldc, _dtype_of(A),
                               scheme.handle if scheme is not None else None, stream))
+    return C
+
+
+def lcma_unfused_workspace_bytes(scheme: Scheme, M: int, N: int, K: int, dtype: int) -> int:
+    return int(lib().lcma_unfused_workspace_bytes(M, N, K, dtype, scheme.handle))
+
+
+def lcma_gemm_unfused(level: int, A, B, C, scheme: Scheme, workspace, reuse_bt: bool = False):
+    """C = A x B by Algorithm 1 (level 1) or Algorithm 2 as printed (level 2); `workspace` is a device
+    tensor of at least lcma_unfused_workspace_bytes bytes."""
+    M, N, K, pa, lda, pb, ldb, pc, ldc, stream = _marshal(A, B, C)
+    assert workspace.is_cuda and workspace.is_contiguous()
+    _check(lib().lcma_gemm_unfused(level, M, N, K, pa, lda, pb, ldb, pc, ldc, _dtype_of(A), scheme.handle,
+                                   workspace.data_ptr(), workspace.numel() * workspace.element_size(),
+                                   int(reuse_bt), stream))
     return C
 
 

@@ -56,6 +56,8 @@ static const Variant *find_variant(const char *name) {
 static lcma_status run(const Variant &v, int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const void *B,
                        int64_t ldb, void *C, int64_t ldc, void *stream) {
     const int es = dtype_size(v.dtype);
+    if (v.left_planes || v.batch)
+        return fail(LCMA_ERR_ARG, "lcma_gemm: %s is a stage kernel of lcma_gemm_unfused and takes no matrices", v.name);
     if (M < 0 || N < 0 || K < 0) return fail(LCMA_ERR_ARG, "lcma_gemm: negative size");
     if (M == 0 || N == 0) return LCMA_OK; // nothing to write
     if (K == 0) return fail(LCMA_ERR_SHAPE, "lcma_gemm: K = 0 is not supported");
@@ -214,9 +216,12 @@ extern "C" int64_t lcma_prepared_b_bytes(const lcma_scheme *scheme, int64_t N, i
            (round_up(K, (int64_t)scheme->k * (64 / es)) / scheme->k) * es;
 }
 
+namespace lcma {
 // transposed: the input is the N x K weight matrix W (W[n][k] = B[k][n]) with leading dimension ldb.
-static lcma_status prepare_b(bool transposed, int64_t N, int64_t K, const void *B, int64_t ldb, lcma_dtype dtype,
-                             const lcma_scheme *scheme, void *Bt, void *stream) {
+// The planes hold N/n rows padded to a multiple of n_gran and K/k columns padded to a multiple of k_gran
+// (multiples of 64 rows and 64 bytes).
+lcma_status prepare_b_planes(bool transposed, int64_t N, int64_t K, const void *B, int64_t ldb, lcma_dtype dtype,
+                             const lcma_scheme *scheme, void *Bt, void *stream, int64_t n_gran, int64_t k_gran) {
     const char *who = transposed ? "lcma_prepare_bt" : "lcma_prepare_b";
     const int es = dtype_size(dtype);
     if (!es) return fail(LCMA_ERR_DTYPE, "%s: unknown dtype %d", who, (int)dtype);
@@ -236,8 +241,8 @@ static lcma_status prepare_b(bool transposed, int64_t N, int64_t K, const void *
         return fail(LCMA_ERR_SHAPE, "%s: N = %lld and K = %lld must be multiples of %d", who, (long long)N, (long long)K,
                     16 / es);
     // the planes hold the padded rows and columns (zeros)
-    const int64_t bn = round_up(N, (int64_t)scheme->n * 64) / scheme->n,
-                  bk = round_up(K, (int64_t)scheme->k * kt) / scheme->k;
+    const int64_t bn = round_up(N, (int64_t)scheme->n * n_gran) / scheme->n,
+                  bk = round_up(K, (int64_t)scheme->k * k_gran) / scheme->k;
     const int64_t b_bytes = ((rows - 1) * ldb + cols) * es, bt_bytes = (int64_t)scheme->R * bn * bk * es;
     const int64_t lim = (int64_t)1 << 31;
     const int64_t prow = transposed ? bn * scheme->n : bk * scheme->k, pcol = transposed ? bk * scheme->k : bn * scheme->n;
@@ -273,6 +278,12 @@ static lcma_status prepare_b(bool transposed, int64_t N, int64_t K, const void *
     }
     if (err) return fail(LCMA_ERR_HIP, "%s: launch failed with HIP error %d", who, err);
     return LCMA_OK;
+}
+} // namespace lcma
+
+static lcma_status prepare_b(bool transposed, int64_t N, int64_t K, const void *B, int64_t ldb, lcma_dtype dtype,
+                             const lcma_scheme *scheme, void *Bt, void *stream) {
+    return prepare_b_planes(transposed, N, K, B, ldb, dtype, scheme, Bt, stream, 64, 64 / (dtype_size(dtype) ? dtype_size(dtype) : 4));
 }
 
 extern "C" lcma_status lcma_prepare_b(int64_t N, int64_t K, const void *B, int64_t ldb, lcma_dtype dtype,
@@ -343,6 +354,7 @@ extern "C" int lcma_variant_prepared(int index) {
 
 extern "C" int lcma_variant_b_layout(int index) {
     if (index < 0 || index >= kVariantCount) return -1;
+    if (kVariants[index].left_planes || kVariants[index].batch) return 3;
     return kVariants[index].prepared ? 1 : kVariants[index].b_nk ? 2 : 0;
 }
 

@@ -45,6 +45,8 @@ struct Variant {
     int products;       // block products it multiplies (R plus residual products)
     int prepared;       // 1: takes the output of the offline Combine-B kernel instead of B
     int b_nk;           // 1: takes B as the N x K weight matrix W (W[n][k] = B[k][n])
+    int left_planes;    // 1: takes the output of the stand-alone Combine-A kernel instead of A (stage kernel)
+    int batch;          // 1: batched plain GEMM over planes (stage kernel of the unfused dataflow)
     int (*launch)(const Params *p, int grid, void *stream); // returns a hipError_t
 };
 extern const Variant kVariants[];
@@ -58,6 +60,19 @@ struct PrepKernel {
 };
 extern const PrepKernel kPrepKernels[];
 extern const int kPrepKernelCount;
+
+// The stand-alone Combine-A and Combine-H kernels of one scheme x dtype (stages 1 and 4 of Algorithm 1).
+struct StageKernel {
+    int scheme_id, dtype;
+    int (*launch_comb_a)(const PrepParams *p, int grid_x, int grid_y, void *stream);
+    int (*launch_comb_h)(const CombHParams *p, int grid_x, int grid_y, void *stream);
+};
+extern const StageKernel kStageKernels[];
+extern const int kStageKernelCount;
+
+// Offline Combine B into planes whose rows (N/n) and columns (K/k) are padded to multiples of n_gran / k_gran.
+lcma_status prepare_b_planes(bool transposed, int64_t N, int64_t K, const void *B, int64_t ldb, lcma_dtype dtype,
+                             const lcma_scheme *scheme, void *Bt, void *stream, int64_t n_gran, int64_t k_gran);
 
 int dtype_size(int dtype); // bytes, or 0
 

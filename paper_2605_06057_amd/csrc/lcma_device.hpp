@@ -129,16 +129,22 @@ template <> struct Round<BF16> {
 //         storage type and are converted on the fragments;
 // TB: 1 = B is given as the N x K matrix W with W[n][k] = B[k][n] (the layout of a linear layer's
 //         weight): its rows are k-contiguous like those of A, so its tiles are staged exactly like
-//         A's (16-byte loads, no transposition).
+//         A's (16-byte loads, no transposition);
+// PA: 1 (staged loop, with PB) = the left operands At_r come from memory ready-made as well (the
+//         stand-alone Combine-A stage of Algorithm 2): R planes of (M/m) x (K/k) elements of the
+//         compute type.  The kernel is then Algorithm 2's fused GEMM + Combine-H stage alone;
+// BATCH: 1 (plain kernels on planes) = the grid covers R independent products: work-group id / tiles
+//         per product selects the plane of A, B and C (the batched GEMM stage of Algorithm 1).
 //
 // LDS layout of a stage: NSA tiles [TM rows][TK] then NSB tiles [TN rows][TK], both k-contiguous,
 // 16-byte chunks XOR-swizzled inside a row.  B arrives n-contiguous from memory and is transposed
 // in registers while it is staged, so that both MFMA operands are read with 16-byte LDS loads
 // (measured on MI355X: ds_read_b128 ~260 B/clk/CU, the transposing ds_read_b64_tr_b16 ~70).
 template <class IN_, class CT_, int TM_, int TN_, int TK_, int WGM_, int WGN_, int NSA_, int NSB_, int PIPE_ = 0,
-          int FC_ = 0, int STAGES_ = 2, int PB_ = 0, int DL_ = 0, int TB_ = 0>
+          int FC_ = 0, int STAGES_ = 2, int PB_ = 0, int DL_ = 0, int TB_ = 0, int PA_ = 0, int BATCH_ = 0>
 struct Tile {
-    static constexpr int PIPE = PIPE_, FC = FC_, PB = PB_, DL = DL_, TB = TB_;
+    static constexpr int PIPE = PIPE_, FC = FC_, PB = PB_, DL = DL_, TB = TB_, PA = PA_, BATCH = BATCH_;
+    static_assert(!PA_ || (PB_ && !FC_), "ready-made left operands: staged loop, both sides from planes");
     static_assert(!TB_ || !PB_, "a prepared operand has one layout only");
     static_assert(!DL_ || PB_, "direct loads need an operand that goes to LDS untouched on both sides");
     static_assert(!PB_ || (FC_ && PIPE_ == 2 && STAGES_ == 2) || (!FC_ && PIPE_ == 0),
@@ -196,6 +202,9 @@ struct Tile {
 // 1-3% with it and do not use it.
 #ifndef LCMA_SETPRIO
 #define LCMA_SETPRIO 1
+#endif
+#ifndef LCMA_EPILOGUE_LDS
+#define LCMA_EPILOGUE_LDS 1 // 16-bit C tiles leave through LDS as 16-byte stores (0: 2-byte stores, for comparison)
 #endif
 LCMA_DEV void mfma_priority(bool on) {
 #if LCMA_SETPRIO > 0
@@ -294,10 +303,16 @@ template <class T> struct Ctx {
         // Tile order.  Hardware deals work-groups to the 8 XCDs round-robin; give each XCD
         // a contiguous run of tiles so that its private L2 sees neighbouring tiles.  Tiles
         // run down x inside column panels of `panel` z-tiles.
-        const int total = p.nx * p.nz;
+        const int tiles = p.nx * p.nz;
+        const int total = T::BATCH ? (int)gridDim.x : tiles;
         int id = blockIdx.x;
         const int per = total >> 3;
         if (id < (per << 3)) id = (id & 7) * per + (id >> 3);
+        int plane = 0;
+        if constexpr (T::BATCH) {
+            plane = id / tiles;
+            id -= plane * tiles;
+        }
         const int pw = p.panel;
         const int full = (p.nz / pw) * pw * p.nx; // tiles inside full-width panels
         int x, z;
@@ -314,6 +329,11 @@ template <class T> struct Ctx {
         b_group = (T::PB || T::TB) ? (uint32_t)z * T::TN * p.ldb_b : (uint32_t)z * T::TN * T::ES;
         c_group = (uint32_t)x * T::TM * p.ldc_b + (uint32_t)z * T::TN * T::ES;
         n_group = (uint32_t)z * T::TN * T::ES;
+        if constexpr (T::BATCH) { // plane strides sit where the block-row steps of a scheme would
+            a_group += (uint32_t)plane * p.a_brow;
+            b_group += (uint32_t)plane * p.b_brow;
+            c_group += (uint32_t)plane * p.c_brow;
+        }
 
 #pragma unroll
         for (int q = 0; q < T::QA; ++q) {
@@ -595,8 +615,52 @@ template <class T> struct Ctx {
 
     // Round and store one fp32 tile into block C_{i,j}.  f(mi, ni) returns the f32x16 of MFMA
     // tile (mi, ni).
+    //
+    // 16-bit output: a lane's 16 accumulator values of an MFMA tile lie in ONE column, so storing them
+    // directly takes sixteen 2-byte stores that cover 64 bytes of a row each.  Instead every wave
+    // passes one 32-row strip of its tile (32 x WN elements) through a private piece of LDS (the stages
+    // are free after the y loop) and writes it out with 16-byte stores, whole 128-byte lines when the
+    // wave tile is 64 columns wide: 8x fewer store instructions.  All waves of the work-group call this
+    // together; the barriers keep the strip apart from the stage buffers of the loop before and after.
     template <class F> LCMA_DEV void store_c(int i, int j, F f) const {
         const uint32_t soff = (uint32_t)i * p.c_brow + (uint32_t)j * p.c_bcol + c_group;
+        if constexpr (T::ES == 2 && LCMA_EPILOGUE_LDS) {
+            constexpr int PITCH = T::WN * 2 + 16;          // bytes; rows 4 apart fall into different banks
+            constexpr int CPRW = T::WN * 2 / 16;           // 16-byte chunks per strip row
+            constexpr int NIT = 32 * CPRW / 64;            // chunks per lane
+            static_assert(T::NT / 64 * 32 * PITCH <= T::LDS_BYTES, "the strips of all waves fit the stage buffers");
+            LCMA_LDS char *strip = lds + (threadIdx.x >> 6) * (32 * PITCH);
+            const int l32 = lane & 31, lh = lane >> 5;
+#pragma unroll
+            for (int mi = 0; mi < T::NMI; ++mi) {
+#pragma unroll
+                for (int ni = 0; ni < T::NNI; ++ni) {
+                    const f32x16 t = f(mi, ni);
+#pragma unroll
+                    for (int v = 0; v < 16; ++v)
+                        *(LCMA_LDS uint16_t *)(strip + ((v >> 2) * 8 + 4 * lh + (v & 3)) * PITCH + (ni * 32 + l32) * 2) =
+                            (uint16_t)Round<IN>::run(t[v]);
+                }
+                __syncthreads();
+#pragma unroll
+                for (int it = 0; it < NIT; ++it) {
+                    const int id = it * 64 + lane, row = id / CPRW, ch = id % CPRW;
+                    const u32x4 v = *(LCMA_LDS u32x4 *)(strip + row * PITCH + ch * 16);
+                    const uint32_t colb = (uint32_t)(wn * T::WN) * 2 + ch * 16; // byte column inside the tile
+                    // a chunk past N goes to the end of the extent: dropped (N is a whole number of chunks)
+                    const uint32_t off = ((uint32_t)j * p.c_bcol + n_group + colb < p.n_row_b)
+                                             ? (uint32_t)(wm * T::WM + mi * 32 + row) * p.ldc_b + colb
+                                             : p.c_bytes;
+                    // The scalar-offset field stays a literal zero on purpose.  A store of more than 8 bytes
+                    // reads its data registers over several cycles, and the compiler keeps later vector
+                    // writes to those registers away from it only for stores WITHOUT a scalar-register
+                    // offset; with one, a following address computation that reused the first data
+                    // register reached the last quarter of the lanes of the store (seen on MI355X).
+                    __builtin_amdgcn_raw_buffer_store_b128(v, rc, (int)(off + soff), 0, 0);
+                }
+                __syncthreads();
+            }
+        } else {
 #pragma unroll
         for (int mi = 0; mi < T::NMI; ++mi)
 #pragma unroll
@@ -615,6 +679,7 @@ template <class T> struct Ctx {
                         __builtin_amdgcn_raw_buffer_store_b32(bits, rc, (int)off, (int)soff, 0);
                 }
             }
+        }
     }
 };
 
@@ -624,18 +689,28 @@ template <class T> struct Ctx {
 //   a_i(t), a_l(t)    block indices of raw A block t; b_l(t), b_j(t) likewise for B
 //   comb_a(in, out)   out[s] = sum_t U * in[t]  (Eq. 3) on 16-byte vectors; comb_b likewise (Eq. 4)
 template <class T, class CH> struct RawSet {
-    u32x4 a[CH::NA][T::QA];
+    u32x4 a[T::PA ? CH::NP : CH::NA][T::QA]; // raw blocks, or with ready-made left operands one tile of At_r per product
     // B side: raw blocks (units of BH vectors), or with prepared B one tile of Bt_r per product
     u32x4 b[T::PB ? CH::NP : CH::NB][T::PB ? T::QBP : T::QB][T::PB ? 1 : T::BH];
 };
 
 // Issue the buffer loads of step y into `r`.
 template <class T, class CH> LCMA_DEV void issue_loads(const Ctx<T> &cx, RawSet<T, CH> &r, int y, bool guard) {
+    if constexpr (T::PA) { // planes are padded with zeros: nothing to guard
 #pragma unroll
-    for (int t = 0; t < CH::NA; ++t) {
-        const uint32_t so = cx.soff_a(CH::a_i(t), CH::a_l(t), y);
+        for (int s = 0; s < CH::NP; ++s) {
+            const uint32_t so = (uint32_t)CH::a_plane(s) * cx.p.a_brow + cx.a_group + (uint32_t)y * (T::TK * T::ES);
 #pragma unroll
-        for (int q = 0; q < T::QA; ++q) r.a[t][q] = cx.load_a(q, so, CH::a_l(t), y, guard);
+            for (int q = 0; q < T::QA; ++q)
+                r.a[s][q] = __builtin_amdgcn_raw_buffer_load_b128(cx.ra, (int)cx.a_voff[q], (int)so, 0);
+        }
+    } else {
+#pragma unroll
+        for (int t = 0; t < CH::NA; ++t) {
+            const uint32_t so = cx.soff_a(CH::a_i(t), CH::a_l(t), y);
+#pragma unroll
+            for (int q = 0; q < T::QA; ++q) r.a[t][q] = cx.load_a(q, so, CH::a_l(t), y, guard);
+        }
     }
     if constexpr (T::PB) {
 #pragma unroll
@@ -671,6 +746,12 @@ template <class T, class CH> LCMA_DEV void combine_store(const Ctx<T> &cx, const
     constexpr int NOA = T::FC ? CH::NA : CH::NP, NOB = T::FC ? CH::NB : CH::NP;
     static_assert(NOA <= T::NSA && NOB <= T::NSB, "chunk larger than the LDS slots");
     const uint32_t sb = st * T::STAGE;
+    if constexpr (T::PA) { // tiles of At_r go to LDS as they are
+#pragma unroll
+        for (int s = 0; s < CH::NP; ++s)
+#pragma unroll
+            for (int q = 0; q < T::QA; ++q) cx.lds_store(sb + s * T::A_SLOT + cx.a_lds[q], r.a[s][q]);
+    } else {
 #pragma unroll
     for (int q = 0; q < T::QA; ++q) {
         V in[CH::NA], out[NOA];
@@ -684,6 +765,7 @@ template <class T, class CH> LCMA_DEV void combine_store(const Ctx<T> &cx, const
         }
 #pragma unroll
         for (int s = 0; s < NOA; ++s) cx.lds_store(sb + s * T::A_SLOT + cx.a_lds[q], __builtin_bit_cast(u32x4, out[s]));
+    }
     }
     if constexpr (T::PB) { // tiles of Bt_r go to LDS as they are
 #pragma unroll

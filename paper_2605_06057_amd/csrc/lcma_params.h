@@ -44,4 +44,16 @@ struct PrepParams {
     uint32_t n_row_b;           // N * element size of B: columns at or beyond it are read as 0
 };
 
+// Argument block of the stand-alone Combine-H kernels (stage 4 of Algorithm 1).
+struct CombHParams {
+    const void *H;
+    void *C;
+    uint32_t h_bytes, c_bytes; // byte extents (< 2 GiB each)
+    uint32_t h_ld_b;           // row pitch of a plane in bytes
+    uint32_t h_plane_b;        // plane stride in bytes
+    uint32_t ldc_b;            // leading dimension of C in bytes
+    uint32_t c_brow, c_bcol;   // byte step from block C_{i,j} to C_{i+1,j} / C_{i,j+1}
+    uint32_t n_row_b;          // N * element size: columns at or beyond it are never written
+};
+
 } // namespace lcma

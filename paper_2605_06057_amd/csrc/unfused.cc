@@ -1,0 +1,199 @@
+// The dataflows the paper starts from, on gfx950, so that they can be measured against the fused
+// kernels (the step-wise ablation of Sec. 4.5):
+//   level 1  Algorithm 1: Combine A, Combine B, R block products and Combine H as four stages, each
+//            reading its operands from and writing its result to device memory;
+//   level 2  Algorithm 2 as printed: Combine A and Combine B write At_r, Bt_r to device memory, one
+//            kernel multiplies them group by group and applies W on chip (H_r never leaves the chip).
+// (lcma_gemm is the third step: nothing but C is written.)  Everything lives in a caller-provided
+// workspace: the planes At (R x bm x bk), Bt (R x bn x bk) and, for level 1, H (R x bm x bn), in
+// the type the products are multiplied in, with bm, bn multiples of 128 and bk of 64 elements (16 for
+// fp32) that cover ceil(M/m), ceil(N/n), ceil(K/k); the padding holds zeros.
+#include "host_common.h"
+
+#include <cstdlib>
+#include <cstring>
+
+namespace lcma {
+namespace {
+
+int64_t round_up(int64_t x, int64_t g) { return (x + g - 1) / g * g; }
+int64_t align256(int64_t x) { return round_up(x, 256); }
+
+struct Geometry {
+    int64_t bm, bn, bk, es;
+    int64_t at_bytes, bt_bytes, h_bytes; // each rounded up to 256
+    int64_t total() const { return at_bytes + bt_bytes + h_bytes; }
+};
+
+Geometry geometry(const lcma_scheme &s, int64_t M, int64_t N, int64_t K, int dtype) {
+    Geometry g;
+    g.es = dtype_size(dtype);
+    const int64_t kg = g.es == 4 ? 16 : 64;
+    g.bm = round_up((M + s.m - 1) / s.m, 128);
+    g.bn = round_up((N + s.n - 1) / s.n, 128);
+    g.bk = round_up((K + s.k - 1) / s.k, kg);
+    g.at_bytes = align256((int64_t)s.R * g.bm * g.bk * g.es);
+    g.bt_bytes = align256((int64_t)s.R * g.bn * g.bk * g.es);
+    g.h_bytes = align256((int64_t)s.R * g.bm * g.bn * g.es);
+    return g;
+}
+
+const StageKernel *find_stage(int scheme_id, int dtype) {
+    for (int i = 0; i < kStageKernelCount; ++i)
+        if (kStageKernels[i].launch_comb_a && kStageKernels[i].scheme_id == scheme_id && kStageKernels[i].dtype == dtype)
+            return &kStageKernels[i];
+    return nullptr;
+}
+
+// Largest tile among the stage kernels of the wanted kind that divides the planes.
+const Variant *find_gemm(bool batch, int scheme_id, int dtype, const Geometry &g) {
+    const Variant *best = nullptr;
+    const char *force = std::getenv("LCMA_UNFUSED_VARIANT"); // ablation override
+    for (int i = 0; i < kVariantCount; ++i) {
+        const Variant &v = kVariants[i];
+        if ((batch ? !v.batch : !v.left_planes) || v.scheme_id != scheme_id || v.dtype != dtype) continue;
+        if (g.bm % v.TM || g.bn % v.TN || g.bk % v.TK) continue;
+        if (force && !std::strcmp(force, v.name)) return &v;
+        if (!best || v.eff > best->eff || (v.eff == best->eff && v.TM * v.TN > best->TM * best->TN)) best = &v;
+    }
+    return best;
+}
+
+} // namespace
+} // namespace lcma
+
+using namespace lcma;
+
+extern "C" int64_t lcma_unfused_workspace_bytes(int64_t M, int64_t N, int64_t K, lcma_dtype dtype, const lcma_scheme *scheme) {
+    if (!scheme || !dtype_size(dtype) || M <= 0 || N <= 0 || K <= 0) return -1;
+    return geometry(*scheme, M, N, K, dtype).total();
+}
+
+extern "C" lcma_status lcma_gemm_unfused(int level, int64_t M, int64_t N, int64_t K, const void *A, int64_t lda,
+                                         const void *B, int64_t ldb, void *C, int64_t ldc, lcma_dtype dtype,
+                                         const lcma_scheme *scheme, void *workspace, int64_t workspace_bytes,
+                                         int reuse_bt, void *stream) {
+    const char *who = "lcma_gemm_unfused";
+    const int es = dtype_size(dtype);
+    if (!es) return fail(LCMA_ERR_DTYPE, "%s: unknown dtype %d", who, (int)dtype);
+    if (level != 1 && level != 2) return fail(LCMA_ERR_ARG, "%s: level must be 1 (Algorithm 1) or 2 (Algorithm 2)", who);
+    if (!scheme) return fail(LCMA_ERR_ARG, "%s: a scheme is required", who);
+    if (const lcma_status st = lcma_scheme_verify(scheme, nullptr)) return st;
+    const int id = scheme->builtin;
+    const StageKernel *sk = id ? find_stage(id, dtype) : nullptr;
+    if (!sk)
+        return fail(LCMA_ERR_NOKERNEL, "%s: no stage kernels were generated for scheme <%d,%d,%d;%d> with dtype %d", who,
+                    scheme->m, scheme->k, scheme->n, scheme->R, (int)dtype);
+    if (M < 0 || N < 0 || K < 0) return fail(LCMA_ERR_ARG, "%s: negative size", who);
+    if (M == 0 || N == 0) return LCMA_OK;
+    if (K == 0) return fail(LCMA_ERR_SHAPE, "%s: K = 0 is not supported", who);
+    if (!A || !B || !C || !workspace) return fail(LCMA_ERR_ARG, "%s: null pointer", who);
+    if (lda < K || ldb < N || ldc < N) return fail(LCMA_ERR_ARG, "%s: leading dimension smaller than the row", who);
+    if ((((uintptr_t)A | (uintptr_t)B | (uintptr_t)C) & 15) || ((uintptr_t)workspace & 255))
+        return fail(LCMA_ERR_ARG, "%s: matrix pointers must be 16-byte aligned, the workspace 256-byte aligned", who);
+    if (((lda * es) | (ldb * es) | (ldc * es)) & 15)
+        return fail(LCMA_ERR_ARG, "%s: leading dimensions must be multiples of 16 bytes", who);
+    const int vec = 16 / es;
+    if (N % vec || K % vec)
+        return fail(LCMA_ERR_SHAPE, "%s: N = %lld and K = %lld must be multiples of %d (16 bytes of elements)", who,
+                    (long long)N, (long long)K, vec);
+    const Geometry g = geometry(*scheme, M, N, K, dtype);
+    if (workspace_bytes < g.total())
+        return fail(LCMA_ERR_ARG, "%s: the workspace holds %lld bytes, %lld are needed", who, (long long)workspace_bytes,
+                    (long long)g.total());
+    const int R = scheme->R;
+    const int64_t lim = (int64_t)1 << 31;
+    const int64_t Mp = g.bm * scheme->m, Np = g.bn * scheme->n, Kp = g.bk * scheme->k;
+    if (g.at_bytes >= lim || g.bt_bytes >= lim || g.h_bytes >= lim || ((Mp - 1) * lda + Kp) * es >= lim ||
+        ((Kp - 1) * ldb + Np) * es >= lim || ((Mp - 1) * ldc + Np) * es >= lim)
+        return fail(LCMA_ERR_SHAPE, "%s: a matrix or a set of planes spans 2 GiB or more", who);
+    char *At = (char *)workspace, *Bt = At + g.at_bytes, *H = Bt + g.bt_bytes;
+    // the products are multiplied in fp16 for both 16-bit storage types
+    const int ct = dtype == LCMA_F32 ? LCMA_F32 : LCMA_F16;
+    const Variant *gemm = level == 1 ? find_gemm(true, LCMA_PLAIN, ct, g) : find_gemm(false, id, dtype, g);
+    if (!gemm) return fail(LCMA_ERR_NOKERNEL, "%s: no GEMM stage kernel for level %d fits the planes", who, level);
+
+    // stage 1: Combine A (Eq. 3).  A takes the place of an N x K weight matrix in the Combine-B kernel
+    // for that layout: block A_{i,l} is block (i, l), rows are k-contiguous.
+    {
+        PrepParams p;
+        p.B = A;
+        p.Bt = At;
+        p.b_bytes = (uint32_t)(((M - 1) * lda + K) * es);
+        p.bt_bytes = (uint32_t)((int64_t)R * g.bm * g.bk * es);
+        p.ldb_b = (uint32_t)(lda * es);
+        p.b_brow = (uint32_t)(g.bm * lda * es);
+        p.b_bcol = (uint32_t)(g.bk * es);
+        p.bt_ld_b = (uint32_t)(g.bk * es);
+        p.bt_plane_b = (uint32_t)(g.bm * g.bk * es);
+        p.bk = (int32_t)g.bk;
+        p.bn = (int32_t)g.bm;
+        p.n_row_b = (uint32_t)(K * es);
+        const int64_t gy = (g.bk * es + 255) / 256;
+        if (gy > 65535) return fail(LCMA_ERR_SHAPE, "%s: K is too large", who);
+        if (const int err = sk->launch_comb_a(&p, (int)(g.bm / 16), (int)gy, stream))
+            return fail(LCMA_ERR_HIP, "%s: Combine-A launch failed with HIP error %d", who, err);
+    }
+    // stage 2: Combine B (Eq. 4), unless the planes of an earlier call are still valid (static weights)
+    if (!reuse_bt) {
+        const lcma_status st = prepare_b_planes(false, N, K, B, ldb, dtype, scheme, Bt, stream, 128, es == 4 ? 16 : 64);
+        if (st != LCMA_OK) return st;
+    }
+    Params p;
+    std::memset(&p, 0, sizeof p);
+    p.A = At;
+    p.B = Bt;
+    p.a_bytes = (uint32_t)((int64_t)R * g.bm * g.bk * es);
+    p.b_bytes = (uint32_t)((int64_t)R * g.bn * g.bk * es);
+    p.lda_b = p.ldb_b = (uint32_t)(g.bk * es);
+    p.a_brow = (uint32_t)(g.bm * g.bk * es); // plane strides
+    p.b_brow = (uint32_t)(g.bn * g.bk * es);
+    p.nx = (int32_t)(g.bm / gemm->TM);
+    p.nz = (int32_t)(g.bn / gemm->TN);
+    p.ny = (int32_t)(g.bk / gemm->TK);
+    p.k_row_b = (uint32_t)(Kp * es); // the planes are padded with zeros: no column of At is past K
+    p.k_tail_b = (uint32_t)(g.bk * es);
+    int panel = 8;
+    if (const char *e = std::getenv("LCMA_PANEL")) panel = std::atoi(e);
+    if (panel < 1) panel = 1;
+    p.panel = panel < p.nz ? panel : p.nz;
+    if (level == 1) {
+        // stage 3: the R products H_r = At_r x Bt_r as one batched launch of the plain kernel
+        p.C = H;
+        p.c_bytes = (uint32_t)((int64_t)R * g.bm * g.bn * es);
+        p.ldc_b = (uint32_t)(g.bn * es);
+        p.c_brow = (uint32_t)(g.bm * g.bn * es);
+        p.n_row_b = (uint32_t)(g.bn * es);
+        const int64_t grid = (int64_t)R * p.nx * p.nz;
+        if (const int err = gemm->launch(&p, (int)grid, stream))
+            return fail(LCMA_ERR_HIP, "%s: launch of %s failed with HIP error %d", who, gemm->name, err);
+        // stage 4: Combine H (Eq. 6)
+        CombHParams h;
+        h.H = H;
+        h.C = C;
+        h.h_bytes = p.c_bytes;
+        h.c_bytes = (uint32_t)(((M - 1) * ldc + N) * es);
+        h.h_ld_b = (uint32_t)(g.bn * es);
+        h.h_plane_b = (uint32_t)(g.bm * g.bn * es);
+        h.ldc_b = (uint32_t)(ldc * es);
+        h.c_brow = (uint32_t)(g.bm * ldc * es);
+        h.c_bcol = (uint32_t)(g.bn * es);
+        h.n_row_b = (uint32_t)(N * es);
+        const int64_t gy = (g.bn * es + 255) / 256;
+        if (gy > 65535) return fail(LCMA_ERR_SHAPE, "%s: N is too large", who);
+        if (const int err = sk->launch_comb_h(&h, (int)(g.bm / 16), (int)gy, stream))
+            return fail(LCMA_ERR_HIP, "%s: Combine-H launch failed with HIP error %d", who, err);
+    } else {
+        // stages 3 and 4 in one kernel: group by group, W applied to the fp32 accumulators
+        p.C = C;
+        p.c_bytes = (uint32_t)(((M - 1) * ldc + N) * es);
+        p.ldc_b = (uint32_t)(ldc * es);
+        p.c_brow = (uint32_t)(g.bm * ldc * es);
+        p.c_bcol = (uint32_t)(g.bn * es);
+        p.n_row_b = (uint32_t)(N * es);
+        const int64_t grid = (int64_t)p.nx * p.nz;
+        if (const int err = gemm->launch(&p, (int)grid, stream))
+            return fail(LCMA_ERR_HIP, "%s: launch of %s failed with HIP error %d", who, gemm->name, err);
+    }
+    return LCMA_OK;
+}

@@ -148,12 +148,14 @@ class Variant:
     pb: int = 0               # 1: B side comes from the offline Combine-B kernel (needs fc, pipe 2)
     dl: int = 0               # 1 (with pb): tiles are loaded from memory straight into LDS
     tb: int = 0               # 1: B is given as the N x K weight matrix (k-contiguous rows)
+    pa: int = 0               # 1 (with pb, staged loop): the left operands come ready-made from planes too
+    batch: int = 0            # 1 (plain, tb): the grid covers R products on planes (Algorithm 1's batched GEMM)
     name: str = field(default="")
 
     def finish(self):
         if not self.name:
             self.name = (f"{self.scheme}_{self.dtype}_t{self.TM}x{self.TN}x{self.TK}_c{self.chunk}"
-                         + (f"x{len(self.comp)}" if self.comp else "") + (f"w{self.wgm}x{self.wgn}" if (self.wgm, self.wgn) != (2, 2) else "") + ("f" if self.fc else "") + ("i" if self.pipe == 2 else "") + ("s3" if self.stages == 3 else "") + ("b" if self.pb else "") + ("d" if self.dl else "") + ("t" if self.tb else "") + (f"o{self.occ}" if self.occ > 1 else ""))
+                         + (f"x{len(self.comp)}" if self.comp else "") + (f"w{self.wgm}x{self.wgn}" if (self.wgm, self.wgn) != (2, 2) else "") + ("f" if self.fc else "") + ("i" if self.pipe == 2 else "") + ("s3" if self.stages == 3 else "") + ("a" if self.pa else "") + ("b" if self.pb else "") + ("d" if self.dl else "") + ("t" if self.tb else "") + ("g" if self.batch else "") + (f"o{self.occ}" if self.occ > 1 else ""))
         return self
 
 
@@ -249,29 +251,35 @@ def emit_kernel(s: Scheme, v: Variant) -> str:
     w('#include "lcma_device.hpp"')
     w("namespace {")
     w("using namespace lcma;")
-    w(f"using T = Tile<{in_t}, {ct_t}, {v.TM}, {v.TN}, {v.TK}, {v.wgm}, {v.wgn}, {nsa}, {nsb}, {v.pipe}, {v.fc}, {v.stages}, {v.pb}, {v.dl}, {v.tb}>;")
+    w(f"using T = Tile<{in_t}, {ct_t}, {v.TM}, {v.TN}, {v.TK}, {v.wgm}, {v.wgn}, {nsa}, {nsb}, {v.pipe}, {v.fc}, {v.stages}, {v.pb}, {v.dl}, {v.tb}, {v.pa}, {v.batch}>;")
     for ci, ch in enumerate(chunks):
         a_blocks = sorted({(i, l) for r in ch for i in range(s.m) for l in range(s.k) if s.U[r, i, l]})
         b_blocks = sorted({(l, j) for r in ch for l in range(s.k) for j in range(s.n) if s.V[r, l, j]})
         w(f"struct Chunk{ci} {{  // products {', '.join(str(r + 1) for r in ch)}")
         if v.pb:
             b_blocks = []
+        if v.pa:
+            a_blocks = []
         w(f"    static constexpr int NA = {len(a_blocks)}, NB = {len(b_blocks)}, NP = {len(ch)};")
         for fn, vals in (("a_i", [b[0] for b in a_blocks]), ("a_l", [b[1] for b in a_blocks]),
                          ("b_l", [b[0] for b in b_blocks]), ("b_j", [b[1] for b in b_blocks])):
             if not vals:
                 continue
             w(f"    static LCMA_DEV constexpr int {fn}(int t) {{ constexpr int v[] = {{{', '.join(map(str, vals))}}}; return v[t]; }}")
-        w("    template <class V> static LCMA_DEV void comb_a(const V (&in)[NA], V (&out)[NP]) {")
-        for si, r in enumerate(ch):
-            terms = [(int(s.U[r, i, l]), f"in[{a_blocks.index((i, l))}]") for (i, l) in a_blocks if s.U[r, i, l]]
-            if r in residual:
-                assert wide and len(terms) >= 2, "residual products need fp16 sums formed in fp32"
-                wsum = signed_sum([(c, f"Wide<V>::up({e})") for c, e in terms])
-                w(f"        out[{si}] = Wide<V>::residual({wsum});")
-            else:
-                w(f"        out[{si}] = {signed_sum(terms, wide, True)};")
-        w("    }")
+        if v.pa:
+            assert not v.comp, "residual products are formed by the fused kernels only"
+            w(f"    static LCMA_DEV constexpr int a_plane(int s) {{ constexpr int v[] = {{{', '.join(map(str, ch))}}}; return v[s]; }}")
+        else:
+            w("    template <class V> static LCMA_DEV void comb_a(const V (&in)[NA], V (&out)[NP]) {")
+            for si, r in enumerate(ch):
+                terms = [(int(s.U[r, i, l]), f"in[{a_blocks.index((i, l))}]") for (i, l) in a_blocks if s.U[r, i, l]]
+                if r in residual:
+                    assert wide and len(terms) >= 2, "residual products need fp16 sums formed in fp32"
+                    wsum = signed_sum([(c, f"Wide<V>::up({e})") for c, e in terms])
+                    w(f"        out[{si}] = Wide<V>::residual({wsum});")
+                else:
+                    w(f"        out[{si}] = {signed_sum(terms, wide, True)};")
+            w("    }")
         if v.pb:
             n_orig = s.R - len(v.comp)  # a residual product multiplies the same right operand as its source
             planes = [r if r < n_orig else v.comp[r - n_orig] for r in ch]
@@ -343,7 +351,7 @@ def emit_registry(schemes: dict[str, Scheme], variants: list[Variant]) -> str:
         s = schemes[v.scheme]
         hash_expr = "0" if s.name == "plain" else f"0x{scheme_hash(s):016x}ull"
         L.append(f'    {{"{v.name}", {SCHEME_IDS[v.scheme]}, {DTYPE_IDS[v.dtype]}, {s.m}, {s.k}, {s.n}, {s.R}, '
-                 f"{hash_expr}, {v.TM}, {v.TN}, {v.TK}, {min(v.chunk, s.R)}, {v.rank}, {v.eff}, {v.occ}, {s.R + len(v.comp)}, {v.pb}, {v.tb}, lcma_launch_{v.name}}},")
+                 f"{hash_expr}, {v.TM}, {v.TN}, {v.TK}, {min(v.chunk, s.R)}, {v.rank}, {v.eff}, {v.occ}, {s.R + len(v.comp)}, {v.pb}, {v.tb}, {v.pa}, {v.batch}, lcma_launch_{v.name}}},")
     L += ["};", f"const int kVariantCount = {len(variants)};"]
     preps = prep_kernels(variants)
     L.append("const PrepKernel kPrepKernels[] = {")
@@ -351,7 +359,17 @@ def emit_registry(schemes: dict[str, Scheme], variants: list[Variant]) -> str:
         L.append(f"    {{{SCHEME_IDS[sch]}, {DTYPE_IDS[dt]}, lcma_launch_prep_b_{sch}_{dt}, lcma_launch_prep_bt_{sch}_{dt}}},")
     if not preps:
         L.append("    {0, 0, nullptr, nullptr},")
-    L += ["};", f"const int kPrepKernelCount = {len(preps)};", "} // namespace lcma", ""]
+    L += ["};", f"const int kPrepKernelCount = {len(preps)};"]
+    stages = stage_kernels(variants)
+    L.append("const StageKernel kStageKernels[] = {")
+    for sch, dt in stages:
+        L.append(f"    {{{SCHEME_IDS[sch]}, {DTYPE_IDS[dt]}, lcma_launch_comb_a_{sch}_{dt}, lcma_launch_comb_h_{sch}_{dt}}},")
+    if not stages:
+        L.append("    {0, 0, nullptr, nullptr},")
+    L += ["};", f"const int kStageKernelCount = {len(stages)};", "} // namespace lcma", ""]
+    for sch, dt in stages:
+        L.insert(3, f'extern "C" int lcma_launch_comb_a_{sch}_{dt}(const lcma::PrepParams *p, int gx, int gy, void *stream);')
+        L.insert(3, f'extern "C" int lcma_launch_comb_h_{sch}_{dt}(const lcma::CombHParams *p, int gx, int gy, void *stream);')
     for sch, dt in preps:
         L.insert(3, f'extern "C" int lcma_launch_prep_b_{sch}_{dt}(const lcma::PrepParams *p, int gx, int gy, void *stream);')
         L.insert(3, f'extern "C" int lcma_launch_prep_bt_{sch}_{dt}(const lcma::PrepParams *p, int gx, int gy, void *stream);')
@@ -361,6 +379,87 @@ def emit_registry(schemes: dict[str, Scheme], variants: list[Variant]) -> str:
 def prep_kernels(variants: list[Variant]) -> list[tuple[str, str]]:
     """(scheme, dtype) pairs that need an offline Combine-B kernel: those with a prepared-B GEMM kernel."""
     return sorted({(v.scheme, v.dtype) for v in variants if v.pb})
+
+
+def stage_kernels(variants: list[Variant]) -> list[tuple[str, str]]:
+    """(scheme, dtype) pairs that get the stand-alone Combine-A and Combine-H kernels of the unfused
+    dataflows: those with a GEMM kernel that takes both operands from planes."""
+    return sorted({(v.scheme, v.dtype) for v in variants if v.pa})
+
+
+def float_sum(terms: list[tuple[int, str]]) -> str:
+    """Left-to-right fp32 sum of signed terms, parenthesised so that the order is the written one."""
+    expr = ""
+    for c, e in terms:
+        mag = e if abs(c) == 1 else f"{float(abs(c))}f * {e}"
+        if not expr:
+            expr = mag if c > 0 else f"-{mag}"
+        else:
+            expr = f"({expr} {'+' if c > 0 else '-'} {mag})"
+    return expr or "0.f"
+
+
+def emit_stage(s: Scheme, dtype: str) -> str:
+    """Stand-alone Combine A (Eq. 3; sums in fp32, ascending (i, l), one rounding to the compute type) and
+    Combine H (Eq. 6; sums in fp32, ascending r, one rounding to the storage type) for one scheme and
+    storage type: stages 1 and 4 of Algorithm 1."""
+    in_t, ct_t = CPP_TYPES[dtype]
+    a_blocks = sorted({(i, l) for r in range(s.R) for i in range(s.m) for l in range(s.k) if s.U[r, i, l]})
+    L = []
+    w = L.append
+    w(f"// GENERATED by gen/generate.py - do not edit.  Stand-alone Combine A and Combine H of scheme {s.name} <{s.m},{s.k},{s.n};{s.R}>, dtype {dtype}.")
+    w('#include "lcma_combine_h.hpp"')
+    w("namespace {")
+    w("using namespace lcma;")
+    w("struct CombA {  // block A_{i,l} takes the place of block (j, l) of an N x K weight matrix")
+    w(f"    static constexpr int NB = {len(a_blocks)}, NP = {s.R};")
+    for fn, vals in (("b_j", [b[0] for b in a_blocks]), ("b_l", [b[1] for b in a_blocks])):
+        w(f"    static LCMA_DEV constexpr int {fn}(int t) {{ constexpr int v[] = {{{', '.join(map(str, vals))}}}; return v[t]; }}")
+    w("    static LCMA_DEV float comb(const float (&in)[NB], int r) {")
+    w("#pragma clang fp contract(off)")
+    w("        switch (r) {")
+    for r in range(s.R):
+        terms = [(int(s.U[r, i, l]), f"in[{a_blocks.index((i, l))}]") for (i, l) in a_blocks if s.U[r, i, l]]
+        w(f"        case {r}: return {float_sum(terms)};")
+    w("        default: return 0.f;")
+    w("        }")
+    w("    }")
+    w("};")
+    w("struct CombH {")
+    w(f"    static constexpr int NP = {s.R}, NC = {s.m * s.n};")
+    w(f"    static LCMA_DEV constexpr int c_i(int o) {{ return o / {s.n}; }}")
+    w(f"    static LCMA_DEV constexpr int c_j(int o) {{ return o % {s.n}; }}")
+    w("    static LCMA_DEV float comb(const float (&in)[NP], int o) {")
+    w("#pragma clang fp contract(off)")
+    w("        switch (o) {")
+    for i in range(s.m):
+        for j in range(s.n):
+            terms = [(int(s.W[r, i, j]), f"in[{r}]") for r in range(s.R) if s.W[r, i, j]]
+            w(f"        case {i * s.n + j}: return {float_sum(terms)};")
+    w("        default: return 0.f;")
+    w("        }")
+    w("    }")
+    w("};")
+    w("} // namespace")
+    w("")
+    w(f'extern "C" __global__ __launch_bounds__(256) void lcma_k_comb_a_{s.name}_{dtype}(const lcma::PrepParams p) {{')
+    w(f"    prepare_bt_tile<{in_t}, {ct_t}, CombA>(p);")
+    w("}")
+    w("")
+    w(f'extern "C" int lcma_launch_comb_a_{s.name}_{dtype}(const lcma::PrepParams *p, int gx, int gy, void *stream) {{')
+    w(f"    lcma_k_comb_a_{s.name}_{dtype}<<<dim3(gx, gy), dim3(256), 0, (hipStream_t)stream>>>(*p);")
+    w("    return (int)hipGetLastError();")
+    w("}")
+    w("")
+    w(f'extern "C" __global__ __launch_bounds__(256) void lcma_k_comb_h_{s.name}_{dtype}(const lcma::CombHParams p) {{')
+    w(f"    combine_h_tile<{in_t}, {ct_t}, CombH>(p);")
+    w("}")
+    w("")
+    w(f'extern "C" int lcma_launch_comb_h_{s.name}_{dtype}(const lcma::CombHParams *p, int gx, int gy, void *stream) {{')
+    w(f"    lcma_k_comb_h_{s.name}_{dtype}<<<dim3(gx, gy), dim3(256), 0, (hipStream_t)stream>>>(*p);")
+    w("    return (int)hipGetLastError();")
+    w("}")
+    return "\n".join(L) + "\n"
 
 
 def emit_prep_b(s: Scheme, dtype: str) -> str:
@@ -518,6 +617,21 @@ def manifest(schemes: dict[str, Scheme] | None = None) -> list[Variant]:
         assert (sch.m * sch.n + 1) * 16 <= ACC_REG_BUDGET, f"{name}: {sch.m}x{sch.n} C tiles do not fit the registers"
         V += [Variant(name, "bf16", 64, 64, 32, chunk=1, eff=0.04), Variant(name, "f16", 64, 64, 32, chunk=1, eff=0.04),
               Variant(name, "f32", 64, 64, 16, chunk=1, eff=0.4)]
+    # The unfused dataflows the paper starts from, built to be measured against the fused kernels
+    # (lcma_gemm_unfused; rank 95: never chosen by lcma_gemm, not callable by name).  Algorithm 1: a
+    # batched plain GEMM over the R planes written by the stand-alone Combine-A / Combine-B kernels ("g");
+    # Algorithm 2 as printed: a GEMM + Combine-H kernel that takes both operands from planes ("ab").
+    for dt in ("f16", "f32"):
+        tk = 64 if dt == "f16" else 16
+        V += [Variant("plain", dt, 256, 256 if dt == "f16" else 128, tk, wgm=2, wgn=4, tb=1, batch=1, rank=95),
+              Variant("plain", dt, 128, 128, tk, occ=2, tb=1, batch=1, rank=95)]
+    for dt in ("bf16", "f16", "f32"):
+        tk = 16 if dt == "f32" else 32
+        V += [Variant("strassen", dt, 64, 64, tk, chunk=7, pa=1, pb=1, rank=95),
+              Variant("strassen", dt, 128, 128 if dt != "f32" else 64, tk, chunk=1, pa=1, pb=1, rank=95),
+              Variant("laderman", dt, 128 if dt != "f32" else 64, 64, tk, chunk=1, pa=1, pb=1, rank=95)]
+        if dt != "f16":
+            V += [Variant("strassen2", dt, 64, 64, tk, chunk=7, pa=1, pb=1, rank=95)]
     # Every kernel that lcma_gemm can pick for the paper's schemes also exists for B given as the N x K
     # weight matrix ("t"): its B tiles are staged like A's, with 16-byte loads and no transposition.
     from dataclasses import replace
@@ -551,6 +665,8 @@ def generate(out_dir: str) -> list[str]:
         hips.append(put(f"k_{v.name}.hip", emit_kernel(s, v)))
     for sch, dt in prep_kernels(variants):
         hips.append(put(f"k_prep_b_{sch}_{dt}.hip", emit_prep_b(schemes[sch], dt)))
+    for sch, dt in stage_kernels(variants):
+        hips.append(put(f"k_stage_{sch}_{dt}.hip", emit_stage(schemes[sch], dt)))
     put("registry.cc", emit_registry(schemes, variants))
     put("builtin_schemes.inc", emit_builtin_inc(schemes))
     keep = {os.path.basename(h) for h in hips} | {"registry.cc", "builtin_schemes.inc"}

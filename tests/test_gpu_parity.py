@@ -29,8 +29,10 @@ def B():
 
 
 def variants():
+    """Every kernel that can be run by name (the stage kernels of lcma_gemm_unfused take planes, not
+    matrices, and are covered by that entry point's tests)."""
     from paper_2605_06057_amd import binding
-    return binding.lcma_variants()
+    return [v for v in binding.lcma_variants() if v["b_layout"] != 3]
 
 
 def small_shape(v):

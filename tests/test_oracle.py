@@ -342,3 +342,79 @@ def test_combine_b_stored_rounds_once_to_nearest_even():
     assert oracle.combine_b_stored(s, B, "f32")[0, 0, 0] == 2.0 ** 24
     B[0, 0], B[1, 1] = 60000.0, 60000.0                                    # beyond fp16's range
     assert np.isinf(oracle.combine_b_stored(s, B, "f16")[0, 0, 0])
+
+
+# ----------------------------------------------------------------------------- unfused dataflows (Algorithm 1; Algorithm 2 as printed)
+def test_combine_a_strassen_textbook_operands_and_rounding():
+    """Left operands of Strassen's seven products as every textbook prints them; sums that fp16 cannot
+    hold are rounded once to nearest-even."""
+    s = S.strassen()
+    A = inp.integers(9, 7, (6, 4)).astype(np.float64)
+    a11, a12, a21, a22 = A[:3, :2], A[:3, 2:], A[3:, :2], A[3:, 2:]
+    want = [a11 + a22, a21 + a22, a11, a22, a11 + a12, a21 - a11, a12 - a22]
+    for dt in ("bf16", "f16", "f32"):
+        got = oracle.combine_a_stored(s, A, dt)
+        assert got.shape == (7, 3, 2)
+        for r in range(7):
+            assert np.array_equal(got[r], want[r]), (dt, r)
+    A = np.zeros((2, 2))
+    for add, want16 in ((1.0, 2048.0), (3.0, 2052.0), (5.0, 2052.0)):
+        A[0, 0], A[1, 1] = 2048.0, add
+        assert oracle.combine_a_stored(s, A, "f16")[0, 0, 0] == want16   # product 1: a11 + a22
+        assert oracle.combine_a_stored(s, A, "bf16")[0, 0, 0] == want16
+        assert oracle.combine_a_stored(s, A, "f32")[0, 0, 0] == 2048.0 + add
+
+
+@pytest.mark.parametrize("name", ALL)
+def test_combine_a_rebuilds_the_product(name):
+    """Eq. 3-6 with Combine A taken from the oracle and the other stages written as einsums here."""
+    s = S.by_name(name)
+    M, N, K = 2 * s.m, 3 * s.n, 2 * s.k
+    A = inp.integers(17, 4, (M, K))
+    B = inp.integers(17, 5, (K, N))
+    At = oracle.combine_a_stored(s, A.astype(np.float64), "f32")           # [r, x, y], exact on small integers
+    Bb = B.reshape(s.k, K // s.k, s.n, N // s.n)                            # [l, y, j, z]
+    Bt = np.einsum("rlj,lyjz->ryz", s.V.astype(np.int64), Bb)
+    H = np.einsum("rxy,ryz->rxz", At, Bt.astype(np.float64))
+    Cb = np.einsum("rij,rxz->ixjz", s.W.astype(np.float64), H)
+    assert np.array_equal(Cb.reshape(M, N), (A @ B).astype(np.float64))
+
+
+@pytest.mark.parametrize("name", ALL)
+@pytest.mark.parametrize("level", [1, 2])
+def test_unfused_is_exact_on_small_integers(name, level):
+    s = S.by_name(name)
+    M, N, K = 3 * s.m, 2 * s.n, 4 * s.k
+    A, B = inp.integers(21, 1, (M, K)), inp.integers(21, 2, (K, N))
+    for dt in ("bf16", "f16", "f32"):
+        got = oracle.lcma_unfused(s, A.astype(np.float64), B.astype(np.float64), dt, level)
+        assert np.array_equal(got, (A @ B).astype(np.float64)), (dt, level)
+
+
+def test_unfused_rounding_points():
+    """One-element blocks, Strassen, values worked out by hand: the stored left operand of product 1,
+    fp16(2048 + 1) = 2048, changes C11 and C22 at both levels; a product that fp16 cannot hold changes
+    C11 at level 1 only."""
+    s = S.strassen()
+    A = np.array([[2048.0, 0.0], [0.0, 1.0]])
+    B = np.eye(2)
+    # stored operands: At1 = fp16(a11 + a22) = 2048 (not 2049), Bt1 = b11 + b22 = 2
+    # M1 = 4096, M2 = (a21 + a22) b11 = 1, M3 = a11 (b12 - b22) = -2048, M4 = a22 (b21 - b11) = -1,
+    # M5 = (a11 + a12) b22 = 2048, M6 = (a21 - a11)(b11 + b12) = -2048, M7 = (a12 - a22)(b21 + b22) = -1
+    # C11 = M1 + M4 - M5 + M7 = 4096 - 1 - 2048 - 1 = 2046 (exact: 2048): the rounding of At1 shows
+    # C22 = M1 - M2 + M3 + M6 = 4096 - 1 - 2048 - 2048 = -1 (exact: 1)
+    for level in (1, 2):
+        got = oracle.lcma_unfused(s, A, B, "f16", level)
+        assert np.array_equal(got, np.array([[2046.0, 0.0], [0.0, -1.0]])), level
+        assert np.array_equal(oracle.lcma_unfused(s, A, B, "f32", level), A)
+    # level 1 also rounds the stored products: a11 = b11 = 45.25 (exact in fp16), everything else 0:
+    # M1 = M3' ... only products with a11 and b11: M1 = a11 b11, M3 = a11 (0 - 0) = 0, M5 = a11 * 0 = 0,
+    # M6 = -a11 b11.  a11 b11 = 2047.5625 -> fp16 2048 (spacing 1 in [1024, 2048], tie-free).
+    A = np.array([[45.25, 0.0], [0.0, 0.0]])
+    B = np.array([[45.25, 0.0], [0.0, 0.0]])
+    exact = 45.25 * 45.25
+    assert exact == 2047.5625
+    got1 = oracle.lcma_unfused(s, A, B, "f16", 1)
+    got2 = oracle.lcma_unfused(s, A, B, "f16", 2)
+    assert got1[0, 0] == 2048.0 and got2[0, 0] == exact       # C11 = M1 + M4 - M5 + M7 = M1
+    assert got1[1, 1] == 0.0 and got2[1, 1] == 0.0            # C22 = M1 - M2 + M3 + M6 = M1 - M1
