@@ -250,3 +250,45 @@ def test_gemm_argument_checks_before_any_launch(B):
     # lcma_gemm_variant: unknown name, null name
     assert L.lcma_gemm_variant(b"no_such_kernel", 256, 256, 256, P, 256, P, 256, P, 256, None) == B.LCMA_ERR_NOKERNEL
     assert L.lcma_gemm_variant(None, 256, 256, 256, P, 256, P, 256, P, 256, None) == B.LCMA_ERR_ARG
+
+
+def test_weight_layout_and_unfused_host_side(B):
+    """lcma_gemm_nt and lcma_gemm_unfused: sizes and refusals decided on the host (fake pointers, nothing launched)."""
+    L = B.lib()
+    s = B.lcma_scheme_load("builtin:strassen")
+    P = 0x100000
+    # N x K layout: the leading dimension of W is checked against K, not N
+    assert L.lcma_gemm_nt(256, 512, 128, P, 128, P, 120, P, 512, B.LCMA_F16, s.handle, None) == B.LCMA_ERR_ARG
+    assert L.lcma_gemm_nt(256, 512, 128, None, 128, P, 128, P, 512, B.LCMA_F16, s.handle, None) == B.LCMA_ERR_ARG
+    assert L.lcma_gemm_nt(256, 512, 128, P, 128, P, 128, P, 512, 17, s.handle, None) == B.LCMA_ERR_DTYPE
+    wide = B.lcma_scheme_load("builtin:strassen_wide")
+    assert L.lcma_gemm_nt(256, 512, 128, P, 128, P, 128, P, 512, B.LCMA_F16, wide.handle, None) == B.LCMA_ERR_NOKERNEL
+    layouts = [v["b_layout"] for v in B.lcma_variants()]
+    assert set(layouts) == {0, 1, 2, 3} and L.lcma_variant_b_layout(len(layouts)) == -1
+    # every selectable kernel of the paper's schemes that takes B has a twin for the N x K layout
+    names = {v["name"] for v in B.lcma_variants()}
+    for v in B.lcma_variants():
+        if v["b_layout"] == 2:
+            base = v["name"].replace("to2", "o2") if v["name"].endswith("to2") else v["name"][:-1]
+            assert base in names, v["name"]
+    # workspace of the unfused dataflows: At, Bt and H planes, blocks padded to 128 rows and 64 (fp32: 16) columns
+    assert B.lcma_unfused_workspace_bytes(s, 4096, 4096, 4096, B.LCMA_BF16) == 3 * 7 * 2048 * 2048 * 2
+    assert B.lcma_unfused_workspace_bytes(s, 100, 200, 72, B.LCMA_F32) == 7 * (128 * 48 + 128 * 48 + 128 * 128) * 4
+    lad = B.lcma_scheme_load("builtin:laderman")
+    assert B.lcma_unfused_workspace_bytes(lad, 384, 384, 192, B.LCMA_F16) == 23 * (128 * 64 * 2 + 128 * 128) * 2
+    assert B.lcma_unfused_workspace_bytes(s, 4096, 4096, 4096, 17) == -1
+
+    def unfused(level=1, M=256, N=256, K=256, a=P, ws=P, nbytes=1 << 30, dt=B.LCMA_F16, sch=s.handle, lda=None):
+        return L.lcma_gemm_unfused(level, M, N, K, a, K if lda is None else lda, P, N, P, N, dt, sch, ws, nbytes, 0, None)
+
+    assert unfused(level=0) == B.LCMA_ERR_ARG and unfused(level=3) == B.LCMA_ERR_ARG
+    assert unfused(sch=None) == B.LCMA_ERR_ARG
+    assert unfused(sch=wide.handle) == B.LCMA_ERR_NOKERNEL
+    assert unfused(dt=17) == B.LCMA_ERR_DTYPE
+    assert unfused(a=None) == B.LCMA_ERR_ARG and unfused(ws=None) == B.LCMA_ERR_ARG
+    assert unfused(ws=P + 16) == B.LCMA_ERR_ARG                 # the workspace must be 256-byte aligned
+    assert unfused(nbytes=3 * 7 * 128 * 128 * 2 - 1) == B.LCMA_ERR_ARG
+    assert b"needed" in L.lcma_last_error()
+    assert unfused(K=252, lda=256) == B.LCMA_ERR_SHAPE
+    assert unfused(K=0) == B.LCMA_ERR_SHAPE
+    assert unfused(M=0) == B.LCMA_OK                            # nothing to write
