@@ -10,6 +10,9 @@ Prints ONE JSON line.  `value` is effective TFLOP/s = 2MNK / time (standard-GEMM
 paper Sec. 4.1 "Measurement"), so it can exceed what the MFMA units did.  Beside it: the same-build
 plain MFMA GEMM timed the same way, the fraction of the dense MFMA peak, a roofline object
 for the dominant kernel and the CPU oracle timed on a bounded sample of the same workload.
+Further legs, each about a second, run unless --no-extras is given and are reported in objects of
+their own beside `value`: the offline Combine-B path, B given as the N x K weight matrix, and the
+unfused dataflows of Algorithm 1 / Algorithm 2.
 """
 from __future__ import annotations
 
@@ -72,7 +75,12 @@ def main():
                     help="also time the dataflows the paper starts from (lcma_gemm_unfused): Algorithm 1 (four stages "
                          "through device memory) and Algorithm 2 as printed (Combine A/B materialised, GEMM + Combine H "
                          "fused), each with Combine B per call and with Combine B done once (static weights)")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="time lcma_gemm, the plain and the vendor GEMM only (by default the prepared-B, weight-layout "
+                         "and ablation legs run too; each adds about a second)")
     args = ap.parse_args()
+    if not args.no_extras:
+        args.prepared_b = args.weight_layout = args.ablation = True
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU (the path would shard over M with no exchange between "
                  "GPUs, each running this same kernel on its rows). Re-run with --gpus 1.")
