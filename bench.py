@@ -36,6 +36,9 @@ WORKLOADS = {
     "laderman_f16_6144": ("laderman", "f16", 6144, 6144, 6144, "uniform", "uniform", 0x5EED0004),
     "strassen_f32_4096": ("strassen", "f32", 4096, 4096, 4096, "uniform", "uniform", 0x5EED0005),
     "strassen2_f32_4096": ("strassen2", "f32", 4096, 4096, 4096, "uniform", "uniform", 0x5EED0005),
+    # Winograd's form of Strassen's algorithm (generated with its common sums shared): not a BASELINE config
+    "winograd_f32_4096": ("winograd", "f32", 4096, 4096, 4096, "uniform", "uniform", 0x5EED0005),
+    "winograd_bf16_4096": ("winograd", "bf16", 4096, 4096, 4096, "normal", "normal", 0x5EED0002),
 }
 
 

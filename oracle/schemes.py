@@ -189,9 +189,32 @@ def strassen_wide() -> Scheme:
     return kronecker(strassen(), classical(1, 1, 2), "strassen_wide")
 
 
+def winograd() -> Scheme:
+    """The Winograd form of Strassen's algorithm, <2,2,2;7> with 15 additions when common sums are
+    shared (S1 = a21 + a22, S2 = S1 - a11, S3 = a11 - a21, S4 = a12 - S2; T1 = b12 - b11, T2 = b22 - T1,
+    T3 = b22 - b12, T4 = T2 - b21), written out flat here.  Not one of the paper's named schemes: it
+    exercises the generator's sharing of common sums."""
+    products = [
+        "(a11) * (b11)",
+        "(a12) * (b21)",
+        "(a12 - a21 - a22 + a11) * (b22)",                      # S4 * b22
+        "(a22) * (b22 - b12 + b11 - b21)",                      # a22 * T4
+        "(a21 + a22) * (b12 - b11)",                            # S1 * T1
+        "(a21 + a22 - a11) * (b22 - b12 + b11)",                # S2 * T2
+        "(a11 - a21) * (b22 - b12)",                            # S3 * T3
+    ]
+    outputs = [
+        "c11 = h1 + h2",
+        "c12 = h1 + h6 + h5 + h3",
+        "c21 = h1 + h6 + h7 - h4",
+        "c22 = h1 + h6 + h7 + h5",
+    ]
+    return from_formulas(2, 2, 2, products, outputs, "winograd")
+
+
 def by_name(name: str) -> Scheme:
     return {"strassen": strassen, "strassen2": strassen2, "laderman": laderman,
-            "strassen_wide": strassen_wide}[name]()
+            "strassen_wide": strassen_wide, "winograd": winograd}[name]()
 
 
 def to_text(s: Scheme) -> str:

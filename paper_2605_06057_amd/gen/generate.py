@@ -232,6 +232,53 @@ def signed_sum(terms: list[tuple[int, str]], wide: bool = False, fn: bool = Fals
     return out
 
 
+def share_sums(rows: list[dict[int, int]], n_in: int):
+    """Common sums of a set of signed sums with +-1 coefficients (the "register reuse" of Sec. 3.1): while
+    some pair of variables occurs with the same relative sign in two or more rows, it becomes a shared
+    temporary t = x +- y that replaces the pair everywhere.  Variables 0..n_in-1 are the inputs, the
+    temporaries follow.  Returns (temps [(x, y, sign)], rewritten rows).  Winograd's form of Strassen's
+    algorithm comes out at its 4 + 4 additions this way; schemes without common pairs are left as they are."""
+    rows = [dict(r) for r in rows]
+    temps = []
+    while True:
+        count = {}
+        for r in rows:
+            vs = sorted(r)
+            for a in range(len(vs)):
+                for b in range(a + 1, len(vs)):
+                    key = (vs[a], vs[b], r[vs[a]] * r[vs[b]])
+                    count[key] = count.get(key, 0) + 1
+        best = max(count.items(), key=lambda kv: (kv[1], -kv[0][0], -kv[0][1]), default=None)
+        if best is None or best[1] < 2:
+            return temps, rows
+        (x, y, rel), _ = best
+        users = [r for r in rows if x in r and y in r and r[x] * r[y] == rel]
+        lone = sum(r[x] for r in users if len(r) == 2)  # rows that are this pair alone would need a negation
+        if rel < 0 and (lone < 0 or (lone == 0 and sum(r[x] for r in users) < 0)):
+            x, y = y, x  # a difference is taken the way round that saves negations
+        t = n_in + len(temps)
+        temps.append((x, y, rel))
+        for r in users:
+            cx = r.pop(x)
+            r.pop(y)
+            r[t] = cx
+
+
+def emit_comb(w, fn_name: str, n_name: str, rows: list[list[tuple[int, int]]], n_in: int, wide: bool):
+    """out[s] = signed sum of in[...] for every row [(coef, input index)], with common sums shared when every
+    coefficient is +-1 and the sums are not formed in a wider type."""
+    w(f"    template <class V> static LCMA_DEV void {fn_name}(const V (&in)[{n_name}], V (&out)[NP]) {{")
+    shareable = not wide and all(abs(c) == 1 for row in rows for c, _ in row)
+    temps, new_rows = share_sums([{i: c for c, i in row} for row in rows], n_in) if shareable else ([], None)
+    name = lambda i: f"in[{i}]" if i < n_in else f"t{i - n_in}"
+    for ti, (x, y, rel) in enumerate(temps):
+        w(f"        const V t{ti} = {'vadd' if rel > 0 else 'vsub'}({name(x)}, {name(y)});")
+    for si, row in enumerate(rows):
+        terms = [(c, name(i)) for i, c in sorted(new_rows[si].items())] if temps else [(c, f"in[{i}]") for c, i in row]
+        w(f"        out[{si}] = {signed_sum(terms, wide, True)};")
+    w("    }")
+
+
 def emit_kernel(s: Scheme, v: Variant) -> str:
     s, residual = with_residuals(s, v.comp)
     in_t, ct_t = CPP_TYPES[v.dtype]
@@ -269,6 +316,9 @@ def emit_kernel(s: Scheme, v: Variant) -> str:
         if v.pa:
             assert not v.comp, "residual products are formed by the fused kernels only"
             w(f"    static LCMA_DEV constexpr int a_plane(int s) {{ constexpr int v[] = {{{', '.join(map(str, ch))}}}; return v[s]; }}")
+        elif not any(r in residual for r in ch):
+            emit_comb(w, "comb_a", "NA", [[(int(s.U[r, i, l]), a_blocks.index((i, l))) for (i, l) in a_blocks if s.U[r, i, l]]
+                                          for r in ch], len(a_blocks), wide)
         else:
             w("    template <class V> static LCMA_DEV void comb_a(const V (&in)[NA], V (&out)[NP]) {")
             for si, r in enumerate(ch):
@@ -285,11 +335,8 @@ def emit_kernel(s: Scheme, v: Variant) -> str:
             planes = [r if r < n_orig else v.comp[r - n_orig] for r in ch]
             w(f"    static LCMA_DEV constexpr int b_plane(int s) {{ constexpr int v[] = {{{', '.join(map(str, planes))}}}; return v[s]; }}")
         if not v.pb:
-            w("    template <class V> static LCMA_DEV void comb_b(const V (&in)[NB], V (&out)[NP]) {")
-            for si, r in enumerate(ch):
-                terms = [(int(s.V[r, l, j]), f"in[{b_blocks.index((l, j))}]") for (l, j) in b_blocks if s.V[r, l, j]]
-                w(f"        out[{si}] = {signed_sum(terms, wide, True)};")
-            w("    }")
+            emit_comb(w, "comb_b", "NB", [[(int(s.V[r, l, j]), b_blocks.index((l, j))) for (l, j) in b_blocks if s.V[r, l, j]]
+                                          for r in ch], len(b_blocks), wide)
         w("};")
     w("")
     w("} // namespace")
@@ -617,6 +664,15 @@ def manifest(schemes: dict[str, Scheme] | None = None) -> list[Variant]:
         assert (sch.m * sch.n + 1) * 16 <= ACC_REG_BUDGET, f"{name}: {sch.m}x{sch.n} C tiles do not fit the registers"
         V += [Variant(name, "bf16", 64, 64, 32, chunk=1, eff=0.04), Variant(name, "f16", 64, 64, 32, chunk=1, eff=0.04),
               Variant(name, "f32", 64, 64, 16, chunk=1, eff=0.4)]
+    # Winograd's form of Strassen's algorithm (a further scheme file): the fragment-combine kernels with the
+    # common sums shared, 4 + 4 additions per fragment set instead of 5 + 5.  fp16 storage forms its 3- and
+    # 4-term sums in fp32 (no sharing) and keeps the default r-loop kernel only.
+    if "winograd" in schemes:
+        for tb in (0, 1):
+            V += [Variant("winograd", "bf16", 128, 64, 32, chunk=7, fc=1, wgm=4, wgn=2, pipe=2, tb=tb, eff=0.27),
+                  Variant("winograd", "bf16", 64, 64, 32, chunk=7, fc=1, occ=2, pipe=2, tb=tb, eff=0.24),
+                  Variant("winograd", "f32", 64, 64, 16, chunk=7, fc=1, occ=2, pipe=2, tb=tb, eff=0.88),
+                  Variant("winograd", "f32", 128, 64, 16, chunk=7, fc=1, wgm=4, wgn=2, pipe=2, tb=tb, eff=0.81)]
     # The unfused dataflows the paper starts from, built to be measured against the fused kernels
     # (lcma_gemm_unfused; rank 95: never chosen by lcma_gemm, not callable by name).  Algorithm 1: a
     # batched plain GEMM over the R planes written by the stand-alone Combine-A / Combine-B kernels ("g");

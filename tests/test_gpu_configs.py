@@ -81,12 +81,13 @@ def test_selector_sweep_runs_its_pick():
 
 
 def test_selector_pick_is_close_to_the_measured_best():
-    """Decision Module (Sec. 3.3) against the clock: on a few shapes, time every scheme that has a kernel
-    and require lcma_select's pick to be within 12 % of the fastest (all timings from this one run)."""
+    """Decision Module (Sec. 3.3) against the clock: on a few shapes, time every scheme lcma_select chooses
+    among (plain and the paper's three) and require its pick to be within 12 % of the fastest (all timings
+    from this one run)."""
     import torch
     from paper_2605_06057_amd import binding as B
 
-    def seconds(fn, iters=12, warm=4):
+    def seconds(fn, iters=16, warm=8):
         for _ in range(warm):
             fn()
         torch.cuda.synchronize()
@@ -98,7 +99,7 @@ def test_selector_pick_is_close_to_the_measured_best():
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) / iters * 1e-3
 
-    schemes = {i: (B.lcma_scheme_load("builtin:" + n) if i else None) for i, n in B.SCHEME_NAMES.items()}
+    schemes = {i: (B.lcma_scheme_load("builtin:" + n) if i else None) for i, n in B.SCHEME_NAMES.items() if i <= 3}
     cases = [("bf16", 4096, 4096, 4096), ("bf16", 2048, 14336, 4096), ("bf16", 1000, 4096, 4096),
              ("f16", 3072, 3072, 3072), ("f32", 4096, 4096, 4096), ("f32", 1024, 1024, 1024), ("f32", 3000, 4096, 2040)]
     heat = torch.randn(4096, 4096, device="cuda", dtype=torch.bfloat16)

@@ -17,7 +17,7 @@ import oracle
 from oracle import schemes as S
 
 PAPER = ["strassen", "laderman", "strassen2"]      # the schemes the paper names
-ALL = PAPER + ["strassen_wide"]                      # plus the rectangular scheme the package ships
+ALL = PAPER + ["strassen_wide", "winograd"]          # plus the two further schemes the package ships
 
 
 # ---------------------------------------------------------------- GEMM triple loop
