@@ -673,6 +673,8 @@ def manifest(schemes: dict[str, Scheme] | None = None) -> list[Variant]:
                   Variant("winograd", "bf16", 64, 64, 32, chunk=7, fc=1, occ=2, pipe=2, tb=tb, eff=0.24),
                   Variant("winograd", "f32", 64, 64, 16, chunk=7, fc=1, occ=2, pipe=2, tb=tb, eff=0.88),
                   Variant("winograd", "f32", 128, 64, 16, chunk=7, fc=1, wgm=4, wgn=2, pipe=2, tb=tb, eff=0.81)]
+        V += [Variant("winograd", "bf16", 128, 64, 32, chunk=7, fc=1, wgm=4, wgn=2, pipe=2, pb=1, eff=0.27),
+              Variant("winograd", "f32", 128, 64, 16, chunk=7, fc=1, wgm=4, wgn=2, pipe=2, pb=1, eff=0.88)]
     # The unfused dataflows the paper starts from, built to be measured against the fused kernels
     # (lcma_gemm_unfused; rank 95: never chosen by lcma_gemm, not callable by name).  Algorithm 1: a
     # batched plain GEMM over the R planes written by the stand-alone Combine-A / Combine-B kernels ("g");
