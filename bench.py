@@ -209,6 +209,9 @@ def main():
         torch.cuda.synchronize()
         nk["_c"] = sets[0][2].clone()
     ablation = None
+    if args.ablation and B.lib().lcma_gemm_unfused(1, 0, 0, 0, None, 0, None, 0, None, 0, B.DTYPE_IDS[dt], scheme.handle,
+                                                   None, 0, 0, None) == B.LCMA_ERR_NOKERNEL:
+        args.ablation = False  # no stage kernels for this scheme (an empty call answers before anything is launched)
     if args.ablation:
         nbytes = B.lcma_unfused_workspace_bytes(scheme, M, N, K, B.DTYPE_IDS[dt])
         ws = torch.empty((nbytes,), dtype=torch.uint8, device="cuda")

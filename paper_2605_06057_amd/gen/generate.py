@@ -638,7 +638,7 @@ def manifest(schemes: dict[str, Scheme] | None = None) -> list[Variant]:
     # two-level Strassen: with fp16 storage its four-term sums exceed the 4x error bound, so it is
     # generated for bf16 (sums nearly exact in fp16) and fp32 only
     V += [
-        Variant("strassen2", "bf16", 64, 64, 32, chunk=7, eff=0.062),
+        Variant("strassen2", "bf16", 64, 64, 32, chunk=7, eff=0.065),
         Variant("strassen2", "bf16", 64, 64, 32, chunk=1, eff=0.030),
     ]
     V += [
@@ -654,7 +654,7 @@ def manifest(schemes: dict[str, Scheme] | None = None) -> list[Variant]:
         Variant("strassen", "f32", 64, 64, 16, chunk=7, eff=0.656, rank=90),
         Variant("strassen", "f32", 128, 64, 16, chunk=1, eff=0.613),
         Variant("laderman", "f32", 64, 64, 16, chunk=1, eff=0.399),
-        Variant("strassen2", "f32", 64, 64, 16, chunk=7, eff=0.511),
+        Variant("strassen2", "f32", 64, 64, 16, chunk=7, eff=0.534),
     ]
     # Further scheme files get Algorithm 2's r loop (one product at a time, the m*n C tiles in registers)
     # on a 64 x 64 tile, which fits any grid up to m*n = 24.
@@ -669,10 +669,10 @@ def manifest(schemes: dict[str, Scheme] | None = None) -> list[Variant]:
     # 4-term sums in fp32 (no sharing) and keeps the default r-loop kernel only.
     if "winograd" in schemes:
         for tb in (0, 1):
-            V += [Variant("winograd", "bf16", 128, 64, 32, chunk=7, fc=1, wgm=4, wgn=2, pipe=2, tb=tb, eff=0.27),
-                  Variant("winograd", "bf16", 64, 64, 32, chunk=7, fc=1, occ=2, pipe=2, tb=tb, eff=0.24),
-                  Variant("winograd", "f32", 64, 64, 16, chunk=7, fc=1, occ=2, pipe=2, tb=tb, eff=0.88),
-                  Variant("winograd", "f32", 128, 64, 16, chunk=7, fc=1, wgm=4, wgn=2, pipe=2, tb=tb, eff=0.81)]
+            V += [Variant("winograd", "bf16", 128, 64, 32, chunk=7, fc=1, wgm=4, wgn=2, pipe=2, tb=tb, eff=0.282 if tb else 0.271),
+                  Variant("winograd", "bf16", 64, 64, 32, chunk=7, fc=1, occ=2, pipe=2, tb=tb, eff=0.250 if tb else 0.243),
+                  Variant("winograd", "f32", 64, 64, 16, chunk=7, fc=1, occ=2, pipe=2, tb=tb, eff=0.90),
+                  Variant("winograd", "f32", 128, 64, 16, chunk=7, fc=1, wgm=4, wgn=2, pipe=2, tb=tb, eff=0.88)]
         V += [Variant("winograd", "bf16", 128, 64, 32, chunk=7, fc=1, wgm=4, wgn=2, pipe=2, pb=1, eff=0.27),
               Variant("winograd", "f32", 128, 64, 16, chunk=7, fc=1, wgm=4, wgn=2, pipe=2, pb=1, eff=0.88)]
     # The unfused dataflows the paper starts from, built to be measured against the fused kernels
