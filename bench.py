@@ -55,6 +55,63 @@ def read_traffic(workload: str):
     return None
 
 
+def selector_sweep(args):
+    """The Decision Module (Sec. 3.3) against the clock on the LLM-shaped sweep."""
+    import torch
+
+    from paper_2605_06057_amd import binding as B
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU. Re-run with --gpus 1.")
+    assert torch.cuda.is_available(), "bench.py needs the MI355X"
+    B.lib()
+    names = {0: "plain", 1: "strassen", 2: "strassen2", 3: "laderman"}
+    handles = {i: (B.lcma_scheme_load("builtin:" + n) if i else None) for i, n in names.items()}
+    gen = torch.Generator(device="cuda").manual_seed(0x5EED0005)
+
+    def timed(fn, steps, warmup):
+        t_heat = time.perf_counter()
+        while time.perf_counter() - t_heat < args.heat_seconds:
+            for _ in range(5):
+                fn()
+            torch.cuda.synchronize()
+        for _ in range(warmup):
+            fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(steps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / steps * 1e-3
+
+    rows = []
+    steps, warmup = max(5, args.steps // 10), max(2, args.warmup // 4)
+    for M in (2048, 8192, 16384):
+        for N, K in ((4096, 4096), (14336, 4096), (4096, 14336)):
+            a = torch.randn((M, K), device="cuda", generator=gen).bfloat16()
+            b = (torch.randn((K, N), device="cuda", generator=gen) * 0.02).bfloat16()
+            c = torch.empty((M, N), device="cuda", dtype=torch.bfloat16)
+            flops = 2.0 * M * N * K
+            row = {"M": M, "N": N, "K": K, "measured_tflops": {}, "predicted_tflops": {}}
+            for i, n in names.items():
+                row["measured_tflops"][n] = flops / timed(lambda: B.lcma_gemm(a, b, c, handles[i]), steps, warmup) / 1e12
+                t = B.lcma_predict_seconds(i, M, N, K, B.LCMA_BF16)
+                row["predicted_tflops"][n] = flops / t / 1e12 if t > 0 else None
+            ws = torch.empty((B.lcma_unfused_workspace_bytes(handles[1], M, N, K, B.LCMA_BF16),), dtype=torch.uint8, device="cuda")
+            B.lcma_gemm_unfused(1, a, b, c, handles[1], ws)
+            row["algorithm1_strassen_combine_b_offline_tflops"] = flops / timed(
+                lambda: B.lcma_gemm_unfused(1, a, b, c, handles[1], ws, reuse_bt=True), steps, warmup) / 1e12
+            row["pick"] = names[B.lcma_select(M, N, K, B.LCMA_BF16)]
+            row["fastest_fused"] = max(row["measured_tflops"], key=row["measured_tflops"].get)
+            rows.append(row)
+            del a, b, c, ws
+    print(json.dumps({"metric": "effective TFLOP/s (2MNK/t) per scheme on the selector's shape sweep, bf16", "unit": "TFLOP/s",
+                      "n_gpus": 1, "steps": steps, "warmup": warmup, "dtype": "f16", "data": "synthetic",
+                      "picks_equal_fastest": sum(r["pick"] == r["fastest_fused"] for r in rows), "shapes": len(rows),
+                      "sweep": rows}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -81,7 +138,14 @@ def main():
     ap.add_argument("--no-extras", action="store_true",
                     help="time lcma_gemm, the plain and the vendor GEMM only (by default the prepared-B, weight-layout "
                          "and ablation legs run too; each adds about a second)")
+    ap.add_argument("--selector-sweep", action="store_true",
+                    help="instead of one workload: the bf16 shape sweep M in {2048, 8192, 16384} x (N, K) in {(4096, 4096), "
+                         "(14336, 4096), (4096, 14336)} with A ~ N(0,1), B ~ N(0, 0.02^2); times plain, Strassen, two-level "
+                         "Strassen and Laderman (lcma_gemm) and Algorithm 1 with Combine B offline for Strassen, and prints "
+                         "lcma_select's pick and its predictions beside them, as one JSON line")
     args = ap.parse_args()
+    if args.selector_sweep:
+        return selector_sweep(args)
     if not args.no_extras:
         args.prepared_b = args.weight_layout = args.ablation = True
     if args.gpus != 1:
