@@ -283,7 +283,8 @@ lcma_status prepare_b_planes(bool transposed, int64_t N, int64_t K, const void *
 
 static lcma_status prepare_b(bool transposed, int64_t N, int64_t K, const void *B, int64_t ldb, lcma_dtype dtype,
                              const lcma_scheme *scheme, void *Bt, void *stream) {
-    return prepare_b_planes(transposed, N, K, B, ldb, dtype, scheme, Bt, stream, 64, 64 / (dtype_size(dtype) ? dtype_size(dtype) : 4));
+    const int es = dtype_size(dtype); // 0 for an unknown dtype, which prepare_b_planes rejects first
+    return prepare_b_planes(transposed, N, K, B, ldb, dtype, scheme, Bt, stream, 64, es ? 64 / es : 16);
 }
 
 extern "C" lcma_status lcma_prepare_b(int64_t N, int64_t K, const void *B, int64_t ldb, lcma_dtype dtype,

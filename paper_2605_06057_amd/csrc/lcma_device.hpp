@@ -651,11 +651,12 @@ template <class T> struct Ctx {
                     const uint32_t off = ((uint32_t)j * p.c_bcol + n_group + colb < p.n_row_b)
                                              ? (uint32_t)(wm * T::WM + mi * 32 + row) * p.ldc_b + colb
                                              : p.c_bytes;
-                    // The scalar-offset field stays a literal zero on purpose.  A store of more than 8 bytes
-                    // reads its data registers over several cycles, and the compiler keeps later vector
-                    // writes to those registers away from it only for stores WITHOUT a scalar-register
-                    // offset; with one, a following address computation that reused the first data
-                    // register reached the last quarter of the lanes of the store (seen on MI355X).
+                    // The scalar offset is added to the vector offset and the scalar-offset field left a
+                    // literal zero on purpose.  A store of more than 8 bytes reads its data registers over
+                    // several cycles; the compiler keeps a following vector write to those registers at a
+                    // distance only when the store has no scalar-register offset.  With one, on MI355X, the
+                    // next row's address computation (which had been given the first data register)
+                    // overwrote the data of the last quarter of the lanes.
                     __builtin_amdgcn_raw_buffer_store_b128(v, rc, (int)(off + soff), 0, 0);
                 }
                 __syncthreads();
