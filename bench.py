@@ -98,17 +98,28 @@ def selector_sweep(args):
                 row["measured_tflops"][n] = flops / timed(lambda: B.lcma_gemm(a, b, c, handles[i]), steps, warmup) / 1e12
                 t = B.lcma_predict_seconds(i, M, N, K, B.LCMA_BF16)
                 row["predicted_tflops"][n] = flops / t / 1e12 if t > 0 else None
-            ws = torch.empty((B.lcma_unfused_workspace_bytes(handles[1], M, N, K, B.LCMA_BF16),), dtype=torch.uint8, device="cuda")
-            B.lcma_gemm_unfused(1, a, b, c, handles[1], ws)
-            row["algorithm1_strassen_combine_b_offline_tflops"] = flops / timed(
-                lambda: B.lcma_gemm_unfused(1, a, b, c, handles[1], ws, reuse_bt=True), steps, warmup) / 1e12
+            row["algorithm1_combine_b_offline_tflops"], row["algorithm1_predicted_tflops"] = {}, {}
+            for i in (1, 2, 3):
+                ws = torch.empty((B.lcma_unfused_workspace_bytes(handles[i], M, N, K, B.LCMA_BF16),), dtype=torch.uint8, device="cuda")
+                B.lcma_gemm_unfused(1, a, b, c, handles[i], ws)
+                row["algorithm1_combine_b_offline_tflops"][names[i]] = flops / timed(
+                    lambda: B.lcma_gemm_unfused(1, a, b, c, handles[i], ws, reuse_bt=True), steps, warmup) / 1e12
+                row["algorithm1_predicted_tflops"][names[i]] = flops / B.lcma_predict_unfused_seconds(i, M, N, K, B.LCMA_BF16, True) / 1e12
+                del ws
             row["pick"] = names[B.lcma_select(M, N, K, B.LCMA_BF16)]
             row["fastest_fused"] = max(row["measured_tflops"], key=row["measured_tflops"].get)
+            ch = B.lcma_select_dataflow(M, N, K, B.LCMA_BF16, True)
+            row["choice"] = names[ch["scheme_id"]] + ("/algorithm1" if ch["dataflow"] else "/fused")
+            every = {n + "/fused": v for n, v in row["measured_tflops"].items()}
+            every.update({n + "/algorithm1": v for n, v in row["algorithm1_combine_b_offline_tflops"].items()})
+            row["fastest_of_all"] = max(every, key=every.get)
+            row["choice_vs_fastest"] = every[row["choice"]] / every[row["fastest_of_all"]]
             rows.append(row)
-            del a, b, c, ws
+            del a, b, c
     print(json.dumps({"metric": "effective TFLOP/s (2MNK/t) per scheme on the selector's shape sweep, bf16", "unit": "TFLOP/s",
                       "n_gpus": 1, "steps": steps, "warmup": warmup, "dtype": "f16", "data": "synthetic",
                       "picks_equal_fastest": sum(r["pick"] == r["fastest_fused"] for r in rows), "shapes": len(rows),
+                      "worst_choice_vs_fastest": min(r["choice_vs_fastest"] for r in rows),
                       "sweep": rows}))
 
 
@@ -141,8 +152,8 @@ def main():
     ap.add_argument("--selector-sweep", action="store_true",
                     help="instead of one workload: the bf16 shape sweep M in {2048, 8192, 16384} x (N, K) in {(4096, 4096), "
                          "(14336, 4096), (4096, 14336)} with A ~ N(0,1), B ~ N(0, 0.02^2); times plain, Strassen, two-level "
-                         "Strassen and Laderman (lcma_gemm) and Algorithm 1 with Combine B offline for Strassen, and prints "
-                         "lcma_select's pick and its predictions beside them, as one JSON line")
+                         "Strassen and Laderman both fused (lcma_gemm) and by Algorithm 1 with Combine B offline, and prints "
+                         "lcma_select's pick, lcma_select_dataflow's choice and the predictions beside them, as one JSON line")
     args = ap.parse_args()
     if args.selector_sweep:
         return selector_sweep(args)

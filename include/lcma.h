@@ -195,6 +195,18 @@ lcma_status lcma_gemm_unfused(int level, int64_t M, int64_t N, int64_t K,
                               void *C, int64_t ldc, lcma_dtype dtype, const lcma_scheme *scheme,
                               void *workspace, int64_t workspace_bytes, int reuse_bt, void *stream);
 
+/* The Decision Module (Sec. 3.3) over both dataflows this library runs: predicted seconds of Algorithm 1
+ * (lcma_gemm_unfused level 1) for a built-in scheme id, stage by stage (Combine A, Combine B unless
+ * combine_b_offline, the batched GEMM, Combine H; negative when the scheme has no stage kernels), and the
+ * choice with the smallest predicted time among plain, the fused kernels and Algorithm 1 of the paper's
+ * schemes.  dataflow: 0 = lcma_gemm (fused; scheme_id LCMA_PLAIN means the plain GEMM), 1 = lcma_gemm_unfused
+ * level 1.  Pure host arithmetic. */
+typedef struct { int scheme_id; int dataflow; double seconds; } lcma_choice;
+double lcma_predict_unfused_seconds(int scheme_id, int64_t M, int64_t N, int64_t K, lcma_dtype dtype,
+                                    int combine_b_offline);
+lcma_status lcma_select_dataflow(int64_t M, int64_t N, int64_t K, lcma_dtype dtype,
+                                 int combine_b_offline, lcma_choice *out);
+
 /* ------------------------------------------------------------------ Decision Module (Sec. 3.3)
  * lcma_select: predicted-fastest algorithm for the shape on MI355X among
  * {plain, <2,2,2;7>, <4,4,4;49>, <3,3,3;23>}; returns a built-in scheme id, or a

@@ -29,6 +29,7 @@ EXPORTS = [
     "lcma_sched_waves", "lcma_sched_range", "lcma_status_str", "lcma_last_error",
     "lcma_scheme_name", "lcma_scheme_id_max", "lcma_variant_prepared", "lcma_prepared_b_bytes", "lcma_prepare_b", "lcma_prepare_bt", "lcma_gemm_prepared",
     "lcma_gemm_nt", "lcma_variant_b_layout", "lcma_unfused_workspace_bytes", "lcma_gemm_unfused",
+    "lcma_predict_unfused_seconds", "lcma_select_dataflow",
 ]
 
 
@@ -40,6 +41,10 @@ class LcmaError(RuntimeError):
 
 class lcma_hw(ctypes.Structure):
     _fields_ = [("flops_mul", ctypes.c_double), ("flops_add", ctypes.c_double), ("beta", ctypes.c_double)]
+
+
+class lcma_choice(ctypes.Structure):
+    _fields_ = [("scheme_id", ctypes.c_int), ("dataflow", ctypes.c_int), ("seconds", ctypes.c_double)]
 
 
 class lcma_stage_costs(ctypes.Structure):
@@ -72,6 +77,9 @@ def lib() -> ctypes.CDLL:
         L.lcma_variant_b_layout.argtypes = [i32]
         L.lcma_unfused_workspace_bytes.argtypes = [i64, i64, i64, i32, vp]
         L.lcma_unfused_workspace_bytes.restype = i64
+        L.lcma_predict_unfused_seconds.argtypes = [i32, i64, i64, i64, i32, i32]
+        L.lcma_predict_unfused_seconds.restype = ctypes.c_double
+        L.lcma_select_dataflow.argtypes = [i64, i64, i64, i32, i32, ctypes.POINTER(lcma_choice)]
         L.lcma_gemm_unfused.argtypes = [i32, i64, i64, i64, vp, i64, vp, i64, vp, i64, i32, vp, vp, i64, i32, vp]
         L.lcma_variant_count.argtypes = []
         L.lcma_variant_name.argtypes = [i32]
@@ -191,6 +199,17 @@ def lcma_gemm_nt(A, W, C, scheme: Scheme | None = None):
     _check(lib().lcma_gemm_nt(M, N, K, pa, lda, pw, ldw, pc, ldc, _dtype_of(A),
                               scheme.handle if scheme is not None else None, stream))
     return C
+
+
+def lcma_predict_unfused_seconds(scheme_id: int, M: int, N: int, K: int, dtype: int, combine_b_offline: bool = False) -> float:
+    return float(lib().lcma_predict_unfused_seconds(scheme_id, M, N, K, dtype, int(combine_b_offline)))
+
+
+def lcma_select_dataflow(M: int, N: int, K: int, dtype: int, combine_b_offline: bool = False) -> dict:
+    """{'scheme_id', 'dataflow' (0 fused / plain, 1 Algorithm 1), 'seconds'} with the smallest predicted time."""
+    c = lcma_choice()
+    _check(lib().lcma_select_dataflow(M, N, K, dtype, int(combine_b_offline), ctypes.byref(c)))
+    return {"scheme_id": int(c.scheme_id), "dataflow": int(c.dataflow), "seconds": float(c.seconds)}
 
 
 def lcma_unfused_workspace_bytes(scheme: Scheme, M: int, N: int, K: int, dtype: int) -> int:

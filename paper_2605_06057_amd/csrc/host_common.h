@@ -66,6 +66,7 @@ struct StageKernel {
     int scheme_id, dtype;
     int (*launch_comb_a)(const PrepParams *p, int grid_x, int grid_y, void *stream);
     int (*launch_comb_h)(const CombHParams *p, int grid_x, int grid_y, void *stream);
+    double rate_a, rate_b, rate_h; // measured algorithmic bytes per second of Combine A, Combine B, Combine H
 };
 extern const StageKernel kStageKernels[];
 extern const int kStageKernelCount;

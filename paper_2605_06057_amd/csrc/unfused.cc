@@ -10,6 +10,7 @@
 // fp32) that cover ceil(M/m), ceil(N/n), ceil(K/k); the padding holds zeros.
 #include "host_common.h"
 
+#include <cmath>
 #include <cstdlib>
 #include <cstring>
 
@@ -45,19 +46,42 @@ const StageKernel *find_stage(int scheme_id, int dtype) {
     return nullptr;
 }
 
-// Largest tile among the stage kernels of the wanted kind that divides the planes.
-const Variant *find_gemm(bool batch, int scheme_id, int dtype, const Geometry &g) {
+// Seconds of the GEMM stage with kernel v on planes of geometry g: R tile-jobs per tile position for the
+// batched plain kernel, one group of R products for the Algorithm 2 kernel, in rounds of 256 * occupancy
+// work-groups.  A round costs its MFMA flops at the kernel's measured fraction of the peak (`eff` of a
+// batched kernel is the slope of its round time over K) plus a fixed part for filling the pipeline and
+// writing the tiles out: 6.4 us for 128 KB of output per CU (measured on the 256 x 256 fp16 kernel,
+// K/k = 2048 against K = 4096), taken proportional to the bytes a CU writes per round.
+double gemm_stage_seconds(const Variant &v, int R, const Geometry &g) {
+    const double peak = v.dtype == LCMA_F32 ? 157.3e12 : 2516.6e12, slots = 256.0 * v.occ;
+    const double tiles = (double)(g.bm / v.TM) * (double)(g.bn / v.TN);
+    const double jobs = v.batch ? tiles * R : tiles, flops_per_job = 2.0 * v.TM * v.TN * (double)g.bk * (v.batch ? 1 : R);
+    const double t_round = slots * flops_per_job / (v.eff * peak) +
+                           (v.batch ? 6.4e-6 * (double)(v.TM * v.TN * dtype_size(v.dtype) * v.occ) / 131072.0 : 0.0);
+    const double full = std::floor(jobs / slots), rest = jobs - full * slots;
+    return (full + (rest > 0 ? ((v.occ > 1 && rest <= 256) ? 0.63 : 1.0) : 0.0)) * t_round;
+}
+
+// The stage kernel of the wanted kind with the smallest predicted time among those that divide the planes.
+const Variant *find_gemm(bool batch, int scheme_id, int dtype, int R, const Geometry &g) {
     const Variant *best = nullptr;
+    double best_t = 0.0;
     const char *force = std::getenv("LCMA_UNFUSED_VARIANT"); // ablation override
     for (int i = 0; i < kVariantCount; ++i) {
         const Variant &v = kVariants[i];
         if ((batch ? !v.batch : !v.left_planes) || v.scheme_id != scheme_id || v.dtype != dtype) continue;
         if (g.bm % v.TM || g.bn % v.TN || g.bk % v.TK) continue;
         if (force && !std::strcmp(force, v.name)) return &v;
-        if (!best || v.eff > best->eff || (v.eff == best->eff && v.TM * v.TN > best->TM * best->TN)) best = &v;
+        const double t = gemm_stage_seconds(v, R, g);
+        if (!best || t < best_t) {
+            best = &v;
+            best_t = t;
+        }
     }
     return best;
 }
+
+const double kLaunch = 4.0e-6; // seconds per launch
 
 } // namespace
 } // namespace lcma
@@ -67,6 +91,43 @@ using namespace lcma;
 extern "C" int64_t lcma_unfused_workspace_bytes(int64_t M, int64_t N, int64_t K, lcma_dtype dtype, const lcma_scheme *scheme) {
     if (!scheme || !dtype_size(dtype) || M <= 0 || N <= 0 || K <= 0) return -1;
     return geometry(*scheme, M, N, K, dtype).total();
+}
+
+// Algorithm 1 priced stage by stage: the three memory-bound kernels at the rates measured for the scheme, the
+// batched GEMM in rounds of work-groups.
+extern "C" double lcma_predict_unfused_seconds(int scheme_id, int64_t M, int64_t N, int64_t K, lcma_dtype dtype,
+                                               int combine_b_offline) {
+    const int es = dtype_size(dtype);
+    const lcma_scheme *s = builtin_scheme(scheme_id);
+    const StageKernel *sk = find_stage(scheme_id, dtype);
+    if (!es || !s || M <= 0 || N <= 0 || K <= 0 || !sk) return -1.0;
+    const Geometry g = geometry(*s, M, N, K, dtype);
+    const Variant *gemm = find_gemm(true, LCMA_PLAIN, dtype == LCMA_F32 ? LCMA_F32 : LCMA_F16, s->R, g);
+    if (!gemm) return -1.0;
+    const double R = s->R, dM = (double)M, dN = (double)N, dK = (double)K;
+    const double at = R * g.bm * g.bk, bt = R * g.bn * g.bk, h = R * g.bm * g.bn; // elements of the planes
+    double t = (dM * dK + at) * es / sk->rate_a + kLaunch;
+    if (!combine_b_offline) t += (dK * dN + bt) * es / sk->rate_b + kLaunch;
+    t += gemm_stage_seconds(*gemm, s->R, g) + kLaunch;
+    t += (h + dM * dN) * es / sk->rate_h + kLaunch;
+    return t;
+}
+
+extern "C" lcma_status lcma_select_dataflow(int64_t M, int64_t N, int64_t K, lcma_dtype dtype, int combine_b_offline,
+                                            lcma_choice *out) {
+    if (!out) return fail(LCMA_ERR_ARG, "lcma_select_dataflow: null output");
+    if (!dtype_size(dtype)) return fail(LCMA_ERR_DTYPE, "lcma_select_dataflow: unknown dtype %d", (int)dtype);
+    if (M <= 0 || N <= 0 || K <= 0) return fail(LCMA_ERR_ARG, "lcma_select_dataflow: bad shape");
+    out->scheme_id = LCMA_PLAIN;
+    out->dataflow = 0;
+    out->seconds = lcma_predict_seconds(LCMA_PLAIN, M, N, K, dtype);
+    for (int id = LCMA_STRASSEN; id <= LCMA_LADERMAN; ++id) {
+        const double fused = lcma_predict_seconds(id, M, N, K, dtype);
+        const double unfused = lcma_predict_unfused_seconds(id, M, N, K, dtype, combine_b_offline);
+        if (fused > 0.0 && (out->seconds <= 0.0 || fused < out->seconds)) *out = lcma_choice{id, 0, fused};
+        if (unfused > 0.0 && (out->seconds <= 0.0 || unfused < out->seconds)) *out = lcma_choice{id, 1, unfused};
+    }
+    return LCMA_OK;
 }
 
 extern "C" lcma_status lcma_gemm_unfused(int level, int64_t M, int64_t N, int64_t K, const void *A, int64_t lda,
@@ -110,7 +171,7 @@ extern "C" lcma_status lcma_gemm_unfused(int level, int64_t M, int64_t N, int64_
     char *At = (char *)workspace, *Bt = At + g.at_bytes, *H = Bt + g.bt_bytes;
     // the products are multiplied in fp16 for both 16-bit storage types
     const int ct = dtype == LCMA_F32 ? LCMA_F32 : LCMA_F16;
-    const Variant *gemm = level == 1 ? find_gemm(true, LCMA_PLAIN, ct, g) : find_gemm(false, id, dtype, g);
+    const Variant *gemm = level == 1 ? find_gemm(true, LCMA_PLAIN, ct, scheme->R, g) : find_gemm(false, id, dtype, scheme->R, g);
     if (!gemm) return fail(LCMA_ERR_NOKERNEL, "%s: no GEMM stage kernel for level %d fits the planes", who, level);
 
     // stage 1: Combine A (Eq. 3).  A takes the place of an N x K weight matrix in the Combine-B kernel

@@ -410,9 +410,10 @@ def emit_registry(schemes: dict[str, Scheme], variants: list[Variant]) -> str:
     stages = stage_kernels(variants)
     L.append("const StageKernel kStageKernels[] = {")
     for sch, dt in stages:
-        L.append(f"    {{{SCHEME_IDS[sch]}, {DTYPE_IDS[dt]}, lcma_launch_comb_a_{sch}_{dt}, lcma_launch_comb_h_{sch}_{dt}}},")
+        ra, rb, rh = STAGE_RATES.get((sch, dt != "f32"), (4.0e12, 3.0e12, 5.0e12))
+        L.append(f"    {{{SCHEME_IDS[sch]}, {DTYPE_IDS[dt]}, lcma_launch_comb_a_{sch}_{dt}, lcma_launch_comb_h_{sch}_{dt}, {ra}, {rb}, {rh}}},")
     if not stages:
-        L.append("    {0, 0, nullptr, nullptr},")
+        L.append("    {0, 0, nullptr, nullptr, 0.0, 0.0, 0.0},")
     L += ["};", f"const int kStageKernelCount = {len(stages)};", "} // namespace lcma", ""]
     for sch, dt in stages:
         L.insert(3, f'extern "C" int lcma_launch_comb_a_{sch}_{dt}(const lcma::PrepParams *p, int gx, int gy, void *stream);')
@@ -426,6 +427,15 @@ def emit_registry(schemes: dict[str, Scheme], variants: list[Variant]) -> str:
 def prep_kernels(variants: list[Variant]) -> list[tuple[str, str]]:
     """(scheme, dtype) pairs that need an offline Combine-B kernel: those with a prepared-B GEMM kernel."""
     return sorted({(v.scheme, v.dtype) for v in variants if v.pb})
+
+
+# Measured rates of the stand-alone Combine-A / Combine-B / Combine-H kernels (algorithmic bytes per second at LLM
+# sizes on MI355X, rocprofv3), per scheme and element size; used by the cost model of the unfused dataflow.
+STAGE_RATES = {  # (scheme, 16-bit?) -> (Combine A, Combine B, Combine H)
+    ("strassen", True): (4.9e12, 3.5e12, 5.3e12), ("strassen", False): (5.0e12, 4.5e12, 5.8e12),
+    ("laderman", True): (5.5e12, 3.1e12, 5.0e12), ("laderman", False): (5.0e12, 3.0e12, 5.0e12),
+    ("strassen2", True): (1.7e12, 1.1e12, 4.4e12), ("strassen2", False): (3.5e12, 3.0e12, 5.6e12),
+}
 
 
 def stage_kernels(variants: list[Variant]) -> list[tuple[str, str]]:
@@ -681,8 +691,9 @@ def manifest(schemes: dict[str, Scheme] | None = None) -> list[Variant]:
     # Algorithm 2 as printed: a GEMM + Combine-H kernel that takes both operands from planes ("ab").
     for dt in ("f16", "f32"):
         tk = 64 if dt == "f16" else 16
-        V += [Variant("plain", dt, 256, 256 if dt == "f16" else 128, tk, wgm=2, wgn=4, tb=1, batch=1, rank=95),
-              Variant("plain", dt, 128, 128, tk, occ=2, tb=1, batch=1, rank=95)]
+        V += [Variant("plain", dt, 256, 256 if dt == "f16" else 128, tk, wgm=2, wgn=4, tb=1, batch=1, rank=95,
+                      eff=0.477 if dt == "f16" else 0.88),
+              Variant("plain", dt, 128, 128, tk, occ=2, tb=1, batch=1, rank=95, eff=0.35 if dt == "f16" else 0.86)]
     for dt in ("bf16", "f16", "f32"):
         tk = 16 if dt == "f32" else 32
         V += [Variant("strassen", dt, 64, 64, tk, chunk=7, pa=1, pb=1, rank=95),

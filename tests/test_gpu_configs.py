@@ -122,3 +122,51 @@ def test_selector_pick_is_close_to_the_measured_best():
         print(f"{dt} {M}x{N}x{K}: pick {B.SCHEME_NAMES[pick]}, measured TFLOP/s {tf}", flush=True)
         assert pick in times
         assert times[pick] <= 1.12 * times[best], (dt, M, N, K, B.SCHEME_NAMES[pick], B.SCHEME_NAMES[best])
+
+
+def test_dataflow_choice_is_close_to_the_measured_best():
+    """lcma_select_dataflow against the clock: plain, the fused kernels and Algorithm 1 (Combine B offline) of the
+    paper's schemes, all timed in this run; the choice must be within 12 % of the fastest."""
+    import torch
+    from paper_2605_06057_amd import binding as B
+
+    def seconds(fn, iters=16, warm=8):
+        for _ in range(warm):
+            fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(iters):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / iters * 1e-3
+
+    names = {0: "plain", 1: "strassen", 2: "strassen2", 3: "laderman"}
+    handles = {i: (B.lcma_scheme_load("builtin:" + n) if i else None) for i, n in names.items()}
+    heat = torch.randn(4096, 4096, device="cuda", dtype=torch.bfloat16)
+    for _ in range(300):  # settle the clocks
+        torch.mm(heat, heat)
+    for dt, M, N, K in (("bf16", 2048, 4096, 14336), ("bf16", 8192, 4096, 4096), ("f16", 3072, 3072, 3072), ("f32", 2048, 2048, 2048)):
+        td = {"bf16": torch.bfloat16, "f16": torch.float16, "f32": torch.float32}[dt]
+        a = torch.randn(M, K, device="cuda").to(td)
+        b = (torch.randn(K, N, device="cuda") * 0.05).to(td)
+        c = torch.empty(M, N, device="cuda", dtype=td)
+        times = {}
+        for i, h in handles.items():
+            try:
+                times[(i, 0)] = seconds(lambda: B.lcma_gemm(a, b, c, h))
+            except B.LcmaError:
+                pass
+            if i and B.lcma_predict_unfused_seconds(i, M, N, K, B.DTYPE_IDS[dt], True) > 0:
+                ws = torch.empty((B.lcma_unfused_workspace_bytes(h, M, N, K, B.DTYPE_IDS[dt]),), dtype=torch.uint8, device="cuda")
+                B.lcma_gemm_unfused(1, a, b, c, h, ws)
+                times[(i, 1)] = seconds(lambda: B.lcma_gemm_unfused(1, a, b, c, h, ws, reuse_bt=True))
+                del ws
+        ch = B.lcma_select_dataflow(M, N, K, B.DTYPE_IDS[dt], True)
+        pick = (ch["scheme_id"], ch["dataflow"])
+        best = min(times, key=times.get)
+        tf = {f"{names[i]}/{'alg1' if d else 'fused'}": round(2.0 * M * N * K / t / 1e12, 1) for (i, d), t in times.items()}
+        print(f"{dt} {M}x{N}x{K}: choice {names[pick[0]]}/{'alg1' if pick[1] else 'fused'}, measured TFLOP/s {tf}", flush=True)
+        assert pick in times
+        assert times[pick] <= 1.12 * times[best], (dt, M, N, K, pick, best)

@@ -292,3 +292,36 @@ def test_weight_layout_and_unfused_host_side(B):
     assert unfused(K=252, lda=256) == B.LCMA_ERR_SHAPE
     assert unfused(K=0) == B.LCMA_ERR_SHAPE
     assert unfused(M=0) == B.LCMA_OK                            # nothing to write
+
+
+def test_selector_over_both_dataflows(B):
+    """lcma_select_dataflow and the Algorithm 1 cost model: pure host arithmetic."""
+    bf16, f32 = B.LCMA_BF16, B.LCMA_F32
+    # large LLM shapes, 16-bit: the plain GEMM; fp32: the fused Strassen kernel
+    assert B.lcma_select_dataflow(8192, 14336, 4096, bf16, True) == {"scheme_id": 0, "dataflow": 0,
+                                                                    "seconds": B.lcma_predict_seconds(0, 8192, 14336, 4096, bf16)}
+    c = B.lcma_select_dataflow(4096, 4096, 4096, f32)
+    assert (c["scheme_id"], c["dataflow"]) == (B.LCMA_STRASSEN, 0)
+    # few rows, long K, static weights: the plain kernel has half a round of tiles, Algorithm 1 seven times as many jobs
+    c = B.lcma_select_dataflow(2048, 4096, 14336, bf16, True)
+    assert (c["scheme_id"], c["dataflow"]) == (B.LCMA_STRASSEN, 1)
+    assert c["seconds"] == B.lcma_predict_unfused_seconds(B.LCMA_STRASSEN, 2048, 4096, 14336, bf16, True)
+    # Combine B per call costs what its bytes cost
+    on = B.lcma_predict_unfused_seconds(1, 8192, 14336, 4096, bf16, False)
+    off = B.lcma_predict_unfused_seconds(1, 8192, 14336, 4096, bf16, True)
+    assert abs((on - off) - ((4096 * 14336 + 7 * 7168 * 2048) * 2 / 3.5e12 + 4e-6)) < 1e-9
+    # the stage sum: Combine A + batched GEMM + Combine H, three launches
+    g = 13 * (256 * 2.0 * 256 * 256 * 2048 / (0.477 * 2516.6e12) + 6.4e-6)   # 3136 tiles of 256 x 256 on 256 CUs: 13 rounds
+    want = (8192 * 4096 + 7 * 4096 * 2048) * 2 / 4.9e12 + g + (7 * 4096 * 7168 + 8192 * 14336) * 2 / 5.3e12 + 3 * 4e-6
+    assert abs(off - want) < 1e-9 * want + 1e-12
+    # no stage kernels: plain, further schemes, unknown ids
+    ids = {n: i for i, n in B.SCHEME_NAMES.items()}
+    for sid in (0, ids["strassen_wide"], 99):
+        assert B.lcma_predict_unfused_seconds(sid, 4096, 4096, 4096, bf16) < 0
+    assert B.lcma_predict_unfused_seconds(1, 0, 4096, 4096, bf16) < 0
+    L = B.lib()
+    assert L.lcma_select_dataflow(4096, 4096, 4096, 17, 0, None) == B.LCMA_ERR_ARG
+    import ctypes
+    out = B.lcma_choice()
+    assert L.lcma_select_dataflow(4096, 4096, 4096, 17, 0, ctypes.byref(out)) == B.LCMA_ERR_DTYPE
+    assert L.lcma_select_dataflow(0, 4096, 4096, bf16, 0, ctypes.byref(out)) == B.LCMA_ERR_ARG
