@@ -106,6 +106,17 @@ lcma_status lcma_gemm_nt(int64_t M, int64_t N, int64_t K,
                          void *C, int64_t ldc, lcma_dtype dtype,
                          const lcma_scheme *scheme, void *stream);
 
+/* lcma_gemm with the usual scaling of a GEMM interface (Eq. 1 has none): C = alpha * (A B) + beta * C, formed in
+ * fp32 from the accumulators (after the W-combination of Eq. 6) and rounded once.  C is read only when beta != 0,
+ * so it may then not hold NaN or Inf where a finite result is wanted; with beta == 0 its old contents are
+ * ignored.  b_layout 0: B given K x N as in lcma_gemm; 2: W given N x K as in lcma_gemm_nt.  alpha = 1, beta = 0
+ * gives the result of those calls bit for bit.  Everything else (sizes, alignment, errors) as for lcma_gemm;
+ * ARG for another b_layout or a NaN factor. */
+lcma_status lcma_gemm_ex(float alpha, float beta, int b_layout, int64_t M, int64_t N, int64_t K,
+                         const void *A, int64_t lda, const void *B, int64_t ldb,
+                         void *C, int64_t ldc, lcma_dtype dtype,
+                         const lcma_scheme *scheme, void *stream);
+
 /* Generated kernels ("variants": one per scheme x dtype x tile shape x dataflow, Sec. 3.1
  * Automated Code Generation).  lcma_gemm picks the preferred variant that fits the shape;
  * lcma_gemm_variant runs the named one (same contract as lcma_gemm; the scheme is the one

@@ -29,7 +29,7 @@ EXPORTS = [
     "lcma_sched_waves", "lcma_sched_range", "lcma_status_str", "lcma_last_error",
     "lcma_scheme_name", "lcma_scheme_id_max", "lcma_variant_prepared", "lcma_prepared_b_bytes", "lcma_prepare_b", "lcma_prepare_bt", "lcma_gemm_prepared",
     "lcma_gemm_nt", "lcma_variant_b_layout", "lcma_unfused_workspace_bytes", "lcma_gemm_unfused",
-    "lcma_predict_unfused_seconds", "lcma_select_dataflow",
+    "lcma_predict_unfused_seconds", "lcma_select_dataflow", "lcma_gemm_ex",
 ]
 
 
@@ -74,6 +74,7 @@ def lib() -> ctypes.CDLL:
         L.lcma_scheme_coeffs.argtypes = [vp, vp, vp, vp]
         L.lcma_gemm.argtypes = [i64, i64, i64, vp, i64, vp, i64, vp, i64, i32, vp, vp]
         L.lcma_gemm_nt.argtypes = L.lcma_gemm.argtypes
+        L.lcma_gemm_ex.argtypes = [ctypes.c_float, ctypes.c_float, i32] + L.lcma_gemm.argtypes
         L.lcma_variant_b_layout.argtypes = [i32]
         L.lcma_unfused_workspace_bytes.argtypes = [i64, i64, i64, i32, vp]
         L.lcma_unfused_workspace_bytes.restype = i64
@@ -190,6 +191,14 @@ def lcma_gemm(A, B, C, scheme: Scheme | None = None):
     M, N, K, pa, lda, pb, ldb, pc, ldc, stream = _marshal(A, B, C)
     _check(lib().lcma_gemm(M, N, K, pa, lda, pb, ldb, pc, ldc, _dtype_of(A),
                            scheme.handle if scheme is not None else None, stream))
+    return C
+
+
+def lcma_gemm_ex(alpha: float, beta: float, A, B, C, scheme: Scheme | None = None, b_nk: bool = False):
+    """C = alpha * (A x B) + beta * C on the current stream; b_nk: the second operand is the N x K weight matrix."""
+    M, N, K, pa, lda, pb, ldb, pc, ldc, stream = _marshal(A, B, C, b_nk)
+    _check(lib().lcma_gemm_ex(alpha, beta, 2 if b_nk else 0, M, N, K, pa, lda, pb, ldb, pc, ldc, _dtype_of(A),
+                              scheme.handle if scheme is not None else None, stream))
     return C
 
 

@@ -54,7 +54,7 @@ static const Variant *find_variant(const char *name) {
 // B and ldb describe the K x N matrix; for a variant that takes the weight layout, the N x K matrix W;
 // for a prepared-B variant, the planes written by lcma_prepare_b (ldb is then ignored).
 static lcma_status run(const Variant &v, int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const void *B,
-                       int64_t ldb, void *C, int64_t ldc, void *stream) {
+                       int64_t ldb, void *C, int64_t ldc, void *stream, float alpha = 1.f, float beta = 0.f) {
     const int es = dtype_size(v.dtype);
     if (v.left_planes || v.batch)
         return fail(LCMA_ERR_ARG, "lcma_gemm: %s is a stage kernel of lcma_gemm_unfused and takes no matrices", v.name);
@@ -117,6 +117,8 @@ static lcma_status run(const Variant &v, int64_t M, int64_t N, int64_t K, const 
     p.ny = (int32_t)(bk / v.TK);
     p.n_row_b = (uint32_t)(N * es);
     p.k_row_b = (uint32_t)(K * es);
+    p.alpha = alpha;
+    p.beta = beta;
     {   // first byte column inside the last block column of A whose tile reaches past K
         const int64_t valid = K - (int64_t)(v.k - 1) * bk; // columns of the last block inside K (may be <= 0)
         const int64_t whole = valid <= 0 ? 0 : valid / v.TK * v.TK;
@@ -138,7 +140,8 @@ static lcma_status run(const Variant &v, int64_t M, int64_t N, int64_t K, const 
 using namespace lcma;
 
 static lcma_status gemm(int b_nk, int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const void *B, int64_t ldb,
-                        void *C, int64_t ldc, lcma_dtype dtype, const lcma_scheme *scheme, void *stream) {
+                        void *C, int64_t ldc, lcma_dtype dtype, const lcma_scheme *scheme, void *stream, float alpha = 1.f,
+                        float beta = 0.f) {
     if (!dtype_size(dtype)) return fail(LCMA_ERR_DTYPE, "lcma_gemm: unknown dtype %d", (int)dtype);
     int id = LCMA_PLAIN;
     if (scheme) {
@@ -168,7 +171,16 @@ static lcma_status gemm(int b_nk, int64_t M, int64_t N, int64_t K, const void *A
         return fail(LCMA_ERR_SHAPE, "lcma_gemm: no kernel of scheme id %d takes N = %lld (whole 16-byte vectors) and K = %lld (whole tiles)",
                     id, (long long)N, (long long)K);
     }
-    return run(*v, M, N, K, A, lda, B, ldb, C, ldc, stream);
+    return run(*v, M, N, K, A, lda, B, ldb, C, ldc, stream, alpha, beta);
+}
+
+extern "C" lcma_status lcma_gemm_ex(float alpha, float beta, int b_layout, int64_t M, int64_t N, int64_t K, const void *A,
+                                    int64_t lda, const void *B, int64_t ldb, void *C, int64_t ldc, lcma_dtype dtype,
+                                    const lcma_scheme *scheme, void *stream) {
+    if (b_layout != 0 && b_layout != 2)
+        return fail(LCMA_ERR_ARG, "lcma_gemm_ex: b_layout must be 0 (B given K x N) or 2 (W given N x K)");
+    if (!(alpha == alpha) || !(beta == beta)) return fail(LCMA_ERR_ARG, "lcma_gemm_ex: alpha or beta is not a number");
+    return gemm(b_layout == 2, M, N, K, A, lda, B, ldb, C, ldc, dtype, scheme, stream, alpha, beta);
 }
 
 extern "C" lcma_status lcma_gemm(int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const void *B,

@@ -613,6 +613,30 @@ template <class T> struct Ctx {
         }
     }
 
+    // alpha * acc + beta * (the element of C at byte offset off + soff), in fp32.  C is read only when beta is
+    // not zero (uniform over the launch), with one small load per element in the accumulator layout: the general
+    // scaling is a convenience, not a fast path.
+    LCMA_DEV float scaled(float acc, uint32_t off, uint32_t soff) const {
+        float o = p.alpha * acc;
+        if (p.beta != 0.f) {
+            float old;
+            if constexpr (T::ES == 2) {
+                const uint32_t bits = (uint16_t)__builtin_amdgcn_raw_buffer_load_b16(rc, (int)off, (int)soff, 0);
+                if constexpr (std::is_same_v<IN, BF16>) old = __builtin_bit_cast(float, bits << 16);
+                else old = (float)__builtin_bit_cast(_Float16, (uint16_t)bits);
+            } else {
+                old = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rc, (int)off, (int)soff, 0));
+            }
+            o = __builtin_fmaf(p.beta, old, o);
+        }
+        return o;
+    }
+    // Byte offset (without soff) of accumulator value v of MFMA tile (mi, ni) of this lane; past N: the end of the extent.
+    LCMA_DEV uint32_t elem_off(int j, int mi, int ni, int v) const {
+        const uint32_t base = ((uint32_t)j * p.c_bcol + c_colb + ni * 32 * T::ES < p.n_row_b) ? c_voff : p.c_bytes;
+        return base + (uint32_t)(mi * 32 + (v >> 2) * 8 + (v & 3)) * p.ldc_b + ni * 32 * T::ES;
+    }
+
     // Round and store one fp32 tile into block C_{i,j}.  f(mi, ni) returns the f32x16 of MFMA
     // tile (mi, ni).
     //
@@ -639,7 +663,7 @@ template <class T> struct Ctx {
 #pragma unroll
                     for (int v = 0; v < 16; ++v)
                         *(LCMA_LDS uint16_t *)(strip + ((v >> 2) * 8 + 4 * lh + (v & 3)) * PITCH + (ni * 32 + l32) * 2) =
-                            (uint16_t)Round<IN>::run(t[v]);
+                            (uint16_t)Round<IN>::run(scaled(t[v], elem_off(j, mi, ni, v), soff));
                 }
                 __syncthreads();
 #pragma unroll
@@ -667,13 +691,11 @@ template <class T> struct Ctx {
 #pragma unroll
             for (int ni = 0; ni < T::NNI; ++ni) {
                 const f32x16 t = f(mi, ni);
-                // a lane whose column lies past N stores to the end of the extent: dropped
-                const uint32_t base = ((uint32_t)j * p.c_bcol + c_colb + ni * 32 * T::ES < p.n_row_b) ? c_voff : p.c_bytes;
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
-                    const uint32_t off =
-                        base + (uint32_t)(mi * 32 + (v >> 2) * 8 + (v & 3)) * p.ldc_b + ni * 32 * T::ES;
-                    const uint32_t bits = Round<IN>::run(t[v]);
+                    // a lane whose column lies past N stores to the end of the extent: dropped
+                    const uint32_t off = elem_off(j, mi, ni, v);
+                    const uint32_t bits = Round<IN>::run(scaled(t[v], off, soff));
                     if constexpr (T::ES == 2)
                         __builtin_amdgcn_raw_buffer_store_b16((short)bits, rc, (int)off, (int)soff, 0);
                     else

@@ -29,6 +29,7 @@ struct Params {
     uint32_t k_row_b;                   // K * element size: columns of A at or beyond it are padding (read as 0)
     uint32_t k_tail_b;                  // byte column inside a block from which the LAST block column of A may
                                         // run past K: K*ES - (k-1)*a_bcol, rounded down to whole tiles
+    float alpha = 1.f, beta = 0.f;      // C = alpha * (A B) + beta * C, in fp32 before the one rounding; C is read only when beta != 0
 };
 
 // Argument block of the offline Combine-B kernels.

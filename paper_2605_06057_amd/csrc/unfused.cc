@@ -202,6 +202,7 @@ extern "C" lcma_status lcma_gemm_unfused(int level, int64_t M, int64_t N, int64_
     }
     Params p;
     std::memset(&p, 0, sizeof p);
+    p.alpha = 1.f;
     p.A = At;
     p.B = Bt;
     p.a_bytes = (uint32_t)((int64_t)R * g.bm * g.bk * es);
