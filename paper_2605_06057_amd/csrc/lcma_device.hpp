@@ -310,8 +310,14 @@ template <class T> struct Ctx {
         if (id < (per << 3)) id = (id & 7) * per + (id >> 3);
         int plane = 0;
         if constexpr (T::BATCH) {
-            plane = id / tiles;
-            id -= plane * tiles;
+            if (p.batch_order == 0) {
+                plane = id / tiles;
+                id -= plane * tiles;
+            } else {
+                const int R = total / tiles;
+                plane = id % R;
+                id /= R;
+            }
         }
         const int pw = p.panel;
         const int full = (p.nz / pw) * pw * p.nx; // tiles inside full-width panels

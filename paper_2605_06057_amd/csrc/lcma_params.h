@@ -29,6 +29,9 @@ struct Params {
     uint32_t k_row_b;                   // K * element size: columns of A at or beyond it are padding (read as 0)
     uint32_t k_tail_b;                  // byte column inside a block from which the LAST block column of A may
                                         // run past K: K*ES - (k-1)*a_bcol, rounded down to whole tiles
+    int32_t batch_order = 0;            // batched kernels: 0 = product-major (all tiles of product r, then r + 1: concurrent
+                                        // work-groups share r, the paper's Cache-Aware order), 1 = group-major (the R products
+                                        // of a tile position next to each other), kept to measure the difference
     float alpha = 1.f, beta = 0.f;      // C = alpha * (A B) + beta * C, in fp32 before the one rounding; C is read only when beta != 0
 };
 

@@ -219,6 +219,7 @@ extern "C" lcma_status lcma_gemm_unfused(int level, int64_t M, int64_t N, int64_
     if (const char *e = std::getenv("LCMA_PANEL")) panel = std::atoi(e);
     if (panel < 1) panel = 1;
     p.panel = panel < p.nz ? panel : p.nz;
+    if (const char *e = std::getenv("LCMA_BATCH_ORDER")) p.batch_order = std::atoi(e) != 0; // ablation: 1 = group-major
     if (level == 1) {
         // stage 3: the R products H_r = At_r x Bt_r as one batched launch of the plain kernel
         p.C = H;
