@@ -246,6 +246,15 @@ lcma_status lcma_model_intensity(const lcma_scheme *s, int64_t M, int64_t N, int
  * negative value when no variant fits the shape. */
 double lcma_predict_seconds(int scheme_id, int64_t M, int64_t N, int64_t K, lcma_dtype dtype);
 
+/* ------------------------------------------------------------------ environment variables (measurement aids)
+ * Read at every call; none changes a result.
+ *   LCMA_VARIANT=<name>          lcma_gemm / lcma_gemm_prepared run this generated kernel when it belongs to the
+ *                                requested scheme, dtype and layout (otherwise ignored)
+ *   LCMA_UNFUSED_VARIANT=<name>  the same for the GEMM stage of lcma_gemm_unfused
+ *   LCMA_PANEL=<n>               width, in tiles, of the column panels of the tile order (default 8)
+ *   LCMA_BATCH_ORDER=1           batched GEMM of lcma_gemm_unfused level 1 in group-major instead of product-major order
+ */
+
 /* ------------------------------------------------------------------ tile scheduling (Sec. 3.2, Split-Group Parallelism)
  * Wave counts for `groups` groups of R tile-products on `units` compute units:
  * tile-level scheduling needs ceil(groups*R/units) waves, group-level ceil(groups/units)*R.
