@@ -146,7 +146,9 @@ struct Tile {
     static constexpr int PIPE = PIPE_, FC = FC_, PB = PB_, DL = DL_, TB = TB_, PA = PA_, BATCH = BATCH_;
     static_assert(!PA_ || (PB_ && !FC_), "ready-made left operands: staged loop, both sides from planes");
     static_assert(!TB_ || !PB_, "a prepared operand has one layout only");
-    static_assert(!DL_ || PB_, "direct loads need an operand that goes to LDS untouched on both sides");
+    static_assert(!DL_ || PB_ || (TB_ && FC_ && PIPE_ == 2 && STAGES_ == 3 && std::is_same_v<IN_, CT_>),
+                  "direct loads need operands that go to LDS untouched on both sides: prepared B, or k-contiguous B "
+                  "in a storage type that is multiplied as it is (three stages, fragment-combine loop)");
     static_assert(!PB_ || (FC_ && PIPE_ == 2 && STAGES_ == 2) || (!FC_ && PIPE_ == 0),
                   "prepared B: the interleaved fragment-combine loop or the staged loop");
     using IN = IN_;
@@ -476,6 +478,33 @@ template <class T> struct Ctx {
 #pragma unroll
             for (int t = 0; t < CH::NB; ++t) f.b[buf][ni][t] = lds_frag(sb + t * T::B_SLOT + b_frag[kk] + ni * 32 * T::ROW);
     }
+    // The same with the stage given as a pointer: a caller that holds the stage it reads and the stage it
+    // fills as two restrict-qualified pointers lets the compiler see that direct loads into the one never
+    // alias fragment reads from the other (without that it waits for every direct load in flight before
+    // each LDS read that follows one).
+    template <class CH> LCMA_DEV void fetch_frags_at(Frags<CH> &f, const LCMA_LDS char *base, int kk, int buf) const {
+#pragma unroll
+        for (int mi = 0; mi < T::NMI; ++mi)
+#pragma unroll
+            for (int t = 0; t < CH::NA; ++t)
+                f.a[buf][mi][t] = __builtin_bit_cast(Frag, *(const LCMA_LDS u32x4 *)(base + t * T::A_SLOT + a_frag[kk] + mi * 32 * T::ROW));
+#pragma unroll
+        for (int ni = 0; ni < T::NNI; ++ni)
+#pragma unroll
+            for (int t = 0; t < CH::NB; ++t)
+                f.b[buf][ni][t] = __builtin_bit_cast(Frag, *(const LCMA_LDS u32x4 *)(base + t * T::B_SLOT + b_frag[kk] + ni * 32 * T::ROW));
+    }
+    template <class CH, class HOOK>
+    LCMA_DEV void mma_stage_fc_at(const LCMA_LDS char *base, typename T::Acc (&acc)[CH::NP], HOOK hook) const {
+        Frags<CH> f;
+        fetch_frags_at<CH>(f, base, 0, 0);
+#pragma unroll
+        for (int kk = 0; kk < T::NKK; ++kk) {
+            const int cur = kk & 1;
+            if (kk + 1 < T::NKK) fetch_frags_at<CH>(f, base, kk + 1, cur ^ 1);
+            combine_and_multiply<CH>(f, cur, kk, acc, hook);
+        }
+    }
     template <class CH> LCMA_DEV void mma_stage_fc(int st, typename T::Acc (&acc)[CH::NP]) const {
         mma_stage_fc<CH>(st, acc, [](int, int) {});
     }
@@ -503,46 +532,53 @@ template <class T> struct Ctx {
                 fetch_frags<CH>(f, nst, 0, cur ^ 1);
                 __builtin_amdgcn_sched_barrier(0);
             }
-            // A few products at a time keeps few combined fragments live (the unused outputs of the
-            // generated combination code are dead and vanish).  With several MFMA instructions per
-            // fragment pair (fp32) two products advance together, so that back-to-back instructions
-            // never accumulate into the same tile.
-            constexpr int G = (Mma<CT>::SUB > 1 && T::NMI * T::NNI == 1) ? LCMA_FP32_GROUP : 1;
+            combine_and_multiply<CH>(f, cur, kk, acc, hook);
+        }
+    }
+
+    // One k sub-step of the fragment-combine loop: form the operand fragments of every product from the raw
+    // fragments in buffer `cur` and multiply.
+    template <class CH, class HOOK>
+    LCMA_DEV void combine_and_multiply(Frags<CH> &f, int cur, int kk, typename T::Acc (&acc)[CH::NP], HOOK hook) const {
+        // A few products at a time keeps few combined fragments live (the unused outputs of the
+        // generated combination code are dead and vanish).  With several MFMA instructions per
+        // fragment pair (fp32) two products advance together, so that back-to-back instructions
+        // never accumulate into the same tile.
+        constexpr int G = (Mma<CT>::SUB > 1 && T::NMI * T::NNI == 1) ? LCMA_FP32_GROUP : 1;
 #pragma unroll
-            for (int s0 = 0; s0 < CH::NP; s0 += G) {
-                Frag at[G][T::NMI], bt[G][T::NNI];
+        for (int s0 = 0; s0 < CH::NP; s0 += G) {
+            Frag at[G][T::NMI], bt[G][T::NNI];
+#pragma unroll
+            for (int g = 0; g < G; ++g) {
+                if (s0 + g >= CH::NP) continue;
+#pragma unroll
+                for (int mi = 0; mi < T::NMI; ++mi) {
+                    Frag o[CH::NP];
+                    CH::comb_a(f.a[cur][mi], o);
+                    at[g][mi] = o[s0 + g];
+                }
+#pragma unroll
+                for (int ni = 0; ni < T::NNI; ++ni) {
+                    Frag o[CH::NP];
+                    CH::comb_b(f.b[cur][ni], o);
+                    bt[g][ni] = o[s0 + g];
+                }
+            }
+            mfma_priority(true);
+#pragma unroll
+            for (int t = 0; t < Mma<CT>::SUB; ++t)
 #pragma unroll
                 for (int g = 0; g < G; ++g) {
                     if (s0 + g >= CH::NP) continue;
 #pragma unroll
-                    for (int mi = 0; mi < T::NMI; ++mi) {
-                        Frag o[CH::NP];
-                        CH::comb_a(f.a[cur][mi], o);
-                        at[g][mi] = o[s0 + g];
-                    }
+                    for (int mi = 0; mi < T::NMI; ++mi)
 #pragma unroll
-                    for (int ni = 0; ni < T::NNI; ++ni) {
-                        Frag o[CH::NP];
-                        CH::comb_b(f.b[cur][ni], o);
-                        bt[g][ni] = o[s0 + g];
-                    }
+                        for (int ni = 0; ni < T::NNI; ++ni)
+                            Mma<CT>::run_sub(at[g][mi], bt[g][ni], acc[s0 + g].v[mi][ni], t);
                 }
-                mfma_priority(true);
-#pragma unroll
-                for (int t = 0; t < Mma<CT>::SUB; ++t)
-#pragma unroll
-                    for (int g = 0; g < G; ++g) {
-                        if (s0 + g >= CH::NP) continue;
-#pragma unroll
-                        for (int mi = 0; mi < T::NMI; ++mi)
-#pragma unroll
-                            for (int ni = 0; ni < T::NNI; ++ni)
-                                Mma<CT>::run_sub(at[g][mi], bt[g][ni], acc[s0 + g].v[mi][ni], t);
-                    }
-                mfma_priority(false);
-                constexpr int NG = (CH::NP + G - 1) / G;
-                hook(kk * NG + s0 / G, T::NKK * NG);
-            }
+            mfma_priority(false);
+            constexpr int NG = (CH::NP + G - 1) / G;
+            hook(kk * NG + s0 / G, T::NKK * NG);
         }
     }
 
@@ -1001,7 +1037,7 @@ template <class T, class CH> struct FlatStage {
 // a side the waves past the end skip (wave-uniform).
 template <class T, class CH> struct DirectStage {
     static constexpr int NCHK_B = T::TN * T::CPR;
-    static constexpr int NCA = CH::NA * T::NCHK_A, NCB = CH::NP * NCHK_B;
+    static constexpr int NCA = CH::NA * T::NCHK_A, NCB = (T::PB ? CH::NP : CH::NB) * NCHK_B;
     static_assert(NCA % 64 == 0 && NCB % 64 == 0, "a wave instruction must not straddle the end of a side");
     static constexpr int QA = (NCA + T::NT - 1) / T::NT, QB = (NCB + T::NT - 1) / T::NT;
     static constexpr int NPIECE = QA + QB;
@@ -1025,10 +1061,21 @@ template <class T, class CH> struct DirectStage {
             const int pp = (q * T::NT + tid) % NCB;
             const int sl = pp / NCHK_B, id2 = pp % NCHK_B;
             const int row = id2 / T::CPR, cs = id2 % T::CPR;
-            b_voff[q] = (uint32_t)sl * cx.p.b_brow + (uint32_t)row * cx.p.ldb_b + T::swz(row, cs) * 16;
+            if constexpr (T::PB) {
+                b_voff[q] = (uint32_t)sl * cx.p.b_brow + (uint32_t)row * cx.p.ldb_b + T::swz(row, cs) * 16;
+            } else { // raw block sl of B given N x K; rows past N read from the end of the extent (zero)
+                b_voff[q] = (uint32_t)CH::b_l(sl) * cx.p.b_brow + (uint32_t)CH::b_j(sl) * cx.p.b_bcol +
+                            (uint32_t)row * cx.p.ldb_b + T::swz(row, cs) * 16;
+                if ((uint32_t)CH::b_j(sl) * cx.p.c_bcol + cx.n_group + (uint32_t)row * T::ES >= cx.p.n_row_b)
+                    b_voff[q] = cx.p.b_bytes;
+            }
         }
     }
     LCMA_DEV void issue_piece(const Ctx<T> &cx, int pc, int st, int y, bool guard) const {
+        issue_piece_at(cx, pc, cx.lds + st * T::STAGE, y, guard);
+    }
+    // `stage`: first byte of the LDS stage to fill
+    LCMA_DEV void issue_piece_at(const Ctx<T> &cx, int pc, LCMA_LDS char *stage, int y, bool guard) const {
         if (pc < QA) {
             const int first = pc * T::NT + wave_chunk;
             uint32_t vo = a_voff[pc];
@@ -1038,13 +1085,22 @@ template <class T, class CH> struct DirectStage {
                 vo = cx.a_inside(vo, (uint32_t)CH::a_l(t) * cx.p.a_bcol + (uint32_t)y * (T::TK * T::ES) + T::swz(row, cs) * 16);
             }
             if (first < NCA)
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(cx.ra, (LCMA_LDS void *)(cx.lds + st * T::STAGE + first * 16), 16,
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(cx.ra, (LCMA_LDS void *)(stage + first * 16), 16,
                                                          (int)vo, (int)(cx.a_group + (uint32_t)y * (T::TK * T::ES)), 0, 0);
         } else {
             const int q = pc - QA, first = q * T::NT + wave_chunk;
+            uint32_t vo = b_voff[q];
+            if constexpr (!T::PB) {
+                if (guard) { // past K a row of W goes on with padding or the next row
+                    const int pp = (q * T::NT + (int)threadIdx.x) % NCB;
+                    const int t = pp / NCHK_B, row = (pp % NCHK_B) / T::CPR, cs = (pp % NCHK_B) % T::CPR;
+                    if ((uint32_t)CH::b_l(t) * cx.p.b_brow + (uint32_t)y * (T::TK * T::ES) + T::swz(row, cs) * 16 >= cx.p.k_row_b)
+                        vo = cx.p.b_bytes;
+                }
+            }
             if (first < NCB)
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(
-                    cx.rb, (LCMA_LDS void *)(cx.lds + st * T::STAGE + T::A_STAGE + first * 16), 16, (int)b_voff[q],
+                    cx.rb, (LCMA_LDS void *)(stage + T::A_STAGE + first * 16), 16, (int)vo,
                     (int)(cx.b_group + (uint32_t)y * (T::TK * T::ES)), 0, 0);
         }
     }
@@ -1054,7 +1110,38 @@ template <class T, class CH> struct DirectStage {
     }
     // every direct load of this wave has landed in LDS
     static LCMA_DEV void landed() { __builtin_amdgcn_s_waitcnt(0x0F70); } // vmcnt(0)
+    // Work-group barrier that leaves the NEWEST direct loads of every wave in flight: each wave waits until all
+    // but its newest NEWEST loads have landed and its own LDS operations are done (vmcnt(NEWEST) lgkmcnt(0)), then
+    // the waves meet.  __syncthreads() cannot be used here: its fences order the LDS writes of the loads in flight
+    // as well, so the compiler makes every wave wait for all of them.  The empty asm statements keep the
+    // compiler from moving LDS accesses across the bare barrier instruction.
+    template <int NEWEST> static LCMA_DEV void barrier_keeping() {
+        static_assert(NEWEST >= 0 && NEWEST < 64, "vmcnt has six bits");
+        __builtin_amdgcn_s_waitcnt((NEWEST & 0xF) | 0x0070 | ((NEWEST >> 4) << 14));
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+    }
 };
+
+// One step of the direct-load loop: multiply out of the stage at `rd` while the tiles of step `nxt` travel
+// into the stage at `wr`, one work-group load instruction after each product group.  The two stages come in
+// as restrict-qualified pointers: that is what tells the compiler that the loads in flight do not touch what
+// the fragment reads read, so that it does not wait for them before every LDS read.
+template <class T, class CH, bool GUARD>
+LCMA_DEV void direct_load_step(const Ctx<T> &cx, const DirectStage<T, CH> &dl, const LCMA_LDS char *__restrict__ rd,
+                               LCMA_LDS char *__restrict__ wr, int nxt, typename T::Acc (&acc)[CH::NP]) {
+    using DS = DirectStage<T, CH>;
+    cx.template mma_stage_fc_at<CH>(rd, acc, [&](int slot, int slots) {
+#pragma unroll
+        for (int pc = 0; pc < DS::NPIECE; ++pc)
+            if (pc * slots / DS::NPIECE == slot) {
+                __builtin_amdgcn_sched_barrier(0);
+                dl.issue_piece_at(cx, pc, wr, nxt, GUARD);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+    });
+}
 
 template <class T, class CH> LCMA_DEV void mma_step(const Ctx<T> &cx, int st, typename T::Acc (&acc)[CH::NP]) {
     if constexpr (T::FC) cx.template mma_stage_fc<CH>(st, acc);
@@ -1114,6 +1201,41 @@ template <class T, class CH> LCMA_DEV void run_chunk(const Ctx<T> &cx, typename 
             const int ym = main_steps(cx, 1, 2);
             stage_loop<LITERAL_STAGE<T>>(0, ym, make_step(std::false_type{}));
             stage_loop<LITERAL_STAGE<T>>(ym, ny, make_step(std::true_type{}));
+            __syncthreads();
+        } else if constexpr (T::DL && T::TB) {
+            // Direct loads of both raw operands, three LDS stages: the tiles of step y+2 travel into stage
+            // (y+2)%3 while step y is multiplied out of stage y%3, a piece (one work-group load instruction)
+            // after each product group.  At the end of a step a wave waits only for its loads of step y+1:
+            // the newest batch stays in flight across the barrier, so a load has two steps to arrive.
+            using DS = DirectStage<T, CH>;
+            static_assert(DS::NCA % T::NT == 0 && DS::NCB % T::NT == 0, "every wave issues every piece, so that the count of loads in flight is known");
+            static_assert(T::NKK % 2 == 0, "fragment buffers must return to buffer 0 at the end of a step");
+            const DS dl(cx);
+            dl.issue(cx, 0, 0);
+            dl.issue(cx, 1, ny > 1 ? 1 : last);
+            DS::template barrier_keeping<DS::NPIECE>();
+            auto make_step = [&](auto guard) {
+                return [&](int y, int st) { // st = y % 3, a literal at every call site
+                    const int nxt = y + 2 < ny ? y + 2 : last; // past the end: the last tile again, unused
+                    direct_load_step<T, CH, decltype(guard)::value>(cx, dl, cx.lds + st * T::STAGE,
+                                                                    cx.lds + ((st + 2) % 3) * T::STAGE, nxt, acc);
+                    DS::template barrier_keeping<DS::NPIECE>();
+                };
+            };
+            auto loop3 = [&](int y0, int y1, auto step) { // y0 a multiple of 3
+                int y = y0;
+                for (; y + 2 < y1; y += 3) {
+                    step(y, 0);
+                    step(y + 1, 1);
+                    step(y + 2, 2);
+                }
+                if (y < y1) step(y, 0);
+                if (y + 1 < y1) step(y + 1, 1);
+            };
+            const int ym = main_steps(cx, 2, 3);
+            loop3(0, ym, make_step(std::false_type{}));
+            loop3(ym, ny, make_step(std::true_type{}));
+            DS::landed(); // the loads issued by the last steps must not land on the epilogue's use of LDS
             __syncthreads();
         } else if constexpr (T::DL) {
             // Direct loads: the tiles of step y+1 travel into the other stage while step y is multiplied;

@@ -674,6 +674,12 @@ def manifest(schemes: dict[str, Scheme] | None = None) -> list[Variant]:
         assert (sch.m * sch.n + 1) * 16 <= ACC_REG_BUDGET, f"{name}: {sch.m}x{sch.n} C tiles do not fit the registers"
         V += [Variant(name, "bf16", 64, 64, 32, chunk=1, eff=0.04), Variant(name, "f16", 64, 64, 32, chunk=1, eff=0.04),
               Variant(name, "f32", 64, 64, 16, chunk=1, eff=0.4)]
+    # Both raw operands straight into LDS by direct loads, three stages ("s3dt"): needs B given N x K and a storage
+    # type that is multiplied as it is.  fp16: +3% over the register-staged twin, chosen by lcma_gemm_nt; fp32: +1%
+    # over its twin but below the 64 x 64 kernel, kept by name.  (bf16 would have to be converted on the fragments:
+    # measured 626 against 764 TFLOP/s, not generated.)
+    V += [Variant("strassen", "f16", 128, 64, 32, chunk=7, fc=1, wgm=4, wgn=2, pipe=2, stages=3, dl=1, tb=1, eff=0.318),
+          Variant("strassen", "f32", 128, 64, 16, chunk=7, fc=1, wgm=4, wgn=2, pipe=2, stages=3, dl=1, tb=1, eff=0.847, rank=90)]
     # Winograd's form of Strassen's algorithm (a further scheme file): the fragment-combine kernels with the
     # common sums shared, 4 + 4 additions per fragment set instead of 5 + 5.  fp16 storage forms its 3- and
     # 4-term sums in fp32 (no sharing) and keeps the default r-loop kernel only.
@@ -704,7 +710,7 @@ def manifest(schemes: dict[str, Scheme] | None = None) -> list[Variant]:
     # Every kernel that lcma_gemm can pick for the paper's schemes also exists for B given as the N x K
     # weight matrix ("t"): its B tiles are staged like A's, with 16-byte loads and no transposition.
     from dataclasses import replace
-    V += [replace(v, tb=1, name="") for v in V if not v.pb and v.rank < 90 and SCHEME_IDS[v.scheme] <= 3]
+    V += [replace(v, tb=1, name="") for v in V if not v.pb and not v.tb and v.rank < 90 and SCHEME_IDS[v.scheme] <= 3]
     return [v.finish() for v in V]
 
 

@@ -268,7 +268,7 @@ def test_weight_layout_and_unfused_host_side(B):
     # every selectable kernel of the paper's schemes that takes B has a twin for the N x K layout
     names = {v["name"] for v in B.lcma_variants()}
     for v in B.lcma_variants():
-        if v["b_layout"] == 2:
+        if v["b_layout"] == 2 and not v["name"].endswith("dt"):   # the direct-load kernels exist for this layout only
             base = v["name"].replace("to2", "o2") if v["name"].endswith("to2") else v["name"][:-1]
             assert base in names, v["name"]
     # workspace of the unfused dataflows: At, Bt and H planes, blocks padded to 128 rows and 64 (fp32: 16) columns
