@@ -678,6 +678,9 @@ def manifest(schemes: dict[str, Scheme] | None = None) -> list[Variant]:
     # type that is multiplied as it is.  fp16: +3% over the register-staged twin, chosen by lcma_gemm_nt; fp32: +1%
     # over its twin but below the 64 x 64 kernel, kept by name.  (bf16 would have to be converted on the fragments:
     # measured 626 against 764 TFLOP/s, not generated.)
+    # the plain fp16 kernel the same way: +3% over the register-staged N x K kernel (batched over planes, for the
+    # GEMM stage of lcma_gemm_unfused, it measured +3% at 4096^3 and -1 to -3% at the larger shapes: not generated)
+    V += [Variant("plain", "f16", 256, 256, 32, wgm=2, wgn=4, fc=1, pipe=2, stages=3, dl=1, tb=1, eff=0.45)]
     V += [Variant("strassen", "f16", 128, 64, 32, chunk=7, fc=1, wgm=4, wgn=2, pipe=2, stages=3, dl=1, tb=1, eff=0.318),
           Variant("strassen", "f32", 128, 64, 16, chunk=7, fc=1, wgm=4, wgn=2, pipe=2, stages=3, dl=1, tb=1, eff=0.847, rank=90)]
     # Winograd's form of Strassen's algorithm (a further scheme file): the fragment-combine kernels with the
