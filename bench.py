@@ -3,8 +3,11 @@
 
 One "step" is one lcma_gemm call: the whole fused path (block split, operand combinations
 in LDS, grouped MFMA sub-GEMMs, W epilogue) over one pair of synthetic matrices that already
-sit in HBM.  The default workload is Strassen <2,2,2;7>, one level, bf16 inputs with fp32
-accumulation, M = N = K = 4096, A, B ~ N(0,1).
+sit in HBM.  The default workload is the largest LLM-shaped configuration: the FFN GEMM
+M = 8192 tokens, N = 14336, K = 4096, bf16 storage with fp32 accumulation, A ~ N(0,1),
+B ~ N(0, 0.02^2), Strassen <2,2,2;7> one level.  The other configurations (Strassen bf16 4096^3,
+two-level Strassen on the FFN shape, Laderman fp16 6144^3, Strassen fp32 4096^3) are timed the
+same way as further legs and reported in `other_workloads` of the same line.
 
 Prints ONE JSON line.  `value` is effective TFLOP/s = 2MNK / time (standard-GEMM flop count,
 paper Sec. 4.1 "Measurement"), so it can exceed what the MFMA units did.  Beside it: the same-build
@@ -122,6 +125,90 @@ def selector_sweep(args):
                       "worst_choice_vs_fastest": min(r["choice_vs_fastest"] for r in rows),
                       "sweep": rows}))
 
+def _timed(torch, step, steps, warmup, heat_seconds):
+    """(wall ms per step, mean and median ms per step by events on the launch stream) after an untimed spell of load
+    that settles the clocks (a cold MI355X needs some milliseconds of load to get there) and `warmup` steps."""
+    t_heat = time.perf_counter()
+    while time.perf_counter() - t_heat < heat_seconds:
+        for i in range(10):
+            step(i)
+        torch.cuda.synchronize()
+    for i in range(warmup):
+        step(i)
+    torch.cuda.synchronize()
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+    t0 = time.perf_counter()
+    ev[0].record()
+    for i in range(steps):
+        step(i)
+        ev[i + 1].record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    per = [ev[i].elapsed_time(ev[i + 1]) for i in range(steps)]
+    return wall / steps * 1e3, sum(per) / steps, sorted(per)[steps // 2]
+
+
+def sampled_rows(np, M, m, per_block=8):
+    """`per_block` rows inside every block row of the scheme grid (first, last, tile edges and a few others)."""
+    bm = M // m
+    inside = np.array([0, 1, 63, 64, 127, bm // 2 + 5, bm // 3, bm - 1][:per_block]) % bm
+    return np.unique(np.concatenate([inside + i * bm for i in range(m)]))
+
+
+def side_workload(name, args):
+    """One further configuration: lcma_gemm (default kernel choice), the plain and the vendor GEMM timed the same way
+    as the main workload on fewer steps, and parity with the oracle on sampled rows."""
+    import numpy as np
+    import torch
+
+    import lcma_inputs as inp
+    from paper_2605_06057_amd import binding as B
+    scheme_name, dt, M, N, K, kind_a, kind_b, seed = WORKLOADS[name]
+    As, Bs = inp.matrices(kind_a, kind_b, M, N, K, dt, seed)
+
+    def dev(x):
+        if dt == "bf16":
+            return torch.from_numpy(x.view(np.int16)).cuda().view(torch.bfloat16)
+        return torch.from_numpy(x).cuda()
+    sets = []
+    for i in range(3):
+        a, b = dev(As), dev(Bs)
+        sets.append((a, b, torch.empty((M, N), dtype=a.dtype, device="cuda")))
+    scheme = B.lcma_scheme_load("builtin:" + scheme_name)
+    info = B.lcma_scheme_info(scheme)
+    steps, warmup = max(20, args.steps // 4), max(5, args.warmup // 2)
+    flops = 2.0 * M * N * K
+    wall, ev, _ = _timed(torch, lambda i: B.lcma_gemm(*sets[i % 3], scheme), steps, warmup, args.heat_seconds)
+    p_wall, _, _ = _timed(torch, lambda i: B.lcma_gemm(*sets[i % 3], None), steps, warmup, args.heat_seconds)
+    v_wall, _, _ = _timed(torch, lambda i: torch.mm(sets[i % 3][0], sets[i % 3][1], out=sets[i % 3][2]), max(10, steps // 2), 3, args.heat_seconds)
+    peak = PEAK_TFLOPS[dt]
+    value = flops / (wall * 1e-3) / 1e12
+    mfma_flops = flops * info["R"] / (info["m"] * info["k"] * info["n"])
+    out = {"config": f"{scheme_name} <{info['m']},{info['k']},{info['n']};{info['R']}>, {dt} storage, M={M} N={N} K={K}, A {kind_a}, B {kind_b}",
+           "value": value, "unit": "TFLOP/s", "ms_per_step": wall, "steps": steps, "frac_of_dense_peak": value / peak,
+           "plain_mfma_gemm_tflops": flops / (p_wall * 1e-3) / 1e12, "vs_plain": p_wall / wall,
+           "vendor_gemm_tflops": flops / (v_wall * 1e-3) / 1e12,
+           "roofline": {"bound": "mfma", "achieved": mfma_flops / (ev * 1e-3) / 1e12, "peak": peak, "unit": "TFLOP/s",
+                        "frac": mfma_flops / (ev * 1e-3) / 1e12 / peak, "traffic": read_traffic(name)}}
+    if not args.no_cpu:
+        import oracle
+        rows = sampled_rows(np, M, info["m"])
+        B.lcma_gemm(*sets[0], scheme)
+        B.lcma_gemm(*sets[1], None)
+        torch.cuda.synchronize()
+        ref = oracle.gemm_rows(inp.widen(As, dt), inp.widen(Bs, dt), rows)
+
+        def host(t):
+            t = t[torch.from_numpy(rows).cuda()]
+            if dt == "bf16":
+                return inp.widen(t.contiguous().view(torch.int16).cpu().numpy().view(np.uint16), dt)
+            return t.cpu().numpy().astype(np.float64)
+        out["rel_frobenius_error"] = {"lcma": oracle.rel_frobenius(host(sets[0][2]), ref),
+                                      "plain": oracle.rel_frobenius(host(sets[1][2]), ref), "rows_checked": int(len(rows))}
+    del sets
+    torch.cuda.empty_cache()
+    return out
+
 
 def main():
     ap = argparse.ArgumentParser()
@@ -130,7 +217,10 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--heat-seconds", type=float, default=0.3,
                     help="untimed load before each timed leg, so that clocks are settled")
-    ap.add_argument("--workload", default="strassen_bf16_4096", choices=sorted(WORKLOADS))
+    ap.add_argument("--workload", default="strassen_bf16_ffn", choices=sorted(WORKLOADS))
+    ap.add_argument("--no-others", action="store_true",
+                    help="skip the further workloads (by default the other configurations are timed as well, about "
+                         "two seconds each, and reported in `other_workloads`)")
     ap.add_argument("--variant", default=None, help="time this generated kernel instead of the default choice")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
     ap.add_argument("--with-copy", action="store_true",
@@ -205,27 +295,7 @@ def main():
         torch.mm(a, b, out=c)
 
     def timed(step, steps, warmup):
-        # Untimed: keep the chip busy for a moment first, so that its clocks have settled where a
-        # long-running job holds them (a cold MI355X needs some milliseconds of load to get there),
-        # then the W warm-up steps.
-        t_heat = time.perf_counter()
-        while time.perf_counter() - t_heat < args.heat_seconds:
-            for i in range(10):
-                step(i)
-            torch.cuda.synchronize()
-        for i in range(warmup):
-            step(i)
-        torch.cuda.synchronize()
-        ev = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
-        t0 = time.perf_counter()
-        ev[0].record()
-        for i in range(steps):
-            step(i)
-            ev[i + 1].record()
-        torch.cuda.synchronize()
-        wall = time.perf_counter() - t0
-        per = [ev[i].elapsed_time(ev[i + 1]) for i in range(steps)]  # ms, on the launch stream
-        return wall / steps * 1e3, sum(per) / steps, sorted(per)[steps // 2]
+        return _timed(torch, step, steps, warmup, args.heat_seconds)
 
     if args.with_copy:
         dst = torch.empty_like(sets[0][0])
@@ -310,9 +380,7 @@ def main():
     lcma_step(0)
     plain_step(1)
     torch.cuda.synchronize()
-    rows_per_block = 4
-    rows = np.concatenate([np.arange(rows_per_block) * 37 % (M // info["m"]) + i * (M // info["m"])
-                           for i in range(info["m"])])
+    rows = sampled_rows(np, M, info["m"])
     cpu = None
     err = err_plain = None
     if not args.no_cpu:
@@ -377,6 +445,12 @@ def main():
         out["weight_layout_nk"] = nk
     if ablation:
         out["ablation_unfused_dataflows"] = ablation
+    if not args.no_others and not args.variant:
+        sets = bts = ws = None  # release the device buffers of the main workload
+        torch.cuda.empty_cache()
+        others = [w for w in ("strassen_bf16_4096", "strassen2_bf16_ffn", "laderman_f16_6144", "strassen_f32_4096",
+                              "strassen_bf16_ffn") if w != args.workload][:4]
+        out["other_workloads"] = {w: side_workload(w, args) for w in others}
     print(json.dumps(out))
 
 

@@ -12,7 +12,9 @@
  * General conventions
  *   - Matrices are row-major, never transposed; ld* are in ELEMENTS (not bytes).
  *   - A, B, C are DEVICE pointers owned by the caller; the library neither keeps nor
- *     frees them and they must not overlap.  C is overwritten (no alpha/beta).
+ *     frees them; C must not overlap A or B (checked: ARG).  lcma_gemm and lcma_gemm_nt overwrite C;
+ *     lcma_gemm_ex adds the usual alpha / beta scaling.  K = 0 is the empty product: C = beta * C, zeros for
+ *     the calls without beta.
  *   - Scheme handles and everything else are HOST objects.
  *   - No function aborts or throws; every failure is a status code, and
  *     lcma_last_error() returns a thread-local description of the latest one.
@@ -32,7 +34,7 @@ typedef enum {
     LCMA_ERR_IO = 2,       /* scheme file cannot be read                              */
     LCMA_ERR_PARSE = 3,    /* scheme text is malformed                                */
     LCMA_ERR_BRENT = 4,    /* coefficients do not multiply matrices                   */
-    LCMA_ERR_SHAPE = 5,    /* M, N, K not divisible by the scheme grid times the tile */
+    LCMA_ERR_SHAPE = 5,    /* N or K not a whole number of 16-byte vectors, or a matrix of 2 GiB or more */
     LCMA_ERR_DTYPE = 6,    /* unknown dtype                                           */
     LCMA_ERR_NOKERNEL = 7, /* no kernel was generated for this scheme / dtype         */
     LCMA_ERR_HIP = 8       /* the HIP runtime reported an error                       */
@@ -195,8 +197,9 @@ lcma_status lcma_gemm_prepared(int64_t M, int64_t N, int64_t K, const void *A, i
  * A, B, C, sizes, alignment, padding and errors as for lcma_gemm; `scheme` is required and must be
  * one of the paper's (NOKERNEL otherwise).  workspace: device memory, 256-byte aligned, at least
  * lcma_unfused_workspace_bytes() bytes (-1 for bad arguments), owned by the caller, overwritten.
- * reuse_bt != 0 skips Combine B: the Bt_r left in the workspace by an earlier call with the same B,
- * scheme, dtype and sizes are used (the paper's offline Combine B for static weights).
+ * reuse_bt != 0 skips Combine B: the Bt_r left in the workspace by an earlier call with the same B, scheme,
+ * dtype, N and K are used (the paper's offline Combine B for static weights).  The Bt_r planes lie at the start
+ * of the workspace and depend on N and K alone, so M may differ between such calls.
  * Asynchronous on `stream`; nothing is launched when an argument is rejected.
  */
 int64_t lcma_unfused_workspace_bytes(int64_t M, int64_t N, int64_t K, lcma_dtype dtype,
@@ -246,14 +249,18 @@ lcma_status lcma_model_intensity(const lcma_scheme *s, int64_t M, int64_t N, int
  * negative value when no variant fits the shape. */
 double lcma_predict_seconds(int scheme_id, int64_t M, int64_t N, int64_t K, lcma_dtype dtype);
 
-/* ------------------------------------------------------------------ environment variables (measurement aids)
- * Read at every call; none changes a result.
- *   LCMA_VARIANT=<name>          lcma_gemm / lcma_gemm_prepared run this generated kernel when it belongs to the
- *                                requested scheme, dtype and layout (otherwise ignored)
- *   LCMA_UNFUSED_VARIANT=<name>  the same for the GEMM stage of lcma_gemm_unfused
- *   LCMA_PANEL=<n>               width, in tiles, of the column panels of the tile order (default 8)
- *   LCMA_BATCH_ORDER=1           batched GEMM of lcma_gemm_unfused level 1 in group-major instead of product-major order
+/* ------------------------------------------------------------------ measurement aids
+ * Process-wide settings; none changes a result.  lcma_set_tuning(key, value) sets one (value "" or NULL restores the
+ * default); the initial values come from the environment variables named below, which are read ONCE, at the first
+ * call that needs them.  Errors: ARG for an unknown key.
+ *   "variant"          LCMA_VARIANT=<name>          lcma_gemm / lcma_gemm_prepared run this generated kernel when it belongs
+ *                                                   to the requested scheme, dtype and layout (otherwise ignored)
+ *   "unfused_variant"  LCMA_UNFUSED_VARIANT=<name>  the same for the GEMM stage of lcma_gemm_unfused
+ *   "panel"            LCMA_PANEL=<n>               width, in tiles, of the column panels of the tile order (default 8)
+ *   "batch_order"      LCMA_BATCH_ORDER=1           batched GEMM of lcma_gemm_unfused level 1 in group-major instead of
+ *                                                   product-major order
  */
+lcma_status lcma_set_tuning(const char *key, const char *value);
 
 /* ------------------------------------------------------------------ tile scheduling (Sec. 3.2, Split-Group Parallelism)
  * Wave counts for `groups` groups of R tile-products on `units` compute units:

@@ -29,7 +29,7 @@ EXPORTS = [
     "lcma_sched_waves", "lcma_sched_range", "lcma_status_str", "lcma_last_error",
     "lcma_scheme_name", "lcma_scheme_id_max", "lcma_variant_prepared", "lcma_prepared_b_bytes", "lcma_prepare_b", "lcma_prepare_bt", "lcma_gemm_prepared",
     "lcma_gemm_nt", "lcma_variant_b_layout", "lcma_unfused_workspace_bytes", "lcma_gemm_unfused",
-    "lcma_predict_unfused_seconds", "lcma_select_dataflow", "lcma_gemm_ex",
+    "lcma_predict_unfused_seconds", "lcma_select_dataflow", "lcma_gemm_ex", "lcma_set_tuning",
 ]
 
 
@@ -108,6 +108,7 @@ def lib() -> ctypes.CDLL:
         L.lcma_status_str.restype = cp
         L.lcma_last_error.argtypes = []
         L.lcma_last_error.restype = cp
+        L.lcma_set_tuning.argtypes = [cp, cp]
         _lib = L
         # schemes that kernels were generated for beyond the paper's three
         for sid in range(4, int(L.lcma_scheme_id_max()) + 1):
@@ -341,6 +342,11 @@ def lcma_model_intensity(s: Scheme | None, M: int, N: int, K: int):
     e = [ctypes.c_double() for _ in range(3)]
     _check(lib().lcma_model_intensity(s.handle if s else None, M, N, K, *[ctypes.byref(x) for x in e]))
     return tuple(float(x.value) for x in e)
+
+
+def lcma_set_tuning(key: str, value: str = ""):
+    """Measurement aid: "variant", "unfused_variant", "panel" or "batch_order"; an empty value restores the default."""
+    _check(lib().lcma_set_tuning(key.encode(), value.encode()))
 
 
 def lcma_sched_waves(groups: int, R: int, units: int):

@@ -1,10 +1,12 @@
 // C ABI entry points: argument checks, variant choice, kernel launch.
 #include "host_common.h"
 
+#include <atomic>
 #include <cstdarg>
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 
 namespace lcma {
 
@@ -51,6 +53,53 @@ static const Variant *find_variant(const char *name) {
     return nullptr;
 }
 
+// Measurement aids (see lcma_set_tuning): process-wide, initialised once from the environment, never read from it again.
+namespace {
+std::atomic<const Variant *> g_forced{nullptr}, g_forced_unfused{nullptr};
+std::atomic<int> g_panel{8}, g_batch_order{0};
+std::once_flag g_tuning_once;
+bool set_tuning(const char *key, const char *value) {
+    const char *v = value ? value : "";
+    if (!std::strcmp(key, "variant")) g_forced = *v ? find_variant(v) : nullptr;
+    else if (!std::strcmp(key, "unfused_variant")) g_forced_unfused = *v ? find_variant(v) : nullptr;
+    else if (!std::strcmp(key, "panel")) g_panel = *v ? (std::atoi(v) < 1 ? 1 : std::atoi(v)) : 8;
+    else if (!std::strcmp(key, "batch_order")) g_batch_order = *v ? std::atoi(v) != 0 : 0;
+    else return false;
+    return true;
+}
+void init_tuning() {
+    std::call_once(g_tuning_once, [] {
+        if (const char *e = std::getenv("LCMA_VARIANT")) set_tuning("variant", e);
+        if (const char *e = std::getenv("LCMA_UNFUSED_VARIANT")) set_tuning("unfused_variant", e);
+        if (const char *e = std::getenv("LCMA_PANEL")) set_tuning("panel", e);
+        if (const char *e = std::getenv("LCMA_BATCH_ORDER")) set_tuning("batch_order", e);
+    });
+}
+} // namespace
+const Variant *forced_variant() { init_tuning(); return g_forced.load(); }
+const Variant *forced_unfused_variant() { init_tuning(); return g_forced_unfused.load(); }
+int tuning_panel() { init_tuning(); return g_panel.load(); }
+int tuning_batch_order() { init_tuning(); return g_batch_order.load(); }
+
+// [p, p + bytes) and [q, q + qbytes) share a byte
+static bool overlap(const void *p, int64_t bytes, const void *q, int64_t qbytes) {
+    const uintptr_t a = (uintptr_t)p, b = (uintptr_t)q;
+    return a < b + (uintptr_t)qbytes && b < a + (uintptr_t)bytes;
+}
+
+// K = 0: the product of Eq. 1 is the zero matrix, so C = beta * C (zeros when beta is 0; C is then not read).
+lcma_status empty_product(int64_t M, int64_t N, void *C, int64_t ldc, int dtype, float beta, void *stream) {
+    const int es = dtype_size(dtype);
+    if (!C) return fail(LCMA_ERR_ARG, "lcma_gemm: null matrix pointer");
+    if (ldc < N) return fail(LCMA_ERR_ARG, "lcma_gemm: leading dimension smaller than the row");
+    if (((uintptr_t)C & 15) || ((ldc * es) & 15) || N % (16 / es))
+        return fail(LCMA_ERR_ARG, "lcma_gemm: C must be 16-byte aligned with rows of whole 16-byte vectors");
+    if (((M - 1) * ldc + N) * es >= ((int64_t)1 << 31)) return fail(LCMA_ERR_SHAPE, "lcma_gemm: a matrix spans 2 GiB or more");
+    if (const int err = lcma_launch_scale_c(C, M, N * es, ldc * es, dtype, beta, stream))
+        return fail(LCMA_ERR_HIP, "lcma_gemm: launch failed with HIP error %d", err);
+    return LCMA_OK;
+}
+
 // B and ldb describe the K x N matrix; for a variant that takes the weight layout, the N x K matrix W;
 // for a prepared-B variant, the planes written by lcma_prepare_b (ldb is then ignored).
 static lcma_status run(const Variant &v, int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const void *B,
@@ -60,7 +109,7 @@ static lcma_status run(const Variant &v, int64_t M, int64_t N, int64_t K, const 
         return fail(LCMA_ERR_ARG, "lcma_gemm: %s is a stage kernel of lcma_gemm_unfused and takes no matrices", v.name);
     if (M < 0 || N < 0 || K < 0) return fail(LCMA_ERR_ARG, "lcma_gemm: negative size");
     if (M == 0 || N == 0) return LCMA_OK; // nothing to write
-    if (K == 0) return fail(LCMA_ERR_SHAPE, "lcma_gemm: K = 0 is not supported");
+    if (K == 0) return empty_product(M, N, C, ldc, v.dtype, beta, stream);
     if (!A || !B || !C) return fail(LCMA_ERR_ARG, "lcma_gemm: null matrix pointer");
     if (v.prepared) ldb = N;
     if (lda < K || ldb < (v.b_nk ? K : N) || ldc < N)
@@ -87,6 +136,8 @@ static lcma_status run(const Variant &v, int64_t M, int64_t N, int64_t K, const 
     if (((Mp - 1) * lda + Kp) * es >= lim || b_span * es >= lim || ((Mp - 1) * ldc + Np) * es >= lim ||
         b_bytes >= lim)
         return fail(LCMA_ERR_SHAPE, "lcma_gemm: a matrix spans 2 GiB or more");
+    if (overlap(C, c_bytes, A, a_bytes) || overlap(C, c_bytes, B, b_bytes))
+        return fail(LCMA_ERR_ARG, "lcma_gemm: C overlaps A or B");
     Params p;
     p.A = A;
     p.B = B;
@@ -126,9 +177,7 @@ static lcma_status run(const Variant &v, int64_t M, int64_t N, int64_t K, const 
     }
     const int64_t grid = (int64_t)p.nx * p.nz;
     if (grid >= lim) return fail(LCMA_ERR_SHAPE, "lcma_gemm: too many tiles");
-    int panel = 8;
-    if (const char *e = std::getenv("LCMA_PANEL")) panel = std::atoi(e);
-    if (panel < 1) panel = 1;
+    const int panel = tuning_panel();
     p.panel = panel < p.nz ? panel : p.nz;
     const int err = v.launch(&p, (int)grid, stream);
     if (err) return fail(LCMA_ERR_HIP, "lcma_gemm: launch of %s failed with HIP error %d", v.name, err);
@@ -154,11 +203,8 @@ static lcma_status gemm(int b_nk, int64_t M, int64_t N, int64_t K, const void *A
     }
     if (M < 0 || N < 0 || K < 0) return fail(LCMA_ERR_ARG, "lcma_gemm: negative size");
     if (M == 0 || N == 0) return LCMA_OK;
-    const Variant *v = nullptr;
-    if (const char *force = std::getenv("LCMA_VARIANT")) { // ablation override
-        v = find_variant(force);
-        if (v && (v->scheme_id != id || v->dtype != (int)dtype || v->prepared || v->b_nk != b_nk)) v = nullptr;
-    }
+    const Variant *v = forced_variant(); // ablation override
+    if (v && (v->scheme_id != id || v->dtype != (int)dtype || v->prepared || v->b_nk != b_nk)) v = nullptr;
     if (!v) v = pick_variant(id, dtype, M, N, K, 0, b_nk);
     if (!v) {
         bool any = false;
@@ -317,11 +363,8 @@ extern "C" lcma_status lcma_gemm_prepared(int64_t M, int64_t N, int64_t K, const
     if (const lcma_status st = prepared_scheme(scheme, "lcma_gemm_prepared", &id)) return st;
     if (M < 0 || N < 0 || K < 0) return fail(LCMA_ERR_ARG, "lcma_gemm_prepared: negative size");
     if (M == 0 || N == 0) return LCMA_OK;
-    const Variant *v = nullptr;
-    if (const char *force = std::getenv("LCMA_VARIANT")) { // ablation override
-        v = find_variant(force);
-        if (v && (v->scheme_id != id || v->dtype != (int)dtype || !v->prepared)) v = nullptr;
-    }
+    const Variant *v = forced_variant(); // ablation override
+    if (v && (v->scheme_id != id || v->dtype != (int)dtype || !v->prepared)) v = nullptr;
     if (!v) v = pick_variant(id, dtype, M, N, K, 1);
     if (!v) {
         bool any = false;
@@ -387,3 +430,10 @@ extern "C" const char *lcma_status_str(lcma_status st) {
 }
 
 extern "C" const char *lcma_last_error(void) { return g_error; }
+
+extern "C" lcma_status lcma_set_tuning(const char *key, const char *value) {
+    if (!key) return fail(LCMA_ERR_ARG, "lcma_set_tuning: null key");
+    init_tuning();
+    if (!set_tuning(key, value)) return fail(LCMA_ERR_ARG, "lcma_set_tuning: unknown key '%s'", key);
+    return LCMA_OK;
+}

@@ -77,6 +77,21 @@ lcma_status prepare_b_planes(bool transposed, int64_t N, int64_t K, const void *
 
 int dtype_size(int dtype); // bytes, or 0
 
+// Measurement aids set by lcma_set_tuning (initial values: the LCMA_* environment variables, read once).
+const Variant *forced_variant();
+const Variant *forced_unfused_variant();
+int tuning_panel();
+int tuning_batch_order();
+
+// C = beta * C for an M x N matrix (the product with K = 0), on `stream`.
+lcma_status empty_product(int64_t M, int64_t N, void *C, int64_t ldc, int dtype, float beta, void *stream);
+
+// The unfused dataflows on a workspace of `workspace_bytes` bytes (lcma_gemm_unfused and its variant on the
+// library's static buffer); `who` names the entry point in messages.
+lcma_status gemm_unfused(const char *who, int level, int64_t M, int64_t N, int64_t K, const void *A, int64_t lda,
+                         const void *B, int64_t ldb, void *C, int64_t ldc, lcma_dtype dtype, const lcma_scheme *scheme,
+                         void *workspace, int64_t workspace_bytes, int reuse_bt, void *stream);
+
 // Variant of (scheme_id, dtype) with the smallest predicted time among those whose tile divides the
 // shape; nullptr if none.
 const Variant *pick_variant(int scheme_id, int dtype, int64_t M, int64_t N, int64_t K, int prepared = 0, int b_nk = 0);
@@ -86,3 +101,6 @@ double predict_variant(const Variant &v, int64_t M, int64_t N, int64_t K);
 bool variant_fits(const Variant &v, int64_t M, int64_t N, int64_t K);
 
 } // namespace lcma
+
+// hand-written auxiliary kernels (csrc/lcma_aux.hip); return a hipError_t
+extern "C" int lcma_launch_scale_c(void *C, int64_t rows, int64_t row_bytes, int64_t ld_bytes, int dtype, float beta, void *stream);

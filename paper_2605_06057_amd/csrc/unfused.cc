@@ -66,12 +66,12 @@ double gemm_stage_seconds(const Variant &v, int R, const Geometry &g) {
 const Variant *find_gemm(bool batch, int scheme_id, int dtype, int R, const Geometry &g) {
     const Variant *best = nullptr;
     double best_t = 0.0;
-    const char *force = std::getenv("LCMA_UNFUSED_VARIANT"); // ablation override
+    const Variant *force = forced_unfused_variant(); // ablation override
     for (int i = 0; i < kVariantCount; ++i) {
         const Variant &v = kVariants[i];
         if ((batch ? !v.batch : !v.left_planes) || v.scheme_id != scheme_id || v.dtype != dtype) continue;
         if (g.bm % v.TM || g.bn % v.TN || g.bk % v.TK) continue;
-        if (force && !std::strcmp(force, v.name)) return &v;
+        if (force == &v) return &v;
         const double t = gemm_stage_seconds(v, R, g);
         if (!best || t < best_t) {
             best = &v;
@@ -134,7 +134,13 @@ extern "C" lcma_status lcma_gemm_unfused(int level, int64_t M, int64_t N, int64_
                                          const void *B, int64_t ldb, void *C, int64_t ldc, lcma_dtype dtype,
                                          const lcma_scheme *scheme, void *workspace, int64_t workspace_bytes,
                                          int reuse_bt, void *stream) {
-    const char *who = "lcma_gemm_unfused";
+    return gemm_unfused("lcma_gemm_unfused", level, M, N, K, A, lda, B, ldb, C, ldc, dtype, scheme, workspace,
+                        workspace_bytes, reuse_bt, stream);
+}
+
+lcma_status lcma::gemm_unfused(const char *who, int level, int64_t M, int64_t N, int64_t K, const void *A, int64_t lda,
+                               const void *B, int64_t ldb, void *C, int64_t ldc, lcma_dtype dtype, const lcma_scheme *scheme,
+                               void *workspace, int64_t workspace_bytes, int reuse_bt, void *stream) {
     const int es = dtype_size(dtype);
     if (!es) return fail(LCMA_ERR_DTYPE, "%s: unknown dtype %d", who, (int)dtype);
     if (level != 1 && level != 2) return fail(LCMA_ERR_ARG, "%s: level must be 1 (Algorithm 1) or 2 (Algorithm 2)", who);
@@ -147,7 +153,7 @@ extern "C" lcma_status lcma_gemm_unfused(int level, int64_t M, int64_t N, int64_
                     scheme->m, scheme->k, scheme->n, scheme->R, (int)dtype);
     if (M < 0 || N < 0 || K < 0) return fail(LCMA_ERR_ARG, "%s: negative size", who);
     if (M == 0 || N == 0) return LCMA_OK;
-    if (K == 0) return fail(LCMA_ERR_SHAPE, "%s: K = 0 is not supported", who);
+    if (K == 0) return empty_product(M, N, C, ldc, dtype, 0.f, stream);
     if (!A || !B || !C || !workspace) return fail(LCMA_ERR_ARG, "%s: null pointer", who);
     if (lda < K || ldb < N || ldc < N) return fail(LCMA_ERR_ARG, "%s: leading dimension smaller than the row", who);
     if ((((uintptr_t)A | (uintptr_t)B | (uintptr_t)C) & 15) || ((uintptr_t)workspace & 255))
@@ -168,7 +174,9 @@ extern "C" lcma_status lcma_gemm_unfused(int level, int64_t M, int64_t N, int64_
     if (g.at_bytes >= lim || g.bt_bytes >= lim || g.h_bytes >= lim || ((Mp - 1) * lda + Kp) * es >= lim ||
         ((Kp - 1) * ldb + Np) * es >= lim || ((Mp - 1) * ldc + Np) * es >= lim)
         return fail(LCMA_ERR_SHAPE, "%s: a matrix or a set of planes spans 2 GiB or more", who);
-    char *At = (char *)workspace, *Bt = At + g.at_bytes, *H = Bt + g.bt_bytes;
+    // Bt first: its place and size depend on N and K alone, so the planes of static weights stay where they are
+    // when the number of rows M changes between calls
+    char *Bt = (char *)workspace, *At = Bt + g.bt_bytes, *H = At + g.at_bytes;
     // the products are multiplied in fp16 for both 16-bit storage types
     const int ct = dtype == LCMA_F32 ? LCMA_F32 : LCMA_F16;
     const Variant *gemm = level == 1 ? find_gemm(true, LCMA_PLAIN, ct, scheme->R, g) : find_gemm(false, id, dtype, scheme->R, g);
@@ -215,11 +223,9 @@ extern "C" lcma_status lcma_gemm_unfused(int level, int64_t M, int64_t N, int64_
     p.ny = (int32_t)(g.bk / gemm->TK);
     p.k_row_b = (uint32_t)(Kp * es); // the planes are padded with zeros: no column of At is past K
     p.k_tail_b = (uint32_t)(g.bk * es);
-    int panel = 8;
-    if (const char *e = std::getenv("LCMA_PANEL")) panel = std::atoi(e);
-    if (panel < 1) panel = 1;
+    const int panel = tuning_panel();
     p.panel = panel < p.nz ? panel : p.nz;
-    if (const char *e = std::getenv("LCMA_BATCH_ORDER")) p.batch_order = std::atoi(e) != 0; // ablation: 1 = group-major
+    p.batch_order = tuning_batch_order(); // ablation: 1 = group-major
     if (level == 1) {
         // stage 3: the R products H_r = At_r x Bt_r as one batched launch of the plain kernel
         p.C = H;

@@ -214,3 +214,47 @@ def test_error_paths_launch_nothing(B, tmp_path):
     assert torch.all(c == 3.0)
     empty = torch.empty((0, 256), dtype=torch.float16, device="cuda")
     B.lcma_gemm(empty, a, torch.empty((0, 256), dtype=torch.float16, device="cuda"), s)  # M = 0: nothing to do
+
+
+@pytest.mark.parametrize("dt", ["f32", "bf16", "f16"])
+def test_empty_inner_dimension_writes_beta_c(B, dt):
+    """K = 0: the product of Eq. 1 is the zero matrix.  lcma_gemm and lcma_gemm_nt write zeros (over NaN), lcma_gemm_ex
+    writes beta * C rounded once, columns beyond N and rows beyond M of a wider buffer stay untouched."""
+    import torch
+    import gpu_util as G
+    M, N = 37, 72
+    td = {"f32": torch.float32, "bf16": torch.bfloat16, "f16": torch.float16}[dt]
+    a = torch.empty((M, 0), dtype=td, device="cuda")
+    b = torch.empty((0, N), dtype=td, device="cuda")
+    for scheme in (None, "strassen"):
+        s = B.lcma_scheme_load("builtin:" + scheme) if scheme else None
+        big = torch.full((M + 3, N + 16), float("nan"), dtype=td, device="cuda")
+        B.lcma_gemm(a, b, big[:M, :N], s)
+        torch.cuda.synchronize()
+        assert torch.all(big[:M, :N] == 0).item()
+        assert torch.isnan(big[M:]).all().item() and torch.isnan(big[:, N:]).all().item()
+        B.lcma_gemm_nt(a, torch.empty((N, 0), dtype=td, device="cuda"), big[:M, :N].fill_(float("nan")), s)
+        assert torch.all(big[:M, :N] == 0).item()
+        vals = inp.store(inp.uniform(77, 1, (M, N)), dt)
+        c = G.to_device(vals, dt)
+        B.lcma_gemm_ex(0.5, -1.75, a, b, c, s)
+        torch.cuda.synchronize()
+        want = inp.store(np.float32(-1.75) * inp.widen(vals, dt).astype(np.float32), dt)
+        assert np.array_equal(G.to_host_stored(c, dt).view(np.uint8), want.view(np.uint8))
+    ws = torch.empty((1 << 20,), dtype=torch.uint8, device="cuda")
+    c = torch.full((M, N), float("nan"), dtype=td, device="cuda")
+    B.lcma_gemm_unfused(1, a, b, c, B.lcma_scheme_load("builtin:strassen"), ws)
+    assert torch.all(c == 0).item()
+
+
+def test_overlapping_output_is_refused(B):
+    import torch
+    buf = torch.ones((512, 256), dtype=torch.float16, device="cuda")
+    with pytest.raises(B.LcmaError) as e:
+        B.lcma_gemm(buf[:256], buf[256:], buf[128:384], None)   # C covers the end of A and the start of B
+    assert e.value.status == B.LCMA_ERR_ARG
+    torch.cuda.synchronize()
+    assert torch.all(buf == 1).item()
+    B.lcma_gemm(buf[:256], buf[:256], buf[256:], None)          # A and B may be the same matrix
+    torch.cuda.synchronize()
+    assert torch.all(buf[256:] == 256).item()

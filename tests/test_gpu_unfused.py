@@ -109,9 +109,9 @@ def test_unfused_error_paths_launch_nothing(B):
     assert B.lcma_unfused_workspace_bytes(h, 0, 256, 256, B.LCMA_F16) == -1
 
 
-def test_batch_order_changes_nothing_but_time(B, monkeypatch):
-    """The batched GEMM of level 1 in group-major instead of product-major order (LCMA_BATCH_ORDER=1, kept to
-    measure the paper's Cache-Aware ordering): the same bits."""
+def test_batch_order_changes_nothing_but_time(B):
+    """The batched GEMM of level 1 in group-major instead of product-major order (lcma_set_tuning("batch_order", "1"),
+    kept to measure the paper's Cache-Aware ordering): the same bits."""
     import torch
     h = B.lcma_scheme_load("builtin:laderman")
     M, N, K = 520, 392, 200
@@ -121,7 +121,10 @@ def test_batch_order_changes_nothing_but_time(B, monkeypatch):
     c0 = torch.empty(M, N, device="cuda", dtype=torch.float16)
     c1 = torch.empty_like(c0)
     B.lcma_gemm_unfused(1, a, b, c0, h, ws)
-    monkeypatch.setenv("LCMA_BATCH_ORDER", "1")
-    B.lcma_gemm_unfused(1, a, b, c1, h, ws)
+    B.lcma_set_tuning("batch_order", "1")
+    try:
+        B.lcma_gemm_unfused(1, a, b, c1, h, ws)
+    finally:
+        B.lcma_set_tuning("batch_order", "")
     torch.cuda.synchronize()
     assert torch.equal(c0.view(torch.uint8), c1.view(torch.uint8))

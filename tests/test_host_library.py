@@ -231,7 +231,8 @@ def test_gemm_argument_checks_before_any_launch(B):
     assert gemm(*ok_shape, a=P + 2) == B.LCMA_ERR_ARG                   # pointer not 16-byte aligned
     assert gemm(*ok_shape, ldc=260) == B.LCMA_ERR_ARG                   # ldc * 2 bytes not a multiple of 16
     assert gemm(-1, 256, 256) == B.LCMA_ERR_ARG
-    assert gemm(256, 256, 0) == B.LCMA_ERR_SHAPE                        # K = 0
+    assert gemm(256, 256, 0, c=None) == B.LCMA_ERR_ARG                  # K = 0 writes zeros: C is needed
+    assert gemm(256, 256, 0, ldc=255) == B.LCMA_ERR_ARG
     assert gemm(256, 256, 252, lda=256) == B.LCMA_ERR_SHAPE             # K = 252: rows of A not 16-byte granular
     assert gemm(256, 250, 256) == B.LCMA_ERR_SHAPE                      # N = 250: rows not 16-byte granular
     assert gemm(*ok_shape, dt=9) == B.LCMA_ERR_DTYPE
@@ -243,6 +244,8 @@ def test_gemm_argument_checks_before_any_launch(B):
     # the largest accepted extent is just below 2 GiB
     lda_max = ((1 << 31) // 2 - 256) // 255 // 8 * 8
     assert (255 * lda_max + 256) * 2 < (1 << 31)
+    assert gemm(*ok_shape, c=P + 256 * 256 * 2 - 16) == B.LCMA_ERR_ARG    # C overlaps the end of A (and of B)
+    assert b"overlaps" in L.lcma_last_error()
     # (accepted arguments would launch: not tried here without a GPU)
     # two-level Strassen has no fp16 kernel
     s2 = B.lcma_scheme_load("builtin:strassen2")
@@ -290,7 +293,7 @@ def test_weight_layout_and_unfused_host_side(B):
     assert unfused(nbytes=3 * 7 * 128 * 128 * 2 - 1) == B.LCMA_ERR_ARG
     assert b"needed" in L.lcma_last_error()
     assert unfused(K=252, lda=256) == B.LCMA_ERR_SHAPE
-    assert unfused(K=0) == B.LCMA_ERR_SHAPE
+    assert L.lcma_gemm_unfused(1, 256, 256, 0, P, 0, P, 256, None, 256, B.LCMA_F16, s.handle, P, 1 << 30, 0, None) == B.LCMA_ERR_ARG  # K = 0 writes zeros: C is needed
     assert unfused(M=0) == B.LCMA_OK                            # nothing to write
 
 

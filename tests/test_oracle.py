@@ -418,3 +418,32 @@ def test_unfused_rounding_points():
     got2 = oracle.lcma_unfused(s, A, B, "f16", 2)
     assert got1[0, 0] == 2048.0 and got2[0, 0] == exact       # C11 = M1 + M4 - M5 + M7 = M1
     assert got1[1, 1] == 0.0 and got2[1, 1] == 0.0            # C22 = M1 - M2 + M3 + M6 = M1 - M1
+
+
+# ---------------------------------------------------------------- the parity metric itself
+def test_rel_frobenius_hand_values():
+    """||C - Cref||_F / ||Cref||_F on cases worked by hand: each fails for a dropped square root, a swapped
+    numerator and denominator, a max-norm or a 1-norm in place of the Frobenius norm, or a missing square."""
+    import math
+    # zero reference: the metric is the absolute norm; sqrt(3^2 + 4^2) = 5 (9 + 16 = 25 without the root, 7 as a 1-norm)
+    assert oracle.rel_frobenius(np.array([[3.0, 0.0], [0.0, 4.0]]), np.zeros((2, 2))) == 5.0
+    # difference (1, 1, 0, 0), reference (1, 2, 2, 4): sqrt(2) / 5, irrational only through the square root
+    ref = np.array([[1.0, 2.0], [2.0, 4.0]])
+    got = ref + np.array([[1.0, 1.0], [0.0, 0.0]])
+    assert oracle.rel_frobenius(got, ref) == pytest.approx(math.sqrt(2.0) / 5.0, rel=1e-15)
+    assert oracle.rel_frobenius(got, ref) != pytest.approx(2.0 / 25.0, rel=1e-3)       # no roots
+    assert oracle.rel_frobenius(got, ref) != pytest.approx(1.0 / 4.0, rel=1e-3)        # max norms
+    assert oracle.rel_frobenius(got, ref) != pytest.approx(2.0 / 9.0, rel=1e-3)        # 1-norms
+    # not symmetric: the reference is the second argument (swapped: sqrt(2) / sqrt(4 + 9 + 4 + 16))
+    assert oracle.rel_frobenius(ref, got) == pytest.approx(math.sqrt(2.0 / 33.0), rel=1e-15)
+    # identical matrices: exactly zero; scaling both leaves the ratio unchanged; a uniform relative error eps gives eps
+    assert oracle.rel_frobenius(ref, ref) == 0.0
+    assert oracle.rel_frobenius(1024.0 * got, 1024.0 * ref) == pytest.approx(math.sqrt(2.0) / 5.0, rel=1e-15)
+    assert oracle.rel_frobenius(ref * (1.0 + 2.0 ** -10), ref) == pytest.approx(2.0 ** -10, rel=1e-12)
+    # one wrong element among many: |d| / ||ref||_F, the whole matrix counts (a mean instead of a sum would divide by 10^4)
+    big = np.ones((100, 100))
+    bad = big.copy()
+    bad[17, 3] = 3.0
+    assert oracle.rel_frobenius(bad, big) == pytest.approx(2.0 / 100.0, rel=1e-15)
+    # narrower storage types are widened, not compared in their own precision
+    assert oracle.rel_frobenius(np.array([[1.0]], np.float32), np.array([[1.0 + 2.0 ** -30]])) == pytest.approx(2.0 ** -30, rel=1e-6)
