@@ -209,6 +209,20 @@ lcma_status lcma_gemm_unfused(int level, int64_t M, int64_t N, int64_t K,
                               void *C, int64_t ldc, lcma_dtype dtype, const lcma_scheme *scheme,
                               void *workspace, int64_t workspace_bytes, int reuse_bt, void *stream);
 
+/* lcma_gemm_unfused for callers that cannot allocate device memory or pass a workspace (code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc): the planes live in a 32 MiB buffer that is part of
+ * the library's device image (lcma_static_scratch_bytes() bytes, one copy per GPU, held until the process ends).
+ * The call allocates nothing and calls no allocating routine.  Shapes whose planes need more than the buffer
+ * (lcma_unfused_workspace_bytes() > lcma_static_scratch_bytes(), e.g. Strassen bf16 beyond about 1700^3) are
+ * rejected with LCMA_ERR_SHAPE and nothing is launched.  Every call on a GPU uses that GPU's one buffer: calls on
+ * different streams of one GPU that overlap in time race; calls on one stream are ordered.  reuse_bt refers to the
+ * Bt_r planes left by the previous call on the same GPU.  Everything else as for lcma_gemm_unfused. */
+int64_t lcma_static_scratch_bytes(void);
+lcma_status lcma_gemm_unfused_static(int level, int64_t M, int64_t N, int64_t K,
+                                     const void *A, int64_t lda, const void *B, int64_t ldb,
+                                     void *C, int64_t ldc, lcma_dtype dtype, const lcma_scheme *scheme,
+                                     int reuse_bt, void *stream);
+
 /* The Decision Module (Sec. 3.3) over both dataflows this library runs: predicted seconds of Algorithm 1
  * (lcma_gemm_unfused level 1) for a built-in scheme id, stage by stage (Combine A, Combine B unless
  * combine_b_offline, the batched GEMM, Combine H; negative when the scheme has no stage kernels), and the

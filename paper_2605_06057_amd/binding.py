@@ -30,6 +30,7 @@ EXPORTS = [
     "lcma_scheme_name", "lcma_scheme_id_max", "lcma_variant_prepared", "lcma_prepared_b_bytes", "lcma_prepare_b", "lcma_prepare_bt", "lcma_gemm_prepared",
     "lcma_gemm_nt", "lcma_variant_b_layout", "lcma_unfused_workspace_bytes", "lcma_gemm_unfused",
     "lcma_predict_unfused_seconds", "lcma_select_dataflow", "lcma_gemm_ex", "lcma_set_tuning",
+    "lcma_static_scratch_bytes", "lcma_gemm_unfused_static",
 ]
 
 
@@ -109,6 +110,9 @@ def lib() -> ctypes.CDLL:
         L.lcma_last_error.argtypes = []
         L.lcma_last_error.restype = cp
         L.lcma_set_tuning.argtypes = [cp, cp]
+        L.lcma_static_scratch_bytes.argtypes = []
+        L.lcma_static_scratch_bytes.restype = i64
+        L.lcma_gemm_unfused_static.argtypes = [i32, i64, i64, i64, vp, i64, vp, i64, vp, i64, i32, vp, i32, vp]
         _lib = L
         # schemes that kernels were generated for beyond the paper's three
         for sid in range(4, int(L.lcma_scheme_id_max()) + 1):
@@ -234,6 +238,18 @@ def lcma_gemm_unfused(level: int, A, B, C, scheme: Scheme, workspace, reuse_bt: 
     _check(lib().lcma_gemm_unfused(level, M, N, K, pa, lda, pb, ldb, pc, ldc, _dtype_of(A), scheme.handle,
                                    workspace.data_ptr(), workspace.numel() * workspace.element_size(),
                                    int(reuse_bt), stream))
+    return C
+
+
+def lcma_static_scratch_bytes() -> int:
+    return int(lib().lcma_static_scratch_bytes())
+
+
+def lcma_gemm_unfused_static(level: int, A, B, C, scheme: Scheme, reuse_bt: bool = False):
+    """lcma_gemm_unfused on the library's static device buffer: allocates nothing, takes no workspace."""
+    M, N, K, pa, lda, pb, ldb, pc, ldc, stream = _marshal(A, B, C)
+    _check(lib().lcma_gemm_unfused_static(level, M, N, K, pa, lda, pb, ldb, pc, ldc, _dtype_of(A), scheme.handle,
+                                          int(reuse_bt), stream))
     return C
 
 

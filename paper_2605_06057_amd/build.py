@@ -46,7 +46,7 @@ def build(force: bool = False, jobs: int | None = None, verbose: bool = True) ->
     headers.append(os.path.join(PKG, "..", "include", "lcma.h"))
     headers.append(os.path.join(GEN, "builtin_schemes.inc"))
     units = [(h, h[:-4] + ".o") for h in hips]
-    for name in ("api.cc", "scheme.cc", "model.cc", "unfused.cc", "lcma_aux.hip"):
+    for name in ("api.cc", "scheme.cc", "model.cc", "unfused.cc", "lcma_aux.hip", "lcma_static.hip"):
         units.append((os.path.join(CSRC, name), os.path.join(GEN, os.path.splitext(name)[0] + ".o")))
     units.append((os.path.join(GEN, "registry.cc"), os.path.join(GEN, "registry.o")))
     jobs = jobs or min(8, os.cpu_count() or 1)
