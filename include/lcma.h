@@ -235,6 +235,45 @@ double lcma_predict_unfused_seconds(int scheme_id, int64_t M, int64_t N, int64_t
 lcma_status lcma_select_dataflow(int64_t M, int64_t N, int64_t K, lcma_dtype dtype,
                                  int combine_b_offline, lcma_choice *out);
 
+/* ------------------------------------------------------------------ FP8 (Sec. 4.1 experimental setup; Sec. 4.3 fused quantisation)
+ * The paper's FP8 workflow: bf16 operands, quantised to FP8 E4M3 with one scale per 1 x 128 block along K, multiplied
+ * block-scaled; in the LCMA form the quantisation is fused into the Combine A stage.  As built here:
+ *   - E4M3 is the OCP format (bias 7, largest finite value 448, no infinities); conversion rounds to nearest, ties to even;
+ *   - a scale is a power of two 2^e stored as the byte e + 127 (E8M0), e the smallest integer with amax <= 448 * 2^e over the
+ *     128 values of the block (e = 0 for an all-zero block): dividing by it is exact, and MI355X's scaled matrix
+ *     instruction applies it in hardware;
+ *   - both operands are scaled along K: A per row, the weights per row of the N x K matrix W (C = A x W^T);
+ *   - the sums of Eq. 3 / Eq. 4 are formed in fp32 in ascending block order before they are quantised; products
+ *     accumulate in fp32; C is bf16, rounded once.
+ * Code matrices hold one byte per element, rows of lcma_fp8_code_pitch(K) = K rounded up to 128 bytes (the padding holds
+ * zero codes); scale matrices hold lcma_fp8_scale_pitch(K) bytes per row (K/128 rounded up, then up to a multiple of 4).
+ * All pointers are device pointers owned by the caller; calls are asynchronous on `stream`; K must be a multiple of 8;
+ * every matrix stays below 2 GiB.  Errors: ARG, SHAPE, BRENT, NOKERNEL, HIP; nothing is launched on error.
+ *
+ * lcma_fp8_quantize   X: rows x K bf16 (ldx in elements, 16-byte aligned) -> Q: rows x code pitch, S: rows x scale pitch.
+ * lcma_fp8_gemm_nt    plain block-scaled product: C[M x N] (bf16, 16-byte aligned, ldc in elements and a multiple of 8, N a
+ *                     multiple of 8) from the codes and scales of A (M x K) and of W (N x K), each as written by
+ *                     lcma_fp8_quantize.
+ * lcma_fp8_prepare_w  offline Combine B (Eq. 4) for static weights W (N x K bf16) with the quantisation fused in: writes R
+ *                     planes of codes and their scales into Wp (lcma_fp8_prepared_w_bytes() bytes, 256-byte aligned).
+ * lcma_fp8_gemm_lcma  C = A x W^T by Algorithm 1 on FP8 operands: Combine A (Eq. 3) from the bf16 matrix A with the
+ *                     quantisation fused in, one batched launch of the block-scaled GEMM over the R planes (Eq. 5, products
+ *                     stored in fp16), Combine H (Eq. 6, fp32 sums in ascending r, one rounding to bf16).  workspace:
+ *                     lcma_fp8_workspace_bytes() bytes, 256-byte aligned, overwritten.  N must be a multiple of 8 as well.
+ * The byte counts return -1 for a bad argument. */
+int64_t lcma_fp8_code_pitch(int64_t K);
+int64_t lcma_fp8_scale_pitch(int64_t K);
+lcma_status lcma_fp8_quantize(int64_t rows, int64_t K, const void *X, int64_t ldx, void *Q, void *S, void *stream);
+lcma_status lcma_fp8_gemm_nt(int64_t M, int64_t N, int64_t K, const void *Aq, const void *Sa,
+                             const void *Wq, const void *Sw, void *C, int64_t ldc, void *stream);
+int64_t lcma_fp8_prepared_w_bytes(const lcma_scheme *scheme, int64_t N, int64_t K);
+lcma_status lcma_fp8_prepare_w(int64_t N, int64_t K, const void *W, int64_t ldw, const lcma_scheme *scheme,
+                               void *Wp, void *stream);
+int64_t lcma_fp8_workspace_bytes(const lcma_scheme *scheme, int64_t M, int64_t N, int64_t K);
+lcma_status lcma_fp8_gemm_lcma(int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const void *Wp,
+                               void *C, int64_t ldc, const lcma_scheme *scheme,
+                               void *workspace, int64_t workspace_bytes, void *stream);
+
 /* ------------------------------------------------------------------ Decision Module (Sec. 3.3)
  * lcma_select: predicted-fastest algorithm for the shape on MI355X among
  * {plain, <2,2,2;7>, <4,4,4;49>, <3,3,3;23>}; returns a built-in scheme id, or a

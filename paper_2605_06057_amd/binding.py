@@ -31,6 +31,8 @@ EXPORTS = [
     "lcma_gemm_nt", "lcma_variant_b_layout", "lcma_unfused_workspace_bytes", "lcma_gemm_unfused",
     "lcma_predict_unfused_seconds", "lcma_select_dataflow", "lcma_gemm_ex", "lcma_set_tuning",
     "lcma_static_scratch_bytes", "lcma_gemm_unfused_static",
+    "lcma_fp8_code_pitch", "lcma_fp8_scale_pitch", "lcma_fp8_quantize", "lcma_fp8_gemm_nt", "lcma_fp8_prepared_w_bytes",
+    "lcma_fp8_prepare_w", "lcma_fp8_workspace_bytes", "lcma_fp8_gemm_lcma",
 ]
 
 
@@ -113,6 +115,18 @@ def lib() -> ctypes.CDLL:
         L.lcma_static_scratch_bytes.argtypes = []
         L.lcma_static_scratch_bytes.restype = i64
         L.lcma_gemm_unfused_static.argtypes = [i32, i64, i64, i64, vp, i64, vp, i64, vp, i64, i32, vp, i32, vp]
+        L.lcma_fp8_code_pitch.argtypes = [i64]
+        L.lcma_fp8_code_pitch.restype = i64
+        L.lcma_fp8_scale_pitch.argtypes = [i64]
+        L.lcma_fp8_scale_pitch.restype = i64
+        L.lcma_fp8_quantize.argtypes = [i64, i64, vp, i64, vp, vp, vp]
+        L.lcma_fp8_gemm_nt.argtypes = [i64, i64, i64, vp, vp, vp, vp, vp, i64, vp]
+        L.lcma_fp8_prepared_w_bytes.argtypes = [vp, i64, i64]
+        L.lcma_fp8_prepared_w_bytes.restype = i64
+        L.lcma_fp8_prepare_w.argtypes = [i64, i64, vp, i64, vp, vp, vp]
+        L.lcma_fp8_workspace_bytes.argtypes = [vp, i64, i64, i64]
+        L.lcma_fp8_workspace_bytes.restype = i64
+        L.lcma_fp8_gemm_lcma.argtypes = [i64, i64, i64, vp, i64, vp, vp, i64, vp, vp, i64, vp]
         _lib = L
         # schemes that kernels were generated for beyond the paper's three
         for sid in range(4, int(L.lcma_scheme_id_max()) + 1):
@@ -358,6 +372,67 @@ def lcma_model_intensity(s: Scheme | None, M: int, N: int, K: int):
     e = [ctypes.c_double() for _ in range(3)]
     _check(lib().lcma_model_intensity(s.handle if s else None, M, N, K, *[ctypes.byref(x) for x in e]))
     return tuple(float(x.value) for x in e)
+
+
+# ---------------------------------------------------------------- FP8 (E4M3 codes, 1 x 128 power-of-two scales)
+def lcma_fp8_quantize(X, Q=None, S=None):
+    """Codes (rows x code pitch, uint8) and scale bytes (rows x scale pitch, uint8) of the bf16 device tensor X."""
+    import torch
+    assert X.is_cuda and X.dim() == 2 and X.stride(1) == 1 and X.dtype == torch.bfloat16
+    rows, K = X.shape
+    kp, ls = int(lib().lcma_fp8_code_pitch(K)), int(lib().lcma_fp8_scale_pitch(K))
+    if Q is None:
+        Q = torch.empty((rows, kp), dtype=torch.uint8, device=X.device)
+    if S is None:
+        S = torch.empty((rows, ls), dtype=torch.uint8, device=X.device)
+    assert Q.is_contiguous() and S.is_contiguous() and tuple(Q.shape) == (rows, kp) and tuple(S.shape) == (rows, ls)
+    stream = torch.cuda.current_stream(X.device).cuda_stream
+    _check(lib().lcma_fp8_quantize(rows, K, X.data_ptr(), X.stride(0), Q.data_ptr(), S.data_ptr(), stream))
+    return Q, S
+
+
+def lcma_fp8_gemm_nt(Aq, Sa, Wq, Sw, C, K: int):
+    """C (bf16, M x N) = dequantised A (codes Aq, scales Sa) times dequantised W (N x K) transposed."""
+    import torch
+    M, N = C.shape
+    assert Aq.is_contiguous() and Wq.is_contiguous() and Sa.is_contiguous() and Sw.is_contiguous()
+    assert Aq.shape[0] == M and Wq.shape[0] == N and C.dtype == torch.bfloat16 and C.stride(1) == 1
+    stream = torch.cuda.current_stream(C.device).cuda_stream
+    _check(lib().lcma_fp8_gemm_nt(M, N, K, Aq.data_ptr(), Sa.data_ptr(), Wq.data_ptr(), Sw.data_ptr(), C.data_ptr(),
+                                  C.stride(0), stream))
+    return C
+
+
+def lcma_fp8_prepare_w(W, scheme: Scheme, Wp=None):
+    """Offline Combine B of the N x K bf16 weight tensor with the quantisation fused in; returns the prepared operand
+    (uint8, lcma_fp8_prepared_w_bytes bytes)."""
+    import torch
+    assert W.is_cuda and W.dim() == 2 and W.stride(1) == 1 and W.dtype == torch.bfloat16
+    N, K = W.shape
+    nbytes = int(lib().lcma_fp8_prepared_w_bytes(scheme.handle, N, K))
+    if Wp is None:
+        Wp = torch.empty((nbytes,), dtype=torch.uint8, device=W.device)
+    assert Wp.is_contiguous() and Wp.numel() == nbytes
+    stream = torch.cuda.current_stream(W.device).cuda_stream
+    _check(lib().lcma_fp8_prepare_w(N, K, W.data_ptr(), W.stride(0), scheme.handle, Wp.data_ptr(), stream))
+    return Wp
+
+
+def lcma_fp8_workspace_bytes(scheme: Scheme, M: int, N: int, K: int) -> int:
+    return int(lib().lcma_fp8_workspace_bytes(scheme.handle, M, N, K))
+
+
+def lcma_fp8_gemm_lcma(A, Wp, C, scheme: Scheme, workspace):
+    """C (bf16) = A (bf16, M x K) x W^T with the prepared weights Wp = lcma_fp8_prepare_w(W, scheme)."""
+    import torch
+    assert A.is_cuda and A.dtype == torch.bfloat16 and C.dtype == torch.bfloat16 and A.stride(1) == C.stride(1) == 1
+    M, K = A.shape
+    M2, N = C.shape
+    assert M == M2 and workspace.is_contiguous() and Wp.is_contiguous()
+    stream = torch.cuda.current_stream(A.device).cuda_stream
+    _check(lib().lcma_fp8_gemm_lcma(M, N, K, A.data_ptr(), A.stride(0), Wp.data_ptr(), C.data_ptr(), C.stride(0),
+                                    scheme.handle, workspace.data_ptr(), workspace.numel(), stream))
+    return C
 
 
 def lcma_set_tuning(key: str, value: str = ""):

@@ -71,6 +71,15 @@ struct StageKernel {
 extern const StageKernel kStageKernels[];
 extern const int kStageKernelCount;
 
+// The FP8 kernels of one scheme: Combine A and Combine B for N x K weights, each with the quantisation fused in.
+struct Fp8Kernel {
+    int scheme_id;
+    int (*launch_comb_a)(const Fp8QuantParams *p, int grid_x, int grid_y, void *stream);
+    int (*launch_prep_w)(const Fp8QuantParams *p, int grid_x, int grid_y, void *stream);
+};
+extern const Fp8Kernel kFp8Kernels[];
+extern const int kFp8KernelCount;
+
 // Offline Combine B into planes whose rows (N/n) and columns (K/k) are padded to multiples of n_gran / k_gran.
 lcma_status prepare_b_planes(bool transposed, int64_t N, int64_t K, const void *B, int64_t ldb, lcma_dtype dtype,
                              const lcma_scheme *scheme, void *Bt, void *stream, int64_t n_gran, int64_t k_gran);

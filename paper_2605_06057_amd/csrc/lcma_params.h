@@ -60,4 +60,30 @@ struct CombHParams {
     uint32_t n_row_b;          // N * element size: columns at or beyond it are never written
 };
 
+// Argument blocks of the FP8 kernels (E4M3 codes, one E8M0 scale byte per 1 x 128 block along K).
+struct Fp8GemmParams {
+    const void *A, *SA, *B, *SB;
+    void *C;
+    uint32_t a_bytes, sa_bytes, b_bytes, sb_bytes, c_bytes; // byte extents (< 2 GiB each; all planes of a batch)
+    uint32_t lda_b, ldb_b;                                  // row pitch of the code matrices in bytes
+    uint32_t lsa_b, lsb_b;                                  // row pitch of the scale matrices in bytes (multiples of 4)
+    uint32_t ldc_b;                                         // row pitch of C in bytes
+    uint32_t a_plane, sa_plane, b_plane, sb_plane, c_plane; // batched: byte step from plane r to r + 1
+    int32_t nx, nz, ny;                                     // tiles along M and N, scale blocks along K
+    int32_t panel;                                          // width (in z tiles) of a column panel of the tile order
+    uint32_t n_row_b;                                       // N * 2: columns of C at or beyond it are never written
+};
+
+struct Fp8QuantParams {
+    const void *X;             // bf16 source, row-major
+    void *Q, *S;               // codes and scale bytes (first plane)
+    uint32_t x_bytes, q_bytes, s_bytes;
+    uint32_t ldx_b;            // row pitch of X in bytes
+    uint32_t x_brow, x_bcol;   // combine kernels: byte step from block (j, l) of X to (j + 1, l) / (j, l + 1)
+    uint32_t ldq_b, lds_b;     // row pitch of a plane of codes / of scale bytes
+    uint32_t q_plane, s_plane; // byte step between planes
+    uint32_t k_row_b;          // K * 2: columns of X at or beyond it read as zero
+    int32_t rows;              // rows of a plane (padded); rows past the extent of X read as zero
+};
+
 } // namespace lcma

@@ -414,7 +414,17 @@ def emit_registry(schemes: dict[str, Scheme], variants: list[Variant]) -> str:
         L.append(f"    {{{SCHEME_IDS[sch]}, {DTYPE_IDS[dt]}, lcma_launch_comb_a_{sch}_{dt}, lcma_launch_comb_h_{sch}_{dt}, {ra}, {rb}, {rh}}},")
     if not stages:
         L.append("    {0, 0, nullptr, nullptr, 0.0, 0.0, 0.0},")
-    L += ["};", f"const int kStageKernelCount = {len(stages)};", "} // namespace lcma", ""]
+    L += ["};", f"const int kStageKernelCount = {len(stages)};"]
+    fp8 = sorted({sch for sch, dt in stages if dt == "bf16"} & {sch for sch, dt in preps if dt == "bf16"})
+    L.append("const Fp8Kernel kFp8Kernels[] = {")
+    for sch in fp8:
+        L.append(f"    {{{SCHEME_IDS[sch]}, lcma_launch_fp8_comb_a_{sch}, lcma_launch_fp8_prep_w_{sch}}},")
+    if not fp8:
+        L.append("    {0, nullptr, nullptr},")
+    L += ["};", f"const int kFp8KernelCount = {len(fp8)};", "} // namespace lcma", ""]
+    for sch in fp8:
+        L.insert(3, f'extern "C" int lcma_launch_fp8_comb_a_{sch}(const lcma::Fp8QuantParams *p, int gx, int gy, void *stream);')
+        L.insert(3, f'extern "C" int lcma_launch_fp8_prep_w_{sch}(const lcma::Fp8QuantParams *p, int gx, int gy, void *stream);')
     for sch, dt in stages:
         L.insert(3, f'extern "C" int lcma_launch_comb_a_{sch}_{dt}(const lcma::PrepParams *p, int gx, int gy, void *stream);')
         L.insert(3, f'extern "C" int lcma_launch_comb_h_{sch}_{dt}(const lcma::CombHParams *p, int gx, int gy, void *stream);')
@@ -466,6 +476,8 @@ def emit_stage(s: Scheme, dtype: str) -> str:
     w = L.append
     w(f"// GENERATED by gen/generate.py - do not edit.  Stand-alone Combine A and Combine H of scheme {s.name} <{s.m},{s.k},{s.n};{s.R}>, dtype {dtype}.")
     w('#include "lcma_combine_h.hpp"')
+    if dtype == "bf16":
+        w('#include "lcma_fp8.hpp"')
     w("namespace {")
     w("using namespace lcma;")
     w("struct CombA {  // block A_{i,l} takes the place of block (j, l) of an N x K weight matrix")
@@ -508,6 +520,17 @@ def emit_stage(s: Scheme, dtype: str) -> str:
     w("    return (int)hipGetLastError();")
     w("}")
     w("")
+    if dtype == "bf16":
+        w("// Combine A with the FP8 quantisation fused in (Eq. 3; E4M3 codes and 1 x 128 power-of-two scales)")
+        w(f'extern "C" __global__ __launch_bounds__(256) void lcma_k_fp8_comb_a_{s.name}(const lcma::Fp8QuantParams p) {{')
+        w("    fp8_combine_quantize_tile<CombA>(p);")
+        w("}")
+        w("")
+        w(f'extern "C" int lcma_launch_fp8_comb_a_{s.name}(const lcma::Fp8QuantParams *p, int gx, int gy, void *stream) {{')
+        w(f"    lcma_k_fp8_comb_a_{s.name}<<<dim3(gx, gy), dim3(256), 0, (hipStream_t)stream>>>(*p);")
+        w("    return (int)hipGetLastError();")
+        w("}")
+        w("")
     w(f'extern "C" __global__ __launch_bounds__(256) void lcma_k_comb_h_{s.name}_{dtype}(const lcma::CombHParams p) {{')
     w(f"    combine_h_tile<{in_t}, {ct_t}, CombH>(p);")
     w("}")
@@ -527,6 +550,8 @@ def emit_prep_b(s: Scheme, dtype: str) -> str:
     w = L.append
     w(f"// GENERATED by gen/generate.py - do not edit.  Offline Combine B of scheme {s.name} <{s.m},{s.k},{s.n};{s.R}>, dtype {dtype}.")
     w('#include "lcma_prepare_b.hpp"')
+    if dtype == "bf16":
+        w('#include "lcma_fp8.hpp"')
     w("namespace {")
     w("using namespace lcma;")
     w("struct Comb {")
@@ -574,6 +599,17 @@ def emit_prep_b(s: Scheme, dtype: str) -> str:
     w(f"    lcma_k_prep_bt_{s.name}_{dtype}<<<dim3(gx, gy), dim3(256), 0, (hipStream_t)stream>>>(*p);")
     w("    return (int)hipGetLastError();")
     w("}")
+    if dtype == "bf16":
+        w("")
+        w("// Combine B for N x K weights with the FP8 quantisation fused in (Eq. 4; E4M3 codes and 1 x 128 power-of-two scales)")
+        w(f'extern "C" __global__ __launch_bounds__(256) void lcma_k_fp8_prep_w_{s.name}(const lcma::Fp8QuantParams p) {{')
+        w("    fp8_combine_quantize_tile<Comb>(p);")
+        w("}")
+        w("")
+        w(f'extern "C" int lcma_launch_fp8_prep_w_{s.name}(const lcma::Fp8QuantParams *p, int gx, int gy, void *stream) {{')
+        w(f"    lcma_k_fp8_prep_w_{s.name}<<<dim3(gx, gy), dim3(256), 0, (hipStream_t)stream>>>(*p);")
+        w("    return (int)hipGetLastError();")
+        w("}")
     return "\n".join(L) + "\n"
 
 
