@@ -204,6 +204,22 @@ lcma_status lcma_gemm_prepared(int64_t M, int64_t N, int64_t K, const void *A, i
  */
 int64_t lcma_unfused_workspace_bytes(int64_t M, int64_t N, int64_t K, lcma_dtype dtype,
                                      const lcma_scheme *scheme);
+/* Split-Group Parallelism (Sec. 3.2) in the batched GEMM of level 1 (16-bit storage) and of lcma_gemm_nt_ws: the steps of all
+ * tile-products are numbered tile-product-major and handed to persistent work-groups in contiguous ranges of
+ * ceil(total / work-groups), so a tile-product may straddle work-groups; a work-group that holds only a piece writes fp32
+ * partial sums to scratch and a second kernel adds the pieces in ascending work-group order (no atomics) and rounds once.
+ * It is used when the time model prefers it to one tile-product per work-group (a poorly filled last round) AND the
+ * workspace holds lcma_split_group_scratch_bytes() bytes beyond lcma_unfused_workspace_bytes(); results on float inputs
+ * then differ from the other schedule in the last bit (the partial sums are cut elsewhere). */
+int64_t lcma_split_group_scratch_bytes(void);
+/* Plain GEMM C = A x W^T for weights stored N x K (as lcma_gemm_nt with scheme == NULL; BF16 and F16) on the kernel of the
+ * batched stage, with a workspace (device, 256-byte aligned, lcma_split_group_scratch_bytes() bytes, overwritten; NULL or
+ * fewer bytes: never split) that lets it hand the steps of all tiles out in Split-Group ranges: the split-K form of a plain
+ * GEMM, chosen when the tiles alone would leave much of the chip idle (few tiles, long K).  K not a multiple of 64 and F32
+ * are passed on to lcma_gemm_nt.  Integer-valued inputs give lcma_gemm_nt's bits; float inputs agree to the last bit or two
+ * (the fp32 sums are cut differently).  Everything else as for lcma_gemm_nt. */
+lcma_status lcma_gemm_nt_ws(int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const void *W, int64_t ldw,
+                            void *C, int64_t ldc, lcma_dtype dtype, void *workspace, int64_t workspace_bytes, void *stream);
 lcma_status lcma_gemm_unfused(int level, int64_t M, int64_t N, int64_t K,
                               const void *A, int64_t lda, const void *B, int64_t ldb,
                               void *C, int64_t ldc, lcma_dtype dtype, const lcma_scheme *scheme,
@@ -312,6 +328,9 @@ double lcma_predict_seconds(int scheme_id, int64_t M, int64_t N, int64_t K, lcma
  *   "panel"            LCMA_PANEL=<n>               width, in tiles, of the column panels of the tile order (default 8)
  *   "batch_order"      LCMA_BATCH_ORDER=1           batched GEMM of lcma_gemm_unfused level 1 in group-major instead of
  *                                                   product-major order
+ *   "schedule"         LCMA_SCHEDULE=static|split   batched GEMM stages: one tile-product per work-group, or contiguous ranges
+ *                                                   of steps per persistent work-group (Sec. 3.2, Split-Group Parallelism);
+ *                                                   default: whichever the time model prefers
  */
 lcma_status lcma_set_tuning(const char *key, const char *value);
 

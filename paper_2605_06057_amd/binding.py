@@ -30,7 +30,7 @@ EXPORTS = [
     "lcma_scheme_name", "lcma_scheme_id_max", "lcma_variant_prepared", "lcma_prepared_b_bytes", "lcma_prepare_b", "lcma_prepare_bt", "lcma_gemm_prepared",
     "lcma_gemm_nt", "lcma_variant_b_layout", "lcma_unfused_workspace_bytes", "lcma_gemm_unfused",
     "lcma_predict_unfused_seconds", "lcma_select_dataflow", "lcma_gemm_ex", "lcma_set_tuning",
-    "lcma_static_scratch_bytes", "lcma_gemm_unfused_static",
+    "lcma_static_scratch_bytes", "lcma_gemm_unfused_static", "lcma_split_group_scratch_bytes", "lcma_gemm_nt_ws",
     "lcma_fp8_code_pitch", "lcma_fp8_scale_pitch", "lcma_fp8_quantize", "lcma_fp8_gemm_nt", "lcma_fp8_prepared_w_bytes",
     "lcma_fp8_prepare_w", "lcma_fp8_workspace_bytes", "lcma_fp8_gemm_lcma",
 ]
@@ -112,6 +112,9 @@ def lib() -> ctypes.CDLL:
         L.lcma_last_error.argtypes = []
         L.lcma_last_error.restype = cp
         L.lcma_set_tuning.argtypes = [cp, cp]
+        L.lcma_gemm_nt_ws.argtypes = [i64, i64, i64, vp, i64, vp, i64, vp, i64, i32, vp, i64, vp]
+        L.lcma_split_group_scratch_bytes.argtypes = []
+        L.lcma_split_group_scratch_bytes.restype = i64
         L.lcma_static_scratch_bytes.argtypes = []
         L.lcma_static_scratch_bytes.restype = i64
         L.lcma_gemm_unfused_static.argtypes = [i32, i64, i64, i64, vp, i64, vp, i64, vp, i64, i32, vp, i32, vp]
@@ -253,6 +256,19 @@ def lcma_gemm_unfused(level: int, A, B, C, scheme: Scheme, workspace, reuse_bt: 
                                    workspace.data_ptr(), workspace.numel() * workspace.element_size(),
                                    int(reuse_bt), stream))
     return C
+
+
+def lcma_gemm_nt_ws(A, W, C, workspace=None):
+    """Plain C = A x W^T (W: N x K) on the plane GEMM; `workspace` (uint8 device tensor) allows the Split-Group schedule."""
+    M, N, K, pa, lda, pw, ldw, pc, ldc, stream = _marshal(A, W, C, True)
+    ws_ptr = workspace.data_ptr() if workspace is not None else None
+    ws_n = workspace.numel() if workspace is not None else 0
+    _check(lib().lcma_gemm_nt_ws(M, N, K, pa, lda, pw, ldw, pc, ldc, _dtype_of(A), ws_ptr, ws_n, stream))
+    return C
+
+
+def lcma_split_group_scratch_bytes() -> int:
+    return int(lib().lcma_split_group_scratch_bytes())
 
 
 def lcma_static_scratch_bytes() -> int:

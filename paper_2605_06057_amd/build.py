@@ -42,11 +42,11 @@ def build(force: bool = False, jobs: int | None = None, verbose: bool = True) ->
     from .gen.generate import generate
 
     hips = generate(GEN)
-    headers = [os.path.join(CSRC, h) for h in ("lcma_device.hpp", "lcma_prepare_b.hpp", "lcma_combine_h.hpp", "lcma_params.h", "host_common.h", "lcma_fp8.hpp")]
+    headers = [os.path.join(CSRC, h) for h in ("lcma_device.hpp", "lcma_prepare_b.hpp", "lcma_combine_h.hpp", "lcma_params.h", "host_common.h", "lcma_fp8.hpp", "lcma_plane_gemm.hpp")]
     headers.append(os.path.join(PKG, "..", "include", "lcma.h"))
     headers.append(os.path.join(GEN, "builtin_schemes.inc"))
     units = [(h, h[:-4] + ".o") for h in hips]
-    for name in ("api.cc", "scheme.cc", "model.cc", "unfused.cc", "lcma_aux.hip", "lcma_static.hip", "lcma_fp8.hip", "fp8_api.cc"):
+    for name in ("api.cc", "scheme.cc", "model.cc", "unfused.cc", "lcma_aux.hip", "lcma_static.hip", "lcma_fp8.hip", "fp8_api.cc", "lcma_plane_gemm.hip", "plane_gemm.cc"):
         units.append((os.path.join(CSRC, name), os.path.join(GEN, os.path.splitext(name)[0] + ".o")))
     units.append((os.path.join(GEN, "registry.cc"), os.path.join(GEN, "registry.o")))
     jobs = jobs or min(8, os.cpu_count() or 1)

@@ -5,10 +5,6 @@
 #include <cstring>
 
 extern "C" int lcma_launch_fp8_quantize_rows(const lcma::Fp8QuantParams *p, int gx, int gy, void *stream);
-extern "C" int lcma_launch_fp8_gemm_t256x256_bf16(const lcma::Fp8GemmParams *p, int grid, void *stream);
-extern "C" int lcma_launch_fp8_gemm_t128x128_bf16(const lcma::Fp8GemmParams *p, int grid, void *stream);
-extern "C" int lcma_launch_fp8_gemm_t256x256_f16g(const lcma::Fp8GemmParams *p, int grid, void *stream);
-extern "C" int lcma_launch_fp8_gemm_t128x128_f16g(const lcma::Fp8GemmParams *p, int grid, void *stream);
 
 namespace lcma {
 namespace {
@@ -108,12 +104,9 @@ extern "C" lcma_status lcma_fp8_gemm_nt(int64_t M, int64_t N, int64_t K, const v
         return fail(LCMA_ERR_ARG, "%s: code matrices and C must be 16-byte aligned (ldc a multiple of 8), scale matrices 4-byte aligned", who);
     if (K % 8 || N % 8) return fail(LCMA_ERR_SHAPE, "%s: N = %lld and K = %lld must be multiples of 8", who, (long long)N, (long long)K);
     const int64_t kp = round_up(K, 128), ls = round_up(kp / 128, 4);
-    const bool big = ((M + 255) / 256) * ((N + 255) / 256) >= 200;
-    const int tm = big ? 256 : 128;
-    const int64_t nx = (M + tm - 1) / tm, nz = (N + tm - 1) / tm;
-    if (nx * tm * kp >= kLim || nz * tm * kp >= kLim || ((nx * tm - 1) * ldc + nz * tm) * 2 >= kLim || nx * nz >= kLim)
+    if ((round_up(M, 256) * kp) >= kLim || (round_up(N, 256) * kp) >= kLim || ((round_up(M, 256) - 1) * ldc + round_up(N, 256)) * 2 >= kLim)
         return fail(LCMA_ERR_SHAPE, "%s: a matrix spans 2 GiB or more", who);
-    Fp8GemmParams p;
+    PlaneGemmParams p;
     std::memset(&p, 0, sizeof p);
     p.A = Aq;
     p.SA = Sa;
@@ -128,16 +121,9 @@ extern "C" lcma_status lcma_fp8_gemm_nt(int64_t M, int64_t N, int64_t K, const v
     p.lda_b = p.ldb_b = (uint32_t)kp;
     p.lsa_b = p.lsb_b = (uint32_t)ls;
     p.ldc_b = (uint32_t)(ldc * 2);
-    p.nx = (int32_t)nx;
-    p.nz = (int32_t)nz;
     p.ny = (int32_t)(kp / 128);
-    const int panel = tuning_panel();
-    p.panel = panel < p.nz ? panel : p.nz;
     p.n_row_b = (uint32_t)(N * 2);
-    const int err = big ? lcma_launch_fp8_gemm_t256x256_bf16(&p, (int)(nx * nz), stream)
-                        : lcma_launch_fp8_gemm_t128x128_bf16(&p, (int)(nx * nz), stream);
-    if (err) return fail(LCMA_ERR_HIP, "%s: launch failed with HIP error %d", who, err);
-    return LCMA_OK;
+    return plane_gemm(who, PG_FP8_BF16, p, 1, M, N, 0, 1, nullptr, 0, stream);
 }
 
 extern "C" int64_t lcma_fp8_prepared_w_bytes(const lcma_scheme *scheme, int64_t N, int64_t K) {
@@ -149,7 +135,7 @@ extern "C" int64_t lcma_fp8_prepared_w_bytes(const lcma_scheme *scheme, int64_t 
 extern "C" int64_t lcma_fp8_workspace_bytes(const lcma_scheme *scheme, int64_t M, int64_t N, int64_t K) {
     if (!scheme || M <= 0 || N <= 0 || K <= 0) return -1;
     const Fp8Geometry g = fp8_geometry(*scheme, M, N, K);
-    return g.aq + g.as + g.h;
+    return g.aq + g.as + g.h + plane_gemm_scratch_bytes(256);
 }
 
 namespace {
@@ -217,9 +203,10 @@ extern "C" lcma_status lcma_fp8_gemm_lcma(int64_t M, int64_t N, int64_t K, const
                                   "workspace 256-byte aligned", who);
     if (K % 8 || N % 8) return fail(LCMA_ERR_SHAPE, "%s: N = %lld and K = %lld must be multiples of 8", who, (long long)N, (long long)K);
     const Fp8Geometry g = fp8_geometry(*scheme, M, N, K);
-    if (workspace_bytes < g.aq + g.as + g.h)
+    const int64_t need = g.aq + g.as + g.h + plane_gemm_scratch_bytes(256);
+    if (workspace_bytes < need)
         return fail(LCMA_ERR_ARG, "%s: the workspace holds %lld bytes, %lld are needed", who, (long long)workspace_bytes,
-                    (long long)(g.aq + g.as + g.h));
+                    (long long)need);
     const int R = scheme->R;
     if (g.aq >= kLim || g.wq >= kLim || g.h >= kLim || ((g.bm * scheme->m - 1) * ldc + g.bn * scheme->n) * 2 >= kLim)
         return fail(LCMA_ERR_SHAPE, "%s: a matrix or a set of planes spans 2 GiB or more", who);
@@ -230,9 +217,7 @@ extern "C" lcma_status lcma_fp8_gemm_lcma(int64_t M, int64_t N, int64_t K, const
                                                 scheme->k, Aq, Sa, stream))
         return st;
     // stage 3: the R products H_r = At_r x Bt_r (Eq. 5) as one batched launch on the codes, product-major order
-    const bool big = g.bm % 256 == 0 && g.bn % 256 == 0 && (int64_t)R * (g.bm / 256) * (g.bn / 256) >= 200;
-    const int tm = big ? 256 : 128;
-    Fp8GemmParams p;
+    PlaneGemmParams p;
     std::memset(&p, 0, sizeof p);
     p.A = Aq;
     p.SA = Sa;
@@ -252,17 +237,10 @@ extern "C" lcma_status lcma_fp8_gemm_lcma(int64_t M, int64_t N, int64_t K, const
     p.b_plane = (uint32_t)(g.bn * g.bk);
     p.sb_plane = (uint32_t)(g.bn * g.ls);
     p.c_plane = (uint32_t)(g.bm * g.bn * 2);
-    p.nx = (int32_t)(g.bm / tm);
-    p.nz = (int32_t)(g.bn / tm);
     p.ny = (int32_t)(g.bk / 128);
-    const int panel = tuning_panel();
-    p.panel = panel < p.nz ? panel : p.nz;
     p.n_row_b = (uint32_t)(g.bn * 2);
-    const int64_t grid = (int64_t)R * p.nx * p.nz;
-    if (grid >= kLim) return fail(LCMA_ERR_SHAPE, "%s: too many tiles", who);
-    if (const int err = big ? lcma_launch_fp8_gemm_t256x256_f16g(&p, (int)grid, stream)
-                            : lcma_launch_fp8_gemm_t128x128_f16g(&p, (int)grid, stream))
-        return fail(LCMA_ERR_HIP, "%s: GEMM launch failed with HIP error %d", who, err);
+    if (const lcma_status st = plane_gemm(who, PG_FP8_F16, p, R, g.bm, g.bn, 0, 0, H + g.h, plane_gemm_scratch_bytes(256), stream))
+        return st;
     // stage 4: Combine H (Eq. 6): fp32 sums of the fp16 products in ascending r, one rounding to bf16
     const StageKernel *sk = find_stage_bf16(scheme->builtin);
     CombHParams h;

@@ -61,17 +61,24 @@ struct CombHParams {
 };
 
 // Argument blocks of the FP8 kernels (E4M3 codes, one E8M0 scale byte per 1 x 128 block along K).
-struct Fp8GemmParams {
-    const void *A, *SA, *B, *SB;
+// Argument block of the plane GEMM (csrc/lcma_plane_gemm.hpp): k-contiguous operands, FP8 codes with scale bytes or
+// 16-bit elements, plain or batched over planes, handed out in contiguous ranges of steps (Sec. 3.2, Split-Group).
+struct PlaneGemmParams {
+    const void *A, *SA, *B, *SB;                            // SA, SB: scale bytes (FP8 only)
     void *C;
     uint32_t a_bytes, sa_bytes, b_bytes, sb_bytes, c_bytes; // byte extents (< 2 GiB each; all planes of a batch)
-    uint32_t lda_b, ldb_b;                                  // row pitch of the code matrices in bytes
+    uint32_t lda_b, ldb_b;                                  // row pitch of the operands in bytes
     uint32_t lsa_b, lsb_b;                                  // row pitch of the scale matrices in bytes (multiples of 4)
     uint32_t ldc_b;                                         // row pitch of C in bytes
     uint32_t a_plane, sa_plane, b_plane, sb_plane, c_plane; // batched: byte step from plane r to r + 1
-    int32_t nx, nz, ny;                                     // tiles along M and N, scale blocks along K
+    int32_t nx, nz, ny;                                     // tiles along M and N; steps of 128 bytes along K
     int32_t panel;                                          // width (in z tiles) of a column panel of the tile order
     uint32_t n_row_b;                                       // N * 2: columns of C at or beyond it are never written
+    int32_t jobs;                                           // tile-products: planes * nx * nz
+    int32_t units;                                          // persistent work-groups launched
+    int64_t cap;                                            // steps per work-group: ceil(jobs * ny / units)
+    void *partial;                                          // fp32 scratch for pieces: 2 slots of TM * TN floats per work-group
+                                                            // (never touched when cap is a multiple of ny)
 };
 
 struct Fp8QuantParams {

@@ -93,6 +93,8 @@ extern "C" int64_t lcma_unfused_workspace_bytes(int64_t M, int64_t N, int64_t K,
     return geometry(*scheme, M, N, K, dtype).total();
 }
 
+extern "C" int64_t lcma_split_group_scratch_bytes(void) { return plane_gemm_scratch_bytes(256); }
+
 // Algorithm 1 priced stage by stage: the three memory-bound kernels at the rates measured for the scheme, the
 // batched GEMM in rounds of work-groups.
 extern "C" double lcma_predict_unfused_seconds(int scheme_id, int64_t M, int64_t N, int64_t K, lcma_dtype dtype,
@@ -233,9 +235,32 @@ lcma_status lcma::gemm_unfused(const char *who, int level, int64_t M, int64_t N,
         p.ldc_b = (uint32_t)(g.bn * es);
         p.c_brow = (uint32_t)(g.bm * g.bn * es);
         p.n_row_b = (uint32_t)(g.bn * es);
-        const int64_t grid = (int64_t)R * p.nx * p.nz;
-        if (const int err = gemm->launch(&p, (int)grid, stream))
-            return fail(LCMA_ERR_HIP, "%s: launch of %s failed with HIP error %d", who, gemm->name, err);
+        if (es == 2 && !forced_unfused_variant() && !p.batch_order) {
+            // 16-bit: the plane GEMM, which can hand the tile-products out in Split-Group ranges (Sec. 3.2) when the
+            // workspace has room for the pieces beyond the planes
+            PlaneGemmParams q;
+            std::memset(&q, 0, sizeof q);
+            q.A = At;
+            q.B = Bt;
+            q.C = H;
+            q.a_bytes = p.a_bytes;
+            q.b_bytes = p.b_bytes;
+            q.c_bytes = p.c_bytes;
+            q.lda_b = q.ldb_b = p.lda_b;
+            q.ldc_b = p.ldc_b;
+            q.a_plane = p.a_brow;
+            q.b_plane = p.b_brow;
+            q.c_plane = p.c_brow;
+            q.ny = (int32_t)(g.bk * es / 128);
+            q.n_row_b = p.n_row_b;
+            if (const lcma_status st = plane_gemm(who, PG_F16, q, R, g.bm, g.bn, 0, 0, H + g.h_bytes,
+                                                  workspace_bytes - g.total(), stream))
+                return st;
+        } else {
+            const int64_t grid = (int64_t)R * p.nx * p.nz;
+            if (const int err = gemm->launch(&p, (int)grid, stream))
+                return fail(LCMA_ERR_HIP, "%s: launch of %s failed with HIP error %d", who, gemm->name, err);
+        }
         // stage 4: Combine H (Eq. 6)
         CombHParams h;
         h.H = H;

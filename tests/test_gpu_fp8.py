@@ -205,3 +205,39 @@ def test_fp8_argument_checks(B):
     assert L.lcma_fp8_gemm_nt(8, 16, 0, None, None, None, None, c.data_ptr(), 16, None) == B.LCMA_OK
     torch.cuda.synchronize()
     assert torch.all(c == 0).item()
+
+
+@pytest.mark.parametrize("name,shape", [("strassen", (300, 272, 528)), ("strassen", (1024, 1536, 4096)), ("laderman", (768, 768, 1536))])
+def test_split_group_schedule_gives_the_same_product(B, name, shape):
+    """The batched GEMM handed out as contiguous ranges of steps to persistent work-groups (Sec. 3.2, Split-Group: a
+    tile-product straddles work-groups, pieces are added in a fixed order by a second kernel) against one tile-product per
+    work-group: identical bits on integer inputs (every partial sum is exact), equal within the accumulation allowance
+    on float inputs."""
+    import torch
+    import gpu_util as G
+    s, h = S.by_name(name), B.lcma_scheme_load("builtin:" + name)
+    M, N, K = shape
+    lo, hi = (-2, 2) if name == "laderman" else (-3, 3)
+    Ai, Wi = inp.integers(61, 1, (M, K), lo, hi), inp.integers(61, 2, (N, K), lo, hi)
+    rng = np.random.default_rng(M)
+    Af, Wf = bf16_values(rng.standard_normal((M, K))), bf16_values(rng.standard_normal((N, K)) * 0.02)
+    ws = torch.empty((B.lcma_fp8_workspace_bytes(h, M, N, K),), dtype=torch.uint8, device="cuda")
+    out = {}
+    try:
+        for sched in ("static", "split"):
+            B.lcma_set_tuning("schedule", sched)
+            for tag, (A, W) in (("int", (Ai.astype(np.float64), Wi.astype(np.float64))), ("float", (Af, Wf))):
+                Wp = B.lcma_fp8_prepare_w(bf16_dev(W), h)
+                c = torch.full((M, N), float("nan"), dtype=torch.bfloat16, device="cuda")
+                print(f"fp8 lcma {name} {M}x{N}x{K} schedule {sched} {tag}", flush=True)
+                B.lcma_fp8_gemm_lcma(bf16_dev(A), Wp, c, h, ws)
+                torch.cuda.synchronize()
+                out[(sched, tag)] = G.to_host_stored(c, "bf16")
+    finally:
+        B.lcma_set_tuning("schedule", "")
+    want = inp.store((Ai @ Wi.T).astype(np.float64), "bf16")
+    assert np.array_equal(out[("static", "int")], want)
+    assert np.array_equal(out[("split", "int")], want)
+    a, b = inp.widen(out[("static", "float")], "bf16"), inp.widen(out[("split", "float")], "bf16")
+    assert not np.isnan(b).any()
+    assert oracle.rel_frobenius(b, a) <= 2.4e-3 + FP8_ACC_TOL      # two independent roundings to bf16 of nearly equal sums
