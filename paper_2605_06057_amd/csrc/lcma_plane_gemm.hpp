@@ -3,11 +3,15 @@
 // Eq. 5 in Algorithm 1), with the work handed out the way the paper's Split-Group Parallelism does (Sec. 3.2).
 //
 // Data path.  A step is 128 bytes of every row of the tile (128 FP8 or 64 16-bit elements of K), two LDS stages, one
-// barrier per step.  Both operands travel global -> registers -> LDS in 16-byte chunks (XOR-swizzled): the loads of
-// step y + 1 are in flight while step y is multiplied and are written to the other stage at the start of step y + 1.
-// DIRECT (kept for comparison) sends them from memory straight into LDS instead (buffer loads with the LDS bit: no
-// staging registers, no LDS write instructions; the swizzle is applied by choosing which chunk of memory each lane
-// fetches); measured on MI355X it is the slower of the two here (FP8, 8192 x 14336 x 4096: 1.62 against 1.99 PFLOP/s).
+// barrier per step.  Both operands travel from memory straight into LDS (buffer loads with the LDS bit: no staging
+// registers, no LDS write instructions; the swizzle is applied by choosing which 16-byte chunk of memory each lane
+// fetches): the loads of step y + 1 are issued at the start of step y into the stage that step y - 1 read, and must
+// have landed at the barrier that ends step y.  Three things decide the speed of this loop on MI355X (each measured
+// in one run against the alternative): the matrix instructions must be pinned above the wait for the loads (they touch
+// no memory, so the compiler otherwise sinks them below it and the wait follows the issue of the loads directly:
+// -20 %); the scale bytes must come as one dword per four steps, not as a byte load per step (six more vector memory
+// instructions per wave and step: -20 %; the vector memory path is the busy one); direct loads beat staging through
+// registers (DIRECT = false, kept for comparison) by 6 % for 16-bit operands and 1 % for FP8.
 //
 // Scheduling (Sec. 3.2).  The unit of work is one step of one tile-product; all steps of all tile-products are
 // numbered tile-product-major (tile-products in product-major order, the paper's Cache-Aware order: work-groups that
@@ -33,7 +37,7 @@ struct FP8 { // E4M3 codes; one E8M0 scale byte per row and step
     static constexpr int ES = 1;
 };
 
-template <class KIND, int TM, int TN, int WGM, int WGN, class OUT, bool SPLIT = true, bool DIRECT = false> struct PlaneGemm {
+template <class KIND, int TM, int TN, int WGM, int WGN, class OUT, bool SPLIT = true, bool DIRECT = true> struct PlaneGemm {
     static constexpr int NT = 64 * WGM * WGN, WM = TM / WGM, WN = TN / WGN, NMI = WM / 32, NNI = WN / 32;
     static constexpr int ROW = 128, A_STAGE = TM * ROW, B_STAGE = TN * ROW, STAGE = A_STAGE + B_STAGE;
     static constexpr int LDS_BYTES = 2 * STAGE;
@@ -257,14 +261,16 @@ template <class KIND, int TM, int TN, int WGM, int WGN, class OUT, bool SPLIT = 
             if constexpr (DIRECT) {
                 issue(s, lds, a_base, b_base, y0);
                 landed_barrier();
-                for (int y = y0; y < y1; ++y) {
-                    const int st = (y - y0) & 1;
+                auto one = [&](int y, int st) {
                     int sa[NMI], sb[NNI];
                     turn_scales(y);
                     scales_of(y, sa, sb);
                     step(s, lds + st * STAGE, lds + (st ^ 1) * STAGE, a_base, b_base, y + 1, y + 1 < y1, sa, sb, acc);
                     landed_barrier();
-                }
+                };
+                // the stage alternates from 0 at the first step of the piece and stays a run-time value: two unrolled
+                // copies with literal stages gain nothing for 16-bit operands and cost the FP8 kernel 10 % (registers)
+                for (int y = y0; y < y1; ++y) one(y, (y - y0) & 1);
             } else {
                 u32x4 rega[QA], regb[QB];
                 auto fetch = [&](int y) {
