@@ -236,6 +236,9 @@ def main():
                     help="also time the dataflows the paper starts from (lcma_gemm_unfused): Algorithm 1 (four stages "
                          "through device memory) and Algorithm 2 as printed (Combine A/B materialised, GEMM + Combine H "
                          "fused), each with Combine B per call and with Combine B done once (static weights)")
+    ap.add_argument("--fp8", action="store_true",
+                    help="also time the FP8 E4M3 workflow with 1 x 128 block scales on the same bf16 matrices: quantise + "
+                         "block-scaled GEMM against the LCMA form with the quantisation fused into Combine A")
     ap.add_argument("--no-extras", action="store_true",
                     help="time lcma_gemm, the plain and the vendor GEMM only (by default the prepared-B, weight-layout "
                          "and ablation legs run too; each adds about a second)")
@@ -248,7 +251,7 @@ def main():
     if args.selector_sweep:
         return selector_sweep(args)
     if not args.no_extras:
-        args.prepared_b = args.weight_layout = args.ablation = True
+        args.prepared_b = args.weight_layout = args.ablation = args.fp8 = True
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU (the path would shard over M with no exchange between "
                  "GPUs, each running this same kernel on its rows). Re-run with --gpus 1.")
@@ -350,15 +353,58 @@ def main():
         nk = {"lcma_tflops": flops / (n_wall_ms * 1e-3) / 1e12, "lcma_kernel_ms": n_ev_ms,
               "plain_mfma_gemm_tflops": flops / (np_wall_ms * 1e-3) / 1e12,
               "vendor_gemm_tflops": flops / (nv_wall_ms * 1e-3) / 1e12}
+        if dt != "f32":  # the plane GEMM (direct loads into LDS; Split-Group schedule where its model prefers it)
+            sg = torch.empty((B.lcma_split_group_scratch_bytes(),), dtype=torch.uint8, device="cuda")
+            pg_wall_ms, _, _ = timed(lambda i: B.lcma_gemm_nt_ws(sets[i % 3][0], ws[i % 3], sets[i % 3][2], sg), args.steps, args.warmup)
+            nk["plain_plane_gemm_tflops"] = flops / (pg_wall_ms * 1e-3) / 1e12
+            del sg
         nt_step(0)
         torch.cuda.synchronize()
         nk["_c"] = sets[0][2].clone()
+    fp8 = None
+    if args.fp8 and dt == "bf16" and scheme_name in ("strassen", "strassen2", "laderman"):
+        # The FP8 workflow of the paper (Sec. 4.1: bf16 operands, E4M3 with 1 x 128 block scales; Sec. 4.3: quantisation
+        # fused into Combine A).  Weights are static: quantised (plain) or combined and quantised (LCMA) once, untimed.
+        # A step of the plain workflow quantises A and multiplies; a step of the LCMA form runs Combine A with the
+        # quantisation fused in, the batched block-scaled GEMM and Combine H.
+        wt = [b.t().contiguous() for _, b, _ in sets]
+        qw = [B.lcma_fp8_quantize(w) for w in wt]
+        qa = [B.lcma_fp8_quantize(a) for a, _, _ in sets]
+        wp = [B.lcma_fp8_prepare_w(w, scheme) for w in wt]
+        wsf = torch.empty((B.lcma_fp8_workspace_bytes(scheme, M, N, K),), dtype=torch.uint8, device="cuda")
+
+        def fp8_plain_step(i):
+            j = i % 3
+            B.lcma_fp8_quantize(sets[j][0], qa[j][0], qa[j][1])
+            B.lcma_fp8_gemm_nt(qa[j][0], qa[j][1], qw[j][0], qw[j][1], sets[j][2], K)
+
+        def fp8_gemm_step(i):
+            j = i % 3
+            B.lcma_fp8_gemm_nt(qa[j][0], qa[j][1], qw[j][0], qw[j][1], sets[j][2], K)
+
+        def fp8_lcma_step(i):
+            j = i % 3
+            B.lcma_fp8_gemm_lcma(sets[j][0], wp[j], sets[j][2], scheme, wsf)
+        fp_wall, _, _ = timed(fp8_plain_step, args.steps, args.warmup)
+        fg_wall, fg_ev, _ = timed(fp8_gemm_step, args.steps, args.warmup)
+        fl_wall, _, _ = timed(fp8_lcma_step, args.steps, args.warmup)
+        fp8 = {"plain_workflow_tflops": flops / (fp_wall * 1e-3) / 1e12, "plain_gemm_only_tflops": flops / (fg_wall * 1e-3) / 1e12,
+               "lcma_tflops": flops / (fl_wall * 1e-3) / 1e12, "lcma_vs_plain_workflow": fp_wall / fl_wall,
+               "lcma_frac_of_dense_fp8_peak": flops / (fl_wall * 1e-3) / 1e12 / 5000.0,
+               "lcma_frac_of_dense_bf16_peak": flops / (fl_wall * 1e-3) / 1e12 / 2500.0,
+               "gemm_roofline": {"bound": "mfma", "achieved": flops / (fg_ev * 1e-3) / 1e12, "peak": 5000.0, "unit": "TFLOP/s",
+                                 "frac": flops / (fg_ev * 1e-3) / 1e12 / 5000.0}}
+        fp8_lcma_step(0)
+        fp8_plain_step(1)
+        torch.cuda.synchronize()
+        fp8["_c"], fp8["_cp"] = sets[0][2].clone(), sets[1][2].clone()
+        del wt, qw, qa, wp, wsf
     ablation = None
     if args.ablation and B.lib().lcma_gemm_unfused(1, 0, 0, 0, None, 0, None, 0, None, 0, B.DTYPE_IDS[dt], scheme.handle,
                                                    None, 0, 0, None) == B.LCMA_ERR_NOKERNEL:
         args.ablation = False  # no stage kernels for this scheme (an empty call answers before anything is launched)
     if args.ablation:
-        nbytes = B.lcma_unfused_workspace_bytes(scheme, M, N, K, B.DTYPE_IDS[dt])
+        nbytes = B.lcma_unfused_workspace_bytes(scheme, M, N, K, B.DTYPE_IDS[dt]) + B.lcma_split_group_scratch_bytes()
         ws = torch.empty((nbytes,), dtype=torch.uint8, device="cuda")
         ablation = {"workspace_bytes": nbytes}
         for level, key in ((1, "algorithm1"), (2, "algorithm2_as_printed")):
@@ -401,6 +447,9 @@ def main():
             prepared["rel_frobenius_error"] = oracle.rel_frobenius(host(prepared["_c"]), ref)
         if nk:
             nk["rel_frobenius_error"] = oracle.rel_frobenius(host(nk["_c"]), ref)
+        if fp8:  # against the UNQUANTISED product: what the FP8 formats cost, plain and LCMA
+            fp8["rel_frobenius_error"] = {"lcma": oracle.rel_frobenius(host(fp8["_c"]), ref),
+                                          "plain": oracle.rel_frobenius(host(fp8["_cp"]), ref)}
         if ablation:
             for key in ("algorithm1", "algorithm2_as_printed"):
                 ablation[key + "_rel_frobenius_error"] = oracle.rel_frobenius(host(ablation["_c" + key]), ref)
@@ -418,6 +467,9 @@ def main():
         prepared.pop("_c")
     if nk:
         nk.pop("_c")
+    if fp8:
+        fp8.pop("_c")
+        fp8.pop("_cp")
     if ablation:
         ablation = {k: v for k, v in ablation.items() if not k.startswith("_c")}
     mfma_flops = flops * info["R"] / (info["m"] * info["k"] * info["n"])
@@ -445,8 +497,10 @@ def main():
         out["weight_layout_nk"] = nk
     if ablation:
         out["ablation_unfused_dataflows"] = ablation
+    if fp8:
+        out["fp8_e4m3_block_scaled"] = fp8
     if not args.no_others and not args.variant:
-        sets = bts = ws = None  # release the device buffers of the main workload
+        sets = bts = ws = wt = None  # release the device buffers of the main workload
         torch.cuda.empty_cache()
         others = [w for w in ("strassen_bf16_4096", "strassen2_bf16_ffn", "laderman_f16_6144", "strassen_f32_4096",
                               "strassen_bf16_ffn") if w != args.workload][:4]
