@@ -98,6 +98,18 @@ lcma_status lcma_gemm(int64_t M, int64_t N, int64_t K,
                       void *C, int64_t ldc, lcma_dtype dtype,
                       const lcma_scheme *scheme, void *stream);
 
+/* Range guard for BF16 storage.  The LCMA kernels (every scheme != NULL, and lcma_gemm_unfused) convert bf16 inputs to
+ * fp16, form the combinations of Eq. 3 / Eq. 4 and multiply in fp16.  That is exact for magnitudes in [2^-14, 32752];
+ * outside it: a magnitude above 65504 is replaced by 65504 (the conversion rounds toward zero), a two-term sum of values
+ * above 32752 can reach fp16 infinity (C then holds Inf or NaN), and a non-zero magnitude below 2^-14 lands in fp16's
+ * subnormal range and loses low bits (below 2^-24: becomes zero).  Nothing is signalled.  The plain GEMM (scheme ==
+ * NULL) multiplies bf16 as it is and has no such limit, and the FP8 path scales per block.  A caller that cannot vouch
+ * for the range runs this check (once for static weights) and takes the plain GEMM when a flag comes back:
+ * lcma_fp16_range_flags writes to the device word *flags (asynchronously on `stream`): bit 0 = some |x| > 32752 (or Inf /
+ * NaN), bit 1 = some 0 < |x| < 2^-14.  X: rows x cols bf16, ld in elements (multiple of 8), 16-byte aligned, cols a
+ * multiple of 8.  One pass over X at memory speed.  Errors: ARG, SHAPE, HIP. */
+lcma_status lcma_fp16_range_flags(int64_t rows, int64_t cols, const void *X, int64_t ld, void *flags, void *stream);
+
 /* lcma_gemm with the right operand given the way a linear layer stores its weight (the operand the
  * paper's end-to-end evaluation multiplies by): W is N x K row-major, ldw in elements, and
  * C[M x N] = A[M x K] x W^T, that is B[k][n] = W[n][k] in Eq. 1.  Everything else (types, sizes,

@@ -30,7 +30,7 @@ EXPORTS = [
     "lcma_scheme_name", "lcma_scheme_id_max", "lcma_variant_prepared", "lcma_prepared_b_bytes", "lcma_prepare_b", "lcma_prepare_bt", "lcma_gemm_prepared",
     "lcma_gemm_nt", "lcma_variant_b_layout", "lcma_unfused_workspace_bytes", "lcma_gemm_unfused",
     "lcma_predict_unfused_seconds", "lcma_select_dataflow", "lcma_gemm_ex", "lcma_set_tuning",
-    "lcma_static_scratch_bytes", "lcma_gemm_unfused_static", "lcma_split_group_scratch_bytes", "lcma_gemm_nt_ws",
+    "lcma_static_scratch_bytes", "lcma_gemm_unfused_static", "lcma_split_group_scratch_bytes", "lcma_gemm_nt_ws", "lcma_fp16_range_flags",
     "lcma_fp8_code_pitch", "lcma_fp8_scale_pitch", "lcma_fp8_quantize", "lcma_fp8_gemm_nt", "lcma_fp8_prepared_w_bytes",
     "lcma_fp8_prepare_w", "lcma_fp8_workspace_bytes", "lcma_fp8_gemm_lcma",
 ]
@@ -113,6 +113,7 @@ def lib() -> ctypes.CDLL:
         L.lcma_last_error.restype = cp
         L.lcma_set_tuning.argtypes = [cp, cp]
         L.lcma_gemm_nt_ws.argtypes = [i64, i64, i64, vp, i64, vp, i64, vp, i64, i32, vp, i64, vp]
+        L.lcma_fp16_range_flags.argtypes = [i64, i64, vp, i64, vp, vp]
         L.lcma_split_group_scratch_bytes.argtypes = []
         L.lcma_split_group_scratch_bytes.restype = i64
         L.lcma_static_scratch_bytes.argtypes = []
@@ -265,6 +266,16 @@ def lcma_gemm_nt_ws(A, W, C, workspace=None):
     ws_n = workspace.numel() if workspace is not None else 0
     _check(lib().lcma_gemm_nt_ws(M, N, K, pa, lda, pw, ldw, pc, ldc, _dtype_of(A), ws_ptr, ws_n, stream))
     return C
+
+
+def lcma_fp16_range_flags(X) -> int:
+    """Bit 0: some |x| > 32752 in the bf16 device tensor X; bit 1: some 0 < |x| < 2^-14 (synchronises to read the word)."""
+    import torch
+    assert X.is_cuda and X.dtype == torch.bfloat16 and X.dim() == 2 and X.stride(1) == 1
+    flags = torch.empty((1,), dtype=torch.int32, device=X.device)
+    stream = torch.cuda.current_stream(X.device).cuda_stream
+    _check(lib().lcma_fp16_range_flags(X.shape[0], X.shape[1], X.data_ptr(), X.stride(0), flags.data_ptr(), stream))
+    return int(flags.item())
 
 
 def lcma_split_group_scratch_bytes() -> int:

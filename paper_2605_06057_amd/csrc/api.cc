@@ -434,6 +434,19 @@ extern "C" const char *lcma_status_str(lcma_status st) {
 
 extern "C" const char *lcma_last_error(void) { return g_error; }
 
+extern "C" lcma_status lcma_fp16_range_flags(int64_t rows, int64_t cols, const void *X, int64_t ld, void *flags, void *stream) {
+    const char *who = "lcma_fp16_range_flags";
+    if (rows < 0 || cols < 0) return fail(LCMA_ERR_ARG, "%s: negative size", who);
+    if (!flags || ((uintptr_t)flags & 3)) return fail(LCMA_ERR_ARG, "%s: flags must be a 4-byte aligned device pointer", who);
+    if (rows && cols) {
+        if (!X || ((uintptr_t)X & 15) || ((ld * 2) & 15) || ld < cols) return fail(LCMA_ERR_ARG, "%s: X must be 16-byte aligned, ld a multiple of 8 and at least the row", who);
+        if (cols % 8) return fail(LCMA_ERR_SHAPE, "%s: the row must be a multiple of 8 elements", who);
+    }
+    if (const int err = lcma_launch_range_flags_bf16(X, rows && cols ? rows : 0, cols * 2, ld * 2, flags, stream))
+        return fail(LCMA_ERR_HIP, "%s: launch failed with HIP error %d", who, err);
+    return LCMA_OK;
+}
+
 extern "C" lcma_status lcma_set_tuning(const char *key, const char *value) {
     if (!key) return fail(LCMA_ERR_ARG, "lcma_set_tuning: null key");
     init_tuning();

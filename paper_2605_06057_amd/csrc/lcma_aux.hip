@@ -31,7 +31,41 @@ __global__ __launch_bounds__(256) void scale_c(char *C, int64_t rows, uint32_t r
     }
     *ptr = out;
 }
+// Range guard for bf16 storage (the LCMA kernels form and multiply their combinations in fp16): bit 0 of *flags is set
+// when some magnitude exceeds 32752 (half the largest fp16 value: a two-term sum may overflow; beyond 65504 the
+// conversion itself saturates), bit 1 when some non-zero magnitude is below 2^-14 (fp16 subnormal range: low bits of
+// the 8-bit significand are dropped).  One 16-byte vector per thread and iteration; one atomic OR per wave that found
+// something.
+__global__ __launch_bounds__(256) void range_flags_bf16(const char *X, int64_t rows, uint32_t row_bytes, int64_t ld_bytes, uint32_t *flags) {
+    uint32_t found = 0;
+    const int64_t vecs_per_row = row_bytes / 16, total = rows * vecs_per_row;
+    for (int64_t v = (int64_t)blockIdx.x * 256 + threadIdx.x; v < total; v += (int64_t)gridDim.x * 256) {
+        const int64_t row = v / vecs_per_row, c = v - row * vecs_per_row;
+        const u32x4 raw = *(const u32x4 *)(X + row * ld_bytes + c * 16);
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const uint32_t mag = (h ? raw[e] >> 16 : raw[e] & 0xffffu) & 0x7fffu; // bf16 magnitude bits
+                if (mag > 0x46ffu) found |= 1u;              // > 32752 (0x46FF is 32640, the largest bf16 not above 32752), Inf, NaN
+                if (mag != 0 && mag < 0x3880u) found |= 2u;  // < 2^-14 (0x3880)
+            }
+    }
+    if (found) atomicOr(flags, found);
+}
+__global__ void zero_word(uint32_t *w) { *w = 0; }
 } // namespace
+
+extern "C" int lcma_launch_range_flags_bf16(const void *X, int64_t rows, int64_t row_bytes, int64_t ld_bytes, void *flags, void *stream) {
+    const hipStream_t st = (hipStream_t)stream;
+    zero_word<<<1, 1, 0, st>>>((uint32_t *)flags);
+    const int64_t total = rows * (row_bytes / 16);
+    if (total == 0) return (int)hipGetLastError();
+    int64_t grid = (total + 255) / 256;
+    if (grid > 4096) grid = 4096;
+    range_flags_bf16<<<dim3((unsigned)grid), dim3(256), 0, st>>>((const char *)X, rows, (uint32_t)row_bytes, ld_bytes, (uint32_t *)flags);
+    return (int)hipGetLastError();
+}
 
 extern "C" int lcma_launch_scale_c(void *C, int64_t rows, int64_t row_bytes, int64_t ld_bytes, int dtype, float beta,
                                    void *stream) {

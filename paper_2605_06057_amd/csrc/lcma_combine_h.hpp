@@ -58,6 +58,7 @@ template <class IN, class HT, class CH> LCMA_DEV void combine_h_tile(const CombH
         }
         const uint32_t cb = (uint32_t)CH::c_j(o) * p.c_bcol + colb;
         const uint32_t off = cb < p.n_row_b ? (uint32_t)CH::c_i(o) * p.c_brow + row * p.ldc_b + cb : p.c_bytes;
+        // (16-byte store: the scalar-offset field stays a literal zero, see Ctx::store_c in lcma_device.hpp)
         __builtin_amdgcn_raw_buffer_store_b128(v, rc, (int)off, 0, 0);
     }
 }

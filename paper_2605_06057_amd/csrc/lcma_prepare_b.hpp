@@ -87,6 +87,7 @@ template <class IN, class CT, class CH> LCMA_DEV void prepare_b_tile(const PrepP
         __syncthreads();
         const u32x4 v = *(const u32x4 *)(tile + rn * PITCH + rc * 16);
         const uint32_t off = (uint32_t)r * p.bt_plane_b + (uint32_t)(z0 + rn) * p.bt_ld_b + (uint32_t)y0 * ES + rc * 16;
+        // (16-byte store: the scalar-offset field stays a literal zero, see Ctx::store_c in lcma_device.hpp)
         __builtin_amdgcn_raw_buffer_store_b128(v, rt, (int)off, 0, 0);
         __syncthreads();
     }
@@ -140,6 +141,7 @@ template <class IN, class CT, class CH> LCMA_DEV void prepare_bt_tile(const Prep
             v = __builtin_bit_cast(u32x4, f);
         }
         const uint32_t off = (uint32_t)r * p.bt_plane_b + (uint32_t)rn * p.bt_ld_b + kb;
+        // (16-byte store: the scalar-offset field stays a literal zero, see Ctx::store_c in lcma_device.hpp)
         __builtin_amdgcn_raw_buffer_store_b128(v, rt, (int)off, 0, 0);
     }
 }

@@ -2,6 +2,7 @@
 #include "host_common.h"
 
 #include <atomic>
+#include <memory>
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
@@ -138,7 +139,7 @@ int builtin_max_id() {
 }
 
 const lcma_scheme *builtin_scheme(int id) {
-    static std::vector<lcma_scheme *> cache(kBuiltinCount, nullptr);
+    static std::vector<std::unique_ptr<lcma_scheme>> cache(kBuiltinCount); // owned: released when the library unloads
     static std::mutex mu;
     const int i = builtin_index_of_id(id);
     if (i < 0) return nullptr;
@@ -151,9 +152,9 @@ const lcma_scheme *builtin_scheme(int id) {
             lcma_scheme_free(s);
             return nullptr;
         }
-        cache[i] = s;
+        cache[i].reset(s);
     }
-    return cache[i];
+    return cache[i].get();
 }
 
 } // namespace lcma

@@ -258,3 +258,81 @@ def test_overlapping_output_is_refused(B):
     B.lcma_gemm(buf[:256], buf[:256], buf[256:], None)          # A and B may be the same matrix
     torch.cuda.synchronize()
     assert torch.all(buf[256:] == 256).item()
+
+
+def test_bf16_outside_the_fp16_range_contract_and_guard(B):
+    """bf16 inputs outside [2^-14, 32752]: what the LCMA kernels return (they multiply in fp16) and what the range guard
+    reports.  The expected values are the oracle's product of the inputs as fp16 arithmetic sees them."""
+    import torch
+    import gpu_util as G
+    M = N = K = 256
+    s = B.lcma_scheme_load("builtin:strassen")
+    eye = torch.eye(K, dtype=torch.bfloat16, device="cuda")
+    # (a) large values: 2^17 in the upper left block of A only, so that no sum of two large values occurs.  The plain
+    # kernel multiplies bf16 as it is; the LCMA kernel sees 65504 in place of 2^17.
+    a = torch.zeros((M, K), dtype=torch.bfloat16, device="cuda")
+    a[:128, :128] = 2.0 ** 17
+    c_plain, c_lcma = torch.empty((M, N), dtype=torch.bfloat16, device="cuda"), torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+    B.lcma_gemm(a, eye, c_plain, None)
+    B.lcma_gemm(a, eye, c_lcma, s)
+    torch.cuda.synchronize()
+    assert torch.equal(c_plain, a)
+    sat = inp.widen(inp.store(np.array([[65504.0]]), "bf16"), "bf16")[0, 0]      # 65504 rounded to bf16 on the way out
+    want = np.zeros((M, N)); want[:128, :128] = sat
+    assert np.array_equal(G.to_host_f64(c_lcma, "bf16"), want), "values above 65504 enter the LCMA kernels as 65504"
+    assert B.lcma_fp16_range_flags(a) == 1
+    # (b) two large values that meet in a combination (A11 + A22 of the first product): fp16 infinity, C not finite
+    a[128:, 128:] = 2.0 ** 17
+    B.lcma_gemm(a, eye, c_lcma, s)
+    torch.cuda.synchronize()
+    assert not torch.isfinite(c_lcma.float()).all().item()
+    # (c) small values: 2^-20 * (1 + 2^-7) needs bits below fp16's subnormal spacing 2^-24 and arrives as 2^-20
+    tiny = 2.0 ** -20 * (1 + 2.0 ** -7)
+    a = torch.zeros((M, K), dtype=torch.bfloat16, device="cuda")
+    a[:128, :128] = tiny
+    B.lcma_gemm(a, eye, c_plain, None)
+    B.lcma_gemm(a, eye, c_lcma, s)
+    torch.cuda.synchronize()
+    assert torch.equal(c_plain, a)
+    want = np.zeros((M, N)); want[:128, :128] = 2.0 ** -20
+    assert np.array_equal(G.to_host_f64(c_lcma, "bf16"), want), "magnitudes below 2^-14 lose their low bits"
+    assert B.lcma_fp16_range_flags(a) == 2
+    # (d) inside the range: no flag, and the LCMA result equals the plain one on exactly representable data
+    a = torch.full((M, K), 32640.0, dtype=torch.bfloat16, device="cuda")
+    a[0, 0] = 2.0 ** -14
+    assert B.lcma_fp16_range_flags(a) == 0
+    assert B.lcma_fp16_range_flags(torch.full((8, 8), float("inf"), dtype=torch.bfloat16, device="cuda")) == 1
+    assert B.lcma_fp16_range_flags(a[:0]) == 0
+
+
+def test_wide_stores_keep_their_data_registers(B):
+    """Regression test for a store hazard: 16-byte buffer stores once lost the data of a quarter of their lanes to the
+    next vector instruction.  C[i][j] = f(i) + g(j) makes every element tell its row and its column, so data that ends up
+    under another lane's address cannot go unnoticed; every kernel family that stores 16 bytes at a time is run: the fused
+    kernels' epilogue, the plane GEMM, Combine B, Combine A and Combine H."""
+    import torch
+    import gpu_util as G
+    M, N, K = 1024, 1024, 256
+    Ai = np.zeros((M, K), np.int64); Bi = np.zeros((K, N), np.int64)
+    Ai[:, 0] = np.arange(M) % 251 - 125; Ai[:, 1] = 1
+    Bi[0, :] = 1; Bi[1, :] = np.arange(N) % 241 - 120
+    want_i = Ai @ Bi
+    for dt in ("bf16", "f16"):
+        want = inp.store(want_i.astype(np.float64), dt)
+        a, b = G.to_device(inp.store(Ai, dt), dt), G.to_device(inp.store(Bi, dt), dt)
+        w = b.t().contiguous()
+        st = B.lcma_scheme_load("builtin:strassen")
+        ws = torch.empty((B.lcma_unfused_workspace_bytes(st, M, N, K, B.DTYPE_IDS[dt]),), dtype=torch.uint8, device="cuda")
+        runs = {
+            "fused strassen": lambda c: B.lcma_gemm(a, b, c, st),
+            "fused strassen N x K": lambda c: B.lcma_gemm_nt(a, w, c, st),
+            "plain": lambda c: B.lcma_gemm(a, b, c, None),
+            "plane gemm": lambda c: B.lcma_gemm_nt_ws(a, w, c, None),
+            "prepared B": lambda c: B.lcma_gemm_prepared(a, B.lcma_prepare_b(b, st), c, st),
+            "algorithm 1": lambda c: B.lcma_gemm_unfused(1, a, b, c, st, ws),
+        }
+        for name, run in runs.items():
+            c = G.empty_like_c(M, N, dt, fill=float("nan"))
+            run(c)
+            torch.cuda.synchronize()
+            assert np.array_equal(G.to_host_stored(c, dt).view(np.uint8), want.view(np.uint8)), (dt, name)

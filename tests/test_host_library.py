@@ -328,3 +328,20 @@ def test_selector_over_both_dataflows(B):
     out = B.lcma_choice()
     assert L.lcma_select_dataflow(4096, 4096, 4096, 17, 0, ctypes.byref(out)) == B.LCMA_ERR_DTYPE
     assert L.lcma_select_dataflow(0, 4096, 4096, bf16, 0, ctypes.byref(out)) == B.LCMA_ERR_ARG
+
+
+def test_wide_buffer_stores_have_a_literal_zero_scalar_offset():
+    """A buffer store of more than 8 bytes whose scalar-offset operand is a register was seen to have its data
+    registers overwritten by the next vector instruction (the compiler keeps the distance only without a scalar
+    offset); every such store in the kernels therefore passes a literal 0 there.  This keeps it that way."""
+    import glob
+    import re
+    csrc = os.path.join(ROOT, "paper_2605_06057_amd", "csrc")
+    calls = 0
+    for path in glob.glob(os.path.join(csrc, "*.hpp")) + glob.glob(os.path.join(csrc, "*.hip")):
+        text = open(path).read()
+        for m in re.finditer(r"raw_buffer_store_b128\((.*?)\);", text, re.S):
+            args = [a.strip() for a in m.group(1).rsplit(",", 2)]
+            assert args[-2:] == ["0", "0"], f"{os.path.basename(path)}: {m.group(0)}"
+            calls += 1
+    assert calls >= 5
