@@ -6,12 +6,17 @@
 // barrier per step.  Both operands travel from memory straight into LDS (buffer loads with the LDS bit: no staging
 // registers, no LDS write instructions; the swizzle is applied by choosing which 16-byte chunk of memory each lane
 // fetches): the loads of step y + 1 are issued at the start of step y into the stage that step y - 1 read, and must
-// have landed at the barrier that ends step y.  Three things decide the speed of this loop on MI355X (each measured
+// have landed at the barrier that ends step y.  Four things decide the speed of this loop on MI355X (each measured
 // in one run against the alternative): the matrix instructions must be pinned above the wait for the loads (they touch
 // no memory, so the compiler otherwise sinks them below it and the wait follows the issue of the loads directly:
 // -20 %); the scale bytes must come as one dword per four steps, not as a byte load per step (six more vector memory
 // instructions per wave and step: -20 %; the vector memory path is the busy one); direct loads beat staging through
-// registers (DIRECT = false, kept for comparison) by 6 % for 16-bit operands and 1 % for FP8.
+// registers (DIRECT = false, kept for comparison) by 6 % for 16-bit operands and 1 % for FP8; and the barrier sits in
+// front of the LAST fragment set's matrix instructions, with the first fragment reads of the next step behind it
+// (step_across: +4 % on random operands, +6 % on all-zero operands, where the chip's power limit does not hide it).
+// Measured and not adopted: a ring of three to five half-step stages (64 bytes of a row each, loads two to four
+// half-steps ahead): 5 % slower at every depth, so the distance of the loads is not what bounds the loop; spreading
+// the loads between the matrix instructions: no gain; four waves with 128 x 128 wave tiles: 6 % slower.
 //
 // Scheduling (Sec. 3.2).  The unit of work is one step of one tile-product; all steps of all tile-products are
 // numbered tile-product-major (tile-products in product-major order, the paper's Cache-Aware order: work-groups that
@@ -37,12 +42,23 @@ struct FP8 { // E4M3 codes; one E8M0 scale byte per row and step
     static constexpr int ES = 1;
 };
 
+template <class K> struct PlaneFrag {
+    using type = typename Mma<K>::frag;
+};
+template <> struct PlaneFrag<FP8> {
+    using type = i32x8;
+};
+
 template <class KIND, int TM, int TN, int WGM, int WGN, class OUT, bool SPLIT = true, bool DIRECT = true> struct PlaneGemm {
     static constexpr int NT = 64 * WGM * WGN, WM = TM / WGM, WN = TN / WGN, NMI = WM / 32, NNI = WN / 32;
     static constexpr int ROW = 128, A_STAGE = TM * ROW, B_STAGE = TN * ROW, STAGE = A_STAGE + B_STAGE;
     static constexpr int LDS_BYTES = 2 * STAGE;
     static constexpr int QA = TM * 8 / NT, QB = TN * 8 / NT; // direct-load instructions per thread and step
     static constexpr bool SCALED = std::is_same_v<KIND, FP8>;
+    // fragment sets of a step (see read_set)
+    static constexpr int SUBS = 4, NA = SCALED ? NMI / 2 : NMI;
+    static_assert(!SCALED || NMI % 2 == 0, "FP8: fragment sets of half the tile rows");
+    using FragT = typename PlaneFrag<KIND>::type;
     static_assert(TM * 8 % NT == 0 && TN * 8 % NT == 0 && WM % 32 == 0 && WN % 32 == 0, "tile and wave grid");
     static_assert(LDS_BYTES <= 160 * 1024, "LDS budget of one CU");
     static constexpr int TILE_FLOATS = TM * TN;
@@ -136,6 +152,76 @@ template <class KIND, int TM, int TN, int WGM, int WGN, class OUT, bool SPLIT = 
                 }
             }
         }
+    }
+
+    // Fragment set `sub` of the stage at `st`.  16-bit: the operands of the sub-th 32x32x16 instruction along K for all
+    // tiles of the wave (buffers alternate with sub).  FP8: sub = 2 kk + mh, the A fragments of tile rows mh * NA ..
+    // of the kk-th 32x32x64 instruction (buffers alternate with sub) and, when mh = 0, the B fragments of kk (buffers
+    // alternate with kk): half a set of A at a time keeps two sets in flight inside the register budget.
+    static LCMA_DEV void read_set(const State &s, const LCMA_LDS char *st, int sub, FragT (&fa)[2][NA], FragT (&fb)[2][NNI]) {
+        if constexpr (SCALED) {
+            const int kk = sub >> 1, mh = sub & 1;
+#pragma unroll
+            for (int i = 0; i < NA; ++i)
+                fa[sub & 1][i] = frag8(st, s.a_frag[kk][0] + (mh * NA + i) * 32 * ROW, s.a_frag[kk][1] + (mh * NA + i) * 32 * ROW);
+            if (mh == 0) {
+#pragma unroll
+                for (int ni = 0; ni < NNI; ++ni)
+                    fb[kk & 1][ni] = frag8(st, s.b_frag[kk][0] + ni * 32 * ROW, s.b_frag[kk][1] + ni * 32 * ROW);
+            }
+        } else {
+            const int kk = sub >> 1, j = sub & 1;
+#pragma unroll
+            for (int mi = 0; mi < NMI; ++mi)
+                fa[sub & 1][mi] = __builtin_bit_cast(FragT, *(const LCMA_LDS u32x4 *)(st + s.a_frag[kk][j] + mi * 32 * ROW));
+#pragma unroll
+            for (int ni = 0; ni < NNI; ++ni)
+                fb[sub & 1][ni] = __builtin_bit_cast(FragT, *(const LCMA_LDS u32x4 *)(st + s.b_frag[kk][j] + ni * 32 * ROW));
+        }
+    }
+
+    static LCMA_DEV void mma_set(int sub, const FragT (&fa)[2][NA], const FragT (&fb)[2][NNI], const int (&sa)[NMI],
+                                 const int (&sb)[NNI], f32x16 (&acc)[NMI][NNI]) {
+#pragma unroll
+        for (int i = 0; i < NA; ++i)
+#pragma unroll
+            for (int ni = 0; ni < NNI; ++ni) {
+                if constexpr (SCALED) {
+                    const int mi = (sub & 1) * NA + i;
+                    acc[mi][ni] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(fa[sub & 1][i], fb[(sub >> 1) & 1][ni], acc[mi][ni], 0, 0,
+                                                                                   0, sa[mi], 0, sb[ni]);
+                } else {
+                    Mma<KIND>::run(fa[sub & 1][i], fb[sub & 1][ni], acc[i][ni]);
+                }
+            }
+    }
+
+    // One step of the direct-load pipeline.  On entry fa[0], fb[0] hold fragment set 0 of the stage at `rd`; the barrier
+    // that ends the step sits in front of the matrix instructions of the LAST fragment set, and the reads of set 0 of
+    // the next step (from `wr`, whose loads have landed by then) are issued behind it: the matrix pipe has the last
+    // set to work on while those reads travel, where otherwise all waves of a SIMD would stand at the start of a step
+    // waiting for their first fragments.  The barrier therefore means "every wave has READ the stage", which is all
+    // the next loads into it need.  (restrict: the loads in flight towards `wr` do not touch what is read from `rd`.)
+    static LCMA_DEV void step_across(const State &s, const LCMA_LDS char *__restrict__ rd, LCMA_LDS char *__restrict__ wr,
+                                     uint32_t a_base, uint32_t b_base, int y_next, bool more, const int (&sa)[NMI],
+                                     const int (&sb)[NNI], f32x16 (&acc)[NMI][NNI], FragT (&fa)[2][NA], FragT (&fb)[2][NNI]) {
+        if (more) issue(s, wr, a_base, b_base, y_next);
+#pragma unroll
+        for (int sub = 0; sub + 1 < SUBS; ++sub) {
+            read_set(s, rd, sub + 1, fa, fb);
+            mma_set(sub, fa, fb, sa, sb, acc);
+            // FP8: no reads of later sets above this line (the scheduler would hoist them all and run out of registers)
+            if constexpr (SCALED) __builtin_amdgcn_sched_barrier(0);
+        }
+        landed_barrier();
+        // (unconditional on purpose: after the last step this reads a stage nobody uses, and a branch here would let
+        // the compiler move the matrix instructions above to this side of the barrier)
+        read_set(s, wr, 0, fa, fb);
+        // the reads stay here, in front of the last set's matrix instructions (they would otherwise be moved to the
+        // top of the next step, behind them)
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_sched_barrier(0);
+        mma_set(SUBS - 1, fa, fb, sa, sb, acc);
     }
 
     static LCMA_DEV void run(const PlaneGemmParams &p, LCMA_LDS char *lds) {
@@ -259,14 +345,15 @@ template <class KIND, int TM, int TN, int WGM, int WGN, class OUT, bool SPLIT = 
             load_scales(y0 >> 2, sa_cur, sb_cur);
             load_scales((y0 >> 2) + 1, sa_nxt, sb_nxt);
             if constexpr (DIRECT) {
+                FragT fa[2][NA], fb[2][NNI];
                 issue(s, lds, a_base, b_base, y0);
                 landed_barrier();
+                read_set(s, lds, 0, fa, fb);
                 auto one = [&](int y, int st) {
                     int sa[NMI], sb[NNI];
                     turn_scales(y);
                     scales_of(y, sa, sb);
-                    step(s, lds + st * STAGE, lds + (st ^ 1) * STAGE, a_base, b_base, y + 1, y + 1 < y1, sa, sb, acc);
-                    landed_barrier();
+                    step_across(s, lds + st * STAGE, lds + (st ^ 1) * STAGE, a_base, b_base, y + 1, y + 1 < y1, sa, sb, acc, fa, fb);
                 };
                 // the stage alternates from 0 at the first step of the piece and stays a run-time value: two unrolled
                 // copies with literal stages gain nothing for 16-bit operands and cost the FP8 kernel 10 % (registers)
