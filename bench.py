@@ -1,9 +1,12 @@
 #!/usr/bin/env python3
 """Benchmark of the LCMA GEMM hot path on one MI355X.
 
-One "step" is one lcma_gemm call: the whole fused path (block split, operand combinations
-in LDS, grouped MFMA sub-GEMMs, W epilogue) over one pair of synthetic matrices that already
-sit in HBM.  The default workload is the largest LLM-shaped configuration: the FFN GEMM
+One "step" is one lcma_gemm_ws call (lcma_gemm with a workspace): the whole LCMA product over one pair of
+synthetic matrices that already sit in HBM, by the dataflow the library's time model (Sec. 3.3) predicts faster
+for the shape: the fused group-parallel kernel (block split, operand combinations in LDS, grouped MFMA
+sub-GEMMs, W epilogue in one launch) or Algorithm 1 (Combine A, Combine B, one batched GEMM over the R
+products, Combine H; every stage runs in every step).  `config.dataflow` says which ran; the fused kernel's
+own rate is reported beside it (`fused_kernel_tflops`), and --fused-only makes it the headline.  The default workload is the largest LLM-shaped configuration: the FFN GEMM
 M = 8192 tokens, N = 14336, K = 4096, bf16 storage with fp32 accumulation, A ~ N(0,1),
 B ~ N(0, 0.02^2), Strassen <2,2,2;7> one level.  The other configurations (Strassen bf16 4096^3,
 two-level Strassen on the FFN shape, Laderman fp16 6144^3, Strassen fp32 4096^3) are timed the
@@ -12,7 +15,7 @@ same way as further legs and reported in `other_workloads` of the same line.
 Prints ONE JSON line.  `value` is effective TFLOP/s = 2MNK / time (standard-GEMM flop count,
 paper Sec. 4.1 "Measurement"), so it can exceed what the MFMA units did.  Beside it: the same-build
 plain MFMA GEMM timed the same way, the fraction of the dense MFMA peak, a roofline object
-for the dominant kernel and the CPU oracle timed on a bounded sample of the same workload.
+for the dominant kernel (under Algorithm 1 the batched GEMM stage, timed alone with HIP events) and the CPU oracle timed on a bounded sample of the same workload.
 Further legs, each about a second, run unless --no-extras is given and are reported in objects of
 their own beside `value`: the offline Combine-B path, B given as the N x K weight matrix, and the
 unfused dataflows of Algorithm 1 / Algorithm 2.
@@ -156,7 +159,7 @@ def sampled_rows(np, M, m, per_block=8):
 
 
 def side_workload(name, args):
-    """One further configuration: lcma_gemm (default kernel choice), the plain and the vendor GEMM timed the same way
+    """One further configuration: lcma_gemm_ws (the dataflow the time model picks), the plain and the vendor GEMM timed the same way
     as the main workload on fewer steps, and parity with the oracle on sampled rows."""
     import numpy as np
     import torch
@@ -178,7 +181,20 @@ def side_workload(name, args):
     info = B.lcma_scheme_info(scheme)
     steps, warmup = max(20, args.steps // 4), max(5, args.warmup // 2)
     flops = 2.0 * M * N * K
-    wall, ev, _ = _timed(torch, lambda i: B.lcma_gemm(*sets[i % 3], scheme), steps, warmup, args.heat_seconds)
+    nbytes = B.lcma_unfused_workspace_bytes(scheme, M, N, K, B.DTYPE_IDS[dt])
+    ws = torch.empty((nbytes + B.lcma_split_group_scratch_bytes(),), dtype=torch.uint8, device="cuda") if nbytes > 0 and not args.fused_only else None
+    ran = {"flow": 0}
+
+    def lcma_step(i):
+        ran["flow"] = B.lcma_gemm_ws(*sets[i % 3], scheme, ws)
+    wall, ev, _ = _timed(torch, lcma_step, steps, warmup, args.heat_seconds)
+    kernel_ms, fused_tf = ev, None
+    if ran["flow"] == 1:   # the dominant kernel is the GEMM stage of Algorithm 1: timed alone
+        f_wall, _, _ = _timed(torch, lambda i: B.lcma_gemm(*sets[i % 3], scheme), max(10, steps // 2), 3, args.heat_seconds)
+        fused_tf = flops / (f_wall * 1e-3) / 1e12
+        B.lcma_set_tuning("unfused_stages", "4")
+        _, kernel_ms, _ = _timed(torch, lambda i: B.lcma_gemm_unfused(1, *sets[i % 3], scheme, ws), max(10, steps // 2), 3, args.heat_seconds)
+        B.lcma_set_tuning("unfused_stages", "")
     p_wall, _, _ = _timed(torch, lambda i: B.lcma_gemm(*sets[i % 3], None), steps, warmup, args.heat_seconds)
     v_wall, _, _ = _timed(torch, lambda i: torch.mm(sets[i % 3][0], sets[i % 3][1], out=sets[i % 3][2]), max(10, steps // 2), 3, args.heat_seconds)
     peak = PEAK_TFLOPS[dt]
@@ -188,12 +204,14 @@ def side_workload(name, args):
            "value": value, "unit": "TFLOP/s", "ms_per_step": wall, "steps": steps, "frac_of_dense_peak": value / peak,
            "plain_mfma_gemm_tflops": flops / (p_wall * 1e-3) / 1e12, "vs_plain": p_wall / wall,
            "vendor_gemm_tflops": flops / (v_wall * 1e-3) / 1e12,
-           "roofline": {"bound": "mfma", "achieved": mfma_flops / (ev * 1e-3) / 1e12, "peak": peak, "unit": "TFLOP/s",
-                        "frac": mfma_flops / (ev * 1e-3) / 1e12 / peak, "traffic": read_traffic(name)}}
+           "dataflow": "algorithm1" if ran["flow"] == 1 else "fused", "fused_kernel_tflops": fused_tf,
+           "roofline": {"bound": "mfma", "achieved": mfma_flops / (kernel_ms * 1e-3) / 1e12, "peak": peak, "unit": "TFLOP/s",
+                        "frac": mfma_flops / (kernel_ms * 1e-3) / 1e12 / peak, "kernel_ms": kernel_ms,
+                        "traffic": read_traffic(name + ("_alg1" if ran["flow"] == 1 else ""))}}
     if not args.no_cpu:
         import oracle
         rows = sampled_rows(np, M, info["m"])
-        B.lcma_gemm(*sets[0], scheme)
+        lcma_step(0)
         B.lcma_gemm(*sets[1], None)
         torch.cuda.synchronize()
         ref = oracle.gemm_rows(inp.widen(As, dt), inp.widen(Bs, dt), rows)
@@ -205,7 +223,7 @@ def side_workload(name, args):
             return t.cpu().numpy().astype(np.float64)
         out["rel_frobenius_error"] = {"lcma": oracle.rel_frobenius(host(sets[0][2]), ref),
                                       "plain": oracle.rel_frobenius(host(sets[1][2]), ref), "rows_checked": int(len(rows))}
-    del sets
+    del sets, ws
     torch.cuda.empty_cache()
     return out
 
@@ -222,6 +240,9 @@ def main():
                     help="skip the further workloads (by default the other configurations are timed as well, about "
                          "two seconds each, and reported in `other_workloads`)")
     ap.add_argument("--variant", default=None, help="time this generated kernel instead of the default choice")
+    ap.add_argument("--fused-only", action="store_true",
+                    help="time lcma_gemm (always the fused kernel) as the headline instead of lcma_gemm_ws, which runs "
+                         "the fused kernel or Algorithm 1, whichever the library's time model predicts faster")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
     ap.add_argument("--with-copy", action="store_true",
                     help="also run a plain device copy of A's bytes (a known-size kernel that calibrates HBM counters)")
@@ -282,12 +303,27 @@ def main():
     B.lcma_scheme_verify(scheme)
     info = B.lcma_scheme_info(scheme)
 
+    # the headline runs lcma_gemm_ws: lcma_gemm with a workspace, i.e. the fused kernel or Algorithm 1, whichever the
+    # Decision Module predicts faster (every stage runs in every step, Combine B included)
+    ws_main = None
+    dataflow = {"ran": 0}
+    if not args.variant and not args.fused_only:
+        nbytes = B.lcma_unfused_workspace_bytes(scheme, M, N, K, B.DTYPE_IDS[dt])
+        if nbytes > 0:
+            ws_main = torch.empty((nbytes + B.lcma_split_group_scratch_bytes(),), dtype=torch.uint8, device="cuda")
+
     def lcma_step(i):
         a, b, c = sets[i % 3]
         if args.variant:
             B.lcma_gemm_variant(args.variant, a, b, c)
+        elif ws_main is not None:
+            dataflow["ran"] = B.lcma_gemm_ws(a, b, c, scheme, ws_main)
         else:
             B.lcma_gemm(a, b, c, scheme)
+
+    def fused_step(i):
+        a, b, c = sets[i % 3]
+        B.lcma_gemm(a, b, c, scheme)
 
     def plain_step(i):
         a, b, c = sets[i % 3]
@@ -312,6 +348,19 @@ def main():
     v_wall_ms, v_ev_ms, v_med_ms = timed(vendor_step, max(10, args.steps // 2), 3)
     value = flops / (wall_ms * 1e-3) / 1e12
     plain_tf = flops / (p_wall_ms * 1e-3) / 1e12
+    # the dominant kernel: the fused kernel itself, or the GEMM stage of Algorithm 1 timed alone (the other stages
+    # switched off through the library's measurement aid; their times are reported beside it)
+    kernel_ms, kernel_name, stage_ms, fused_tf = ev_ms, "fused group-parallel kernel (lcma_gemm)", None, None
+    if dataflow["ran"] == 1:
+        f_wall_ms, _, _ = timed(fused_step, max(10, args.steps // 2), 3)
+        fused_tf = flops / (f_wall_ms * 1e-3) / 1e12
+        stage_ms = {}
+        for bit, key in ((1, "combine_a"), (2, "combine_b"), (4, "gemm"), (8, "combine_h")):
+            B.lcma_set_tuning("unfused_stages", str(bit))
+            _, s_ev, _ = timed(lambda i: B.lcma_gemm_unfused(1, *sets[i % 3], scheme, ws_main), max(10, args.steps // 2), 3)
+            stage_ms[key] = s_ev
+        B.lcma_set_tuning("unfused_stages", "")
+        kernel_ms, kernel_name = stage_ms["gemm"], "batched plane GEMM of Algorithm 1 (lcma_k_pg_*), R products in one launch"
     prepared = None
     if args.prepared_b:
         if scheme is None:
@@ -473,7 +522,7 @@ def main():
     if ablation:
         ablation = {k: v for k, v in ablation.items() if not k.startswith("_c")}
     mfma_flops = flops * info["R"] / (info["m"] * info["k"] * info["n"])
-    achieved = mfma_flops / (ev_ms * 1e-3) / 1e12
+    achieved = mfma_flops / (kernel_ms * 1e-3) / 1e12
     out = {
         "metric": "effective TFLOP/s (2MNK/t) and fraction of MI355X dense MFMA peak",
         "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -481,16 +530,23 @@ def main():
         "dtype": "f16" if dt == "bf16" else dt, "data": "synthetic",
         "config": {"workload": f"{scheme_name} <{info['m']},{info['k']},{info['n']};{info['R']}> one launch, "
                                f"{dt} storage, fp32 accumulate, M={M} N={N} K={K}, A {kind_a}, B {kind_b}",
-                   "variant": args.variant or "library default"},
+                   "variant": args.variant or "library default",
+                   "entry": "lcma_gemm_variant" if args.variant else ("lcma_gemm_ws" if ws_main is not None else "lcma_gemm"),
+                   "dataflow": "Algorithm 1 (Combine A, Combine B, batched GEMM, Combine H; chosen by the time model)"
+                               if dataflow["ran"] == 1 else "fused group-parallel kernel"},
         "frac_of_dense_peak": value / peak,
         "plain_mfma_gemm_tflops": plain_tf, "vs_plain": value / plain_tf,
         "vendor_gemm_tflops": flops / (v_wall_ms * 1e-3) / 1e12,
         "kernel_ms_events": {"lcma_mean": ev_ms, "lcma_median": med_ms, "plain_mean": p_ev_ms, "plain_median": p_med_ms},
         "rel_frobenius_error": {"lcma": err, "plain": err_plain, "rows_checked": int(len(rows))},
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
-                     "frac": achieved / peak, "traffic": read_traffic(args.workload)},
+                     "frac": achieved / peak, "traffic": read_traffic(args.workload + ("_alg1" if dataflow["ran"] == 1 else "")),
+                     "kernel": kernel_name, "kernel_ms": kernel_ms},
         "cpu_baseline": cpu,
     }
+    if stage_ms:
+        out["algorithm1_stage_ms_events"] = stage_ms
+        out["fused_kernel_tflops"] = fused_tf
     if prepared:
         out["offline_combine_b"] = prepared
     if nk:

@@ -237,6 +237,20 @@ lcma_status lcma_gemm_unfused(int level, int64_t M, int64_t N, int64_t K,
                               void *C, int64_t ldc, lcma_dtype dtype, const lcma_scheme *scheme,
                               void *workspace, int64_t workspace_bytes, int reuse_bt, void *stream);
 
+/* lcma_gemm with a workspace (Sec. 3.3, the Decision Module applied to the two dataflows of one scheme): the same product
+ * C = A x B, run as the fused kernel of lcma_gemm or as Algorithm 1 (lcma_gemm_unfused level 1), whichever the time model
+ * (lcma_predict_seconds against lcma_predict_unfused_seconds with Combine B counted) predicts faster for the shape.
+ * workspace: device memory, 256-byte aligned, overwritten; Algorithm 1 is considered only when it holds at least
+ * lcma_unfused_workspace_bytes() bytes (lcma_split_group_scratch_bytes() more let its GEMM stage split tile-products
+ * between work-groups); NULL, too small, scheme == NULL, a scheme that is not built in, a shape that Algorithm 1 does
+ * not take, or dtype F16 (the fp16 products of Algorithm 1 would put the result past four times the plain kernel's
+ * error): lcma_gemm.  *dataflow (may be NULL) receives what ran: 0 = lcma_gemm, 1 = Algorithm 1.  The two dataflows
+ * round differently (Algorithm 1 stores the products H_r in fp16 for 16-bit dtypes): each meets the error bounds stated
+ * for it, their results are not bit-identical.  Errors: those of the call that ran. */
+lcma_status lcma_gemm_ws(int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const void *B, int64_t ldb,
+                         void *C, int64_t ldc, lcma_dtype dtype, const lcma_scheme *scheme,
+                         void *workspace, int64_t workspace_bytes, int *dataflow, void *stream);
+
 /* lcma_gemm_unfused for callers that cannot allocate device memory or pass a workspace (code under HIP graph
  * capture, tight serving loops, harnesses that forbid hipMalloc): the planes live in a 32 MiB buffer that is part of
  * the library's device image (lcma_static_scratch_bytes() bytes, one copy per GPU, held until the process ends).
@@ -331,7 +345,7 @@ lcma_status lcma_model_intensity(const lcma_scheme *s, int64_t M, int64_t N, int
 double lcma_predict_seconds(int scheme_id, int64_t M, int64_t N, int64_t K, lcma_dtype dtype);
 
 /* ------------------------------------------------------------------ measurement aids
- * Process-wide settings; none changes a result.  lcma_set_tuning(key, value) sets one (value "" or NULL restores the
+ * Process-wide settings; none but the last changes a result.  lcma_set_tuning(key, value) sets one (value "" or NULL restores the
  * default); the initial values come from the environment variables named below, which are read ONCE, at the first
  * call that needs them.  Errors: ARG for an unknown key.
  *   "variant"          LCMA_VARIANT=<name>          lcma_gemm / lcma_gemm_prepared run this generated kernel when it belongs
@@ -343,6 +357,10 @@ double lcma_predict_seconds(int scheme_id, int64_t M, int64_t N, int64_t K, lcma
  *   "schedule"         LCMA_SCHEDULE=static|split   batched GEMM stages: one tile-product per work-group, or contiguous ranges
  *                                                   of steps per persistent work-group (Sec. 3.2, Split-Group Parallelism);
  *                                                   default: whichever the time model prefers
+ *   "unfused_stages"   LCMA_UNFUSED_STAGES=<mask>   for timing one stage of lcma_gemm_unfused alone: bit 0 Combine A, bit 1
+ *                                                   Combine B, bit 2 the GEMM stage, bit 3 Combine H (default 15, all).  The one
+ *                                                   setting that is not result-neutral: a stage switched off leaves its output
+ *                                                   as an earlier call wrote it, so C is only valid with all four on.
  */
 lcma_status lcma_set_tuning(const char *key, const char *value);
 

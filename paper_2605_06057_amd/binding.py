@@ -30,7 +30,7 @@ EXPORTS = [
     "lcma_scheme_name", "lcma_scheme_id_max", "lcma_variant_prepared", "lcma_prepared_b_bytes", "lcma_prepare_b", "lcma_prepare_bt", "lcma_gemm_prepared",
     "lcma_gemm_nt", "lcma_variant_b_layout", "lcma_unfused_workspace_bytes", "lcma_gemm_unfused",
     "lcma_predict_unfused_seconds", "lcma_select_dataflow", "lcma_gemm_ex", "lcma_set_tuning",
-    "lcma_static_scratch_bytes", "lcma_gemm_unfused_static", "lcma_split_group_scratch_bytes", "lcma_gemm_nt_ws", "lcma_fp16_range_flags",
+    "lcma_static_scratch_bytes", "lcma_gemm_unfused_static", "lcma_split_group_scratch_bytes", "lcma_gemm_nt_ws", "lcma_gemm_ws", "lcma_fp16_range_flags",
     "lcma_fp8_code_pitch", "lcma_fp8_scale_pitch", "lcma_fp8_quantize", "lcma_fp8_gemm_nt", "lcma_fp8_prepared_w_bytes",
     "lcma_fp8_prepare_w", "lcma_fp8_workspace_bytes", "lcma_fp8_gemm_lcma",
 ]
@@ -113,6 +113,7 @@ def lib() -> ctypes.CDLL:
         L.lcma_last_error.restype = cp
         L.lcma_set_tuning.argtypes = [cp, cp]
         L.lcma_gemm_nt_ws.argtypes = [i64, i64, i64, vp, i64, vp, i64, vp, i64, i32, vp, i64, vp]
+        L.lcma_gemm_ws.argtypes = [i64, i64, i64, vp, i64, vp, i64, vp, i64, i32, vp, vp, i64, ctypes.POINTER(ctypes.c_int), vp]
         L.lcma_fp16_range_flags.argtypes = [i64, i64, vp, i64, vp, vp]
         L.lcma_split_group_scratch_bytes.argtypes = []
         L.lcma_split_group_scratch_bytes.restype = i64
@@ -257,6 +258,17 @@ def lcma_gemm_unfused(level: int, A, B, C, scheme: Scheme, workspace, reuse_bt: 
                                    workspace.data_ptr(), workspace.numel() * workspace.element_size(),
                                    int(reuse_bt), stream))
     return C
+
+
+def lcma_gemm_ws(A, B, C, scheme, workspace=None) -> int:
+    """lcma_gemm with a workspace (uint8 device tensor or None); returns the dataflow that ran: 0 fused, 1 Algorithm 1."""
+    M, N, K, pa, lda, pb, ldb, pc, ldc, stream = _marshal(A, B, C)
+    ws_ptr = workspace.data_ptr() if workspace is not None else None
+    ws_n = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    flow = ctypes.c_int(0)
+    _check(lib().lcma_gemm_ws(M, N, K, pa, lda, pb, ldb, pc, ldc, _dtype_of(A), scheme.handle if scheme is not None else None,
+                              ws_ptr, ws_n, ctypes.byref(flow), stream))
+    return int(flow.value)
 
 
 def lcma_gemm_nt_ws(A, W, C, workspace=None):

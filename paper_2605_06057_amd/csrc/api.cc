@@ -56,7 +56,7 @@ static const Variant *find_variant(const char *name) {
 // Measurement aids (see lcma_set_tuning): process-wide, initialised once from the environment, never read from it again.
 namespace {
 std::atomic<const Variant *> g_forced{nullptr}, g_forced_unfused{nullptr};
-std::atomic<int> g_panel{8}, g_batch_order{0}, g_schedule{0};
+std::atomic<int> g_panel{8}, g_batch_order{0}, g_schedule{0}, g_stages{15};
 std::once_flag g_tuning_once;
 bool set_tuning(const char *key, const char *value) {
     const char *v = value ? value : "";
@@ -65,6 +65,7 @@ bool set_tuning(const char *key, const char *value) {
     else if (!std::strcmp(key, "panel")) g_panel = *v ? (std::atoi(v) < 1 ? 1 : std::atoi(v)) : 8;
     else if (!std::strcmp(key, "batch_order")) g_batch_order = *v ? std::atoi(v) != 0 : 0;
     else if (!std::strcmp(key, "schedule")) g_schedule = !std::strcmp(v, "static") ? 1 : !std::strcmp(v, "split") ? 2 : 0;
+    else if (!std::strcmp(key, "unfused_stages")) g_stages = *v ? (std::atoi(v) & 15) : 15;
     else return false;
     return true;
 }
@@ -75,6 +76,7 @@ void init_tuning() {
         if (const char *e = std::getenv("LCMA_PANEL")) set_tuning("panel", e);
         if (const char *e = std::getenv("LCMA_BATCH_ORDER")) set_tuning("batch_order", e);
         if (const char *e = std::getenv("LCMA_SCHEDULE")) set_tuning("schedule", e);
+        if (const char *e = std::getenv("LCMA_UNFUSED_STAGES")) set_tuning("unfused_stages", e);
     });
 }
 } // namespace
@@ -83,6 +85,7 @@ const Variant *forced_unfused_variant() { init_tuning(); return g_forced_unfused
 int tuning_panel() { init_tuning(); return g_panel.load(); }
 int tuning_batch_order() { init_tuning(); return g_batch_order.load(); }
 int tuning_schedule() { init_tuning(); return g_schedule.load(); }
+int tuning_unfused_stages() { init_tuning(); return g_stages.load(); }
 
 // [p, p + bytes) and [q, q + qbytes) share a byte
 static bool overlap(const void *p, int64_t bytes, const void *q, int64_t qbytes) {

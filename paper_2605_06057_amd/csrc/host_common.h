@@ -96,11 +96,14 @@ int tuning_batch_order();
 // the Split-Group schedule, launch.
 enum { PG_FP8_BF16 = 0, PG_FP8_F16 = 1, PG_F16 = 2, PG_BF16 = 3, PG_F16_OUT = 4 /* fp16 operands, fp16 C: same kernels as PG_F16 */ };
 int64_t plane_gemm_scratch_bytes(int tile);
+// predicted seconds of plane_gemm on `planes` planes of rows x cols with ny steps of 128 bytes (negative: no kernel fits)
+double plane_gemm_seconds(int planes, int64_t rows, int64_t cols, int ny, int64_t scratch_bytes);
 int64_t plane_gemm_static_steps(int64_t jobs, int ny, int tile);
 int64_t plane_gemm_split_steps(int64_t jobs, int ny, int tile);
 lcma_status plane_gemm(const char *who, int kind, PlaneGemmParams p, int planes, int64_t rows, int64_t cols, int tile,
                        int schedule, void *scratch, int64_t scratch_bytes, void *stream);
 int tuning_schedule(); // 0 = choose, 1 = one tile-product per work-group, 2 = Split-Group ranges
+int tuning_unfused_stages(); // bit 0 Combine A, bit 1 Combine B, bit 2 GEMM, bit 3 Combine H of lcma_gemm_unfused level 1
 
 // C = beta * C for an M x N matrix (the product with K = 0), on `stream`.
 lcma_status empty_product(int64_t M, int64_t N, void *C, int64_t ldc, int dtype, float beta, void *stream);

@@ -46,21 +46,18 @@ int64_t plane_gemm_scratch_bytes(int tile) { return (int64_t)slots_of(tile) * 2 
 int64_t plane_gemm_static_steps(int64_t jobs, int ny, int tile) { return ceil_div(jobs, slots_of(tile)) * ny; }
 int64_t plane_gemm_split_steps(int64_t jobs, int ny, int tile) { return ceil_div(jobs * ny, slots_of(tile)); }
 
-// p: operands, extents, pitches, plane strides, ny, n_row_b filled in by the caller for `planes` planes of rows x cols
-// (padded sizes, multiples of the tile when batched).  tile: 256 or 128, 0 = choose.  schedule: 0 = choose, 1 = one
-// tile-product per work-group, 2 = Split-Group ranges (needs `scratch` of plane_gemm_scratch_bytes(tile) bytes).
-lcma_status plane_gemm(const char *who, int kind, PlaneGemmParams p, int planes, int64_t rows, int64_t cols, int tile,
-                       int schedule, void *scratch, int64_t scratch_bytes, void *stream) {
-    const int forced = tuning_schedule();
-    if (forced) schedule = forced;
-    // Tile and schedule together, by the steps the slowest work-group runs, in units of a step of the large tile.  A step of
-    // the small tile does a quarter of the work with two work-groups per CU, at three quarters of the efficiency
-    // (measured): 0.76 of a large step for two of them, so 0.38 each, twice as many run at once.  The Split-Group schedule
-    // adds the pieces: nearly every work-group holds two, 134 MB of fp32 partial sums in all, written at the end of the
-    // first kernel and read back by the second, about 70 us at the rates these kernels reach, as long as 40 large steps
-    // (measured: the schedule loses wherever fewer steps than that are saved).
+namespace {
+// Tile and schedule together, by the steps the slowest work-group runs, in units of a step of the large tile.  A step of
+// the small tile does a quarter of the work with two work-groups per CU, at three quarters of the efficiency
+// (measured): 0.76 of a large step for two of them, so 0.38 each, twice as many run at once.  The Split-Group schedule
+// adds the pieces: nearly every work-group holds two, 134 MB of fp32 partial sums in all, written at the end of the
+// first kernel and read back by the second, about 70 us at the rates these kernels reach, as long as 40 large steps
+// (measured: the schedule loses wherever fewer steps than that are saved).
+// tile, schedule: 0 = choose.  Returns the cost in large steps (0 when nothing fits).
+double choose(int planes, int64_t rows, int64_t cols, int ny, int tile, int schedule, int64_t scratch_bytes, int *best_tile,
+              int *best_sched) {
     double best = 0.0;
-    int best_tile = 0, best_sched = 0;
+    *best_tile = *best_sched = 0;
     for (int t : {256, 128}) {
         if (tile && t != tile) continue;
         if (planes > 1 && (rows % t || cols % t)) continue; // planes lie back to back: a tile must not hang over the end of one
@@ -68,16 +65,42 @@ lcma_status plane_gemm(const char *who, int kind, PlaneGemmParams p, int planes,
         const double unit = t == 256 ? 1.0 : 0.76;
         for (int sc : {1, 2}) {
             if (schedule && sc != schedule) continue;
-            if (sc == 2 && !(scratch && scratch_bytes >= plane_gemm_scratch_bytes(t))) continue;
-            const double steps = sc == 1 ? (double)plane_gemm_static_steps(jobs, p.ny, t) : (double)plane_gemm_split_steps(jobs, p.ny, t) + 40.0;
+            if (sc == 2 && scratch_bytes < plane_gemm_scratch_bytes(t)) continue;
+            const double steps = sc == 1 ? (double)plane_gemm_static_steps(jobs, ny, t) : (double)plane_gemm_split_steps(jobs, ny, t) + 40.0;
             const double cost = steps * unit * (sc == 2 ? 1.05 : 1.0); // the persistent kernel's step is 5 % slower
-            if (!best_tile || cost < best) {
+            if (!*best_tile || cost < best) {
                 best = cost;
-                best_tile = t;
-                best_sched = sc;
+                *best_tile = t;
+                *best_sched = sc;
             }
         }
     }
+    return best;
+}
+} // namespace
+
+// Seconds of a plane GEMM for the time model (Sec. 3.3): the steps of the slowest work-group under the tile and schedule
+// that plane_gemm would choose, at the time of a step of the 256 x 256 tile measured on the FFN shapes with random
+// operands (1.62 us for 16-bit and for FP8 operands: a step is 128 bytes of K either way and both run into the
+// chip's power limit), plus a fixed 8 us for every tile a work-group works through (launch, first loads, epilogue).
+double plane_gemm_seconds(int planes, int64_t rows, int64_t cols, int ny, int64_t scratch_bytes) {
+    int t = 0, sc = 0;
+    const double steps = choose(planes, rows, cols, ny, 0, tuning_schedule(), scratch_bytes, &t, &sc);
+    if (!t) return -1.0;
+    const int64_t jobs = (int64_t)planes * ceil_div(rows, t) * ceil_div(cols, t);
+    const double rounds = sc == 1 ? (double)ceil_div(jobs, slots_of(t)) : 1.0;
+    return steps * 1.62e-6 + rounds * 8.0e-6;
+}
+
+// p: operands, extents, pitches, plane strides, ny, n_row_b filled in by the caller for `planes` planes of rows x cols
+// (padded sizes, multiples of the tile when batched).  tile: 256 or 128, 0 = choose.  schedule: 0 = choose, 1 = one
+// tile-product per work-group, 2 = Split-Group ranges (needs `scratch` of plane_gemm_scratch_bytes(tile) bytes).
+lcma_status plane_gemm(const char *who, int kind, PlaneGemmParams p, int planes, int64_t rows, int64_t cols, int tile,
+                       int schedule, void *scratch, int64_t scratch_bytes, void *stream) {
+    const int forced = tuning_schedule();
+    if (forced) schedule = forced;
+    int best_tile = 0, best_sched = 0;
+    choose(planes, rows, cols, p.ny, tile, schedule, scratch ? scratch_bytes : 0, &best_tile, &best_sched);
     if (!best_tile) {
         if (schedule == 2)
             return fail(LCMA_ERR_ARG, "%s: the Split-Group schedule needs %lld bytes of scratch", who,

@@ -110,7 +110,10 @@ extern "C" double lcma_predict_unfused_seconds(int scheme_id, int64_t M, int64_t
     const double at = R * g.bm * g.bk, bt = R * g.bn * g.bk, h = R * g.bm * g.bn; // elements of the planes
     double t = (dM * dK + at) * es / sk->rate_a + kLaunch;
     if (!combine_b_offline) t += (dK * dN + bt) * es / sk->rate_b + kLaunch;
-    t += gemm_stage_seconds(*gemm, s->R, g) + kLaunch;
+    // 16-bit: the plane GEMM runs the stage (priced without the scratch of the Split-Group schedule, which only a
+    // workspace larger than lcma_unfused_workspace_bytes() provides)
+    const double t_planes = es == 2 ? plane_gemm_seconds(s->R, g.bm, g.bn, (int)(g.bk * es / 128), 0) : -1.0;
+    t += (t_planes > 0.0 ? t_planes : gemm_stage_seconds(*gemm, s->R, g)) + kLaunch;
     t += (h + dM * dN) * es / sk->rate_h + kLaunch;
     return t;
 }
@@ -138,6 +141,29 @@ extern "C" lcma_status lcma_gemm_unfused(int level, int64_t M, int64_t N, int64_
                                          int reuse_bt, void *stream) {
     return gemm_unfused("lcma_gemm_unfused", level, M, N, K, A, lda, B, ldb, C, ldc, dtype, scheme, workspace,
                         workspace_bytes, reuse_bt, stream);
+}
+
+// lcma_gemm with a workspace: the fused kernel or Algorithm 1, whichever the time model predicts faster for the shape.
+extern "C" lcma_status lcma_gemm_ws(int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const void *B, int64_t ldb,
+                                    void *C, int64_t ldc, lcma_dtype dtype, const lcma_scheme *scheme, void *workspace,
+                                    int64_t workspace_bytes, int *dataflow, void *stream) {
+    if (dataflow) *dataflow = 0;
+    const int id = scheme ? scheme->builtin : 0;
+    bool alg1 = false;
+    // (fp16 storage: the products H_r that Algorithm 1 keeps in fp16 carry as many bits as C itself, and their roundings
+    // put the result past four times the plain kernel's error; it is not offered there)
+    if (id && dtype != LCMA_F16 && workspace && !((uintptr_t)workspace & 255) && dtype_size(dtype) && M > 0 && N > 0 && K > 0 &&
+        find_stage(id, dtype) &&
+        workspace_bytes >= geometry(*scheme, M, N, K, dtype).total()) {
+        const double fused = lcma_predict_seconds(id, M, N, K, dtype), unfused = lcma_predict_unfused_seconds(id, M, N, K, dtype, 0);
+        alg1 = unfused > 0.0 && (fused <= 0.0 || unfused < fused);
+    }
+    if (!alg1) return lcma_gemm(M, N, K, A, lda, B, ldb, C, ldc, dtype, scheme, stream);
+    const lcma_status st = gemm_unfused("lcma_gemm_ws", 1, M, N, K, A, lda, B, ldb, C, ldc, dtype, scheme, workspace, workspace_bytes, 0, stream);
+    // shapes that only the fused kernels take (no whole 16-byte vectors along K, ...) fall back to them
+    if (st == LCMA_ERR_SHAPE) return lcma_gemm(M, N, K, A, lda, B, ldb, C, ldc, dtype, scheme, stream);
+    if (st == LCMA_OK && dataflow) *dataflow = 1;
+    return st;
 }
 
 lcma_status lcma::gemm_unfused(const char *who, int level, int64_t M, int64_t N, int64_t K, const void *A, int64_t lda,
@@ -184,9 +210,10 @@ lcma_status lcma::gemm_unfused(const char *who, int level, int64_t M, int64_t N,
     const Variant *gemm = level == 1 ? find_gemm(true, LCMA_PLAIN, ct, scheme->R, g) : find_gemm(false, id, dtype, scheme->R, g);
     if (!gemm) return fail(LCMA_ERR_NOKERNEL, "%s: no GEMM stage kernel for level %d fits the planes", who, level);
 
+    const int stages = tuning_unfused_stages(); // measurement aid: stages switched off keep the output of an earlier call
     // stage 1: Combine A (Eq. 3).  A takes the place of an N x K weight matrix in the Combine-B kernel
     // for that layout: block A_{i,l} is block (i, l), rows are k-contiguous.
-    {
+    if (stages & 1) {
         PrepParams p;
         p.B = A;
         p.Bt = At;
@@ -206,7 +233,7 @@ lcma_status lcma::gemm_unfused(const char *who, int level, int64_t M, int64_t N,
             return fail(LCMA_ERR_HIP, "%s: Combine-A launch failed with HIP error %d", who, err);
     }
     // stage 2: Combine B (Eq. 4), unless the planes of an earlier call are still valid (static weights)
-    if (!reuse_bt) {
+    if (!reuse_bt && (stages & 2)) {
         const lcma_status st = prepare_b_planes(false, N, K, B, ldb, dtype, scheme, Bt, stream, 128, es == 4 ? 16 : 64);
         if (st != LCMA_OK) return st;
     }
@@ -235,7 +262,8 @@ lcma_status lcma::gemm_unfused(const char *who, int level, int64_t M, int64_t N,
         p.ldc_b = (uint32_t)(g.bn * es);
         p.c_brow = (uint32_t)(g.bm * g.bn * es);
         p.n_row_b = (uint32_t)(g.bn * es);
-        if (es == 2 && !forced_unfused_variant() && !p.batch_order) {
+        if (!(stages & 4)) {
+        } else if (es == 2 && !forced_unfused_variant() && !p.batch_order) {
             // 16-bit: the plane GEMM, which can hand the tile-products out in Split-Group ranges (Sec. 3.2) when the
             // workspace has room for the pieces beyond the planes
             PlaneGemmParams q;
@@ -262,6 +290,7 @@ lcma_status lcma::gemm_unfused(const char *who, int level, int64_t M, int64_t N,
                 return fail(LCMA_ERR_HIP, "%s: launch of %s failed with HIP error %d", who, gemm->name, err);
         }
         // stage 4: Combine H (Eq. 6)
+        if (!(stages & 8)) return LCMA_OK;
         CombHParams h;
         h.H = H;
         h.C = C;

@@ -1,0 +1,78 @@
+"""lcma_gemm_ws (lcma_gemm with a workspace: the fused kernel or Algorithm 1, whichever the time model predicts
+faster, Sec. 3.3) through the C ABI: the dataflow it reports is the one the model's two predictions name, and the
+result meets the bounds of that dataflow against the oracle (exact on integer inputs either way)."""
+import numpy as np
+import pytest
+
+import lcma_inputs as inp
+import oracle
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": 1e-5, "bf16": 2e-2, "f16": 2e-2}
+# shapes on both sides of the model's choice (checked below: both dataflows must occur), one ragged
+CASES = [("strassen", "bf16", (2048, 3584, 1024)), ("strassen", "bf16", (1000, 520, 264)), ("strassen", "f32", (512, 512, 512)),
+         ("strassen2", "bf16", (2048, 2048, 1024)), ("laderman", "f16", (1536, 1536, 1536)), ("laderman", "bf16", (1536, 1536, 1536)), ("strassen", "f16", (4096, 7168, 2048))]
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2605_06057_amd import binding
+    binding.lib()
+    return binding
+
+
+def model_says_algorithm1(B, sid, M, N, K, dtid):
+    if dtid == B.LCMA_F16:   # never offered for fp16 storage (error bound)
+        return False
+    fused, unfused = B.lcma_predict_seconds(sid, M, N, K, dtid), B.lcma_predict_unfused_seconds(sid, M, N, K, dtid, False)
+    return unfused > 0 and (fused <= 0 or unfused < fused)
+
+
+def test_both_dataflows_are_covered(B):
+    ids = {n: i for i, n in B.SCHEME_NAMES.items()}
+    flows = {model_says_algorithm1(B, ids[name], *shape, B.DTYPE_IDS[dt]) for name, dt, shape in CASES}
+    assert flows == {False, True}
+
+
+@pytest.mark.parametrize("name,dt,shape", CASES, ids=lambda c: str(c))
+def test_gemm_ws_against_oracle(B, name, dt, shape):
+    import torch
+    import gpu_util as G
+    M, N, K = shape
+    print(f"lcma_gemm_ws {name} {dt} {M}x{N}x{K}", flush=True)
+    h = B.lcma_scheme_load("builtin:" + name)
+    sid = {n: i for i, n in B.SCHEME_NAMES.items()}[name]
+    dtid = B.DTYPE_IDS[dt]
+    expect = 1 if model_says_algorithm1(B, sid, M, N, K, dtid) else 0
+    nbytes = B.lcma_unfused_workspace_bytes(h, M, N, K, dtid)
+    ws = torch.full((nbytes,), 0x7f, dtype=torch.uint8, device="cuda")
+    # integers: exact by either dataflow (entries in [-1, 1]: the products H_r that Algorithm 1 stores in fp16 stay
+    # below 2048 in magnitude, where fp16 holds every integer)
+    Ai, Bi = inp.integers(71, 1, (M, K), -1, 1), inp.integers(71, 2, (K, N), -1, 1)
+    want = inp.store(oracle.gemm(Ai, Bi).astype(np.float64), dt)
+    a, b = G.to_device(inp.store(Ai, dt), dt), G.to_device(inp.store(Bi, dt), dt)
+    c = G.empty_like_c(M, N, dt, fill=float("nan"))
+    flow = B.lcma_gemm_ws(a, b, c, h, ws)
+    print(f"dataflow {flow} (model: {expect})", flush=True)
+    assert flow == expect
+    assert np.array_equal(G.to_host_stored(c, dt).view(np.uint8), want.view(np.uint8))
+    # floats: the project's bound against the fp64 product, and no worse than 4x the plain kernel
+    As, Bs = inp.store(inp.normal(72, 1, (M, K)), dt), inp.store(inp.normal(72, 2, (K, N)), dt)
+    a, b = G.to_device(As, dt), G.to_device(Bs, dt)
+    ref = oracle.gemm(inp.widen(As, dt), inp.widen(Bs, dt))
+    c = G.empty_like_c(M, N, dt, fill=float("nan"))
+    assert B.lcma_gemm_ws(a, b, c, h, ws) == expect
+    err = oracle.rel_frobenius(G.to_host_f64(c, dt), ref)
+    cp = G.empty_like_c(M, N, dt, fill=float("nan"))
+    assert B.lcma_gemm_ws(a, b, cp, None, ws) == 0
+    err_plain = oracle.rel_frobenius(G.to_host_f64(cp, dt), ref)
+    print(f"relF {err:.3e}, plain {err_plain:.3e}", flush=True)
+    assert err <= TOL[dt] and err <= 4.0 * err_plain
+    # without a workspace, or with one that is too small: the fused kernel, same bounds
+    c2 = G.empty_like_c(M, N, dt, fill=float("nan"))
+    assert B.lcma_gemm_ws(a, b, c2, h, None) == 0
+    assert B.lcma_gemm_ws(a, b, c2, h, ws[:256]) == 0
+    assert oracle.rel_frobenius(G.to_host_f64(c2, dt), ref) <= TOL[dt]
+    if expect == 0:   # the same kernel ran: same bits
+        assert torch.equal(c2, c)
