@@ -203,9 +203,11 @@ lcma_status lcma_gemm_prepared(int64_t M, int64_t N, int64_t K, const void *A, i
  *            H_r = At_r Bt_r (Eq. 5), Combine H (Eq. 6) reads the H_r and writes C;
  *   level 2  Algorithm 2 as the paper runs it: Combine A and Combine B as above, then one kernel that
  *            multiplies group by group and applies W to the fp32 accumulators (H_r stays on chip).
- * At_r, Bt_r and H_r are stored in the type the products are multiplied in (fp16 for BF16 and F16
- * storage, fp32 for F32): each is an fp32 sum (ascending block order, ascending r) or an fp32 MFMA
- * accumulation rounded once, to nearest-even.  C is rounded once from fp32.
+ * At_r and Bt_r are stored in the type the products are multiplied in (fp16 for BF16 and F16
+ * storage, fp32 for F32): each is an fp32 sum (ascending block order) rounded once, to nearest-even.  H_r at level 1 is
+ * the fp32 MFMA accumulation, stored in fp16 (rounded once) for BF16 and as it is, in fp32, for F16 and F32: fp16 planes
+ * carry no more bits than an fp16 C, and their roundings would put the result past four times the plain kernel's error.
+ * C is rounded once from fp32.
  * A, B, C, sizes, alignment, padding and errors as for lcma_gemm; `scheme` is required and must be
  * one of the paper's (NOKERNEL otherwise).  workspace: device memory, 256-byte aligned, at least
  * lcma_unfused_workspace_bytes() bytes (-1 for bad arguments), owned by the caller, overwritten.
@@ -243,9 +245,9 @@ lcma_status lcma_gemm_unfused(int level, int64_t M, int64_t N, int64_t K,
  * workspace: device memory, 256-byte aligned, overwritten; Algorithm 1 is considered only when it holds at least
  * lcma_unfused_workspace_bytes() bytes (lcma_split_group_scratch_bytes() more let its GEMM stage split tile-products
  * between work-groups); NULL, too small, scheme == NULL, a scheme that is not built in, a shape that Algorithm 1 does
- * not take, or dtype F16 (the fp16 products of Algorithm 1 would put the result past four times the plain kernel's
- * error): lcma_gemm.  *dataflow (may be NULL) receives what ran: 0 = lcma_gemm, 1 = Algorithm 1.  The two dataflows
- * round differently (Algorithm 1 stores the products H_r in fp16 for 16-bit dtypes): each meets the error bounds stated
+ * not take, or F16 storage with a scheme that sums more than 4 blocks in a row of U or V (<3,3,3;23>: its fp16
+ * combinations put Algorithm 1 at 4.04 times the plain kernel's error, past the bound of 4): lcma_gemm.  *dataflow (may be NULL) receives what ran: 0 = lcma_gemm, 1 = Algorithm 1.  The two dataflows
+ * round differently (Algorithm 1 stores the products H_r: in fp16 for BF16, in fp32 for F16 and F32): each meets the error bounds stated
  * for it, their results are not bit-identical.  Errors: those of the call that ran. */
 lcma_status lcma_gemm_ws(int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const void *B, int64_t ldb,
                          void *C, int64_t ldc, lcma_dtype dtype, const lcma_scheme *scheme,

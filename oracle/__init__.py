@@ -195,12 +195,13 @@ def combine_a_stored(s: Scheme, A: np.ndarray, dtype: str) -> np.ndarray:
     return out
 
 
-def lcma_unfused(s: Scheme, A: np.ndarray, B: np.ndarray, dtype: str, level: int) -> np.ndarray:
+def lcma_unfused(s: Scheme, A: np.ndarray, B: np.ndarray, dtype: str, level: int, h_dtype: str | None = None) -> np.ndarray:
     """C by the dataflows that keep intermediate results in memory, with the roundings that storing
     them implies (values in fp64, before the final rounding of C to the storage type):
       level 1  Algorithm 1: At_r and Bt_r stored (combine_a_stored, combine_b_stored), H_r = At_r Bt_r
-               (Eq. 5; exact product, rounded once to fp16 / fp32 when it is stored), C_{i,j} =
-               sum_r W[r,i,j] H_r (Eq. 6);
+               (Eq. 5; exact product, rounded once when it is stored: Algorithm 1 does not say in which type, so the
+               caller names it with h_dtype "f16" or "f32"; None: fp16 for 16-bit storage, fp32 for fp32 storage),
+               C_{i,j} = sum_r W[r,i,j] H_r (Eq. 6);
       level 2  Algorithm 2 as printed: At_r and Bt_r stored, H_r kept unrounded on chip.
     A and B hold values representable in the storage type; shapes divisible by the grid."""
     if level not in (1, 2):
@@ -213,7 +214,10 @@ def lcma_unfused(s: Scheme, A: np.ndarray, B: np.ndarray, dtype: str, level: int
         for r in range(s.R):
             H = gemm(np.ascontiguousarray(At[r]), np.ascontiguousarray(Bt[r]))
             if level == 1:
-                H = (H.astype(np.float16) if dtype in ("bf16", "f16") else H.astype(np.float32)).astype(np.float64)
+                ht = h_dtype or ("f16" if dtype in ("bf16", "f16") else "f32")
+                if ht not in ("f16", "f32"):
+                    raise ValueError("h_dtype is f16 or f32")
+                H = (H.astype(np.float16) if ht == "f16" else H.astype(np.float32)).astype(np.float64)
             for i in range(s.m):
                 for j in range(s.n):
                     w = int(s.W[r, i, j])

@@ -66,6 +66,7 @@ struct StageKernel {
     int scheme_id, dtype;
     int (*launch_comb_a)(const PrepParams *p, int grid_x, int grid_y, void *stream);
     int (*launch_comb_h)(const CombHParams *p, int grid_x, int grid_y, void *stream);
+    int (*launch_comb_h32)(const CombHParams *p, int grid_x, int grid_y, void *stream); // fp32 planes, 16-bit C; null for fp32 storage
     double rate_a, rate_b, rate_h; // measured algorithmic bytes per second of Combine A, Combine B, Combine H
 };
 extern const StageKernel kStageKernels[];
@@ -94,7 +95,8 @@ int tuning_batch_order();
 
 // The plane GEMM (csrc/lcma_plane_gemm.hpp, csrc/plane_gemm.cc): kinds of operand and output, scratch for the pieces of
 // the Split-Group schedule, launch.
-enum { PG_FP8_BF16 = 0, PG_FP8_F16 = 1, PG_F16 = 2, PG_BF16 = 3, PG_F16_OUT = 4 /* fp16 operands, fp16 C: same kernels as PG_F16 */ };
+enum { PG_FP8_BF16 = 0, PG_FP8_F16 = 1, PG_F16 = 2, PG_BF16 = 3, PG_F16_OUT = 4 /* fp16 operands, fp16 C: same kernels as PG_F16 */,
+       PG_F16_F32 = 5 /* fp16 operands, the fp32 sums stored as they are */ };
 int64_t plane_gemm_scratch_bytes(int tile);
 // predicted seconds of plane_gemm on `planes` planes of rows x cols with ny steps of 128 bytes (negative: no kernel fits)
 double plane_gemm_seconds(int planes, int64_t rows, int64_t cols, int ny, int64_t scratch_bytes);

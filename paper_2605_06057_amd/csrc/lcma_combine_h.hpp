@@ -4,12 +4,13 @@
 // to fp32 accumulators in registers and never run this.
 //
 // H: R planes of (padded M/m) x (padded N/n) elements in the type the products were written in
-// (fp16 for 16-bit storage, fp32 for fp32 storage).  The terms are widened to fp32 (exact), added in
+// (fp16 or fp32 for 16-bit storage, fp32 for fp32 storage).  The terms are widened to fp32 (exact), added in
 // ascending r and the sum is rounded once, to nearest-even, to the storage type of C.  Rows past M
 // fall outside the extent of C (dropped by the range check), columns past N are sent there.
 //
 // HBM-bound: reads R/(m n) and writes 1 element per element of C.  One thread handles one 16-byte
-// vector position of every plane and writes the m*n vectors it yields.
+// vector position of C in every plane (two 16-byte loads per plane when the planes hold fp32 and C 16-bit
+// elements) and writes the m*n vectors it yields.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -21,18 +22,30 @@ namespace lcma {
 // CH (generated): NP planes, NC = m*n outputs with c_i(o), c_j(o); comb(in, o) = Eq. 6 for output o on floats.
 // HT: element type of the planes; IN: storage type of C (same element size).
 template <class IN, class HT, class CH> LCMA_DEV void combine_h_tile(const CombHParams &p) {
-    constexpr int ES = IN::ES, EPT = 16 / ES;
-    static_assert(HT::ES == ES, "planes and C have the same element size");
+    constexpr int ES = IN::ES, EPT = 16 / ES, HV = HT::ES / ES; // HV: 16-byte vectors of a plane per vector of C
+    static_assert(HT::ES == ES || (HT::ES == 4 && ES == 2), "planes in the element size of C, or fp32 planes for 16-bit C");
     const auto rh = __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(p.H), 0, (int)p.h_bytes, 0x00020000);
     const auto rc = __builtin_amdgcn_make_buffer_rsrc(p.C, 0, (int)p.c_bytes, 0x00020000);
-    // 256 threads: 16 rows x 16 vectors (256 bytes of a row)
+    // 256 threads: 16 rows x 16 vectors (256 bytes of a row of C)
     const uint32_t row = blockIdx.x * 16 + threadIdx.x / 16;
-    const uint32_t colb = (blockIdx.y * 16 + threadIdx.x % 16) * 16; // byte column inside a block
-    if (colb >= p.h_ld_b) return;
+    const uint32_t colb = (blockIdx.y * 16 + threadIdx.x % 16) * 16; // byte column inside a block of C
+    if (colb * HV >= p.h_ld_b) return;
     float h[CH::NP][EPT];
 #pragma unroll
-    for (int r = 0; r < CH::NP; ++r)
-        Widen<HT>::run(__builtin_amdgcn_raw_buffer_load_b128(rh, (int)(row * p.h_ld_b + colb), (int)(r * p.h_plane_b), 0), h[r]);
+    for (int r = 0; r < CH::NP; ++r) {
+        if constexpr (HV == 1) {
+            Widen<HT>::run(__builtin_amdgcn_raw_buffer_load_b128(rh, (int)(row * p.h_ld_b + colb), (int)(r * p.h_plane_b), 0), h[r]);
+        } else {
+            float lo[4], hi[4];
+            Widen<F32>::run(__builtin_amdgcn_raw_buffer_load_b128(rh, (int)(row * p.h_ld_b + colb * 2), (int)(r * p.h_plane_b), 0), lo);
+            Widen<F32>::run(__builtin_amdgcn_raw_buffer_load_b128(rh, (int)(row * p.h_ld_b + colb * 2 + 16), (int)(r * p.h_plane_b), 0), hi);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                h[r][e] = lo[e];
+                h[r][4 + e] = hi[e];
+            }
+        }
+    }
 #pragma unroll
     for (int o = 0; o < CH::NC; ++o) {
         u32x4 v;

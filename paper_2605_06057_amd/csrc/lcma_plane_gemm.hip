@@ -40,6 +40,8 @@ LCMA_PLANE_GEMM(fp8_t256_f16, FP8, 256, 256, 2, 4, 1, F16)
 LCMA_PLANE_GEMM(fp8_t128_f16, FP8, 128, 128, 2, 2, 2, F16)
 LCMA_PLANE_GEMM(f16_t256_f16, F16, 256, 256, 2, 4, 1, F16)
 LCMA_PLANE_GEMM(f16_t128_f16, F16, 128, 128, 2, 2, 2, F16)
+LCMA_PLANE_GEMM(f16_t256_f32, F16, 256, 256, 2, 4, 1, F32)
+LCMA_PLANE_GEMM(f16_t128_f32, F16, 128, 128, 2, 2, 2, F32)
 LCMA_PLANE_GEMM(bf16_t256_bf16, BF16, 256, 256, 2, 4, 1, BF16)
 LCMA_PLANE_GEMM(bf16_t128_bf16, BF16, 128, 128, 2, 2, 2, BF16)
 

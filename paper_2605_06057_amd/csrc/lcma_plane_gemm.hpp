@@ -415,27 +415,30 @@ template <class KIND, int TM, int TN, int WGM, int WGN, class OUT, bool SPLIT = 
     // only then.
     static LCMA_DEV void store_tile(const PlaneGemmParams &p, const State &s, LCMA_LDS char *lds, int plane, int x, int z,
                                     const f32x16 (&acc)[NMI][NNI]) {
-        constexpr int PITCH = WN * 2 + 16, CPRW = WN * 2 / 16, NIT = 32 * CPRW / 64;
+        constexpr int OES = OUT::ES; // 2: C rounded to fp16 / bf16; 4: the fp32 sums as they are
+        constexpr int PITCH = WN * OES + 16, CPRW = WN * OES / 16, NIT = 32 * CPRW / 64;
         static_assert(NT / 64 * 32 * PITCH <= LDS_BYTES, "the strips of all waves fit the stage buffers");
-        const uint32_t c_base = (uint32_t)plane * p.c_plane + (uint32_t)x * TM * p.ldc_b + (uint32_t)z * TN * 2;
+        const uint32_t c_base = (uint32_t)plane * p.c_plane + (uint32_t)x * TM * p.ldc_b + (uint32_t)z * TN * OES;
         LCMA_LDS char *strip = lds + s.w * (32 * PITCH);
 #pragma unroll
         for (int mi = 0; mi < NMI; ++mi) {
 #pragma unroll
             for (int ni = 0; ni < NNI; ++ni)
 #pragma unroll
-                for (int v = 0; v < 16; ++v)
-                    *(LCMA_LDS uint16_t *)(strip + ((v >> 2) * 8 + 4 * s.lh + (v & 3)) * PITCH + (ni * 32 + s.l32) * 2) =
-                        (uint16_t)Round<OUT>::run(acc[mi][ni][v]);
+                for (int v = 0; v < 16; ++v) {
+                    LCMA_LDS char *at = strip + ((v >> 2) * 8 + 4 * s.lh + (v & 3)) * PITCH + (ni * 32 + s.l32) * OES;
+                    if constexpr (OES == 2) *(LCMA_LDS uint16_t *)at = (uint16_t)Round<OUT>::run(acc[mi][ni][v]);
+                    else *(LCMA_LDS float *)at = acc[mi][ni][v];
+                }
             __syncthreads();
 #pragma unroll
             for (int it = 0; it < NIT; ++it) {
                 const int idx = it * 64 + s.lane, row = idx / CPRW, ch = idx % CPRW;
                 const u32x4 v = *(LCMA_LDS u32x4 *)(strip + row * PITCH + ch * 16);
-                const uint32_t colb = (uint32_t)(s.wn * WN) * 2 + ch * 16; // byte column inside the tile
+                const uint32_t colb = (uint32_t)(s.wn * WN) * OES + ch * 16; // byte column inside the tile
                 // a vector past N goes to the end of the extent and is dropped (N is a whole number of vectors); rows
                 // past M fall outside the extent by themselves
-                const uint32_t off = ((uint32_t)z * TN * 2 + colb < p.n_row_b)
+                const uint32_t off = ((uint32_t)z * TN * OES + colb < p.n_row_b)
                                          ? c_base + (uint32_t)(s.wm * WM + mi * 32 + row) * p.ldc_b + colb
                                          : p.c_bytes;
                 __builtin_amdgcn_raw_buffer_store_b128(v, s.rc, (int)off, 0, 0);

@@ -11,6 +11,8 @@ LCMA_PG_DECL(fp8_t256_f16)
 LCMA_PG_DECL(fp8_t128_f16)
 LCMA_PG_DECL(f16_t256_f16)
 LCMA_PG_DECL(f16_t128_f16)
+LCMA_PG_DECL(f16_t256_f32)
+LCMA_PG_DECL(f16_t128_f32)
 LCMA_PG_DECL(bf16_t256_bf16)
 LCMA_PG_DECL(bf16_t128_bf16)
 
@@ -31,6 +33,8 @@ Launch launcher(int kind, int tile) {
     case PG_BF16 * 2: return lcma_launch_pg_bf16_t128_bf16;
     case PG_F16_OUT * 2 + 1: return lcma_launch_pg_f16_t256_f16;
     case PG_F16_OUT * 2: return lcma_launch_pg_f16_t128_f16;
+    case PG_F16_F32 * 2 + 1: return lcma_launch_pg_f16_t256_f32;
+    case PG_F16_F32 * 2: return lcma_launch_pg_f16_t128_f32;
     }
     return nullptr;
 }

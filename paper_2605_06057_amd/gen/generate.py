@@ -411,9 +411,10 @@ def emit_registry(schemes: dict[str, Scheme], variants: list[Variant]) -> str:
     L.append("const StageKernel kStageKernels[] = {")
     for sch, dt in stages:
         ra, rb, rh = STAGE_RATES.get((sch, dt != "f32"), (4.0e12, 3.0e12, 5.0e12))
-        L.append(f"    {{{SCHEME_IDS[sch]}, {DTYPE_IDS[dt]}, lcma_launch_comb_a_{sch}_{dt}, lcma_launch_comb_h_{sch}_{dt}, {ra}, {rb}, {rh}}},")
+        h32 = f"lcma_launch_comb_h32_{sch}_{dt}" if dt != "f32" else "nullptr"
+        L.append(f"    {{{SCHEME_IDS[sch]}, {DTYPE_IDS[dt]}, lcma_launch_comb_a_{sch}_{dt}, lcma_launch_comb_h_{sch}_{dt}, {h32}, {ra}, {rb}, {rh}}},")
     if not stages:
-        L.append("    {0, 0, nullptr, nullptr, 0.0, 0.0, 0.0},")
+        L.append("    {0, 0, nullptr, nullptr, nullptr, 0.0, 0.0, 0.0},")
     L += ["};", f"const int kStageKernelCount = {len(stages)};"]
     fp8 = sorted({sch for sch, dt in stages if dt == "bf16"} & {sch for sch, dt in preps if dt == "bf16"})
     L.append("const Fp8Kernel kFp8Kernels[] = {")
@@ -428,6 +429,8 @@ def emit_registry(schemes: dict[str, Scheme], variants: list[Variant]) -> str:
     for sch, dt in stages:
         L.insert(3, f'extern "C" int lcma_launch_comb_a_{sch}_{dt}(const lcma::PrepParams *p, int gx, int gy, void *stream);')
         L.insert(3, f'extern "C" int lcma_launch_comb_h_{sch}_{dt}(const lcma::CombHParams *p, int gx, int gy, void *stream);')
+        if dt != "f32":
+            L.insert(3, f'extern "C" int lcma_launch_comb_h32_{sch}_{dt}(const lcma::CombHParams *p, int gx, int gy, void *stream);')
     for sch, dt in preps:
         L.insert(3, f'extern "C" int lcma_launch_prep_b_{sch}_{dt}(const lcma::PrepParams *p, int gx, int gy, void *stream);')
         L.insert(3, f'extern "C" int lcma_launch_prep_bt_{sch}_{dt}(const lcma::PrepParams *p, int gx, int gy, void *stream);')
@@ -539,6 +542,16 @@ def emit_stage(s: Scheme, dtype: str) -> str:
     w(f"    lcma_k_comb_h_{s.name}_{dtype}<<<dim3(gx, gy), dim3(256), 0, (hipStream_t)stream>>>(*p);")
     w("    return (int)hipGetLastError();")
     w("}")
+    if dtype != "f32":  # the same sums from planes that hold the products in fp32
+        w("")
+        w(f'extern "C" __global__ __launch_bounds__(256) void lcma_k_comb_h32_{s.name}_{dtype}(const lcma::CombHParams p) {{')
+        w(f"    combine_h_tile<{in_t}, F32, CombH>(p);")
+        w("}")
+        w("")
+        w(f'extern "C" int lcma_launch_comb_h32_{s.name}_{dtype}(const lcma::CombHParams *p, int gx, int gy, void *stream) {{')
+        w(f"    lcma_k_comb_h32_{s.name}_{dtype}<<<dim3(gx, gy), dim3(256), 0, (hipStream_t)stream>>>(*p);")
+        w("    return (int)hipGetLastError();")
+        w("}")
     return "\n".join(L) + "\n"
 
 

@@ -278,7 +278,9 @@ def test_weight_layout_and_unfused_host_side(B):
     assert B.lcma_unfused_workspace_bytes(s, 4096, 4096, 4096, B.LCMA_BF16) == 3 * 7 * 2048 * 2048 * 2
     assert B.lcma_unfused_workspace_bytes(s, 100, 200, 72, B.LCMA_F32) == 7 * (128 * 48 + 128 * 48 + 128 * 128) * 4
     lad = B.lcma_scheme_load("builtin:laderman")
-    assert B.lcma_unfused_workspace_bytes(lad, 384, 384, 192, B.LCMA_F16) == 23 * (128 * 64 * 2 + 128 * 128) * 2
+    # fp16 storage: planes of At and Bt in fp16, the products in fp32
+    assert B.lcma_unfused_workspace_bytes(lad, 384, 384, 192, B.LCMA_F16) == 23 * (128 * 64 * 2 * 2 + 128 * 128 * 4)
+    assert B.lcma_unfused_workspace_bytes(lad, 384, 384, 192, B.LCMA_BF16) == 23 * (128 * 64 * 2 + 128 * 128) * 2
     assert B.lcma_unfused_workspace_bytes(s, 4096, 4096, 4096, 17) == -1
 
     def unfused(level=1, M=256, N=256, K=256, a=P, ws=P, nbytes=1 << 30, dt=B.LCMA_F16, sch=s.handle, lda=None):
