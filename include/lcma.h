@@ -356,9 +356,10 @@ double lcma_predict_seconds(int scheme_id, int64_t M, int64_t N, int64_t K, lcma
  *   "panel"            LCMA_PANEL=<n>               width, in tiles, of the column panels of the tile order (default 8)
  *   "batch_order"      LCMA_BATCH_ORDER=1           batched GEMM of lcma_gemm_unfused level 1 in group-major instead of
  *                                                   product-major order
- *   "schedule"         LCMA_SCHEDULE=static|split   batched GEMM stages: one tile-product per work-group, or contiguous ranges
- *                                                   of steps per persistent work-group (Sec. 3.2, Split-Group Parallelism);
- *                                                   default: whichever the time model prefers
+ *   "schedule"         LCMA_SCHEDULE=static|split|persist   batched GEMM stages: one tile-product per work-group, contiguous
+ *                                                   ranges of steps per persistent work-group (Sec. 3.2, Split-Group
+ *                                                   Parallelism), or persistent work-groups that take whole tile-products in
+ *                                                   turn; default: whichever the time model prefers
  *   "unfused_stages"   LCMA_UNFUSED_STAGES=<mask>   for timing one stage of lcma_gemm_unfused alone: bit 0 Combine A, bit 1
  *                                                   Combine B, bit 2 the GEMM stage, bit 3 Combine H (default 15, all).  The one
  *                                                   setting that is not result-neutral: a stage switched off leaves its output

@@ -64,7 +64,7 @@ bool set_tuning(const char *key, const char *value) {
     else if (!std::strcmp(key, "unfused_variant")) g_forced_unfused = *v ? find_variant(v) : nullptr;
     else if (!std::strcmp(key, "panel")) g_panel = *v ? (std::atoi(v) < 1 ? 1 : std::atoi(v)) : 8;
     else if (!std::strcmp(key, "batch_order")) g_batch_order = *v ? std::atoi(v) != 0 : 0;
-    else if (!std::strcmp(key, "schedule")) g_schedule = !std::strcmp(v, "static") ? 1 : !std::strcmp(v, "split") ? 2 : 0;
+    else if (!std::strcmp(key, "schedule")) g_schedule = !std::strcmp(v, "static") ? 1 : !std::strcmp(v, "split") ? 2 : !std::strcmp(v, "persist") ? 3 : 0;
     else if (!std::strcmp(key, "unfused_stages")) g_stages = *v ? (std::atoi(v) & 15) : 15;
     else return false;
     return true;

@@ -62,6 +62,9 @@ template <class KIND, int TM, int TN, int WGM, int WGN, class OUT, bool SPLIT = 
     static_assert(TM * 8 % NT == 0 && TN * 8 % NT == 0 && WM % 32 == 0 && WN % 32 == 0, "tile and wave grid");
     static_assert(LDS_BYTES <= 160 * 1024, "LDS budget of one CU");
     static constexpr int TILE_FLOATS = TM * TN;
+    // the persistent kernel sends the first loads of its next tile-product during the last step of the current one when
+    // the epilogue's strips fit the one stage that is free by then
+    static constexpr bool XTILE = SPLIT && DIRECT && NT / 64 * 32 * (WN * OUT::ES + 16) <= STAGE;
 
     // 128-byte rows: two rows per 256-byte bank window; 16 consecutive rows at one chunk column spread over the 16
     // chunk positions of a window
@@ -202,10 +205,12 @@ template <class KIND, int TM, int TN, int WGM, int WGN, class OUT, bool SPLIT = 
     // set to work on while those reads travel, where otherwise all waves of a SIMD would stand at the start of a step
     // waiting for their first fragments.  The barrier therefore means "every wave has READ the stage", which is all
     // the next loads into it need.  (restrict: the loads in flight towards `wr` do not touch what is read from `rd`.)
+    // a_next / b_next: byte offsets in the operands of the step whose loads leave now (the next step of this
+    // tile-product, or the first step of the work-group's next one), if `more`.
     static LCMA_DEV void step_across(const State &s, const LCMA_LDS char *__restrict__ rd, LCMA_LDS char *__restrict__ wr,
-                                     uint32_t a_base, uint32_t b_base, int y_next, bool more, const int (&sa)[NMI],
+                                     uint32_t a_next, uint32_t b_next, bool more, const int (&sa)[NMI],
                                      const int (&sb)[NNI], f32x16 (&acc)[NMI][NNI], FragT (&fa)[2][NA], FragT (&fb)[2][NNI]) {
-        if (more) issue(s, wr, a_base, b_base, y_next);
+        if (more) issue(s, wr, a_next, b_next, 0);
 #pragma unroll
         for (int sub = 0; sub + 1 < SUBS; ++sub) {
             read_set(s, rd, sub + 1, fa, fb);
@@ -277,16 +282,31 @@ template <class KIND, int TM, int TN, int WGM, int WGN, class OUT, bool SPLIT = 
         const int per = p.units >> 3;
         if (unit < (per << 3)) unit = (unit & 7) * per + (unit >> 3);
         const int cap = (int)p.cap, begin = unit * cap, end = begin + cap < total ? begin + cap : total;
-        int pos = begin;
-        while (pos < end) {
-            // (without SPLIT the launch has one work-group per tile-product and cap = ny: one pass, whole tile)
-            const int job = SPLIT ? pos / ny : unit, y0 = SPLIT ? pos - job * ny : 0;
-            const int y1 = SPLIT ? ((job + 1) * ny <= end ? ny : end - job * ny) : ny;
-            // tile of this job: product-major; inside a product tiles run down x inside column panels of `panel` z tiles
-            const int plane = job / tiles;
-            int id = job - plane * tiles;
+        // the pieces of this work-group, in order: steps [y0, y1) of tile-product `job`
+        struct Piece {
+            int job, y0, y1;
+            bool ok;
+        };
+        auto piece_from = [&](int pos) { // ranges of steps: the piece that starts at step `pos`
+            if (pos >= end) return Piece{0, 0, 0, false};
+            const int job = pos / ny;
+            return Piece{job, pos - job * ny, (job + 1) * ny <= end ? ny : end - job * ny, true};
+        };
+        auto first_piece = [&]() {
+            if constexpr (!SPLIT) return Piece{unit, 0, ny, true}; // one work-group per tile-product
+            if (p.interleave) return Piece{unit, 0, ny, unit < p.jobs};
+            return piece_from(begin);
+        };
+        auto piece_after = [&](const Piece &c) {
+            if constexpr (!SPLIT) return Piece{0, 0, 0, false};
+            if (p.interleave) return Piece{c.job + p.units, 0, ny, c.job + p.units < p.jobs};
+            return piece_from(c.job * ny + c.y1);
+        };
+        // tile of a job: product-major; inside a product tiles run down x inside column panels of `panel` z tiles
+        auto locate = [&](int job, int &plane, int &x, int &z) {
+            plane = job / tiles;
+            const int id = job - plane * tiles;
             const int pw = p.panel, full = (p.nz / pw) * pw * p.nx;
-            int x, z;
             if (id < full) {
                 const int pi = id / (pw * p.nx), rem = id - pi * (pw * p.nx);
                 x = rem / pw;
@@ -295,6 +315,26 @@ template <class KIND, int TM, int TN, int WGM, int WGN, class OUT, bool SPLIT = 
                 const int w2 = p.nz - (p.nz / pw) * pw, rem = id - full;
                 x = rem / w2;
                 z = (p.nz / pw) * pw + rem % w2;
+            }
+        };
+        FragT fa[2][NA], fb[2][NNI]; // fragment sets in flight (direct loads); set 0 of a primed piece is read before its loop
+        int st = 0;                  // stage that holds the first step of the coming piece
+        bool primed = false;         // ... whose loads were sent during the last step of the piece before
+        Piece cur = first_piece();
+        while (cur.ok) {
+            const int y0 = cur.y0, y1 = cur.y1;
+            int plane, x, z;
+            locate(cur.job, plane, x, z);
+            Piece nxt{0, 0, 0, false};
+            uint32_t a_first = 0, b_first = 0; // first step of the next piece
+            if constexpr (XTILE) {
+                nxt = piece_after(cur);
+                if (nxt.ok) {
+                    int pl, nx_, nz_;
+                    locate(nxt.job, pl, nx_, nz_);
+                    a_first = (uint32_t)pl * p.a_plane + (uint32_t)nx_ * TM * p.lda_b + (uint32_t)nxt.y0 * ROW;
+                    b_first = (uint32_t)pl * p.b_plane + (uint32_t)nz_ * TN * p.ldb_b + (uint32_t)nxt.y0 * ROW;
+                }
             }
             const uint32_t a_base = (uint32_t)plane * p.a_plane + (uint32_t)x * TM * p.lda_b;
             const uint32_t b_base = (uint32_t)plane * p.b_plane + (uint32_t)z * TN * p.ldb_b;
@@ -340,24 +380,26 @@ template <class KIND, int TM, int TN, int WGM, int WGN, class OUT, bool SPLIT = 
 #pragma unroll
                 for (int ni = 0; ni < NNI; ++ni) zero(acc[mi][ni]);
 
-            // the stage alternates from 0 at the first step of the piece; it is kept a run-time value on purpose: one
-            // copy of the step, no accumulator copies where unrolled copies would join
             load_scales(y0 >> 2, sa_cur, sb_cur);
             load_scales((y0 >> 2) + 1, sa_nxt, sb_nxt);
             if constexpr (DIRECT) {
-                FragT fa[2][NA], fb[2][NNI];
-                issue(s, lds, a_base, b_base, y0);
-                landed_barrier();
-                read_set(s, lds, 0, fa, fb);
-                auto one = [&](int y, int st) {
+                if (!primed) {
+                    issue(s, lds + st * STAGE, a_base, b_base, y0);
+                    landed_barrier();
+                    read_set(s, lds + st * STAGE, 0, fa, fb);
+                }
+                // the stage alternates and stays a run-time value: two unrolled copies with literal stages gain nothing
+                // for 16-bit operands and cost the FP8 kernel 10 % (registers)
+                for (int y = y0; y < y1; ++y) {
                     int sa[NMI], sb[NNI];
                     turn_scales(y);
                     scales_of(y, sa, sb);
-                    step_across(s, lds + st * STAGE, lds + (st ^ 1) * STAGE, a_base, b_base, y + 1, y + 1 < y1, sa, sb, acc, fa, fb);
-                };
-                // the stage alternates from 0 at the first step of the piece and stays a run-time value: two unrolled
-                // copies with literal stages gain nothing for 16-bit operands and cost the FP8 kernel 10 % (registers)
-                for (int y = y0; y < y1; ++y) one(y, (y - y0) & 1);
+                    const bool last = y + 1 == y1;
+                    step_across(s, lds + st * STAGE, lds + (st ^ 1) * STAGE, last ? a_first : a_base + (uint32_t)(y + 1) * ROW,
+                                last ? b_first : b_base + (uint32_t)(y + 1) * ROW, !last || nxt.ok, sa, sb, acc, fa, fb);
+                    st ^= 1;
+                }
+                primed = nxt.ok; // its first step sits in stage st, fragment set 0 of it in fa[0], fb[0]
             } else {
                 u32x4 rega[QA], regb[QB];
                 auto fetch = [&](int y) {
@@ -401,9 +443,14 @@ template <class KIND, int TM, int TN, int WGM, int WGN, class OUT, bool SPLIT = 
                 __syncthreads(); // the stages are free for the epilogue and for the next tile-product
             }
 
-            if (!SPLIT || (y0 == 0 && y1 == ny)) store_tile(p, s, lds, plane, x, z, acc);
+            // the strips of the epilogue go through the stage the last step read when the other one may already hold the
+            // first step of the next piece (they fit one stage then), else through both from the start; every wave has
+            // passed the barrier of the last step
+            LCMA_LDS char *strips = XTILE ? lds + (st ^ 1) * STAGE : lds;
+            if (!SPLIT || (y0 == 0 && y1 == ny)) store_tile(p, s, strips, plane, x, z, acc);
             else store_piece(p, s, unit * 2 + (y0 == 0 ? 1 : 0), acc);
-            pos = SPLIT ? job * ny + y1 : end;
+            if constexpr (XTILE) cur = nxt;
+            else cur = piece_after(cur);
         }
     }
 
@@ -417,7 +464,7 @@ template <class KIND, int TM, int TN, int WGM, int WGN, class OUT, bool SPLIT = 
                                     const f32x16 (&acc)[NMI][NNI]) {
         constexpr int OES = OUT::ES; // 2: C rounded to fp16 / bf16; 4: the fp32 sums as they are
         constexpr int PITCH = WN * OES + 16, CPRW = WN * OES / 16, NIT = 32 * CPRW / 64;
-        static_assert(NT / 64 * 32 * PITCH <= LDS_BYTES, "the strips of all waves fit the stage buffers");
+        static_assert(NT / 64 * 32 * PITCH <= (XTILE ? STAGE : LDS_BYTES), "the strips of all waves fit the stage buffers");
         const uint32_t c_base = (uint32_t)plane * p.c_plane + (uint32_t)x * TM * p.ldc_b + (uint32_t)z * TN * OES;
         LCMA_LDS char *strip = lds + s.w * (32 * PITCH);
 #pragma unroll

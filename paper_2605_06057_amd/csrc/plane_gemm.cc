@@ -58,8 +58,15 @@ namespace {
 // first kernel and read back by the second, about 70 us at the rates these kernels reach, as long as 40 large steps
 // (measured: the schedule loses wherever fewer steps than that are saved).
 // tile, schedule: 0 = choose.  Returns the cost in large steps (0 when nothing fits).
-double choose(int planes, int64_t rows, int64_t cols, int ny, int tile, int schedule, int64_t scratch_bytes, int *best_tile,
-              int *best_sched) {
+// What starting and finishing a tile-product costs, in steps of the large tile: a work-group of its own per tile-product
+// (launch, first loads with nothing to overlap them, epilogue) against a persistent work-group that sends the first
+// loads of its next tile-product during the last step of the current one (measured on the FFN shapes: the batched
+// stage of Algorithm 1, 32 steps per tile-product, gains 9 %, the plain 16-bit product with 64 steps 2 to 4 %).
+const double kTileCost = 5.0, kTileCostPersistent = 2.0;
+// persist_ok: the persistent whole-tile schedule may be chosen (16-bit operands; the FP8 kernel loses 8 % with it: the
+// scale bytes of the next tile-product are not fetched ahead)
+double choose(int planes, int64_t rows, int64_t cols, int ny, int tile, int schedule, int64_t scratch_bytes, bool persist_ok,
+              int *best_tile, int *best_sched) {
     double best = 0.0;
     *best_tile = *best_sched = 0;
     for (int t : {256, 128}) {
@@ -67,10 +74,14 @@ double choose(int planes, int64_t rows, int64_t cols, int ny, int tile, int sche
         if (planes > 1 && (rows % t || cols % t)) continue; // planes lie back to back: a tile must not hang over the end of one
         const int64_t jobs = (int64_t)planes * ceil_div(rows, t) * ceil_div(cols, t);
         const double unit = t == 256 ? 1.0 : 0.76;
-        for (int sc : {1, 2}) {
-            if (schedule && sc != schedule) continue;
+        for (int sc : {1, 2, 3}) {
+            if (schedule ? sc != schedule : sc == 3 && !persist_ok) continue;
             if (sc == 2 && scratch_bytes < plane_gemm_scratch_bytes(t)) continue;
-            const double steps = sc == 1 ? (double)plane_gemm_static_steps(jobs, ny, t) : (double)plane_gemm_split_steps(jobs, ny, t) + 40.0;
+            // whole tile-products (one per work-group, or persistent work-groups that take every units-th one): rounds of
+            // ny steps plus, per round, what starting and finishing a tile costs in steps; ranges of steps: one long round
+            const double rounds = (double)ceil_div(jobs, slots_of(t));
+            const double steps = sc == 2 ? (double)plane_gemm_split_steps(jobs, ny, t) + 40.0
+                                         : rounds * (ny + (sc == 3 && rounds > 1 ? kTileCostPersistent : kTileCost));
             const double cost = steps * unit * (sc == 2 ? 1.05 : 1.0); // the persistent kernel's step is 5 % slower
             if (!*best_tile || cost < best) {
                 best = cost;
@@ -89,22 +100,22 @@ double choose(int planes, int64_t rows, int64_t cols, int ny, int tile, int sche
 // chip's power limit), plus a fixed 8 us for every tile a work-group works through (launch, first loads, epilogue).
 double plane_gemm_seconds(int planes, int64_t rows, int64_t cols, int ny, int64_t scratch_bytes) {
     int t = 0, sc = 0;
-    const double steps = choose(planes, rows, cols, ny, 0, tuning_schedule(), scratch_bytes, &t, &sc);
+    const double steps = choose(planes, rows, cols, ny, 0, tuning_schedule(), scratch_bytes, true, &t, &sc);
     if (!t) return -1.0;
-    const int64_t jobs = (int64_t)planes * ceil_div(rows, t) * ceil_div(cols, t);
-    const double rounds = sc == 1 ? (double)ceil_div(jobs, slots_of(t)) : 1.0;
-    return steps * 1.62e-6 + rounds * 8.0e-6;
+    return steps * 1.62e-6;
 }
 
 // p: operands, extents, pitches, plane strides, ny, n_row_b filled in by the caller for `planes` planes of rows x cols
 // (padded sizes, multiples of the tile when batched).  tile: 256 or 128, 0 = choose.  schedule: 0 = choose, 1 = one
-// tile-product per work-group, 2 = Split-Group ranges (needs `scratch` of plane_gemm_scratch_bytes(tile) bytes).
+// tile-product per work-group, 2 = Split-Group ranges (needs `scratch` of plane_gemm_scratch_bytes(tile) bytes), 3 =
+// persistent work-groups that each take every units-th whole tile-product.
 lcma_status plane_gemm(const char *who, int kind, PlaneGemmParams p, int planes, int64_t rows, int64_t cols, int tile,
                        int schedule, void *scratch, int64_t scratch_bytes, void *stream) {
     const int forced = tuning_schedule();
     if (forced) schedule = forced;
     int best_tile = 0, best_sched = 0;
-    choose(planes, rows, cols, p.ny, tile, schedule, scratch ? scratch_bytes : 0, &best_tile, &best_sched);
+    choose(planes, rows, cols, p.ny, tile, schedule, scratch ? scratch_bytes : 0, kind != PG_FP8_BF16 && kind != PG_FP8_F16, &best_tile,
+           &best_sched);
     if (!best_tile) {
         if (schedule == 2)
             return fail(LCMA_ERR_ARG, "%s: the Split-Group schedule needs %lld bytes of scratch", who,
@@ -123,7 +134,13 @@ lcma_status plane_gemm(const char *who, int kind, PlaneGemmParams p, int planes,
     const int panel = tuning_panel();
     p.panel = panel < p.nz ? panel : p.nz;
     const int slots = slots_of(tile);
-    if (schedule == 2) {
+    p.interleave = 0;
+    if (schedule == 3) { // persistent work-groups, whole tile-products u, u + units, ...
+        p.units = (int32_t)(jobs < slots ? jobs : slots);
+        p.cap = p.ny;
+        p.interleave = 1;
+        p.partial = nullptr;
+    } else if (schedule == 2) {
         p.units = (int32_t)(total < slots ? total : slots);
         p.cap = ceil_div(total, p.units);
         p.units = (int32_t)ceil_div(total, p.cap); // no idle work-group at the end
