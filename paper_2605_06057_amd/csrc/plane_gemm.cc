@@ -55,14 +55,17 @@ namespace {
 // the small tile does a quarter of the work with two work-groups per CU, at three quarters of the efficiency
 // (measured): 0.76 of a large step for two of them, so 0.38 each, twice as many run at once.  The Split-Group schedule
 // adds the pieces: nearly every work-group holds two, 134 MB of fp32 partial sums in all, written at the end of the
-// first kernel and read back by the second, about 70 us at the rates these kernels reach, as long as 40 large steps
-// (measured: the schedule loses wherever fewer steps than that are saved).
+// first kernel and read back by the second.  Measured against the other schedules on seven LLM shapes (plain, batched
+// 16-bit and batched FP8 products): it wins only where it saves more than about 80 steps (few tile-products, long K:
+// 64 tiles of K = 16384 run 26 % faster), and loses 3 to 25 % where the model had priced the pieces at 40.
 // tile, schedule: 0 = choose.  Returns the cost in large steps (0 when nothing fits).
 // What starting and finishing a tile-product costs, in steps of the large tile: a work-group of its own per tile-product
 // (launch, first loads with nothing to overlap them, epilogue) against a persistent work-group that sends the first
 // loads of its next tile-product during the last step of the current one (measured on the FFN shapes: the batched
 // stage of Algorithm 1, 32 steps per tile-product, gains 9 %, the plain 16-bit product with 64 steps 2 to 4 %).
 const double kTileCost = 5.0, kTileCostPersistent = 2.0;
+// The Split-Group schedule adds the pieces (see below): as long as 80 steps of the large tile.
+const double kSplitCost = 80.0;
 // persist_ok: the persistent whole-tile schedule may be chosen (16-bit operands; the FP8 kernel loses 8 % with it: the
 // scale bytes of the next tile-product are not fetched ahead)
 double choose(int planes, int64_t rows, int64_t cols, int ny, int tile, int schedule, int64_t scratch_bytes, bool persist_ok,
@@ -80,7 +83,7 @@ double choose(int planes, int64_t rows, int64_t cols, int ny, int tile, int sche
             // whole tile-products (one per work-group, or persistent work-groups that take every units-th one): rounds of
             // ny steps plus, per round, what starting and finishing a tile costs in steps; ranges of steps: one long round
             const double rounds = (double)ceil_div(jobs, slots_of(t));
-            const double steps = sc == 2 ? (double)plane_gemm_split_steps(jobs, ny, t) + 40.0
+            const double steps = sc == 2 ? (double)plane_gemm_split_steps(jobs, ny, t) + kSplitCost
                                          : rounds * (ny + (sc == 3 && rounds > 1 ? kTileCostPersistent : kTileCost));
             const double cost = steps * unit * (sc == 2 ? 1.05 : 1.0); // the persistent kernel's step is 5 % slower
             if (!*best_tile || cost < best) {
