@@ -382,6 +382,13 @@ template <class KIND, int TM, int TN, int WGM, int WGN, class OUT, bool SPLIT = 
 
             load_scales(y0 >> 2, sa_cur, sb_cur);
             load_scales((y0 >> 2) + 1, sa_nxt, sb_nxt);
+            if constexpr (SCALED && XTILE) {
+                // the scale dwords are waited for here, once per piece: with these loads still counted as in flight at the
+                // top of the step loop the compiler puts a wait for them behind the direct loads of EVERY step, which then
+                // waits for two of those as well (the counter runs in order)
+                __builtin_amdgcn_s_waitcnt(0x0070);
+                asm volatile("" ::: "memory");
+            }
             if constexpr (DIRECT) {
                 if (!primed) {
                     issue(s, lds + st * STAGE, a_base, b_base, y0);

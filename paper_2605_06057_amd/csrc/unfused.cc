@@ -84,7 +84,7 @@ const Variant *find_gemm(bool batch, int scheme_id, int dtype, int R, const Geom
     return best;
 }
 
-const double kLaunch = 4.0e-6; // seconds per launch
+const double kLaunch = 2.0e-6; // seconds per launch of a stage (the launches of one call follow each other on one stream)
 
 } // namespace
 } // namespace lcma
