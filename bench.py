@@ -195,6 +195,12 @@ def side_workload(name, args):
         B.lcma_set_tuning("unfused_stages", "4")
         _, kernel_ms, _ = _timed(torch, lambda i: B.lcma_gemm_unfused(1, *sets[i % 3], scheme, ws), max(10, steps // 2), 3, args.heat_seconds)
         B.lcma_set_tuning("unfused_stages", "")
+    alg1_tf = None
+    if ran["flow"] == 0 and ws is not None:  # Algorithm 1 called directly, for comparison with what the library chose
+        a_wall, _, _ = _timed(torch, lambda i: B.lcma_gemm_unfused(1, *sets[i % 3], scheme, ws), max(10, steps // 2), 3, args.heat_seconds)
+        alg1_tf = flops / (a_wall * 1e-3) / 1e12
+        alg1_c = sets[2][2].clone()
+        B.lcma_gemm_unfused(1, sets[2][0], sets[2][1], alg1_c, scheme, ws)
     p_wall, _, _ = _timed(torch, lambda i: B.lcma_gemm(*sets[i % 3], None), steps, warmup, args.heat_seconds)
     v_wall, _, _ = _timed(torch, lambda i: torch.mm(sets[i % 3][0], sets[i % 3][1], out=sets[i % 3][2]), max(10, steps // 2), 3, args.heat_seconds)
     peak = PEAK_TFLOPS[dt]
@@ -205,6 +211,7 @@ def side_workload(name, args):
            "plain_mfma_gemm_tflops": flops / (p_wall * 1e-3) / 1e12, "vs_plain": p_wall / wall,
            "vendor_gemm_tflops": flops / (v_wall * 1e-3) / 1e12,
            "dataflow": "algorithm1" if ran["flow"] == 1 else "fused", "fused_kernel_tflops": fused_tf,
+           "algorithm1_not_chosen_tflops": alg1_tf,
            "roofline": {"bound": "mfma", "achieved": mfma_flops / (kernel_ms * 1e-3) / 1e12, "peak": peak, "unit": "TFLOP/s",
                         "frac": mfma_flops / (kernel_ms * 1e-3) / 1e12 / peak, "kernel_ms": kernel_ms,
                         "traffic": read_traffic(name + ("_alg1" if ran["flow"] == 1 else ""))}}
@@ -223,6 +230,8 @@ def side_workload(name, args):
             return t.cpu().numpy().astype(np.float64)
         out["rel_frobenius_error"] = {"lcma": oracle.rel_frobenius(host(sets[0][2]), ref),
                                       "plain": oracle.rel_frobenius(host(sets[1][2]), ref), "rows_checked": int(len(rows))}
+        if alg1_tf is not None:  # (for <3,3,3;23> in fp16 this is why the library does not offer it: past 4 x plain)
+            out["rel_frobenius_error"]["algorithm1_not_chosen"] = oracle.rel_frobenius(host(alg1_c), ref)
     del sets, ws
     torch.cuda.empty_cache()
     return out
@@ -407,6 +416,14 @@ def main():
             pg_wall_ms, _, _ = timed(lambda i: B.lcma_gemm_nt_ws(sets[i % 3][0], ws[i % 3], sets[i % 3][2], sg), args.steps, args.warmup)
             nk["plain_plane_gemm_tflops"] = flops / (pg_wall_ms * 1e-3) / 1e12
             del sg
+        if ws_main is not None:  # lcma_gemm_ws on this layout: the time model's dataflow, Combine B straight from the N x K weights
+            flow_nk = {"ran": 0}
+
+            def nt_ws_step(i):
+                flow_nk["ran"] = B.lcma_gemm_ws(sets[i % 3][0], ws[i % 3], sets[i % 3][2], scheme, ws_main, b_nk=True)
+            w_wall_ms, _, _ = timed(nt_ws_step, args.steps, args.warmup)
+            nk["lcma_gemm_ws_tflops"] = flops / (w_wall_ms * 1e-3) / 1e12
+            nk["lcma_gemm_ws_dataflow"] = "algorithm1" if flow_nk["ran"] == 1 else "fused"
         nt_step(0)
         torch.cuda.synchronize()
         nk["_c"] = sets[0][2].clone()

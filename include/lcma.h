@@ -207,6 +207,10 @@ lcma_status lcma_gemm_prepared(int64_t M, int64_t N, int64_t K, const void *A, i
  * storage, fp32 for F32): each is an fp32 sum (ascending block order) rounded once, to nearest-even.  H_r at level 1 is
  * the fp32 MFMA accumulation, stored in fp16 (rounded once) for BF16 and as it is, in fp32, for F16 and F32: fp16 planes
  * carry no more bits than an fp16 C, and their roundings would put the result past four times the plain kernel's error.
+ * <3,3,3;23> with F16 storage at level 1 works on 25 planes instead of 23: products 4 and 7 (three blocks on either side)
+ * have the remainder of rounding their left combination to fp16 stored as a further plane and multiplied with a second
+ * copy of Bt_r, both products entering Eq. 6 with the W row of r (without it the result lies at 4.04 times the plain
+ * kernel's error, with it at 3.8, where the fused kernels of the scheme are for the same reason).
  * C is rounded once from fp32.
  * A, B, C, sizes, alignment, padding and errors as for lcma_gemm; `scheme` is required and must be
  * one of the paper's (NOKERNEL otherwise).  workspace: device memory, 256-byte aligned, at least
@@ -239,17 +243,23 @@ lcma_status lcma_gemm_unfused(int level, int64_t M, int64_t N, int64_t K,
                               void *C, int64_t ldc, lcma_dtype dtype, const lcma_scheme *scheme,
                               void *workspace, int64_t workspace_bytes, int reuse_bt, void *stream);
 
-/* lcma_gemm with a workspace (Sec. 3.3, the Decision Module applied to the two dataflows of one scheme): the same product
- * C = A x B, run as the fused kernel of lcma_gemm or as Algorithm 1 (lcma_gemm_unfused level 1), whichever the time model
- * (lcma_predict_seconds against lcma_predict_unfused_seconds with Combine B counted) predicts faster for the shape.
+/* lcma_gemm / lcma_gemm_nt with a workspace (Sec. 3.3, the Decision Module applied to the dataflows of one scheme): the same
+ * product C = A x B (b_layout 0: B given K x N as in lcma_gemm) or C = A x W^T (b_layout 2: W given N x K as in lcma_gemm_nt),
+ * run as the fused kernel of those calls or as Algorithm 1 (lcma_gemm_unfused level 1; for N x K weights its Combine B reads
+ * W without transposing), whichever the time model (lcma_predict_seconds against lcma_predict_unfused_seconds with Combine
+ * B counted) predicts faster for the shape.
  * workspace: device memory, 256-byte aligned, overwritten; Algorithm 1 is considered only when it holds at least
  * lcma_unfused_workspace_bytes() bytes (lcma_split_group_scratch_bytes() more let its GEMM stage split tile-products
- * between work-groups); NULL, too small, scheme == NULL, a scheme that is not built in, a shape that Algorithm 1 does
- * not take, or F16 storage with a scheme that sums more than 4 blocks in a row of U or V (<3,3,3;23>: its fp16
- * combinations put Algorithm 1 at 4.04 times the plain kernel's error, past the bound of 4): lcma_gemm.  *dataflow (may be NULL) receives what ran: 0 = lcma_gemm, 1 = Algorithm 1.  The two dataflows
- * round differently (Algorithm 1 stores the products H_r: in fp16 for BF16, in fp32 for F16 and F32): each meets the error bounds stated
- * for it, their results are not bit-identical.  Errors: those of the call that ran. */
-lcma_status lcma_gemm_ws(int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const void *B, int64_t ldb,
+ * between work-groups); NULL, too small, a scheme that is not built in, a shape that Algorithm 1 does not take, or F16
+ * storage with a scheme that sums more than 4 blocks in a row of U or V and whose stage kernels do not compensate for it
+ * (its fp16 combinations would put Algorithm 1 past four times the plain kernel's error; the kernels of <3,3,3;23> do
+ * compensate, see lcma_gemm_unfused): the fused kernel.  scheme == NULL: the plain product
+ * (b_layout 2: lcma_gemm_nt_ws, which uses the workspace for its Split-Group schedule).
+ * *dataflow (may be NULL) receives what ran: 0 = the fused kernel or the plain product, 1 = Algorithm 1.  The two dataflows
+ * round differently (Algorithm 1 stores the products H_r: in fp16 for BF16, in fp32 for F16 and F32): each meets the error
+ * bounds stated for it, their results are not bit-identical.  Errors: ARG for another b_layout, else those of the call
+ * that ran. */
+lcma_status lcma_gemm_ws(int b_layout, int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const void *B, int64_t ldb,
                          void *C, int64_t ldc, lcma_dtype dtype, const lcma_scheme *scheme,
                          void *workspace, int64_t workspace_bytes, int *dataflow, void *stream);
 

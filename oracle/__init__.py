@@ -195,7 +195,8 @@ def combine_a_stored(s: Scheme, A: np.ndarray, dtype: str) -> np.ndarray:
     return out
 
 
-def lcma_unfused(s: Scheme, A: np.ndarray, B: np.ndarray, dtype: str, level: int, h_dtype: str | None = None) -> np.ndarray:
+def lcma_unfused(s: Scheme, A: np.ndarray, B: np.ndarray, dtype: str, level: int, h_dtype: str | None = None,
+                 residual_products: tuple = ()) -> np.ndarray:
     """C by the dataflows that keep intermediate results in memory, with the roundings that storing
     them implies (values in fp64, before the final rounding of C to the storage type):
       level 1  Algorithm 1: At_r and Bt_r stored (combine_a_stored, combine_b_stored), H_r = At_r Bt_r
@@ -203,6 +204,9 @@ def lcma_unfused(s: Scheme, A: np.ndarray, B: np.ndarray, dtype: str, level: int
                caller names it with h_dtype "f16" or "f32"; None: fp16 for 16-bit storage, fp32 for fp32 storage),
                C_{i,j} = sum_r W[r,i,j] H_r (Eq. 6);
       level 2  Algorithm 2 as printed: At_r and Bt_r stored, H_r kept unrounded on chip.
+    residual_products (level 1, 16-bit storage): products r whose left combination is kept as TWO stored values, the
+    rounded sum and the rounded remainder of that rounding, each multiplied with Bt_r and both products (each rounded as
+    H_r is) entering Eq. 6 with W[r]: the error compensation for combinations of many blocks.
     A and B hold values representable in the storage type; shapes divisible by the grid."""
     if level not in (1, 2):
         raise ValueError("level is 1 (Algorithm 1) or 2 (Algorithm 2)")
@@ -210,14 +214,22 @@ def lcma_unfused(s: Scheme, A: np.ndarray, B: np.ndarray, dtype: str, level: int
     Bt = combine_b_stored(s, B, dtype)       # [r, y, z]
     bm, bn = At.shape[1], Bt.shape[2]
     C = np.zeros((s.m * bm, s.n * bn), np.float64)
+    ht = h_dtype or ("f16" if dtype in ("bf16", "f16") else "f32")
+    if ht not in ("f16", "f32"):
+        raise ValueError("h_dtype is f16 or f32")
+    stored_h = lambda H: (H.astype(np.float16) if ht == "f16" else H.astype(np.float32)).astype(np.float64)
+    At32 = combine_a_stored(s, A, "f32") if residual_products else None   # the fp32 sums of Eq. 3 before they are rounded
+    if residual_products and (level != 1 or dtype not in ("bf16", "f16")):
+        raise ValueError("residual products belong to level 1 with 16-bit storage")
     with np.errstate(over="ignore"):
         for r in range(s.R):
             H = gemm(np.ascontiguousarray(At[r]), np.ascontiguousarray(Bt[r]))
             if level == 1:
-                ht = h_dtype or ("f16" if dtype in ("bf16", "f16") else "f32")
-                if ht not in ("f16", "f32"):
-                    raise ValueError("h_dtype is f16 or f32")
-                H = (H.astype(np.float16) if ht == "f16" else H.astype(np.float32)).astype(np.float64)
+                H = stored_h(H)
+                if r in residual_products:
+                    # the unrounded fp32 sum of Eq. 3 minus its stored value, stored in fp16 itself
+                    rest = (At32[r] - At[r]).astype(np.float16).astype(np.float64)
+                    H = H + stored_h(gemm(np.ascontiguousarray(rest), np.ascontiguousarray(Bt[r])))
             for i in range(s.m):
                 for j in range(s.n):
                     w = int(s.W[r, i, j])

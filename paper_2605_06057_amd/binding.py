@@ -113,7 +113,7 @@ def lib() -> ctypes.CDLL:
         L.lcma_last_error.restype = cp
         L.lcma_set_tuning.argtypes = [cp, cp]
         L.lcma_gemm_nt_ws.argtypes = [i64, i64, i64, vp, i64, vp, i64, vp, i64, i32, vp, i64, vp]
-        L.lcma_gemm_ws.argtypes = [i64, i64, i64, vp, i64, vp, i64, vp, i64, i32, vp, vp, i64, ctypes.POINTER(ctypes.c_int), vp]
+        L.lcma_gemm_ws.argtypes = [i32, i64, i64, i64, vp, i64, vp, i64, vp, i64, i32, vp, vp, i64, ctypes.POINTER(ctypes.c_int), vp]
         L.lcma_fp16_range_flags.argtypes = [i64, i64, vp, i64, vp, vp]
         L.lcma_split_group_scratch_bytes.argtypes = []
         L.lcma_split_group_scratch_bytes.restype = i64
@@ -260,13 +260,14 @@ def lcma_gemm_unfused(level: int, A, B, C, scheme: Scheme, workspace, reuse_bt: 
     return C
 
 
-def lcma_gemm_ws(A, B, C, scheme, workspace=None) -> int:
-    """lcma_gemm with a workspace (uint8 device tensor or None); returns the dataflow that ran: 0 fused, 1 Algorithm 1."""
-    M, N, K, pa, lda, pb, ldb, pc, ldc, stream = _marshal(A, B, C)
+def lcma_gemm_ws(A, B, C, scheme, workspace=None, b_nk: bool = False) -> int:
+    """lcma_gemm (b_nk: lcma_gemm_nt, B is the N x K weight matrix) with a workspace (uint8 device tensor or None);
+    returns the dataflow that ran: 0 fused, 1 Algorithm 1."""
+    M, N, K, pa, lda, pb, ldb, pc, ldc, stream = _marshal(A, B, C, b_nk)
     ws_ptr = workspace.data_ptr() if workspace is not None else None
     ws_n = workspace.numel() * workspace.element_size() if workspace is not None else 0
     flow = ctypes.c_int(0)
-    _check(lib().lcma_gemm_ws(M, N, K, pa, lda, pb, ldb, pc, ldc, _dtype_of(A), scheme.handle if scheme is not None else None,
+    _check(lib().lcma_gemm_ws(2 if b_nk else 0, M, N, K, pa, lda, pb, ldb, pc, ldc, _dtype_of(A), scheme.handle if scheme is not None else None,
                               ws_ptr, ws_n, ctypes.byref(flow), stream))
     return int(flow.value)
 

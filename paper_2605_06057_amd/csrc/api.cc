@@ -285,14 +285,17 @@ namespace lcma {
 // The planes hold N/n rows padded to a multiple of n_gran and K/k columns padded to a multiple of k_gran
 // (multiples of 64 rows and 64 bytes).
 lcma_status prepare_b_planes(bool transposed, int64_t N, int64_t K, const void *B, int64_t ldb, lcma_dtype dtype,
-                             const lcma_scheme *scheme, void *Bt, void *stream, int64_t n_gran, int64_t k_gran) {
+                             const lcma_scheme *scheme, void *Bt, void *stream, int64_t n_gran, int64_t k_gran,
+                             const StageKernel *stage) {
     const char *who = transposed ? "lcma_prepare_bt" : "lcma_prepare_b";
     const int es = dtype_size(dtype);
     if (!es) return fail(LCMA_ERR_DTYPE, "%s: unknown dtype %d", who, (int)dtype);
     int id = 0;
     if (const lcma_status st = prepared_scheme(scheme, who, &id)) return st;
     const PrepKernel *pk = find_prep(id, dtype);
-    if (!pk) return fail(LCMA_ERR_NOKERNEL, "%s: no Combine-B kernel for scheme id %d with dtype %d", who, id, (int)dtype);
+    const bool own = stage && stage->launch_comb_b; // the stage kernels bring their own Combine B (more planes than R)
+    if (!pk && !own) return fail(LCMA_ERR_NOKERNEL, "%s: no Combine-B kernel for scheme id %d with dtype %d", who, id, (int)dtype);
+    const int planes = own ? stage->planes : scheme->R;
     if (N < 0 || K < 0) return fail(LCMA_ERR_ARG, "%s: negative size", who);
     if (N == 0 || K == 0) return LCMA_OK;
     if (!B || !Bt) return fail(LCMA_ERR_ARG, "%s: null pointer", who);
@@ -307,7 +310,7 @@ lcma_status prepare_b_planes(bool transposed, int64_t N, int64_t K, const void *
     // the planes hold the padded rows and columns (zeros)
     const int64_t bn = round_up(N, (int64_t)scheme->n * n_gran) / scheme->n,
                   bk = round_up(K, (int64_t)scheme->k * k_gran) / scheme->k;
-    const int64_t b_bytes = ((rows - 1) * ldb + cols) * es, bt_bytes = (int64_t)scheme->R * bn * bk * es;
+    const int64_t b_bytes = ((rows - 1) * ldb + cols) * es, bt_bytes = (int64_t)planes * bn * bk * es;
     const int64_t lim = (int64_t)1 << 31;
     const int64_t prow = transposed ? bn * scheme->n : bk * scheme->k, pcol = transposed ? bk * scheme->k : bn * scheme->n;
     if (((prow - 1) * ldb + pcol) * es >= lim || bt_bytes >= lim)
@@ -330,7 +333,7 @@ lcma_status prepare_b_planes(bool transposed, int64_t N, int64_t K, const void *
         gx = (int)(bn / 16);
         gy = (int)((bk * es + 255) / 256);
         if (gy > 65535) return fail(LCMA_ERR_SHAPE, "%s: K is too large", who);
-        err = pk->launch_t(&p, gx, gy, stream);
+        err = (own ? stage->launch_comb_bt : pk->launch_t)(&p, gx, gy, stream);
     } else {
         p.b_brow = (uint32_t)(bk * ldb * es);
         p.b_bcol = (uint32_t)(bn * es);
@@ -338,7 +341,7 @@ lcma_status prepare_b_planes(bool transposed, int64_t N, int64_t K, const void *
         gx = (int)(bn / 64);
         gy = (int)(bk / kt);
         if (gy > 65535) return fail(LCMA_ERR_SHAPE, "%s: K is too large", who);
-        err = pk->launch(&p, gx, gy, stream);
+        err = (own ? stage->launch_comb_b : pk->launch)(&p, gx, gy, stream);
     }
     if (err) return fail(LCMA_ERR_HIP, "%s: launch failed with HIP error %d", who, err);
     return LCMA_OK;

@@ -64,7 +64,12 @@ extern const int kPrepKernelCount;
 // The stand-alone Combine-A and Combine-H kernels of one scheme x dtype (stages 1 and 4 of Algorithm 1).
 struct StageKernel {
     int scheme_id, dtype;
+    int planes; // planes every stage works on: R, or more when some products also have the rounding residual of their left
+                // combination multiplied (a second plane pair with the W row of the product)
     int (*launch_comb_a)(const PrepParams *p, int grid_x, int grid_y, void *stream);
+    // Combine B for `planes` planes, B given K x N / N x K; null when planes == R (the offline Combine-B kernels serve)
+    int (*launch_comb_b)(const PrepParams *p, int grid_x, int grid_y, void *stream);
+    int (*launch_comb_bt)(const PrepParams *p, int grid_x, int grid_y, void *stream);
     int (*launch_comb_h)(const CombHParams *p, int grid_x, int grid_y, void *stream);
     int (*launch_comb_h32)(const CombHParams *p, int grid_x, int grid_y, void *stream); // fp32 planes, 16-bit C; null for fp32 storage
     double rate_a, rate_b, rate_h; // measured algorithmic bytes per second of Combine A, Combine B, Combine H
@@ -82,8 +87,10 @@ extern const Fp8Kernel kFp8Kernels[];
 extern const int kFp8KernelCount;
 
 // Offline Combine B into planes whose rows (N/n) and columns (K/k) are padded to multiples of n_gran / k_gran.
+// stage (may be null): its Combine-B kernels and plane count take the place of the scheme's offline Combine-B kernels.
 lcma_status prepare_b_planes(bool transposed, int64_t N, int64_t K, const void *B, int64_t ldb, lcma_dtype dtype,
-                             const lcma_scheme *scheme, void *Bt, void *stream, int64_t n_gran, int64_t k_gran);
+                             const lcma_scheme *scheme, void *Bt, void *stream, int64_t n_gran, int64_t k_gran,
+                             const StageKernel *stage = nullptr);
 
 int dtype_size(int dtype); // bytes, or 0
 
@@ -114,7 +121,7 @@ lcma_status empty_product(int64_t M, int64_t N, void *C, int64_t ldc, int dtype,
 // library's static buffer); `who` names the entry point in messages.
 lcma_status gemm_unfused(const char *who, int level, int64_t M, int64_t N, int64_t K, const void *A, int64_t lda,
                          const void *B, int64_t ldb, void *C, int64_t ldc, lcma_dtype dtype, const lcma_scheme *scheme,
-                         void *workspace, int64_t workspace_bytes, int reuse_bt, void *stream);
+                         void *workspace, int64_t workspace_bytes, int reuse_bt, void *stream, bool b_nk = false);
 
 // Variant of (scheme_id, dtype) with the smallest predicted time among those whose tile divides the
 // shape; nullptr if none.

@@ -47,7 +47,8 @@ template <> struct Widen<F16> {
     }
 };
 
-// CH (generated): NB raw blocks with b_l(t), b_j(t); NP outputs; comb(in, r) = Eq. 4 for product r on floats.
+// CH (generated): NB raw blocks with b_l(t), b_j(t); NP outputs; comb(in, r) = Eq. 4 for product r on floats;
+// residual(r): plane r holds what rounding that sum to fp16 loses instead of the rounded sum (16-bit types only).
 template <class IN, class CT, class CH> LCMA_DEV void prepare_b_tile(const PrepParams &p) {
     constexpr int ES = IN::ES, EPT = 16 / ES;       // elements per 16-byte vector
     constexpr int KT = 64 / ES;                     // k rows of the tile (32 or 16): 64-byte output rows
@@ -79,7 +80,10 @@ template <class IN, class CT, class CH> LCMA_DEV void prepare_b_tile(const PrepP
             float col[CH::NB];
 #pragma unroll
             for (int t = 0; t < CH::NB; ++t) col[t] = in[t][e];
-            const float o = CH::comb(col, r);
+            float o = CH::comb(col, r);
+            if constexpr (ES == 2) {
+                if (CH::residual(r)) o -= (float)(_Float16)o; // what rounding the sum loses (exact in fp32)
+            }
             char *dst = tile + (tx * EPT + e) * PITCH + ky * ES;
             if constexpr (ES == 2) *(_Float16 *)dst = (_Float16)o; // one rounding, nearest-even
             else *(float *)dst = o;
@@ -126,7 +130,9 @@ template <class IN, class CT, class CH> LCMA_DEV void prepare_bt_tile(const Prep
                 float col[CH::NB];
 #pragma unroll
                 for (int t = 0; t < CH::NB; ++t) col[t] = in[t][e];
-                h[e] = (_Float16)CH::comb(col, r); // one rounding, nearest-even
+                float o = CH::comb(col, r);
+                if (CH::residual(r)) o -= (float)(_Float16)o; // what rounding the sum loses (exact in fp32)
+                h[e] = (_Float16)o; // one rounding, nearest-even
             }
             v = __builtin_bit_cast(u32x4, h);
         } else {

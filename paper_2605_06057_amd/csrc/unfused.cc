@@ -26,19 +26,22 @@ struct Geometry {
     int64_t total() const { return at_bytes + bt_bytes + h_bytes; }
 };
 
+// planes: what the stage kernels of (scheme, dtype) work on (StageKernel::planes), R without stage kernels
+int planes_of(const lcma_scheme &s, int dtype);
 Geometry geometry(const lcma_scheme &s, int64_t M, int64_t N, int64_t K, int dtype) {
     Geometry g;
+    const int64_t R = planes_of(s, dtype);
     g.es = dtype_size(dtype);
     const int64_t kg = g.es == 4 ? 16 : 64;
     g.bm = round_up((M + s.m - 1) / s.m, 128);
     g.bn = round_up((N + s.n - 1) / s.n, 128);
     g.bk = round_up((K + s.k - 1) / s.k, kg);
-    g.at_bytes = align256((int64_t)s.R * g.bm * g.bk * g.es);
-    g.bt_bytes = align256((int64_t)s.R * g.bn * g.bk * g.es);
+    g.at_bytes = align256(R * g.bm * g.bk * g.es);
+    g.bt_bytes = align256(R * g.bn * g.bk * g.es);
     // fp16 storage: the products are kept in fp32 (fp16 planes would carry no more bits than C itself and put the
     // result past four times the plain kernel's error); bf16 storage keeps them in fp16, fp32 storage in fp32
     g.h_es = dtype == LCMA_F16 ? 4 : g.es;
-    g.h_bytes = align256((int64_t)s.R * g.bm * g.bn * g.h_es);
+    g.h_bytes = align256(R * g.bm * g.bn * g.h_es);
     return g;
 }
 
@@ -47,6 +50,10 @@ const StageKernel *find_stage(int scheme_id, int dtype) {
         if (kStageKernels[i].launch_comb_a && kStageKernels[i].scheme_id == scheme_id && kStageKernels[i].dtype == dtype)
             return &kStageKernels[i];
     return nullptr;
+}
+int planes_of(const lcma_scheme &s, int dtype) {
+    const StageKernel *sk = s.builtin ? find_stage(s.builtin, dtype) : nullptr;
+    return sk ? sk->planes : s.R;
 }
 
 // Seconds of the GEMM stage with kernel v on planes of geometry g: R tile-jobs per tile position for the
@@ -107,16 +114,16 @@ extern "C" double lcma_predict_unfused_seconds(int scheme_id, int64_t M, int64_t
     const StageKernel *sk = find_stage(scheme_id, dtype);
     if (!es || !s || M <= 0 || N <= 0 || K <= 0 || !sk) return -1.0;
     const Geometry g = geometry(*s, M, N, K, dtype);
-    const Variant *gemm = find_gemm(true, LCMA_PLAIN, dtype == LCMA_F32 ? LCMA_F32 : LCMA_F16, s->R, g);
+    const Variant *gemm = find_gemm(true, LCMA_PLAIN, dtype == LCMA_F32 ? LCMA_F32 : LCMA_F16, sk->planes, g);
     if (!gemm) return -1.0;
-    const double R = s->R, dM = (double)M, dN = (double)N, dK = (double)K;
+    const double R = sk->planes, dM = (double)M, dN = (double)N, dK = (double)K;
     const double at = R * g.bm * g.bk, bt = R * g.bn * g.bk, h = R * g.bm * g.bn; // elements of the planes
     double t = (dM * dK + at) * es / sk->rate_a + kLaunch;
     if (!combine_b_offline) t += (dK * dN + bt) * es / sk->rate_b + kLaunch;
     // 16-bit: the plane GEMM runs the stage (priced without the scratch of the Split-Group schedule, which only a
     // workspace larger than lcma_unfused_workspace_bytes() provides)
-    const double t_planes = es == 2 ? plane_gemm_seconds(s->R, g.bm, g.bn, (int)(g.bk * es / 128), 0) : -1.0;
-    t += (t_planes > 0.0 ? t_planes : gemm_stage_seconds(*gemm, s->R, g)) + kLaunch;
+    const double t_planes = es == 2 ? plane_gemm_seconds(sk->planes, g.bm, g.bn, (int)(g.bk * es / 128), 0) : -1.0;
+    t += (t_planes > 0.0 ? t_planes : gemm_stage_seconds(*gemm, sk->planes, g)) + kLaunch;
     t += (h * g.h_es + dM * dN * es) / sk->rate_h + kLaunch;
     return t;
 }
@@ -152,6 +159,9 @@ extern "C" lcma_status lcma_gemm_unfused(int level, int64_t M, int64_t N, int64_
 // same figure), past the bound of 4 this library promises; with rows of up to 4 blocks it stays below 3.
 static bool stored_combinations_meet_the_bound(const lcma_scheme &s, lcma_dtype dtype) {
     if (dtype != LCMA_F16) return true;
+    // (stage kernels that multiply the rounding residuals of the worst combinations as well are inside the bound)
+    if (const StageKernel *sk = s.builtin ? find_stage(s.builtin, dtype) : nullptr)
+        if (sk->planes > s.R) return true;
     auto longest_row = [&](const std::vector<int8_t> &T, int per_row) {
         int most = 0;
         for (int r = 0; r < s.R; ++r) {
@@ -164,30 +174,39 @@ static bool stored_combinations_meet_the_bound(const lcma_scheme &s, lcma_dtype 
     return longest_row(s.U, s.m * s.k) <= 4 && longest_row(s.V, s.k * s.n) <= 4;
 }
 
-// lcma_gemm with a workspace: the fused kernel or Algorithm 1, whichever the time model predicts faster for the shape.
-extern "C" lcma_status lcma_gemm_ws(int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const void *B, int64_t ldb,
-                                    void *C, int64_t ldc, lcma_dtype dtype, const lcma_scheme *scheme, void *workspace,
-                                    int64_t workspace_bytes, int *dataflow, void *stream) {
+// lcma_gemm / lcma_gemm_nt with a workspace: the fused kernel or Algorithm 1, whichever the time model predicts faster for
+// the shape; without a scheme the plain product, for N x K weights on the plane GEMM.
+extern "C" lcma_status lcma_gemm_ws(int b_layout, int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const void *B,
+                                    int64_t ldb, void *C, int64_t ldc, lcma_dtype dtype, const lcma_scheme *scheme,
+                                    void *workspace, int64_t workspace_bytes, int *dataflow, void *stream) {
     if (dataflow) *dataflow = 0;
+    if (b_layout != 0 && b_layout != 2) return fail(LCMA_ERR_ARG, "lcma_gemm_ws: b_layout must be 0 (B is K x N) or 2 (W is N x K)");
+    const bool nk = b_layout == 2;
+    auto fused = [&]() {
+        if (!nk) return lcma_gemm(M, N, K, A, lda, B, ldb, C, ldc, dtype, scheme, stream);
+        if (!scheme) return lcma_gemm_nt_ws(M, N, K, A, lda, B, ldb, C, ldc, dtype, workspace, workspace ? workspace_bytes : 0, stream);
+        return lcma_gemm_nt(M, N, K, A, lda, B, ldb, C, ldc, dtype, scheme, stream);
+    };
     const int id = scheme ? scheme->builtin : 0;
     bool alg1 = false;
     if (id && workspace && !((uintptr_t)workspace & 255) && dtype_size(dtype) && M > 0 && N > 0 && K > 0 &&
         find_stage(id, dtype) && stored_combinations_meet_the_bound(*scheme, dtype) &&
         workspace_bytes >= geometry(*scheme, M, N, K, dtype).total()) {
-        const double fused = lcma_predict_seconds(id, M, N, K, dtype), unfused = lcma_predict_unfused_seconds(id, M, N, K, dtype, 0);
-        alg1 = unfused > 0.0 && (fused <= 0.0 || unfused < fused);
+        const double t_fused = lcma_predict_seconds(id, M, N, K, dtype), t_alg1 = lcma_predict_unfused_seconds(id, M, N, K, dtype, 0);
+        alg1 = t_alg1 > 0.0 && (t_fused <= 0.0 || t_alg1 < t_fused);
     }
-    if (!alg1) return lcma_gemm(M, N, K, A, lda, B, ldb, C, ldc, dtype, scheme, stream);
-    const lcma_status st = gemm_unfused("lcma_gemm_ws", 1, M, N, K, A, lda, B, ldb, C, ldc, dtype, scheme, workspace, workspace_bytes, 0, stream);
+    if (!alg1) return fused();
+    const lcma_status st = gemm_unfused("lcma_gemm_ws", 1, M, N, K, A, lda, B, ldb, C, ldc, dtype, scheme, workspace, workspace_bytes, 0,
+                                        stream, nk);
     // shapes that only the fused kernels take (no whole 16-byte vectors along K, ...) fall back to them
-    if (st == LCMA_ERR_SHAPE) return lcma_gemm(M, N, K, A, lda, B, ldb, C, ldc, dtype, scheme, stream);
+    if (st == LCMA_ERR_SHAPE) return fused();
     if (st == LCMA_OK && dataflow) *dataflow = 1;
     return st;
 }
 
 lcma_status lcma::gemm_unfused(const char *who, int level, int64_t M, int64_t N, int64_t K, const void *A, int64_t lda,
                                const void *B, int64_t ldb, void *C, int64_t ldc, lcma_dtype dtype, const lcma_scheme *scheme,
-                               void *workspace, int64_t workspace_bytes, int reuse_bt, void *stream) {
+                               void *workspace, int64_t workspace_bytes, int reuse_bt, void *stream, bool b_nk) {
     const int es = dtype_size(dtype);
     if (!es) return fail(LCMA_ERR_DTYPE, "%s: unknown dtype %d", who, (int)dtype);
     if (level != 1 && level != 2) return fail(LCMA_ERR_ARG, "%s: level must be 1 (Algorithm 1) or 2 (Algorithm 2)", who);
@@ -202,7 +221,8 @@ lcma_status lcma::gemm_unfused(const char *who, int level, int64_t M, int64_t N,
     if (M == 0 || N == 0) return LCMA_OK;
     if (K == 0) return empty_product(M, N, C, ldc, dtype, 0.f, stream);
     if (!A || !B || !C || !workspace) return fail(LCMA_ERR_ARG, "%s: null pointer", who);
-    if (lda < K || ldb < N || ldc < N) return fail(LCMA_ERR_ARG, "%s: leading dimension smaller than the row", who);
+    // (b_nk: B is the N x K weight matrix W, rows k-contiguous, and the product is A W^T)
+    if (lda < K || ldb < (b_nk ? K : N) || ldc < N) return fail(LCMA_ERR_ARG, "%s: leading dimension smaller than the row", who);
     if ((((uintptr_t)A | (uintptr_t)B | (uintptr_t)C) & 15) || ((uintptr_t)workspace & 255))
         return fail(LCMA_ERR_ARG, "%s: matrix pointers must be 16-byte aligned, the workspace 256-byte aligned", who);
     if (((lda * es) | (ldb * es) | (ldc * es)) & 15)
@@ -215,18 +235,19 @@ lcma_status lcma::gemm_unfused(const char *who, int level, int64_t M, int64_t N,
     if (workspace_bytes < g.total())
         return fail(LCMA_ERR_ARG, "%s: the workspace holds %lld bytes, %lld are needed", who, (long long)workspace_bytes,
                     (long long)g.total());
-    const int R = scheme->R;
+    // level 1 works on the planes of the stage kernels (R, or more with compensated products); level 2 on the first R
+    const int R = level == 1 ? sk->planes : scheme->R;
     const int64_t lim = (int64_t)1 << 31;
     const int64_t Mp = g.bm * scheme->m, Np = g.bn * scheme->n, Kp = g.bk * scheme->k;
     if (g.at_bytes >= lim || g.bt_bytes >= lim || g.h_bytes >= lim || ((Mp - 1) * lda + Kp) * es >= lim ||
-        ((Kp - 1) * ldb + Np) * es >= lim || ((Mp - 1) * ldc + Np) * es >= lim)
+        (b_nk ? (Np - 1) * ldb + Kp : (Kp - 1) * ldb + Np) * es >= lim || ((Mp - 1) * ldc + Np) * es >= lim)
         return fail(LCMA_ERR_SHAPE, "%s: a matrix or a set of planes spans 2 GiB or more", who);
     // Bt first: its place and size depend on N and K alone, so the planes of static weights stay where they are
     // when the number of rows M changes between calls
     char *Bt = (char *)workspace, *At = Bt + g.bt_bytes, *H = At + g.at_bytes;
     // the products are multiplied in fp16 for both 16-bit storage types
     const int ct = dtype == LCMA_F32 ? LCMA_F32 : LCMA_F16;
-    const Variant *gemm = level == 1 ? find_gemm(true, LCMA_PLAIN, ct, scheme->R, g) : find_gemm(false, id, dtype, scheme->R, g);
+    const Variant *gemm = level == 1 ? find_gemm(true, LCMA_PLAIN, ct, R, g) : find_gemm(false, id, dtype, scheme->R, g);
     if (!gemm) return fail(LCMA_ERR_NOKERNEL, "%s: no GEMM stage kernel for level %d fits the planes", who, level);
 
     const int stages = tuning_unfused_stages(); // measurement aid: stages switched off keep the output of an earlier call
@@ -253,7 +274,7 @@ lcma_status lcma::gemm_unfused(const char *who, int level, int64_t M, int64_t N,
     }
     // stage 2: Combine B (Eq. 4), unless the planes of an earlier call are still valid (static weights)
     if (!reuse_bt && (stages & 2)) {
-        const lcma_status st = prepare_b_planes(false, N, K, B, ldb, dtype, scheme, Bt, stream, 128, es == 4 ? 16 : 64);
+        const lcma_status st = prepare_b_planes(b_nk, N, K, B, ldb, dtype, scheme, Bt, stream, 128, es == 4 ? 16 : 64, sk);
         if (st != LCMA_OK) return st;
     }
     Params p;

@@ -412,9 +412,12 @@ def emit_registry(schemes: dict[str, Scheme], variants: list[Variant]) -> str:
     for sch, dt in stages:
         ra, rb, rh = STAGE_RATES.get((sch, dt != "f32"), (4.0e12, 3.0e12, 5.0e12))
         h32 = f"lcma_launch_comb_h32_{sch}_{dt}" if dt != "f32" else "nullptr"
-        L.append(f"    {{{SCHEME_IDS[sch]}, {DTYPE_IDS[dt]}, lcma_launch_comb_a_{sch}_{dt}, lcma_launch_comb_h_{sch}_{dt}, {h32}, {ra}, {rb}, {rh}}},")
+        ext = (sch, dt) in STAGE_COMP
+        cb, cbt = (f"lcma_launch_comb_b_{sch}_{dt}", f"lcma_launch_comb_bt_{sch}_{dt}") if ext else ("nullptr", "nullptr")
+        L.append(f"    {{{SCHEME_IDS[sch]}, {DTYPE_IDS[dt]}, {stage_planes(schemes[sch], dt)}, lcma_launch_comb_a_{sch}_{dt}, {cb}, {cbt}, "
+                 f"lcma_launch_comb_h_{sch}_{dt}, {h32}, {ra}, {rb}, {rh}}},")
     if not stages:
-        L.append("    {0, 0, nullptr, nullptr, nullptr, 0.0, 0.0, 0.0},")
+        L.append("    {0, 0, 0, nullptr, nullptr, nullptr, nullptr, nullptr, 0.0, 0.0, 0.0},")
     L += ["};", f"const int kStageKernelCount = {len(stages)};"]
     fp8 = sorted({sch for sch, dt in stages if dt == "bf16"} & {sch for sch, dt in preps if dt == "bf16"})
     L.append("const Fp8Kernel kFp8Kernels[] = {")
@@ -431,6 +434,9 @@ def emit_registry(schemes: dict[str, Scheme], variants: list[Variant]) -> str:
         L.insert(3, f'extern "C" int lcma_launch_comb_h_{sch}_{dt}(const lcma::CombHParams *p, int gx, int gy, void *stream);')
         if dt != "f32":
             L.insert(3, f'extern "C" int lcma_launch_comb_h32_{sch}_{dt}(const lcma::CombHParams *p, int gx, int gy, void *stream);')
+        if (sch, dt) in STAGE_COMP:
+            L.insert(3, f'extern "C" int lcma_launch_comb_b_{sch}_{dt}(const lcma::PrepParams *p, int gx, int gy, void *stream);')
+            L.insert(3, f'extern "C" int lcma_launch_comb_bt_{sch}_{dt}(const lcma::PrepParams *p, int gx, int gy, void *stream);')
     for sch, dt in preps:
         L.insert(3, f'extern "C" int lcma_launch_prep_b_{sch}_{dt}(const lcma::PrepParams *p, int gx, int gy, void *stream);')
         L.insert(3, f'extern "C" int lcma_launch_prep_bt_{sch}_{dt}(const lcma::PrepParams *p, int gx, int gy, void *stream);')
@@ -469,11 +475,23 @@ def float_sum(terms: list[tuple[int, str]]) -> str:
     return expr or "0.f"
 
 
-def emit_stage(s: Scheme, dtype: str) -> str:
+# Algorithm 1 with fp16 storage: products whose left combination also gets its rounding residual multiplied (as a further
+# plane pair: the residual of At_r beside a second copy of Bt_r, with the W row of r), the compensation the fused kernels
+# of the scheme use (see with_residuals): without it <3,3,3;23> lands at 4.04 x the plain kernel's error.
+STAGE_COMP = {("laderman", "f16"): (3, 6)}
+
+
+def stage_planes(s: Scheme, dtype: str) -> int:
+    return s.R + len(STAGE_COMP.get((s.name, dtype), ()))
+
+
+def emit_stage(s0: Scheme, dtype: str) -> str:
     """Stand-alone Combine A (Eq. 3; sums in fp32, ascending (i, l), one rounding to the compute type) and
     Combine H (Eq. 6; sums in fp32, ascending r, one rounding to the storage type) for one scheme and
-    storage type: stages 1 and 4 of Algorithm 1."""
+    storage type: stages 1 and 4 of Algorithm 1.  With compensated products (STAGE_COMP) every stage works on
+    the longer list of planes, and the Combine B kernels for it are emitted here as well."""
     in_t, ct_t = CPP_TYPES[dtype]
+    s, residual = with_residuals(s0, STAGE_COMP.get((s0.name, dtype), ()))
     a_blocks = sorted({(i, l) for r in range(s.R) for i in range(s.m) for l in range(s.k) if s.U[r, i, l]})
     L = []
     w = L.append
@@ -485,6 +503,8 @@ def emit_stage(s: Scheme, dtype: str) -> str:
     w("using namespace lcma;")
     w("struct CombA {  // block A_{i,l} takes the place of block (j, l) of an N x K weight matrix")
     w(f"    static constexpr int NB = {len(a_blocks)}, NP = {s.R};")
+    w("    // planes that hold what rounding the sum to the compute type loses (the sum is that of the plane's source product)")
+    w(f"    static LCMA_DEV constexpr bool residual(int r) {{ return r >= {s0.R}; }}")
     for fn, vals in (("b_j", [b[0] for b in a_blocks]), ("b_l", [b[1] for b in a_blocks])):
         w(f"    static LCMA_DEV constexpr int {fn}(int t) {{ constexpr int v[] = {{{', '.join(map(str, vals))}}}; return v[t]; }}")
     w("    static LCMA_DEV float comb(const float (&in)[NB], int r) {")
@@ -512,8 +532,21 @@ def emit_stage(s: Scheme, dtype: str) -> str:
     w("        }")
     w("    }")
     w("};")
+    if residual:
+        L += comb_b_struct(s, "CombB")
     w("} // namespace")
     w("")
+    if residual:
+        for kind, fn in (("b", "prepare_b_tile"), ("bt", "prepare_bt_tile")):
+            w(f'extern "C" __global__ __launch_bounds__(256) void lcma_k_comb_{kind}_{s.name}_{dtype}(const lcma::PrepParams p) {{')
+            w(f"    {fn}<{in_t}, {ct_t}, CombB>(p);")
+            w("}")
+            w("")
+            w(f'extern "C" int lcma_launch_comb_{kind}_{s.name}_{dtype}(const lcma::PrepParams *p, int gx, int gy, void *stream) {{')
+            w(f"    lcma_k_comb_{kind}_{s.name}_{dtype}<<<dim3(gx, gy), dim3(256), 0, (hipStream_t)stream>>>(*p);")
+            w("    return (int)hipGetLastError();")
+            w("}")
+            w("")
     w(f'extern "C" __global__ __launch_bounds__(256) void lcma_k_comb_a_{s.name}_{dtype}(const lcma::PrepParams p) {{')
     w(f"    prepare_bt_tile<{in_t}, {ct_t}, CombA>(p);")
     w("}")
@@ -555,10 +588,35 @@ def emit_stage(s: Scheme, dtype: str) -> str:
     return "\n".join(L) + "\n"
 
 
+def comb_b_struct(s: Scheme, name: str) -> list[str]:
+    """The generated description of Combine B (Eq. 4) for the kernels of csrc/lcma_prepare_b.hpp: raw blocks, planes,
+    the signed fp32 sum of plane r in ascending (l, j) order."""
+    b_blocks = sorted({(l, j) for r in range(s.R) for l in range(s.k) for j in range(s.n) if s.V[r, l, j]})
+    L = []
+    w = L.append
+    w(f"struct {name} {{")
+    w(f"    static constexpr int NB = {len(b_blocks)}, NP = {s.R};")
+    for fn, vals in (("b_l", [b[0] for b in b_blocks]), ("b_j", [b[1] for b in b_blocks])):
+        w(f"    static LCMA_DEV constexpr int {fn}(int t) {{ constexpr int v[] = {{{', '.join(map(str, vals))}}}; return v[t]; }}")
+    w("    static LCMA_DEV constexpr bool residual(int) { return false; }")
+    w("    // Bt_r at one element position; r is a literal at every call site, so the switch folds")
+    w("    static LCMA_DEV float comb(const float (&in)[NB], int r) {")
+    w("#pragma clang fp contract(off)")
+    w("        switch (r) {")
+    for r in range(s.R):
+        # ascending (l, j), left to right: the order the stored result is defined in
+        terms = [(int(s.V[r, l, j]), f"in[{b_blocks.index((l, j))}]") for (l, j) in b_blocks if s.V[r, l, j]]
+        w(f"        case {r}: return {float_sum(terms)};")
+    w("        default: return 0.f;")
+    w("        }")
+    w("    }")
+    w("};")
+    return L
+
+
 def emit_prep_b(s: Scheme, dtype: str) -> str:
     """Offline Combine B (Eq. 4) for one scheme and storage type; sums in fp32, ascending (l, j)."""
     in_t, ct_t = CPP_TYPES[dtype]
-    b_blocks = sorted({(l, j) for r in range(s.R) for l in range(s.k) for j in range(s.n) if s.V[r, l, j]})
     L = []
     w = L.append
     w(f"// GENERATED by gen/generate.py - do not edit.  Offline Combine B of scheme {s.name} <{s.m},{s.k},{s.n};{s.R}>, dtype {dtype}.")
@@ -567,31 +625,7 @@ def emit_prep_b(s: Scheme, dtype: str) -> str:
         w('#include "lcma_fp8.hpp"')
     w("namespace {")
     w("using namespace lcma;")
-    w("struct Comb {")
-    w(f"    static constexpr int NB = {len(b_blocks)}, NP = {s.R};")
-    for fn, vals in (("b_l", [b[0] for b in b_blocks]), ("b_j", [b[1] for b in b_blocks])):
-        w(f"    static LCMA_DEV constexpr int {fn}(int t) {{ constexpr int v[] = {{{', '.join(map(str, vals))}}}; return v[t]; }}")
-    w("    // Bt_r at one element position; r is a literal at every call site, so the switch folds")
-    w("    static LCMA_DEV float comb(const float (&in)[NB], int r) {")
-    w("#pragma clang fp contract(off)")
-    w("        switch (r) {")
-    for r in range(s.R):
-        # ascending (l, j), left to right: the order the stored result is defined in
-        expr = ""
-        for (l, j) in b_blocks:
-            c = int(s.V[r, l, j])
-            if not c:
-                continue
-            mag = f"in[{b_blocks.index((l, j))}]" if abs(c) == 1 else f"{float(abs(c))}f * in[{b_blocks.index((l, j))}]"
-            if not expr:
-                expr = mag if c > 0 else f"-{mag}"
-            else:
-                expr = f"({expr} {'+' if c > 0 else '-'} {mag})"
-        w(f"        case {r}: return {expr or '0.f'};")
-    w("        default: return 0.f;")
-    w("        }")
-    w("    }")
-    w("};")
+    L += comb_b_struct(s, "Comb")
     w("} // namespace")
     w("")
     w(f'extern "C" __global__ __launch_bounds__(256) void lcma_k_prep_b_{s.name}_{dtype}(const lcma::PrepParams p) {{')

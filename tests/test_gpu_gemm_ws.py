@@ -23,8 +23,6 @@ def B():
 
 
 def model_says_algorithm1(B, sid, M, N, K, dtid):
-    if dtid == B.LCMA_F16 and sid == B.LCMA_LADERMAN:   # rows of 7 blocks in fp16: not offered (error bound)
-        return False
     fused, unfused = B.lcma_predict_seconds(sid, M, N, K, dtid), B.lcma_predict_unfused_seconds(sid, M, N, K, dtid, False)
     return unfused > 0 and (fused <= 0 or unfused < fused)
 
@@ -73,18 +71,29 @@ def test_gemm_ws_against_oracle(B, name, dt, shape):
     assert B.lcma_gemm_ws(a, b, c2, h, ws[:256]) == 0
     err_fused = oracle.rel_frobenius(G.to_host_f64(c2, dt), ref)
     print(f"relF {err:.3e}, fused kernel {err_fused:.3e}, plain {err_plain:.3e}", flush=True)
-    # the project's bounds (on these N(0,1) inputs the fused <3,3,3;23> kernel in fp16 sits just below the 4x mark)
+    # the project's bounds
     assert err <= TOL[dt] and err_fused <= TOL[dt]
-    assert err <= 4.0 * err_plain * (1.01 if flow == 0 else 1.0)
+    assert err <= 4.0 * err_plain
     if expect == 0:   # the same kernel ran: same bits
         assert torch.equal(c2, c)
+    # the weights given N x K (C = A W^T): the same choice; Algorithm 1 then reads W without transposing and writes
+    # the bits it writes for B = W^T; the fused route is lcma_gemm_nt's kernel (same bits as lcma_gemm's, tested elsewhere)
+    w = b.t().contiguous()
+    c3 = G.empty_like_c(M, N, dt, fill=float("nan"))
+    assert B.lcma_gemm_ws(a, w, c3, h, ws, b_nk=True) == expect
+    assert torch.equal(c3.view(torch.uint8), c.view(torch.uint8))
+    # without a scheme: the plain product on the plane GEMM (16-bit) with the workspace for its schedule
+    c4 = G.empty_like_c(M, N, dt, fill=float("nan"))
+    assert B.lcma_gemm_ws(a, w, c4, None, ws, b_nk=True) == 0
+    assert oracle.rel_frobenius(G.to_host_f64(c4, dt), ref) <= 1.05 * err_plain + 1e-7
 
 
-@pytest.mark.parametrize("name,ratio", [("strassen", 4.0), ("laderman", 4.2)])
+@pytest.mark.parametrize("name,ratio", [("strassen", 3.2), ("laderman", 3.9)])
 def test_fp16_storage_error_of_algorithm1_against_the_plain_kernel(B, name, ratio):
-    """What decides whether lcma_gemm_ws offers Algorithm 1 for fp16 storage: with the products kept in fp32 the error
-    is that of the fp16 combinations; <2,2,2;7> (rows of 2 blocks) stays inside four times the plain kernel's error,
-    <3,3,3;23> (rows of up to 7) lands just past it (4.04), which is why it is not offered there."""
+    """Algorithm 1 with fp16 storage against the bound of four times the plain kernel's error: with the products kept in
+    fp32 the error is that of the fp16 combinations.  <2,2,2;7> (rows of 2 blocks) is well inside; <3,3,3;23> (rows of up
+    to 7) would land at 4.04 and is inside because the stage kernels multiply the rounding residuals of the left
+    combinations of products 4 and 7 as well (25 planes instead of 23), as the fused kernels of the scheme do."""
     import torch
     import gpu_util as G
     M = N = K = 1536
@@ -100,5 +109,3 @@ def test_fp16_storage_error_of_algorithm1_against_the_plain_kernel(B, name, rati
     err_plain = oracle.rel_frobenius(G.to_host_f64(c, "f16"), ref)
     print(f"{name}: Algorithm 1 {err:.3e}, plain {err_plain:.3e}, ratio {err / err_plain:.2f}", flush=True)
     assert err <= ratio * err_plain
-    if name == "laderman":
-        assert err > 4.0 * err_plain   # the reason for the rule; if this ever fails the rule can go

@@ -72,7 +72,10 @@ def test_unfused_against_oracle(B, name, dt, shape, level):
     up = lambda x, g: -(-x // g) * g
     Mp, Np, Kp = up(M, s.m), up(N, s.n), up(K, s.k)
     # (the products H_r of level 1 are kept in fp32 for fp16 storage, in fp16 for bf16 storage)
-    model = oracle.lcma_unfused(s, padded(Aw, Mp, Kp), padded(Bw, Kp, Np), dt, level, h_dtype="f32" if dt == "f16" else None)[:M, :N]
+    # and <3,3,3;23> with fp16 storage multiplies the rounding residuals of the left combinations of products 4 and 7 as well
+    comp = (3, 6) if (name, dt, level) == ("laderman", "f16", 1) else ()
+    model = oracle.lcma_unfused(s, padded(Aw, Mp, Kp), padded(Bw, Kp, Np), dt, level, h_dtype="f32" if dt == "f16" else None,
+                                residual_products=comp)[:M, :N]
     err_model = oracle.rel_frobenius(got, model)
     print(f"relF vs fp64 product {err:.3e}, vs the oracle's level-{level} evaluation {err_model:.3e}", flush=True)
     assert err <= TOL[dt]

@@ -278,8 +278,8 @@ def test_weight_layout_and_unfused_host_side(B):
     assert B.lcma_unfused_workspace_bytes(s, 4096, 4096, 4096, B.LCMA_BF16) == 3 * 7 * 2048 * 2048 * 2
     assert B.lcma_unfused_workspace_bytes(s, 100, 200, 72, B.LCMA_F32) == 7 * (128 * 48 + 128 * 48 + 128 * 128) * 4
     lad = B.lcma_scheme_load("builtin:laderman")
-    # fp16 storage: planes of At and Bt in fp16, the products in fp32
-    assert B.lcma_unfused_workspace_bytes(lad, 384, 384, 192, B.LCMA_F16) == 23 * (128 * 64 * 2 * 2 + 128 * 128 * 4)
+    # fp16 storage: planes of At and Bt in fp16, the products in fp32; 25 planes (two compensated products)
+    assert B.lcma_unfused_workspace_bytes(lad, 384, 384, 192, B.LCMA_F16) == 25 * (128 * 64 * 2 * 2 + 128 * 128 * 4)
     assert B.lcma_unfused_workspace_bytes(lad, 384, 384, 192, B.LCMA_BF16) == 23 * (128 * 64 * 2 + 128 * 128) * 2
     assert B.lcma_unfused_workspace_bytes(s, 4096, 4096, 4096, 17) == -1
 
