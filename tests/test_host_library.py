@@ -298,6 +298,22 @@ def test_weight_layout_and_unfused_host_side(B):
     assert L.lcma_gemm_unfused(1, 256, 256, 0, P, 0, P, 256, None, 256, B.LCMA_F16, s.handle, P, 1 << 30, 0, None) == B.LCMA_ERR_ARG  # K = 0 writes zeros: C is needed
     assert unfused(M=0) == B.LCMA_OK                            # nothing to write
 
+    # lcma_gemm_ws: layout argument, refusals of the call it routes to, nothing to do
+    import ctypes
+    flow = ctypes.c_int(7)
+
+    def ws_call(layout=0, M=256, N=256, K=256, a=P, ldb=256, sch=s.handle, ws=P, nbytes=1 << 30, dt=B.LCMA_F16):
+        return L.lcma_gemm_ws(layout, M, N, K, a, K, P, ldb, P, N, dt, sch, ws, nbytes, ctypes.byref(flow), None)
+    assert ws_call(layout=1) == B.LCMA_ERR_ARG and b"b_layout" in L.lcma_last_error() and flow.value == 0
+    assert ws_call(layout=3) == B.LCMA_ERR_ARG
+    assert ws_call(a=None) == B.LCMA_ERR_ARG and ws_call(layout=2, a=None) == B.LCMA_ERR_ARG
+    assert ws_call(dt=17) == B.LCMA_ERR_DTYPE
+    assert ws_call(layout=2, N=512, K=128, ldb=120) == B.LCMA_ERR_ARG      # W is N x K: its pitch is checked against K
+    assert ws_call(M=0) == B.LCMA_OK and ws_call(layout=2, M=0, sch=None, ws=None, nbytes=0) == B.LCMA_OK
+    # <3,3,3;23> with fp16 storage works on 25 planes (two compensated products), with bf16 storage on 23
+    assert B.lcma_unfused_workspace_bytes(lad, 768, 768, 768, B.LCMA_F16) == 25 * 256 * 256 * (2 + 2 + 4)
+    assert B.lcma_unfused_workspace_bytes(lad, 768, 768, 768, B.LCMA_BF16) == 23 * 256 * 256 * (2 + 2 + 2)
+
 
 def test_selector_over_both_dataflows(B):
     """lcma_select_dataflow and the Algorithm 1 cost model: pure host arithmetic."""
