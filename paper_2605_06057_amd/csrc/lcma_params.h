@@ -76,8 +76,9 @@ struct PlaneGemmParams {
     uint32_t n_row_b;                                       // N * 2: columns of C at or beyond it are never written
     int32_t jobs;                                           // tile-products: planes * nx * nz
     int32_t units;                                          // persistent work-groups launched
-    int32_t interleave;                                     // persistent kernel: 0 = work-group u owns the steps [u * cap, (u + 1) * cap),
-                                                            // 1 = it owns the whole tile-products u, u + units, u + 2 units, ...
+    int32_t interleave;                                     // persistent kernel: 0 = work-group u owns the steps [u * cap, (u + 1) * cap);
+                                                            // whole tile-products in turn: 1 = u, u + units, ... (rounds of consecutive
+                                                            // ones), 2 = each XCD an eighth of them (units is a multiple of 8)
     int64_t cap;                                            // steps per work-group: ceil(jobs * ny / units)
     void *partial;                                          // fp32 scratch for pieces: 2 slots of TM * TN floats per work-group
                                                             // (never touched when cap is a multiple of ny)

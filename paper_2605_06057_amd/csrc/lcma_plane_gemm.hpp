@@ -211,6 +211,9 @@ template <class KIND, int TM, int TN, int WGM, int WGN, class OUT, bool SPLIT = 
                                      uint32_t a_next, uint32_t b_next, bool more, const int (&sa)[NMI],
                                      const int (&sb)[NNI], f32x16 (&acc)[NMI][NNI], FragT (&fa)[2][NA], FragT (&fb)[2][NNI]) {
         if (more) issue(s, wr, a_next, b_next, 0);
+        // the loads leave FIRST (the compiler otherwise rotates the loop and sends them half a step later, behind two
+        // fragment sets: they then land late and the wait at the barrier grows; measured -14 % on all-zero operands)
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int sub = 0; sub + 1 < SUBS; ++sub) {
             read_set(s, rd, sub + 1, fa, fb);
@@ -292,14 +295,25 @@ template <class KIND, int TM, int TN, int WGM, int WGN, class OUT, bool SPLIT = 
             const int job = pos / ny;
             return Piece{job, pos - job * ny, (job + 1) * ny <= end ? ny : end - job * ny, true};
         };
+        // whole tile-products in turn, two ways of dealing them to the XCDs (p.interleave; measured, FFN shapes):
+        //  1  rounds: the work-groups running at one time take `units` consecutive tile-products, 32 consecutive ones per
+        //     XCD.  All XCDs then work inside the same plane of a batch, whose operands stay in the Infinity Cache for all of
+        //     them: the batched stage of Algorithm 1 is 5 % faster this way than with 2;
+        //  2  each XCD owns a contiguous eighth of the tile-products (as in the launch with a work-group per tile-product)
+        //     and its work-groups take every (units / 8)-th of them.  For a single large product 1 is markedly slower
+        //     (all eight XCDs ask the memory side for the same rows at the same time: -17 % on all-zero operands).
+        const int xcd_jobs = (p.jobs + 7) >> 3, turn = p.interleave == 2 ? p.units >> 3 : p.units;
+        const int turn_lo = p.interleave == 2 ? (int)(blockIdx.x & 7) * xcd_jobs : 0;
+        const int turn_hi = p.interleave == 2 && turn_lo + xcd_jobs < p.jobs ? turn_lo + xcd_jobs : p.jobs;
+        const int turn_first = p.interleave == 2 ? turn_lo + (int)(blockIdx.x >> 3) : unit;
         auto first_piece = [&]() {
             if constexpr (!SPLIT) return Piece{unit, 0, ny, true}; // one work-group per tile-product
-            if (p.interleave) return Piece{unit, 0, ny, unit < p.jobs};
+            if (p.interleave) return Piece{turn_first, 0, ny, turn_first < turn_hi};
             return piece_from(begin);
         };
         auto piece_after = [&](const Piece &c) {
             if constexpr (!SPLIT) return Piece{0, 0, 0, false};
-            if (p.interleave) return Piece{c.job + p.units, 0, ny, c.job + p.units < p.jobs};
+            if (p.interleave) return Piece{c.job + turn, 0, ny, c.job + turn < turn_hi};
             return piece_from(c.job * ny + c.y1);
         };
         // tile of a job: product-major; inside a product tiles run down x inside column panels of `panel` z tiles

@@ -141,7 +141,7 @@ lcma_status plane_gemm(const char *who, int kind, PlaneGemmParams p, int planes,
     if (schedule == 3) { // persistent work-groups, whole tile-products u, u + units, ...
         p.units = (int32_t)(jobs < slots ? jobs : slots);
         p.cap = p.ny;
-        p.interleave = 1;
+        p.interleave = planes > 1 ? 1 : 2; // (see PlaneGemm::run)
         p.partial = nullptr;
     } else if (schedule == 2) {
         p.units = (int32_t)(total < slots ? total : slots);
