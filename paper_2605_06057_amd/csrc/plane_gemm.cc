@@ -141,7 +141,10 @@ lcma_status plane_gemm(const char *who, int kind, PlaneGemmParams p, int planes,
     if (schedule == 3) { // persistent work-groups, whole tile-products u, u + units, ...
         p.units = (int32_t)(jobs < slots ? jobs : slots);
         p.cap = p.ny;
-        p.interleave = planes > 1 ? 1 : 2; // (see PlaneGemm::run)
+        // batches of planes: rounds of consecutive tile-products; one product: an eighth of them per XCD (see
+        // PlaneGemm::run), which needs the same number of work-groups on every XCD (with fewer tile-products than slots
+        // units == jobs and the launcher takes the kernel with a work-group per tile-product anyway)
+        p.interleave = planes > 1 || (p.units & 7) ? 1 : 2;
         p.partial = nullptr;
     } else if (schedule == 2) {
         p.units = (int32_t)(total < slots ? total : slots);

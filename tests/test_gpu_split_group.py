@@ -1,8 +1,9 @@
 """Split-Group Parallelism in a kernel (Sec. 3.2): the plane GEMM hands the steps of all tile-products to persistent
 work-groups in contiguous ranges of ceil(total / work-groups) steps, a tile-product that straddles work-groups is put
 together from fp32 pieces by a second kernel in ascending work-group order.  Checked here through the plain GEMM for
-N x K weights (lcma_gemm_nt_ws) and through Algorithm 1 (lcma_gemm_unfused level 1): both schedules against the oracle's
-exact product on integer inputs (identical bits), and against each other on float inputs."""
+N x K weights (lcma_gemm_nt_ws) and through Algorithm 1 (lcma_gemm_unfused level 1): that schedule, the launch with a
+work-group per tile-product and the persistent work-groups that take whole tile-products in turn, each against the
+oracle's exact product on integer inputs (identical bits), and against each other on float inputs."""
 import numpy as np
 import pytest
 
@@ -22,8 +23,9 @@ def B():
 
 
 # few tiles and long K (the split-K case: every tile is cut into many pieces), a single tile, more tiles than
-# work-groups (pieces only where a range ends inside a tile), ragged M and N
-PLAIN_SHAPES = [(256, 256, 4096), (100, 72, 1024), (2048, 4096, 2048), (4352, 4608, 320), (520, 392, 1216)]
+# work-groups (pieces only where a range ends inside a tile; the persistent work-groups take several whole
+# tile-products each, 306 and 323 of them: a number no multiple of 8, the last XCD's share shorter), ragged M and N
+PLAIN_SHAPES = [(256, 256, 4096), (100, 72, 1024), (2048, 4096, 2048), (4352, 4608, 320), (4800, 4200, 192), (520, 392, 1216)]
 
 
 @pytest.mark.parametrize("dt", ["bf16", "f16"])
@@ -42,7 +44,7 @@ def test_plain_gemm_both_schedules(B, dt, shape):
     ref = oracle.gemm(inp.widen(Af, dt), np.ascontiguousarray(inp.widen(Wf, dt).T))
     got = {}
     try:
-        for sched in ("static", "split"):
+        for sched in ("static", "split", "persist"):
             B.lcma_set_tuning("schedule", sched)
             big = G.empty_like_c(M + 3, N + 8, dt, fill=float("nan"))
             print(f"plane gemm {dt} {M}x{N}x{K} schedule {sched}", flush=True)
@@ -70,7 +72,8 @@ def test_plain_gemm_both_schedules(B, dt, shape):
     assert np.array_equal(G.to_host_stored(c1, dt).view(np.uint8), want.view(np.uint8))
 
 
-@pytest.mark.parametrize("name,shape", [("strassen", (520, 776, 328)), ("laderman", (768, 768, 1536)), ("strassen2", (2048, 1024, 4096))])
+@pytest.mark.parametrize("name,shape", [("strassen", (520, 776, 328)), ("strassen", (4104, 4608, 128)), ("laderman", (768, 768, 1536)),
+                                        ("strassen2", (2048, 1024, 4096))])
 def test_algorithm1_both_schedules(B, name, shape):
     import torch
     import gpu_util as G
@@ -84,7 +87,7 @@ def test_algorithm1_both_schedules(B, name, shape):
     nb = B.lcma_unfused_workspace_bytes(h, M, N, K, B.LCMA_BF16) + B.lcma_split_group_scratch_bytes()
     ws = torch.empty((nb,), dtype=torch.uint8, device="cuda")
     try:
-        for sched in ("static", "split"):
+        for sched in ("static", "split", "persist"):
             B.lcma_set_tuning("schedule", sched)
             c = G.empty_like_c(M, N, dt, fill=float("nan"))
             print(f"algorithm 1 {name} {M}x{N}x{K} schedule {sched}", flush=True)
