@@ -34,11 +34,11 @@ template <class IN, class HT, class CH> LCMA_DEV void combine_h_tile(const CombH
 #pragma unroll
     for (int r = 0; r < CH::NP; ++r) {
         if constexpr (HV == 1) {
-            Widen<HT>::run(__builtin_amdgcn_raw_buffer_load_b128(rh, (int)(row * p.h_ld_b + colb), (int)(r * p.h_plane_b), 0), h[r]);
+            Widen<HT>::run(__builtin_amdgcn_raw_buffer_load_b128(rh, (int)(row * p.h_ld_b + colb), (int)(r * p.h_plane_b), kStreamed), h[r]);
         } else {
             float lo[4], hi[4];
-            Widen<F32>::run(__builtin_amdgcn_raw_buffer_load_b128(rh, (int)(row * p.h_ld_b + colb * 2), (int)(r * p.h_plane_b), 0), lo);
-            Widen<F32>::run(__builtin_amdgcn_raw_buffer_load_b128(rh, (int)(row * p.h_ld_b + colb * 2 + 16), (int)(r * p.h_plane_b), 0), hi);
+            Widen<F32>::run(__builtin_amdgcn_raw_buffer_load_b128(rh, (int)(row * p.h_ld_b + colb * 2), (int)(r * p.h_plane_b), kStreamed), lo);
+            Widen<F32>::run(__builtin_amdgcn_raw_buffer_load_b128(rh, (int)(row * p.h_ld_b + colb * 2 + 16), (int)(r * p.h_plane_b), kStreamed), hi);
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 h[r][e] = lo[e];
@@ -72,7 +72,7 @@ template <class IN, class HT, class CH> LCMA_DEV void combine_h_tile(const CombH
         const uint32_t cb = (uint32_t)CH::c_j(o) * p.c_bcol + colb;
         const uint32_t off = cb < p.n_row_b ? (uint32_t)CH::c_i(o) * p.c_brow + row * p.ldc_b + cb : p.c_bytes;
         // (16-byte store: the scalar-offset field stays a literal zero, see Ctx::store_c in lcma_device.hpp)
-        __builtin_amdgcn_raw_buffer_store_b128(v, rc, (int)off, 0, 0);
+        __builtin_amdgcn_raw_buffer_store_b128(v, rc, (int)off, 0, kStreamed);
     }
 }
 

@@ -509,7 +509,7 @@ template <class KIND, int TM, int TN, int WGM, int WGN, class OUT, bool SPLIT = 
                 const uint32_t off = ((uint32_t)z * TN * OES + colb < p.n_row_b)
                                          ? c_base + (uint32_t)(s.wm * WM + mi * 32 + row) * p.ldc_b + colb
                                          : p.c_bytes;
-                __builtin_amdgcn_raw_buffer_store_b128(v, s.rc, (int)off, 0, 0);
+                __builtin_amdgcn_raw_buffer_store_b128(v, s.rc, (int)off, 0, kStreamed);
             }
             __syncthreads();
         }
