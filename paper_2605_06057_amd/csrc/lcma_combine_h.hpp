@@ -30,24 +30,18 @@ template <class IN, class HT, class CH> LCMA_DEV void combine_h_tile(const CombH
     const uint32_t row = blockIdx.x * 16 + threadIdx.x / 16;
     const uint32_t colb = (blockIdx.y * 16 + threadIdx.x % 16) * 16; // byte column inside a block of C
     if (colb * HV >= p.h_ld_b) return;
-    float h[CH::NP][EPT];
+    // the planes stay in registers as loaded and are widened where a sum uses them (see forget_derived)
+    u32x4 h[HV][CH::NP];
 #pragma unroll
-    for (int r = 0; r < CH::NP; ++r) {
-        if constexpr (HV == 1) {
-            Widen<HT>::run(__builtin_amdgcn_raw_buffer_load_b128(rh, (int)(row * p.h_ld_b + colb), (int)(r * p.h_plane_b), kStreamed), h[r]);
-        } else {
-            float lo[4], hi[4];
-            Widen<F32>::run(__builtin_amdgcn_raw_buffer_load_b128(rh, (int)(row * p.h_ld_b + colb * 2), (int)(r * p.h_plane_b), kStreamed), lo);
-            Widen<F32>::run(__builtin_amdgcn_raw_buffer_load_b128(rh, (int)(row * p.h_ld_b + colb * 2 + 16), (int)(r * p.h_plane_b), kStreamed), hi);
+    for (int r = 0; r < CH::NP; ++r)
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                h[r][e] = lo[e];
-                h[r][4 + e] = hi[e];
-            }
-        }
-    }
+        for (int q = 0; q < HV; ++q)
+            h[q][r] = __builtin_amdgcn_raw_buffer_load_b128(rh, (int)(row * p.h_ld_b + colb * HV + q * 16), (int)(r * p.h_plane_b), kStreamed);
+    constexpr int HPV = 16 / HT::ES; // elements of a plane per 16-byte vector
 #pragma unroll
     for (int o = 0; o < CH::NC; ++o) {
+#pragma unroll
+        for (int q = 0; q < HV; ++q) forget_derived(h[q]);
         u32x4 v;
         if constexpr (ES == 2) {
 #pragma unroll
@@ -55,8 +49,8 @@ template <class IN, class HT, class CH> LCMA_DEV void combine_h_tile(const CombH
                 float col0[CH::NP], col1[CH::NP];
 #pragma unroll
                 for (int r = 0; r < CH::NP; ++r) {
-                    col0[r] = h[r][2 * e];
-                    col1[r] = h[r][2 * e + 1];
+                    col0[r] = Elem<HT>::get(h[(2 * e) / HPV][r], (2 * e) % HPV);
+                    col1[r] = Elem<HT>::get(h[(2 * e + 1) / HPV][r], (2 * e + 1) % HPV);
                 }
                 v[e] = Round<IN>::run(CH::comb(col0, o)) | (Round<IN>::run(CH::comb(col1, o)) << 16);
             }
@@ -65,7 +59,7 @@ template <class IN, class HT, class CH> LCMA_DEV void combine_h_tile(const CombH
             for (int e = 0; e < 4; ++e) {
                 float col[CH::NP];
 #pragma unroll
-                for (int r = 0; r < CH::NP; ++r) col[r] = h[r][e];
+                for (int r = 0; r < CH::NP; ++r) col[r] = Elem<HT>::get(h[0][r], e);
                 v[e] = Round<IN>::run(CH::comb(col, o));
             }
         }

@@ -11,9 +11,11 @@
 // packed fp16; here the work is HBM-bound and the wider sum is free.)
 //
 // One work-group of 256 threads handles KT x 64 elements (k x n) of every block: it reads the tile of
-// each block that any product uses (one 16-byte vector per thread and block, kept in registers as
-// fp32), and for each r forms the sums, transposes them through LDS and writes 64 rows of KT
-// k-contiguous elements.  HBM traffic is the compulsory K*N*ES in + R/(k*n) * K*N*ES out.
+// each block that any product uses (one or two 16-byte vectors per thread and block, kept in registers
+// as fp32), and for each r forms the sums, transposes them through LDS and writes 64 rows of KT
+// k-contiguous elements: 128 bytes, a whole line, where the registers allow (64 bytes for schemes with more
+// than 9 blocks of B; whole lines and dword LDS writes measured 9 % and more faster for <2,2,2;7>).  HBM traffic is the compulsory K*N*ES in +
+// R/(k*n) * K*N*ES out.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -47,52 +49,109 @@ template <> struct Widen<F16> {
     }
 };
 
+// Element e of a raw 16-byte vector as fp32 (exact).
+template <class IN> struct Elem;
+template <> struct Elem<F32> {
+    static LCMA_DEV float get(u32x4 raw, int e) {
+        const uint32_t w = raw[e]; // (a copy: __builtin_bit_cast applied to the vector element itself reads element 0)
+        return __builtin_bit_cast(float, w);
+    }
+};
+template <> struct Elem<BF16> {
+    static LCMA_DEV float get(u32x4 raw, int e) {
+        return __builtin_bit_cast(float, (e & 1) ? raw[e >> 1] & 0xffff0000u : raw[e >> 1] << 16);
+    }
+};
+template <> struct Elem<F16> {
+    static LCMA_DEV float get(u32x4 raw, int e) { return (float)__builtin_bit_cast(f16x8, raw)[e]; }
+};
+
+// The blocks stay in registers as loaded and are widened where a sum uses them.  Before every product the compiler is
+// made to forget what it derived from them: the sums of different products share parts, and kept alive across the R
+// products of a scheme with many blocks (16 for <4,4,4;49>) those parts fill the register file to one wave per SIMD,
+// which for a kernel that only waits for memory is three times slower.
+template <int NB> LCMA_DEV void forget_derived(u32x4 (&raw)[NB]) {
+#pragma unroll
+    for (int t = 0; t < NB; ++t) asm volatile("" : "+v"(raw[t]));
+}
+
+// 64-byte segments of an output row that one work-group writes: two (whole 128-byte lines) while the raw blocks of two
+// segments fit the registers.  A launcher is handed the number of segments in K/k and divides it by this.
+template <class CH> constexpr int kPrepBSegments = CH::NB <= 9 ? 2 : 1;
+
 // CH (generated): NB raw blocks with b_l(t), b_j(t); NP outputs; comb(in, r) = Eq. 4 for product r on floats;
 // residual(r): plane r holds what rounding that sum to fp16 loses instead of the rounded sum (16-bit types only).
 template <class IN, class CT, class CH> LCMA_DEV void prepare_b_tile(const PrepParams &p) {
     constexpr int ES = IN::ES, EPT = 16 / ES;       // elements per 16-byte vector
-    constexpr int KT = 64 / ES;                     // k rows of the tile (32 or 16): 64-byte output rows
-    constexpr int PITCH = 80;                       // LDS row pitch in bytes (64 of data), 16-byte aligned
+    constexpr int KV = kPrepBSegments<CH>;
+    constexpr int KS = 64 / ES;                     // k rows per 64-byte segment of an output row (32 or 16)
+    constexpr int KT = KV * KS;                     // k rows of the tile
+    constexpr int PITCH = KV * 64 + 16;             // LDS row pitch in bytes, 16-byte aligned
     static_assert(CT::ES == ES, "the output keeps the element size");
     __shared__ __attribute__((aligned(16))) char tile[64 * PITCH];
     const auto rb = __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(p.B), 0, (int)p.b_bytes, 0x00020000);
     const auto rt = __builtin_amdgcn_make_buffer_rsrc(p.Bt, 0, (int)p.bt_bytes, 0x00020000);
     const int tid = threadIdx.x;
-    const int z0 = blockIdx.x * 64, y0 = blockIdx.y * KT;
-    // consecutive lanes take consecutive k rows, so that the transposed LDS writes fall into
-    // consecutive addresses
-    const int ky = tid % KT, tx = tid / KT; // tx: which vector of EPT columns
-    float in[CH::NB][EPT];
+    const int z0 = blockIdx.y * 64, y0 = blockIdx.x * KT;
+    // a lane takes KV consecutive k rows and consecutive lanes the next ones, so that the transposed LDS writes are
+    // whole dwords at consecutive addresses
+    const int ky = tid % KS, tx = tid / KS; // tx: which vector of EPT columns
+    u32x4 in[KV][CH::NB];
 #pragma unroll
-    for (int t = 0; t < CH::NB; ++t) {
-        const uint32_t colb = (uint32_t)CH::b_j(t) * p.b_bcol + (uint32_t)(z0 + tx * EPT) * ES;
-        // columns past N are padding: read from the end of the extent, which returns zero
-        const uint32_t off = colb < p.n_row_b ? (uint32_t)CH::b_l(t) * p.b_brow + (uint32_t)(y0 + ky) * p.ldb_b + colb
-                                              : p.b_bytes;
-        Widen<IN>::run(__builtin_amdgcn_raw_buffer_load_b128(rb, (int)off, 0, 0), in[t]);
-    }
-    // read-back assignment: 4 threads per output row, 16 bytes each
-    const int rn = tid / 4, rc = tid % 4;
+    for (int v = 0; v < KV; ++v)
+#pragma unroll
+        for (int t = 0; t < CH::NB; ++t) {
+            const int k = y0 + KV * ky + v;
+            const uint32_t colb = (uint32_t)CH::b_j(t) * p.b_bcol + (uint32_t)(z0 + tx * EPT) * ES;
+            // columns past N are padding, and so are rows past K/k (they belong to the next block): read from the end
+            // of the extent, which returns zero
+            const uint32_t off = colb < p.n_row_b && k < p.bk ? (uint32_t)CH::b_l(t) * p.b_brow + (uint32_t)k * p.ldb_b + colb
+                                                              : p.b_bytes;
+            in[v][t] = __builtin_amdgcn_raw_buffer_load_b128(rb, (int)off, 0, 0);
+        }
 #pragma unroll
     for (int r = 0; r < CH::NP; ++r) {
 #pragma unroll
-        for (int e = 0; e < EPT; ++e) {
-            float col[CH::NB];
+        for (int v = 0; v < KV; ++v) forget_derived(in[v]);
 #pragma unroll
-            for (int t = 0; t < CH::NB; ++t) col[t] = in[t][e];
-            float o = CH::comb(col, r);
-            if constexpr (ES == 2) {
-                if (CH::residual(r)) o -= (float)(_Float16)o; // what rounding the sum loses (exact in fp32)
+        for (int e = 0; e < EPT; ++e) {
+            float o[KV];
+#pragma unroll
+            for (int v = 0; v < KV; ++v) {
+                float col[CH::NB];
+#pragma unroll
+                for (int t = 0; t < CH::NB; ++t) col[t] = Elem<IN>::get(in[v][t], e);
+                o[v] = CH::comb(col, r);
+                if constexpr (ES == 2) {
+                    if (CH::residual(r)) o[v] -= (float)(_Float16)o[v]; // what rounding the sum loses (exact in fp32)
+                }
             }
-            char *dst = tile + (tx * EPT + e) * PITCH + ky * ES;
-            if constexpr (ES == 2) *(_Float16 *)dst = (_Float16)o; // one rounding, nearest-even
-            else *(float *)dst = o;
+            char *dst = tile + (tx * EPT + e) * PITCH + KV * ky * ES;
+            if constexpr (ES == 2) { // one rounding, nearest-even
+                if constexpr (KV == 2) {
+                    typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+                    const f16x2 h = {(_Float16)o[0], (_Float16)o[1]};
+                    *(f16x2 *)dst = h;
+                } else {
+                    *(_Float16 *)dst = (_Float16)o[0];
+                }
+            } else {
+#pragma unroll
+                for (int v = 0; v < KV; ++v) ((float *)dst)[v] = o[v];
+            }
         }
         __syncthreads();
-        const u32x4 v = *(const u32x4 *)(tile + rn * PITCH + rc * 16);
-        const uint32_t off = (uint32_t)r * p.bt_plane_b + (uint32_t)(z0 + rn) * p.bt_ld_b + (uint32_t)y0 * ES + rc * 16;
-        // (16-byte store: the scalar-offset field stays a literal zero, see Ctx::store_c in lcma_device.hpp)
-        __builtin_amdgcn_raw_buffer_store_b128(v, rt, (int)off, 0, 0);
+        // read back: 4 * KV threads per output row, 16 bytes each
+#pragma unroll
+        for (int i = 0; i < KV; ++i) {
+            const int idx = tid + 256 * i, rn = idx / (4 * KV), rc = idx % (4 * KV);
+            const u32x4 v = *(const u32x4 *)(tile + rn * PITCH + rc * 16);
+            const uint32_t kb = (uint32_t)y0 * ES + rc * 16; // byte column in the row of the plane
+            // a segment past K/k is dropped (stored to the end of the extent)
+            const uint32_t off = kb < (uint32_t)p.bk * ES ? (uint32_t)r * p.bt_plane_b + (uint32_t)(z0 + rn) * p.bt_ld_b + kb : p.bt_bytes;
+            // (16-byte store: the scalar-offset field stays a literal zero, see Ctx::store_c in lcma_device.hpp)
+            __builtin_amdgcn_raw_buffer_store_b128(v, rt, (int)off, 0, 0);
+        }
         __syncthreads();
     }
 }
@@ -111,17 +170,18 @@ template <class IN, class CT, class CH> LCMA_DEV void prepare_bt_tile(const Prep
     const int rn = blockIdx.x * 16 + (int)threadIdx.x / 16;
     const uint32_t kb = (uint32_t)(blockIdx.y * 16 + (int)threadIdx.x % 16) * 16; // byte column inside a block
     if (kb >= p.bt_ld_b) return; // past the padded K/k (whole work-group columns only when K/k < 256 B)
-    float in[CH::NB][EPT];
+    u32x4 in[CH::NB];
 #pragma unroll
     for (int t = 0; t < CH::NB; ++t) {
         // block B_{l,j} of B is block (j, l) of W; rows past N lie outside the extent, columns past K
         // would alias the next row
         const uint32_t colb = (uint32_t)CH::b_l(t) * p.b_bcol + kb;
         const uint32_t off = colb < p.n_row_b ? (uint32_t)CH::b_j(t) * p.b_brow + (uint32_t)rn * p.ldb_b + colb : p.b_bytes;
-        Widen<IN>::run(__builtin_amdgcn_raw_buffer_load_b128(rb, (int)off, 0, 0), in[t]);
+        in[t] = __builtin_amdgcn_raw_buffer_load_b128(rb, (int)off, 0, 0);
     }
 #pragma unroll
     for (int r = 0; r < CH::NP; ++r) {
+        forget_derived(in);
         u32x4 v;
         if constexpr (ES == 2) {
             f16x8 h;
@@ -129,7 +189,7 @@ template <class IN, class CT, class CH> LCMA_DEV void prepare_bt_tile(const Prep
             for (int e = 0; e < EPT; ++e) {
                 float col[CH::NB];
 #pragma unroll
-                for (int t = 0; t < CH::NB; ++t) col[t] = in[t][e];
+                for (int t = 0; t < CH::NB; ++t) col[t] = Elem<IN>::get(in[t], e);
                 float o = CH::comb(col, r);
                 if (CH::residual(r)) o -= (float)(_Float16)o; // what rounding the sum loses (exact in fp32)
                 h[e] = (_Float16)o; // one rounding, nearest-even
@@ -141,7 +201,7 @@ template <class IN, class CT, class CH> LCMA_DEV void prepare_bt_tile(const Prep
             for (int e = 0; e < EPT; ++e) {
                 float col[CH::NB];
 #pragma unroll
-                for (int t = 0; t < CH::NB; ++t) col[t] = in[t][e];
+                for (int t = 0; t < CH::NB; ++t) col[t] = Elem<IN>::get(in[t], e);
                 f[e] = CH::comb(col, r);
             }
             v = __builtin_bit_cast(u32x4, f);
