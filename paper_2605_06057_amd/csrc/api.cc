@@ -332,7 +332,7 @@ lcma_status prepare_b_planes(bool transposed, int64_t N, int64_t K, const void *
         p.n_row_b = (uint32_t)(K * es);       // row length of W
         gx = (int)(bn / 16);
         gy = (int)((bk * es + 255) / 256);
-        if (gy > 65535) return fail(LCMA_ERR_SHAPE, "%s: K is too large", who);
+        if (gx > 65535) return fail(LCMA_ERR_SHAPE, "%s: N is too large", who); // (the rows are the y dimension of the grid)
         err = (own ? stage->launch_comb_bt : pk->launch_t)(&p, gx, gy, stream);
     } else {
         p.b_brow = (uint32_t)(bk * ldb * es);
@@ -340,7 +340,7 @@ lcma_status prepare_b_planes(bool transposed, int64_t N, int64_t K, const void *
         p.n_row_b = (uint32_t)(N * es);
         gx = (int)(bn / 64);
         gy = (int)(bk / kt);
-        if (gy > 65535) return fail(LCMA_ERR_SHAPE, "%s: K is too large", who);
+        if (gx > 65535) return fail(LCMA_ERR_SHAPE, "%s: N is too large", who);
         err = (own ? stage->launch_comb_b : pk->launch)(&p, gx, gy, stream);
     }
     if (err) return fail(LCMA_ERR_HIP, "%s: launch failed with HIP error %d", who, err);

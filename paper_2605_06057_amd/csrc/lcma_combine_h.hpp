@@ -38,10 +38,13 @@ template <class IN, class HT, class CH> LCMA_DEV void combine_h_tile(const CombH
         for (int q = 0; q < HV; ++q)
             h[q][r] = __builtin_amdgcn_raw_buffer_load_b128(rh, (int)(row * p.h_ld_b + colb * HV + q * 16), (int)(r * p.h_plane_b), kStreamed);
     constexpr int HPV = 16 / HT::ES; // elements of a plane per 16-byte vector
+    for_each_const<CH::NC>([&](auto oc_) {
+        constexpr int o = decltype(oc_)::value;
+        // (not where the planes alone overflow the vector registers: fp32 planes of a scheme with 49 products)
+        if constexpr (HV * CH::NP * 4 <= 224) {
 #pragma unroll
-    for (int o = 0; o < CH::NC; ++o) {
-#pragma unroll
-        for (int q = 0; q < HV; ++q) forget_derived(h[q]);
+            for (int q = 0; q < HV; ++q) forget_derived(h[q]);
+        }
         u32x4 v;
         if constexpr (ES == 2) {
 #pragma unroll
@@ -67,7 +70,7 @@ template <class IN, class HT, class CH> LCMA_DEV void combine_h_tile(const CombH
         const uint32_t off = cb < p.n_row_b ? (uint32_t)CH::c_i(o) * p.c_brow + row * p.ldc_b + cb : p.c_bytes;
         // (16-byte store: the scalar-offset field stays a literal zero, see Ctx::store_c in lcma_device.hpp)
         __builtin_amdgcn_raw_buffer_store_b128(v, rc, (int)off, 0, kStreamed);
-    }
+    });
 }
 
 } // namespace lcma

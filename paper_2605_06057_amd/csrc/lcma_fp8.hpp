@@ -20,7 +20,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
-#include "lcma_device.hpp"
+#include "lcma_prepare_b.hpp" // Elem, forget_derived, for_each_const
 
 namespace lcma {
 
@@ -97,7 +97,7 @@ template <class CH> LCMA_DEV void fp8_combine_quantize_tile(const Fp8QuantParams
     const auto rs = __builtin_amdgcn_make_buffer_rsrc(p.S, 0, (int)p.s_bytes, 0x00020000);
     const uint32_t row = blockIdx.x * 16 + threadIdx.x / 16, kb = blockIdx.y, c = threadIdx.x % 16;
     if ((int)row >= p.rows) return;
-    float in[CH::NB][8];
+    u32x4 in[CH::NB]; // as loaded; widened where a sum uses them (see forget_derived)
 #pragma unroll
     for (int t = 0; t < CH::NB; ++t) {
         // blocks are cut from the matrix padded (virtually, with zeros) to whole planes: the block steps are those of
@@ -105,16 +105,17 @@ template <class CH> LCMA_DEV void fp8_combine_quantize_tile(const Fp8QuantParams
         // columns past K are sent there
         const uint32_t colb = (uint32_t)CH::b_l(t) * p.x_bcol + kb * 256 + c * 16;
         const uint32_t off = colb < p.k_row_b ? (uint32_t)CH::b_j(t) * p.x_brow + row * p.ldx_b + colb : p.x_bytes;
-        widen_bf16(__builtin_amdgcn_raw_buffer_load_b128(rx, (int)off, 0, 0), in[t]);
+        in[t] = __builtin_amdgcn_raw_buffer_load_b128(rx, (int)off, 0, 0);
     }
-#pragma unroll
-    for (int r = 0; r < CH::NP; ++r) {
+    for_each_const<CH::NP>([&](auto rc_) {
+        constexpr int r = decltype(rc_)::value;
+        forget_derived(in);
         float v[8], m = 0.f;
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
             float col[CH::NB];
 #pragma unroll
-            for (int t = 0; t < CH::NB; ++t) col[t] = in[t][e];
+            for (int t = 0; t < CH::NB; ++t) col[t] = Elem<BF16>::get(in[t], e);
             v[e] = CH::comb(col, r);
             m = __builtin_fmaxf(m, __builtin_fabsf(v[e]));
         }
@@ -122,7 +123,7 @@ template <class CH> LCMA_DEV void fp8_combine_quantize_tile(const Fp8QuantParams
         const u32x2 q = quantize8(v, sb - 127);
         __builtin_amdgcn_raw_buffer_store_b64(q, rq, (int)(row * p.ldq_b + kb * 128 + c * 8), (int)(r * p.q_plane), 0);
         if (c == 0) __builtin_amdgcn_raw_buffer_store_b8((uint8_t)sb, rs, (int)(row * p.lds_b + kb), (int)(r * p.s_plane), 0);
-    }
+    });
 }
 
 } // namespace lcma

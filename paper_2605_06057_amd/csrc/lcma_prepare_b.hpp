@@ -11,14 +11,15 @@
 // packed fp16; here the work is HBM-bound and the wider sum is free.)
 //
 // One work-group of 256 threads handles KT x 64 elements (k x n) of every block: it reads the tile of
-// each block that any product uses (one or two 16-byte vectors per thread and block, kept in registers
-// as fp32), and for each r forms the sums, transposes them through LDS and writes 64 rows of KT
-// k-contiguous elements: 128 bytes, a whole line, where the registers allow (64 bytes for schemes with more
-// than 9 blocks of B; whole lines and dword LDS writes measured 9 % and more faster for <2,2,2;7>).  HBM traffic is the compulsory K*N*ES in +
+// each block that any product uses (two 16-byte vectors per thread and block, kept in registers as
+// loaded), and for each r forms the sums, transposes them through LDS and writes 64 rows of KT
+// k-contiguous elements: 128 bytes, a whole line.  HBM traffic is the compulsory K*N*ES in +
 // R/(k*n) * K*N*ES out.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+
+#include <utility>
 
 #include "lcma_device.hpp"
 
@@ -49,6 +50,15 @@ template <> struct Widen<F16> {
     }
 };
 
+// f(integral_constant<int, 0>), ..., f(integral_constant<int, N - 1>) in turn.  The loops over the products of a scheme are
+// written with this instead of `#pragma unroll`: every pass selects its sum by a switch over the product, which folds
+// only for a constant, and the unroller gives up on 49 passes of a body that still holds 49 cases (the loop then
+// stays, with a branch tree per element).
+template <class F, int... Is> LCMA_DEV void for_each_const(F &&f, std::integer_sequence<int, Is...>) {
+    (f(std::integral_constant<int, Is>{}), ...);
+}
+template <int N, class F> LCMA_DEV void for_each_const(F &&f) { for_each_const(f, std::make_integer_sequence<int, N>{}); }
+
 // Element e of a raw 16-byte vector as fp32 (exact).
 template <class IN> struct Elem;
 template <> struct Elem<F32> {
@@ -75,15 +85,16 @@ template <int NB> LCMA_DEV void forget_derived(u32x4 (&raw)[NB]) {
     for (int t = 0; t < NB; ++t) asm volatile("" : "+v"(raw[t]));
 }
 
-// 64-byte segments of an output row that one work-group writes: two (whole 128-byte lines) while the raw blocks of two
-// segments fit the registers.  A launcher is handed the number of segments in K/k and divides it by this.
-template <class CH> constexpr int kPrepBSegments = CH::NB <= 9 ? 2 : 1;
+// 64-byte segments of an output row that one work-group of the K x N kernel writes: two, i.e. whole 128-byte lines (with
+// one: 9 % slower for <2,2,2;7>, 26 % for <4,4,4;49>).  A launcher is handed the number of segments in K/k and divides it
+// by this.
+constexpr int kPrepBSegments = 2;
 
 // CH (generated): NB raw blocks with b_l(t), b_j(t); NP outputs; comb(in, r) = Eq. 4 for product r on floats;
 // residual(r): plane r holds what rounding that sum to fp16 loses instead of the rounded sum (16-bit types only).
 template <class IN, class CT, class CH> LCMA_DEV void prepare_b_tile(const PrepParams &p) {
     constexpr int ES = IN::ES, EPT = 16 / ES;       // elements per 16-byte vector
-    constexpr int KV = kPrepBSegments<CH>;
+    constexpr int KV = kPrepBSegments;
     constexpr int KS = 64 / ES;                     // k rows per 64-byte segment of an output row (32 or 16)
     constexpr int KT = KV * KS;                     // k rows of the tile
     constexpr int PITCH = KV * 64 + 16;             // LDS row pitch in bytes, 16-byte aligned
@@ -92,6 +103,8 @@ template <class IN, class CT, class CH> LCMA_DEV void prepare_b_tile(const PrepP
     const auto rb = __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(p.B), 0, (int)p.b_bytes, 0x00020000);
     const auto rt = __builtin_amdgcn_make_buffer_rsrc(p.Bt, 0, (int)p.bt_bytes, 0x00020000);
     const int tid = threadIdx.x;
+    // work-groups that start together cover consecutive pieces of the same 64 rows of the planes (23 % faster at
+    // 8192 x 14336 x 4096 than the other order, which reads B in whole rows instead)
     const int z0 = blockIdx.y * 64, y0 = blockIdx.x * KT;
     // a lane takes KV consecutive k rows and consecutive lanes the next ones, so that the transposed LDS writes are
     // whole dwords at consecutive addresses
@@ -109,8 +122,8 @@ template <class IN, class CT, class CH> LCMA_DEV void prepare_b_tile(const PrepP
                                                               : p.b_bytes;
             in[v][t] = __builtin_amdgcn_raw_buffer_load_b128(rb, (int)off, 0, 0);
         }
-#pragma unroll
-    for (int r = 0; r < CH::NP; ++r) {
+    for_each_const<CH::NP>([&](auto rc_) {
+        constexpr int r = decltype(rc_)::value;
 #pragma unroll
         for (int v = 0; v < KV; ++v) forget_derived(in[v]);
 #pragma unroll
@@ -153,7 +166,7 @@ template <class IN, class CT, class CH> LCMA_DEV void prepare_b_tile(const PrepP
             __builtin_amdgcn_raw_buffer_store_b128(v, rt, (int)off, 0, 0);
         }
         __syncthreads();
-    }
+    });
 }
 
 // The same stage for a weight matrix stored as N x K (row n holds the K inputs of output n, the layout
@@ -166,9 +179,10 @@ template <class IN, class CT, class CH> LCMA_DEV void prepare_bt_tile(const Prep
     static_assert(CT::ES == ES, "the output keeps the element size");
     const auto rb = __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(p.B), 0, (int)p.b_bytes, 0x00020000);
     const auto rt = __builtin_amdgcn_make_buffer_rsrc(p.Bt, 0, (int)p.bt_bytes, 0x00020000);
-    // 256 threads: 16 rows (n) x 16 vectors (k) of every block
-    const int rn = blockIdx.x * 16 + (int)threadIdx.x / 16;
-    const uint32_t kb = (uint32_t)(blockIdx.y * 16 + (int)threadIdx.x % 16) * 16; // byte column inside a block
+    // 256 threads: 16 rows (n) x 16 vectors (k) of every block; work-groups that start together cover consecutive
+    // pieces of the same rows (whole rows of the planes are written at a time: 19 % faster at 4096^3 than row-major order)
+    const int rn = blockIdx.y * 16 + (int)threadIdx.x / 16;
+    const uint32_t kb = (uint32_t)(blockIdx.x * 16 + (int)threadIdx.x % 16) * 16; // byte column inside a block
     if (kb >= p.bt_ld_b) return; // past the padded K/k (whole work-group columns only when K/k < 256 B)
     u32x4 in[CH::NB];
 #pragma unroll
@@ -179,8 +193,8 @@ template <class IN, class CT, class CH> LCMA_DEV void prepare_bt_tile(const Prep
         const uint32_t off = colb < p.n_row_b ? (uint32_t)CH::b_j(t) * p.b_brow + (uint32_t)rn * p.ldb_b + colb : p.b_bytes;
         in[t] = __builtin_amdgcn_raw_buffer_load_b128(rb, (int)off, 0, 0);
     }
-#pragma unroll
-    for (int r = 0; r < CH::NP; ++r) {
+    for_each_const<CH::NP>([&](auto rc_) {
+        constexpr int r = decltype(rc_)::value;
         forget_derived(in);
         u32x4 v;
         if constexpr (ES == 2) {
@@ -209,7 +223,7 @@ template <class IN, class CT, class CH> LCMA_DEV void prepare_bt_tile(const Prep
         const uint32_t off = (uint32_t)r * p.bt_plane_b + (uint32_t)rn * p.bt_ld_b + kb;
         // (16-byte store: the scalar-offset field stays a literal zero, see Ctx::store_c in lcma_device.hpp)
         __builtin_amdgcn_raw_buffer_store_b128(v, rt, (int)off, 0, 0);
-    }
+    });
 }
 
 } // namespace lcma

@@ -268,7 +268,7 @@ lcma_status lcma::gemm_unfused(const char *who, int level, int64_t M, int64_t N,
         p.bn = (int32_t)g.bm;
         p.n_row_b = (uint32_t)(K * es);
         const int64_t gy = (g.bk * es + 255) / 256;
-        if (gy > 65535) return fail(LCMA_ERR_SHAPE, "%s: K is too large", who);
+        if (g.bm / 16 > 65535) return fail(LCMA_ERR_SHAPE, "%s: M is too large", who); // (the rows are the y dimension of the grid)
         if (const int err = sk->launch_comb_a(&p, (int)(g.bm / 16), (int)gy, stream))
             return fail(LCMA_ERR_HIP, "%s: Combine-A launch failed with HIP error %d", who, err);
     }

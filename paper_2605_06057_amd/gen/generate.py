@@ -543,8 +543,8 @@ def emit_stage(s0: Scheme, dtype: str) -> str:
             w("}")
             w("")
             w(f'extern "C" int lcma_launch_comb_{kind}_{s.name}_{dtype}(const lcma::PrepParams *p, int gx, int gy, void *stream) {{')
-            seg = " / kPrepBSegments<CombB> + (gy % kPrepBSegments<CombB> != 0)" if kind == "b" else ""
-            w(f"    lcma_k_comb_{kind}_{s.name}_{dtype}<<<{'dim3(gy' + seg + ', gx)' if kind == 'b' else 'dim3(gx, gy)'}, dim3(256), 0, (hipStream_t)stream>>>(*p);")
+            seg = " / kPrepBSegments + (gy % kPrepBSegments != 0)" if kind == "b" else ""
+            w(f"    lcma_k_comb_{kind}_{s.name}_{dtype}<<<dim3(gy{seg}, gx), dim3(256), 0, (hipStream_t)stream>>>(*p);")
             w("    return (int)hipGetLastError();")
             w("}")
             w("")
@@ -553,7 +553,7 @@ def emit_stage(s0: Scheme, dtype: str) -> str:
     w("}")
     w("")
     w(f'extern "C" int lcma_launch_comb_a_{s.name}_{dtype}(const lcma::PrepParams *p, int gx, int gy, void *stream) {{')
-    w(f"    lcma_k_comb_a_{s.name}_{dtype}<<<dim3(gx, gy), dim3(256), 0, (hipStream_t)stream>>>(*p);")
+    w(f"    lcma_k_comb_a_{s.name}_{dtype}<<<dim3(gy, gx), dim3(256), 0, (hipStream_t)stream>>>(*p);")
     w("    return (int)hipGetLastError();")
     w("}")
     w("")
@@ -635,7 +635,7 @@ def emit_prep_b(s: Scheme, dtype: str) -> str:
     w("")
     w(f'extern "C" int lcma_launch_prep_b_{s.name}_{dtype}(const lcma::PrepParams *p, int gx, int gy, void *stream) {{')
     w("    // gy counts 64-byte segments of a row of a plane; a work-group writes kPrepBSegments of them")
-    w(f"    lcma_k_prep_b_{s.name}_{dtype}<<<dim3(gy / kPrepBSegments<Comb> + (gy % kPrepBSegments<Comb> != 0), gx), dim3(256), 0, (hipStream_t)stream>>>(*p);")
+    w(f"    lcma_k_prep_b_{s.name}_{dtype}<<<dim3(gy / kPrepBSegments + (gy % kPrepBSegments != 0), gx), dim3(256), 0, (hipStream_t)stream>>>(*p);")
     w("    return (int)hipGetLastError();")
     w("}")
     w("")
@@ -645,7 +645,7 @@ def emit_prep_b(s: Scheme, dtype: str) -> str:
     w("}")
     w("")
     w(f'extern "C" int lcma_launch_prep_bt_{s.name}_{dtype}(const lcma::PrepParams *p, int gx, int gy, void *stream) {{')
-    w(f"    lcma_k_prep_bt_{s.name}_{dtype}<<<dim3(gx, gy), dim3(256), 0, (hipStream_t)stream>>>(*p);")
+    w(f"    lcma_k_prep_bt_{s.name}_{dtype}<<<dim3(gy, gx), dim3(256), 0, (hipStream_t)stream>>>(*p);")
     w("    return (int)hipGetLastError();")
     w("}")
     if dtype == "bf16":
