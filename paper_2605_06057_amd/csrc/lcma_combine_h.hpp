@@ -36,12 +36,13 @@ template <class IN, class HT, class CH> LCMA_DEV void combine_h_tile(const CombH
     for (int r = 0; r < CH::NP; ++r)
 #pragma unroll
         for (int q = 0; q < HV; ++q)
-            h[q][r] = __builtin_amdgcn_raw_buffer_load_b128(rh, (int)(row * p.h_ld_b + colb * HV + q * 16), (int)(r * p.h_plane_b), kStreamed);
+            h[q][r] = __builtin_amdgcn_raw_buffer_load_b128(rh, (int)(row * p.h_ld_b + colb * HV + q * 16), (int)(r * p.h_plane_b), 0);
     constexpr int HPV = 16 / HT::ES; // elements of a plane per 16-byte vector
     for_each_const<CH::NC>([&](auto oc_) {
         constexpr int o = decltype(oc_)::value;
-        // (not where the planes alone overflow the vector registers: fp32 planes of a scheme with 49 products)
-        if constexpr (HV * CH::NP * 4 <= 224) {
+        // (only where the widened copies of all planes would not fit beside them and the planes themselves do, <4,4,4;49>
+        // with 16-bit planes: two waves per SIMD instead of one; with fewer planes the barrier only delays the first sums)
+        if constexpr (HV * CH::NP * 4 > 128 && HV * CH::NP * 4 <= 224) {
 #pragma unroll
             for (int q = 0; q < HV; ++q) forget_derived(h[q]);
         }

@@ -22,12 +22,12 @@
 
 namespace lcma {
 
-// Cache-policy operand of the buffer builtins for data written once and read once, or never, by the stages that follow:
-// the products H_r between the batched GEMM and Combine H (Algorithm 1), and C.  Bit 1 = non-temporal: such lines are
+// Cache-policy operand of the buffer builtins for the stores of data that no later stage re-reads from the caches: the
+// products H_r that the batched GEMM of Algorithm 1 hands to Combine H, and C.  Bit 1 = non-temporal: such lines are
 // the first to leave the L2 and the Infinity Cache, instead of displacing the planes At_r / Bt_r that the work-groups of
-// the batched GEMM read again and again.  Measured on the whole of Algorithm 1, bf16: +5 % at 8192 x 14336 x 4096, +7 %
-// at 4096^3.  The inputs A and B of Combine A / Combine B are NOT read this way: the policy makes those two stages 15 %
-// (large shape) to 90 % (4096^3) slower and the pipeline as a whole no faster.
+// the batched GEMM read again and again.  Measured on the whole of Algorithm 1, bf16: +4 % at 8192 x 14336 x 4096, +6 %
+// at 4096^3.  Loads are NOT given the policy: on the inputs A and B it makes Combine A / Combine B 15 % (large shape)
+// to 90 % (4096^3) slower, on the planes H_r in Combine H it gains 0.3 % for fp16 planes and loses 4 % for fp32 planes.
 constexpr int kStreamed = 2;
 
 

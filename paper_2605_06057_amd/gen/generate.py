@@ -451,9 +451,9 @@ def prep_kernels(variants: list[Variant]) -> list[tuple[str, str]]:
 # Measured rates of the stand-alone Combine-A / Combine-B / Combine-H kernels (algorithmic bytes per second at LLM
 # sizes on MI355X, rocprofv3), per scheme and element size; used by the cost model of the unfused dataflow.
 STAGE_RATES = {  # (scheme, 16-bit?) -> (Combine A, Combine B, Combine H)
-    ("strassen", True): (4.9e12, 3.5e12, 5.3e12), ("strassen", False): (5.0e12, 4.5e12, 5.8e12),
-    ("laderman", True): (5.5e12, 3.1e12, 5.0e12), ("laderman", False): (5.0e12, 3.0e12, 5.0e12),
-    ("strassen2", True): (1.7e12, 1.1e12, 4.4e12), ("strassen2", False): (3.5e12, 3.0e12, 5.6e12),
+    ("strassen", True): (5.6e12, 4.5e12, 5.2e12), ("strassen", False): (5.0e12, 4.5e12, 5.8e12),
+    ("laderman", True): (6.0e12, 4.5e12, 4.6e12), ("laderman", False): (5.0e12, 3.0e12, 5.0e12),
+    ("strassen2", True): (6.3e12, 4.2e12, 5.1e12), ("strassen2", False): (3.5e12, 3.0e12, 5.6e12),
 }
 
 
