@@ -790,8 +790,11 @@ def manifest(schemes: dict[str, Scheme] | None = None) -> list[Variant]:
               Variant("plain", dt, 128, 128, tk, occ=2, tb=1, batch=1, rank=95, eff=0.35 if dt == "f16" else 0.86)]
     for dt in ("bf16", "f16", "f32"):
         tk = 16 if dt == "f32" else 32
-        V += [Variant("strassen", dt, 64, 64, tk, chunk=7, pa=1, pb=1, rank=95),
-              Variant("strassen", dt, 128, 128 if dt != "f32" else 64, tk, chunk=1, pa=1, pb=1, rank=95),
+        # (eff: what the GEMM stage of lcma_gemm_unfused level 2 sustains with each at 4096^3 and at the FFN shape: the choice
+        # between the two goes by it)
+        V += [Variant("strassen", dt, 64, 64, tk, chunk=7, pa=1, pb=1, rank=95, eff=0.16 if dt != "f32" else 0.70),
+              Variant("strassen", dt, 128, 128 if dt != "f32" else 64, tk, chunk=1, pa=1, pb=1, rank=95,
+                      eff=0.30 if dt != "f32" else 0.85),
               Variant("laderman", dt, 128 if dt != "f32" else 64, 64, tk, chunk=1, pa=1, pb=1, rank=95)]
         if dt != "f16":
             V += [Variant("strassen2", dt, 64, 64, tk, chunk=7, pa=1, pb=1, rank=95)]
