@@ -62,8 +62,10 @@ namespace {
 // What starting and finishing a tile-product costs, in steps of the large tile: a work-group of its own per tile-product
 // (launch, first loads with nothing to overlap them, epilogue) against a persistent work-group that sends the first
 // loads of its next tile-product during the last step of the current one (measured on the FFN shapes: the batched
-// stage of Algorithm 1, 32 steps per tile-product, gains 9 %, the plain 16-bit product with 64 steps 2 to 4 %).
-const double kTileCost = 5.0, kTileCostPersistent = 2.0;
+// stage of Algorithm 1, 32 steps per tile-product, gains 9 %, the plain 16-bit product with 64 steps 2 to 4 %).  3.5
+// fits both the 32-step tile-products of <2,2,2;7> (0.72 to 0.75 ms for 13 rounds) and the 16-step ones of <4,4,4;49>
+// (0.74 ms for 22 rounds) at the FFN shape; what cannot be hidden is the tile of H_r a work-group writes out.
+const double kTileCost = 5.0, kTileCostPersistent = 3.5;
 // The Split-Group schedule adds the pieces (see below): as long as 80 steps of the large tile.
 const double kSplitCost = 80.0;
 // persist_ok: the persistent whole-tile schedule may be chosen (16-bit operands; the FP8 kernel loses 8 % with it: the
