@@ -64,7 +64,10 @@ template <class KIND, int TM, int TN, int WGM, int WGN, class OUT, bool SPLIT = 
     static constexpr int TILE_FLOATS = TM * TN;
     // the persistent kernel sends the first loads of its next tile-product during the last step of the current one when
     // the epilogue's strips fit the one stage that is free by then
-    static constexpr bool XTILE = SPLIT && DIRECT && NT / 64 * 32 * (WN * OUT::ES + 16) <= STAGE;
+    // rows of the strip a wave passes through LDS at a time in the epilogue: 32, or 16 for fp32 output, so that the strips
+    // of all waves fit one stage
+    static constexpr int STRIP_ROWS = OUT::ES == 4 ? 16 : 32;
+    static constexpr bool XTILE = SPLIT && DIRECT && NT / 64 * STRIP_ROWS * (WN * OUT::ES + 16) <= STAGE;
 
     // 128-byte rows: two rows per 256-byte bank window; 16 consecutive rows at one chunk column spread over the 16
     // chunk positions of a window
@@ -302,10 +305,15 @@ template <class KIND, int TM, int TN, int WGM, int WGN, class OUT, bool SPLIT = 
         //  2  each XCD owns a contiguous eighth of the tile-products (as in the launch with a work-group per tile-product)
         //     and its work-groups take every (units / 8)-th of them.  For a single large product 1 is markedly slower
         //     (all eight XCDs ask the memory side for the same rows at the same time: -17 % on all-zero operands).
+        //     The tile-products of the last, partial round are dealt work-group by work-group instead, i.e. evenly over the
+        //     XCDs (by 32s they would keep two XCDs busy and leave six idle: 448 tile-products of 4096^3 ran 5 % slower than
+        //     with a work-group each).
         const int xcd_jobs = (p.jobs + 7) >> 3, turn = p.interleave == 2 ? p.units >> 3 : p.units;
         const int turn_lo = p.interleave == 2 ? (int)(blockIdx.x & 7) * xcd_jobs : 0;
         const int turn_hi = p.interleave == 2 && turn_lo + xcd_jobs < p.jobs ? turn_lo + xcd_jobs : p.jobs;
-        const int turn_first = p.interleave == 2 ? turn_lo + (int)(blockIdx.x >> 3) : unit;
+        const int whole_rounds = p.jobs / p.units * p.units; // tile-products in whole rounds (1)
+        auto in_round = [&](int base) { return base + (p.interleave == 1 && base >= whole_rounds ? (int)blockIdx.x : unit); };
+        const int turn_first = p.interleave == 2 ? turn_lo + (int)(blockIdx.x >> 3) : in_round(0);
         auto first_piece = [&]() {
             if constexpr (!SPLIT) return Piece{unit, 0, ny, true}; // one work-group per tile-product
             if (p.interleave) return Piece{turn_first, 0, ny, turn_first < turn_hi};
@@ -313,7 +321,11 @@ template <class KIND, int TM, int TN, int WGM, int WGN, class OUT, bool SPLIT = 
         };
         auto piece_after = [&](const Piece &c) {
             if constexpr (!SPLIT) return Piece{0, 0, 0, false};
-            if (p.interleave) return Piece{c.job + turn, 0, ny, c.job + turn < turn_hi};
+            if (p.interleave == 2) return Piece{c.job + turn, 0, ny, c.job + turn < turn_hi};
+            if (p.interleave) {
+                const int job = in_round((c.job / p.units + 1) * p.units);
+                return Piece{job, 0, ny, job < p.jobs};
+            }
             return piece_from(c.job * ny + c.y1);
         };
         // tile of a job: product-major; inside a product tiles run down x inside column panels of `panel` z tiles
@@ -476,43 +488,49 @@ template <class KIND, int TM, int TN, int WGM, int WGN, class OUT, bool SPLIT = 
     }
 
     // Accumulator value v of tile (mi, ni) is row 8 (v / 4) + 4 (lane / 32) + v % 4, column lane % 32: a lane's values
-    // lie in one column.  Each wave passes one 32-row strip of its tile at a time through a private piece of LDS
-    // (the stages are free: every wave has passed the barrier that ends the last step) and writes it out as 16-byte
-    // vectors, whole 128-byte lines.  The scalar-offset field of these stores stays a literal zero (everything is in
-    // the vector offset): the compiler keeps a following vector write at a distance from a store of more than 8 bytes
-    // only then.
+    // lie in one column.  Each wave passes one strip of STRIP_ROWS rows of its tile at a time through a private piece of
+    // LDS (the stages are free: every wave has passed the barrier that ends the last step) and writes it out as 16-byte
+    // vectors, whole 128-byte lines.  A strip is private to its wave and a wave's LDS instructions execute in order, so
+    // no barrier separates its writes from its reads; one barrier at the end keeps the next loads into these stages
+    // behind the last read (eight barriers per tile-product before: the waves no longer wait for each other strip by
+    // strip).  The scalar-offset field of these stores stays a literal zero (everything is in the vector offset): the
+    // compiler keeps a following vector write at a distance from a store of more than 8 bytes only then.
     static LCMA_DEV void store_tile(const PlaneGemmParams &p, const State &s, LCMA_LDS char *lds, int plane, int x, int z,
                                     const f32x16 (&acc)[NMI][NNI]) {
         constexpr int OES = OUT::ES; // 2: C rounded to fp16 / bf16; 4: the fp32 sums as they are
-        constexpr int PITCH = WN * OES + 16, CPRW = WN * OES / 16, NIT = 32 * CPRW / 64;
-        static_assert(NT / 64 * 32 * PITCH <= (XTILE ? STAGE : LDS_BYTES), "the strips of all waves fit the stage buffers");
+        constexpr int SR = STRIP_ROWS, PITCH = WN * OES + 16, CPRW = WN * OES / 16, NIT = SR * CPRW / 64;
+        static_assert(NT / 64 * SR * PITCH <= (XTILE ? STAGE : LDS_BYTES), "the strips of all waves fit the stage buffers");
         const uint32_t c_base = (uint32_t)plane * p.c_plane + (uint32_t)x * TM * p.ldc_b + (uint32_t)z * TN * OES;
-        LCMA_LDS char *strip = lds + s.w * (32 * PITCH);
+        LCMA_LDS char *strip = lds + s.w * (SR * PITCH);
 #pragma unroll
         for (int mi = 0; mi < NMI; ++mi) {
 #pragma unroll
-            for (int ni = 0; ni < NNI; ++ni)
+            for (int h = 0; h < 32 / SR; ++h) {
 #pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    LCMA_LDS char *at = strip + ((v >> 2) * 8 + 4 * s.lh + (v & 3)) * PITCH + (ni * 32 + s.l32) * OES;
-                    if constexpr (OES == 2) *(LCMA_LDS uint16_t *)at = (uint16_t)Round<OUT>::run(acc[mi][ni][v]);
-                    else *(LCMA_LDS float *)at = acc[mi][ni][v];
+                for (int ni = 0; ni < NNI; ++ni)
+#pragma unroll
+                    for (int v = h * (SR / 2); v < (h + 1) * (SR / 2); ++v) {
+                        LCMA_LDS char *at = strip + ((v >> 2) * 8 + 4 * s.lh + (v & 3) - h * SR) * PITCH + (ni * 32 + s.l32) * OES;
+                        if constexpr (OES == 2) *(LCMA_LDS uint16_t *)at = (uint16_t)Round<OUT>::run(acc[mi][ni][v]);
+                        else *(LCMA_LDS float *)at = acc[mi][ni][v];
+                    }
+                __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront"); // (for the compiler: the reads stay behind the writes)
+#pragma unroll
+                for (int it = 0; it < NIT; ++it) {
+                    const int idx = it * 64 + s.lane, row = idx / CPRW, ch = idx % CPRW;
+                    const u32x4 v = *(LCMA_LDS u32x4 *)(strip + row * PITCH + ch * 16);
+                    const uint32_t colb = (uint32_t)(s.wn * WN) * OES + ch * 16; // byte column inside the tile
+                    // a vector past N goes to the end of the extent and is dropped (N is a whole number of vectors); rows
+                    // past M fall outside the extent by themselves
+                    const uint32_t off = ((uint32_t)z * TN * OES + colb < p.n_row_b)
+                                             ? c_base + (uint32_t)(s.wm * WM + mi * 32 + h * SR + row) * p.ldc_b + colb
+                                             : p.c_bytes;
+                    __builtin_amdgcn_raw_buffer_store_b128(v, s.rc, (int)off, 0, kStreamed);
                 }
-            __syncthreads();
-#pragma unroll
-            for (int it = 0; it < NIT; ++it) {
-                const int idx = it * 64 + s.lane, row = idx / CPRW, ch = idx % CPRW;
-                const u32x4 v = *(LCMA_LDS u32x4 *)(strip + row * PITCH + ch * 16);
-                const uint32_t colb = (uint32_t)(s.wn * WN) * OES + ch * 16; // byte column inside the tile
-                // a vector past N goes to the end of the extent and is dropped (N is a whole number of vectors); rows
-                // past M fall outside the extent by themselves
-                const uint32_t off = ((uint32_t)z * TN * OES + colb < p.n_row_b)
-                                         ? c_base + (uint32_t)(s.wm * WM + mi * 32 + row) * p.ldc_b + colb
-                                         : p.c_bytes;
-                __builtin_amdgcn_raw_buffer_store_b128(v, s.rc, (int)off, 0, kStreamed);
+                __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
             }
-            __syncthreads();
         }
+        __syncthreads();
     }
 
     // fp32 partial sums of a piece, in accumulator order (value v of tile (mi, ni) of every thread): the fix-up kernel
