@@ -206,6 +206,13 @@ def test_prepared_b_host_side(B):
     assert L.lcma_prepare_b(256, 256, None, 256, 17, s.handle, None, None) == B.LCMA_ERR_DTYPE
     assert L.lcma_prepare_bt(256, 256, None, 256, B.LCMA_F16, s.handle, None, None) == B.LCMA_ERR_ARG
     assert L.lcma_prepare_bt(256, 512, 0x1000, 256, B.LCMA_F16, s.handle, 0x2000, None) == B.LCMA_ERR_ARG  # ldw < K
+    # the rows of the planes are the y dimension of the Combine kernels' grids (at most 65535 work-groups of 16 rows of W,
+    # or of 64 columns of B): taller matrices are refused, however short their rows
+    P = 0x100000
+    assert L.lcma_prepare_bt(2 * 16 * 65536 + 128, 64, P, 64, B.LCMA_F16, s.handle, P, None) == B.LCMA_ERR_SHAPE
+    assert b"N is too large" in L.lcma_last_error()
+    assert L.lcma_prepare_b(2 * 64 * 65536 + 128, 64, P, 2 * 64 * 65536 + 128, B.LCMA_F16, s.handle, P, None) == B.LCMA_ERR_SHAPE
+    assert b"N is too large" in L.lcma_last_error()
     assert L.lcma_gemm_prepared(256, 256, 256, None, 256, None, None, 256, B.LCMA_F16, None, None) == B.LCMA_ERR_ARG
     assert L.lcma_gemm_prepared(256, 256, 256, None, 256, None, None, 256, B.LCMA_F16, s.handle, None) == B.LCMA_ERR_ARG
     assert b"null" in L.lcma_last_error()
@@ -295,6 +302,9 @@ def test_weight_layout_and_unfused_host_side(B):
     assert unfused(nbytes=3 * 7 * 128 * 128 * 2 - 1) == B.LCMA_ERR_ARG
     assert b"needed" in L.lcma_last_error()
     assert unfused(K=252, lda=256) == B.LCMA_ERR_SHAPE
+    # more than 65535 x 16 rows per block of A: the rows are the y dimension of Combine A's grid
+    assert unfused(M=2 * 16 * 65536 + 256, N=256, K=64, nbytes=1 << 40, dt=B.LCMA_BF16) == B.LCMA_ERR_SHAPE
+    assert b"M is too large" in L.lcma_last_error()
     assert L.lcma_gemm_unfused(1, 256, 256, 0, P, 0, P, 256, None, 256, B.LCMA_F16, s.handle, P, 1 << 30, 0, None) == B.LCMA_ERR_ARG  # K = 0 writes zeros: C is needed
     assert unfused(M=0) == B.LCMA_OK                            # nothing to write
 
