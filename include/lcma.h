@@ -171,7 +171,8 @@ int lcma_variant_b_layout(int index);
  * (l, j) order and the sum is rounded once, to nearest-even.  B: device, K x N row-major, ldb in
  * elements (multiple of 16 bytes).  N and K must be multiples of 16 bytes of elements; the planes
  * hold N/n rows and K/k columns padded with zeros to multiples of 64 and of 32 (16 for F32); both
- * buffers stay below 2 GiB.  Asynchronous on `stream`.  Errors: ARG, BRENT, SHAPE, DTYPE, NOKERNEL
+ * buffers stay below 2 GiB, and the padded N/n is at most 65535 * 64 (lcma_prepare_bt: 65535 * 16), else SHAPE.
+ * Asynchronous on `stream`.  Errors: ARG, BRENT, SHAPE, DTYPE, NOKERNEL
  * (no prepared-B kernels were generated for this scheme and dtype), HIP.
  *
  * lcma_prepared_b_bytes returns R * (padded N/n) * (padded K/k) * element size, or -1 for a bad
@@ -195,7 +196,8 @@ lcma_status lcma_gemm_prepared(int64_t M, int64_t N, int64_t K, const void *A, i
 
 
 /* ------------------------------------------------------------------ the unfused dataflows (Algorithm 1; Algorithm 2 as printed)
- * Provided to be measured against lcma_gemm (the step-wise ablation of Sec. 4.5), not as a faster path.
+ * Provided to be measured against lcma_gemm (the step-wise ablation of Sec. 4.5); for 16-bit storage at large shapes level 1
+ * is the faster form on MI355X, and lcma_gemm_ws (below) chooses between the two.
  *
  * lcma_gemm_unfused computes C = A B like lcma_gemm, with intermediate results in device memory:
  *   level 1  Algorithm 1: four stages, each through device memory: Combine A (Eq. 3) writes At_r,
@@ -214,7 +216,8 @@ lcma_status lcma_gemm_prepared(int64_t M, int64_t N, int64_t K, const void *A, i
  * C is rounded once from fp32.
  * A, B, C, sizes, alignment, padding and errors as for lcma_gemm; `scheme` is required and must be
  * one of the paper's (NOKERNEL otherwise).  workspace: device memory, 256-byte aligned, at least
- * lcma_unfused_workspace_bytes() bytes (-1 for bad arguments), owned by the caller, overwritten.
+ * lcma_unfused_workspace_bytes() bytes (-1 for bad arguments), owned by the caller, overwritten.  Every set of planes stays
+ * below 2 GiB and the padded M/m is at most 65535 * 16 (SHAPE otherwise).
  * reuse_bt != 0 skips Combine B: the Bt_r left in the workspace by an earlier call with the same B, scheme,
  * dtype, N and K are used (the paper's offline Combine B for static weights).  The Bt_r planes lie at the start
  * of the workspace and depend on N and K alone, so M may differ between such calls.
