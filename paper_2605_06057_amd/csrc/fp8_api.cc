@@ -210,6 +210,7 @@ extern "C" lcma_status lcma_fp8_gemm_lcma(int64_t M, int64_t N, int64_t K, const
     const int R = scheme->R;
     if (g.aq >= kLim || g.wq >= kLim || g.h >= kLim || ((g.bm * scheme->m - 1) * ldc + g.bn * scheme->n) * 2 >= kLim)
         return fail(LCMA_ERR_SHAPE, "%s: a matrix or a set of planes spans 2 GiB or more", who);
+    if (g.bm / 16 > 65535) return fail(LCMA_ERR_SHAPE, "%s: M is too large", who); // (rows: the y dimension of Combine H's grid)
     char *Aq = (char *)workspace, *Sa = Aq + g.aq, *H = Sa + g.as;
     const char *Wq = (const char *)Wp, *Sw = Wq + g.wq;
     // stage 1: Combine A (Eq. 3) with the quantisation fused in
@@ -255,7 +256,6 @@ extern "C" lcma_status lcma_fp8_gemm_lcma(int64_t M, int64_t N, int64_t K, const
     h.c_bcol = (uint32_t)(g.bn * 2);
     h.n_row_b = (uint32_t)(N * 2);
     const int64_t gy = (g.bn * 2 + 255) / 256;
-    if (gy > 65535) return fail(LCMA_ERR_SHAPE, "%s: N is too large", who);
     if (const int err = sk->launch_comb_h(&h, (int)(g.bm / 16), (int)gy, stream))
         return fail(LCMA_ERR_HIP, "%s: Combine-H launch failed with HIP error %d", who, err);
     return LCMA_OK;

@@ -26,9 +26,10 @@ template <class IN, class HT, class CH> LCMA_DEV void combine_h_tile(const CombH
     static_assert(HT::ES == ES || (HT::ES == 4 && ES == 2), "planes in the element size of C, or fp32 planes for 16-bit C");
     const auto rh = __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(p.H), 0, (int)p.h_bytes, 0x00020000);
     const auto rc = __builtin_amdgcn_make_buffer_rsrc(p.C, 0, (int)p.c_bytes, 0x00020000);
-    // 256 threads: 16 rows x 16 vectors (256 bytes of a row of C)
-    const uint32_t row = blockIdx.x * 16 + threadIdx.x / 16;
-    const uint32_t colb = (blockIdx.y * 16 + threadIdx.x % 16) * 16; // byte column inside a block of C
+    // 256 threads: 16 rows x 16 vectors (256 bytes of a row of C); work-groups that start together cover consecutive pieces
+    // of the same rows (4 to 24 % faster than consecutive rows of the same piece)
+    const uint32_t row = blockIdx.y * 16 + threadIdx.x / 16;
+    const uint32_t colb = (blockIdx.x * 16 + threadIdx.x % 16) * 16; // byte column inside a block of C
     if (colb * HV >= p.h_ld_b) return;
     // the planes stay in registers as loaded and are widened where a sum uses them (see forget_derived)
     u32x4 h[HV][CH::NP];

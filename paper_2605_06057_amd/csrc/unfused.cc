@@ -250,6 +250,8 @@ lcma_status lcma::gemm_unfused(const char *who, int level, int64_t M, int64_t N,
     const Variant *gemm = level == 1 ? find_gemm(true, LCMA_PLAIN, ct, R, g) : find_gemm(false, id, dtype, scheme->R, g);
     if (!gemm) return fail(LCMA_ERR_NOKERNEL, "%s: no GEMM stage kernel for level %d fits the planes", who, level);
 
+    // (the rows of the planes are the y dimension of the grids of Combine A and Combine H)
+    if (g.bm / 16 > 65535) return fail(LCMA_ERR_SHAPE, "%s: M is too large", who);
     const int stages = tuning_unfused_stages(); // measurement aid: stages switched off keep the output of an earlier call
     // stage 1: Combine A (Eq. 3).  A takes the place of an N x K weight matrix in the Combine-B kernel
     // for that layout: block A_{i,l} is block (i, l), rows are k-contiguous.
@@ -268,7 +270,6 @@ lcma_status lcma::gemm_unfused(const char *who, int level, int64_t M, int64_t N,
         p.bn = (int32_t)g.bm;
         p.n_row_b = (uint32_t)(K * es);
         const int64_t gy = (g.bk * es + 255) / 256;
-        if (g.bm / 16 > 65535) return fail(LCMA_ERR_SHAPE, "%s: M is too large", who); // (the rows are the y dimension of the grid)
         if (const int err = sk->launch_comb_a(&p, (int)(g.bm / 16), (int)gy, stream))
             return fail(LCMA_ERR_HIP, "%s: Combine-A launch failed with HIP error %d", who, err);
     }
@@ -346,7 +347,6 @@ lcma_status lcma::gemm_unfused(const char *who, int level, int64_t M, int64_t N,
         h.c_bcol = (uint32_t)(g.bn * es);
         h.n_row_b = (uint32_t)(N * es);
         const int64_t gy = (g.bn * es + 255) / 256;
-        if (gy > 65535) return fail(LCMA_ERR_SHAPE, "%s: N is too large", who);
         if (const int err = (h_es != es ? sk->launch_comb_h32 : sk->launch_comb_h)(&h, (int)(g.bm / 16), (int)gy, stream))
             return fail(LCMA_ERR_HIP, "%s: Combine-H launch failed with HIP error %d", who, err);
     } else {

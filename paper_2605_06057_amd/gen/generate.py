@@ -573,7 +573,7 @@ def emit_stage(s0: Scheme, dtype: str) -> str:
     w("}")
     w("")
     w(f'extern "C" int lcma_launch_comb_h_{s.name}_{dtype}(const lcma::CombHParams *p, int gx, int gy, void *stream) {{')
-    w(f"    lcma_k_comb_h_{s.name}_{dtype}<<<dim3(gx, gy), dim3(256), 0, (hipStream_t)stream>>>(*p);")
+    w(f"    lcma_k_comb_h_{s.name}_{dtype}<<<dim3(gy, gx), dim3(256), 0, (hipStream_t)stream>>>(*p);")
     w("    return (int)hipGetLastError();")
     w("}")
     if dtype != "f32":  # the same sums from planes that hold the products in fp32
@@ -583,7 +583,7 @@ def emit_stage(s0: Scheme, dtype: str) -> str:
         w("}")
         w("")
         w(f'extern "C" int lcma_launch_comb_h32_{s.name}_{dtype}(const lcma::CombHParams *p, int gx, int gy, void *stream) {{')
-        w(f"    lcma_k_comb_h32_{s.name}_{dtype}<<<dim3(gx, gy), dim3(256), 0, (hipStream_t)stream>>>(*p);")
+        w(f"    lcma_k_comb_h32_{s.name}_{dtype}<<<dim3(gy, gx), dim3(256), 0, (hipStream_t)stream>>>(*p);")
         w("    return (int)hipGetLastError();")
         w("}")
     return "\n".join(L) + "\n"
