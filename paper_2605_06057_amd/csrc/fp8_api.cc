@@ -73,7 +73,7 @@ extern "C" lcma_status lcma_fp8_quantize(int64_t rows, int64_t K, const void *X,
     if (K % 8) return fail(LCMA_ERR_SHAPE, "%s: K = %lld must be a multiple of 8 (16 bytes of bf16)", who, (long long)K);
     const int64_t kp = round_up(K, 128), ls = round_up(kp / 128, 4);
     if (((rows - 1) * ldx + kp) * 2 >= kLim || rows * kp >= kLim) return fail(LCMA_ERR_SHAPE, "%s: a matrix spans 2 GiB or more", who);
-    if (kp / 128 > 65535) return fail(LCMA_ERR_SHAPE, "%s: K is too large", who);
+    if ((rows + 15) / 16 > 65535) return fail(LCMA_ERR_SHAPE, "%s: too many rows", who); // (the y dimension of the grid)
     Fp8QuantParams p;
     std::memset(&p, 0, sizeof p);
     p.X = X;
@@ -146,7 +146,7 @@ lcma_status combine_quantize(const char *who, int (*launch)(const Fp8QuantParams
                              int grid_k, void *Q, void *S, void *stream) {
     if (((grid_rows * brows - 1) * ldx + grid_k * bk) * 2 >= kLim || (int64_t)R * brows * bk >= kLim)
         return fail(LCMA_ERR_SHAPE, "%s: a matrix or a set of planes spans 2 GiB or more", who);
-    if (bk / 128 > 65535) return fail(LCMA_ERR_SHAPE, "%s: K is too large", who);
+    if (brows / 16 > 65535) return fail(LCMA_ERR_SHAPE, "%s: too many rows", who); // (the y dimension of the grid)
     Fp8QuantParams p;
     std::memset(&p, 0, sizeof p);
     p.X = X;

@@ -74,7 +74,8 @@ LCMA_DEV void fp8_quantize_rows_tile(const Fp8QuantParams &p) {
     const auto rx = __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(p.X), 0, (int)p.x_bytes, 0x00020000);
     const auto rq = __builtin_amdgcn_make_buffer_rsrc(p.Q, 0, (int)p.q_bytes, 0x00020000);
     const auto rs = __builtin_amdgcn_make_buffer_rsrc(p.S, 0, (int)p.s_bytes, 0x00020000);
-    const uint32_t row = blockIdx.x * 16 + threadIdx.x / 16, kb = blockIdx.y, c = threadIdx.x % 16;
+    // (work-groups that start together cover consecutive 128-element blocks of the same 16 rows)
+    const uint32_t row = blockIdx.y * 16 + threadIdx.x / 16, kb = blockIdx.x, c = threadIdx.x % 16;
     if ((int)row >= p.rows) return;
     const uint32_t colb = kb * 256 + c * 16; // byte column in X
     float v[8];
@@ -95,7 +96,8 @@ template <class CH> LCMA_DEV void fp8_combine_quantize_tile(const Fp8QuantParams
     const auto rx = __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(p.X), 0, (int)p.x_bytes, 0x00020000);
     const auto rq = __builtin_amdgcn_make_buffer_rsrc(p.Q, 0, (int)p.q_bytes, 0x00020000);
     const auto rs = __builtin_amdgcn_make_buffer_rsrc(p.S, 0, (int)p.s_bytes, 0x00020000);
-    const uint32_t row = blockIdx.x * 16 + threadIdx.x / 16, kb = blockIdx.y, c = threadIdx.x % 16;
+    // (work-groups that start together cover consecutive 128-element blocks of the same 16 rows)
+    const uint32_t row = blockIdx.y * 16 + threadIdx.x / 16, kb = blockIdx.x, c = threadIdx.x % 16;
     if ((int)row >= p.rows) return;
     u32x4 in[CH::NB]; // as loaded; widened where a sum uses them (see forget_derived)
 #pragma unroll

@@ -564,7 +564,7 @@ def emit_stage(s0: Scheme, dtype: str) -> str:
         w("}")
         w("")
         w(f'extern "C" int lcma_launch_fp8_comb_a_{s.name}(const lcma::Fp8QuantParams *p, int gx, int gy, void *stream) {{')
-        w(f"    lcma_k_fp8_comb_a_{s.name}<<<dim3(gx, gy), dim3(256), 0, (hipStream_t)stream>>>(*p);")
+        w(f"    lcma_k_fp8_comb_a_{s.name}<<<dim3(gy, gx), dim3(256), 0, (hipStream_t)stream>>>(*p);")
         w("    return (int)hipGetLastError();")
         w("}")
         w("")
@@ -656,7 +656,7 @@ def emit_prep_b(s: Scheme, dtype: str) -> str:
         w("}")
         w("")
         w(f'extern "C" int lcma_launch_fp8_prep_w_{s.name}(const lcma::Fp8QuantParams *p, int gx, int gy, void *stream) {{')
-        w(f"    lcma_k_fp8_prep_w_{s.name}<<<dim3(gx, gy), dim3(256), 0, (hipStream_t)stream>>>(*p);")
+        w(f"    lcma_k_fp8_prep_w_{s.name}<<<dim3(gy, gx), dim3(256), 0, (hipStream_t)stream>>>(*p);")
         w("    return (int)hipGetLastError();")
         w("}")
     return "\n".join(L) + "\n"
