@@ -366,7 +366,9 @@ double lcma_predict_seconds(int scheme_id, int64_t M, int64_t N, int64_t K, lcma
  *   "variant"          LCMA_VARIANT=<name>          lcma_gemm / lcma_gemm_prepared run this generated kernel when it belongs
  *                                                   to the requested scheme, dtype and layout (otherwise ignored)
  *   "unfused_variant"  LCMA_UNFUSED_VARIANT=<name>  the same for the GEMM stage of lcma_gemm_unfused
- *   "panel"            LCMA_PANEL=<n>               width, in tiles, of the column panels of the tile order (default 8)
+ *   "panel"            LCMA_PANEL=<n>               width, in tiles, of the column panels of the tile order (default 8; the
+ *                                                   plane GEMM then takes 7, 6 or 5 where that divides the columns of tiles
+ *                                                   and 8 does not)
  *   "batch_order"      LCMA_BATCH_ORDER=1           batched GEMM of lcma_gemm_unfused level 1 in group-major instead of
  *                                                   product-major order
  *   "schedule"         LCMA_SCHEDULE=static|split|persist   batched GEMM stages: one tile-product per work-group, contiguous
