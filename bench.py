@@ -489,6 +489,18 @@ def main():
     peak = PEAK_TFLOPS[dt]
 
     # parity on sampled rows (one row range inside every block row of the scheme grid)
+    # what the matrix pipe alone sustains on zeros and on this workload's values (16-bit storage; no memory traffic at all):
+    # on MI355X the second is well below the first, and it, not the dense peak, is what a kernel could reach on these inputs
+    pipe = None
+    if dt != "f32" and not args.no_extras:
+        sink = torch.empty((512 * 1024,), dtype=torch.float32, device="cuda")
+        pipe = {"unit": "TFLOP/s", "kernel": "lcma_mfma_probe: 32x32x16 fp16 MFMA on fragments held in registers"}
+        for key, src in (("zeros", torch.zeros((32768,), dtype=torch.float16, device="cuda")),
+                         ("values_of_A", sets[0][0].reshape(-1)[:32768].to(torch.float16).contiguous())):
+            iters = 10000
+            probe_flops = B.lcma_mfma_probe(src, sink, iters)
+            _, p_ms, _ = timed(lambda i: B.lcma_mfma_probe(src, sink, iters), 8, 2)
+            pipe[key] = probe_flops / (p_ms * 1e-3) / 1e12
     lcma_step(0)
     plain_step(1)
     torch.cuda.synchronize()
@@ -561,6 +573,9 @@ def main():
                      "kernel": kernel_name, "kernel_ms": kernel_ms},
         "cpu_baseline": cpu,
     }
+    if pipe:
+        pipe["roofline_achieved_over_values_of_A"] = achieved / pipe["values_of_A"]
+        out["mfma_pipe_alone"] = pipe
     if stage_ms:
         out["algorithm1_stage_ms_events"] = stage_ms
         out["fused_kernel_tflops"] = fused_tf

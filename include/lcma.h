@@ -110,6 +110,15 @@ lcma_status lcma_gemm(int64_t M, int64_t N, int64_t K,
  * multiple of 8.  One pass over X at memory speed.  Errors: ARG, SHAPE, HIP. */
 lcma_status lcma_fp16_range_flags(int64_t rows, int64_t cols, const void *X, int64_t ld, void *flags, void *stream);
 
+/* Measurement aid, not part of the path: what the matrix pipe sustains on given operand VALUES with no memory traffic at
+ * all (the 16-bit roofline of a power-limited chip: MI355X runs dense fp16 / bf16 products of random values well below
+ * the rate it reaches on zeros).  2048 work-groups of four waves; every wave takes eight fragments from `operands`
+ * (device, 64 KiB = 4096 vectors of eight fp16 values, 16-byte aligned, read only) and runs `iters` (1 .. 10^7) rounds of
+ * eight independent 32x32x16 fp16 MFMA instructions; one float per thread goes to `sink` (device, 2 MiB, overwritten).
+ * *flops (host, may be NULL) receives the floating-point operations of the launch, 2048 * 4 * iters * 8 * 32768; the
+ * caller times the launch.  Asynchronous on `stream`.  Errors: ARG, HIP. */
+lcma_status lcma_mfma_probe(const void *operands, void *sink, int64_t iters, double *flops, void *stream);
+
 /* lcma_gemm with the right operand given the way a linear layer stores its weight (the operand the
  * paper's end-to-end evaluation multiplies by): W is N x K row-major, ldw in elements, and
  * C[M x N] = A[M x K] x W^T, that is B[k][n] = W[n][k] in Eq. 1.  Everything else (types, sizes,

@@ -30,7 +30,7 @@ EXPORTS = [
     "lcma_scheme_name", "lcma_scheme_id_max", "lcma_variant_prepared", "lcma_prepared_b_bytes", "lcma_prepare_b", "lcma_prepare_bt", "lcma_gemm_prepared",
     "lcma_gemm_nt", "lcma_variant_b_layout", "lcma_unfused_workspace_bytes", "lcma_gemm_unfused",
     "lcma_predict_unfused_seconds", "lcma_select_dataflow", "lcma_gemm_ex", "lcma_set_tuning",
-    "lcma_static_scratch_bytes", "lcma_gemm_unfused_static", "lcma_split_group_scratch_bytes", "lcma_gemm_nt_ws", "lcma_gemm_ws", "lcma_fp16_range_flags",
+    "lcma_static_scratch_bytes", "lcma_gemm_unfused_static", "lcma_split_group_scratch_bytes", "lcma_gemm_nt_ws", "lcma_gemm_ws", "lcma_fp16_range_flags", "lcma_mfma_probe",
     "lcma_fp8_code_pitch", "lcma_fp8_scale_pitch", "lcma_fp8_quantize", "lcma_fp8_gemm_nt", "lcma_fp8_prepared_w_bytes",
     "lcma_fp8_prepare_w", "lcma_fp8_workspace_bytes", "lcma_fp8_gemm_lcma",
 ]
@@ -115,6 +115,7 @@ def lib() -> ctypes.CDLL:
         L.lcma_gemm_nt_ws.argtypes = [i64, i64, i64, vp, i64, vp, i64, vp, i64, i32, vp, i64, vp]
         L.lcma_gemm_ws.argtypes = [i32, i64, i64, i64, vp, i64, vp, i64, vp, i64, i32, vp, vp, i64, ctypes.POINTER(ctypes.c_int), vp]
         L.lcma_fp16_range_flags.argtypes = [i64, i64, vp, i64, vp, vp]
+        L.lcma_mfma_probe.argtypes = [vp, vp, i64, ctypes.POINTER(ctypes.c_double), vp]
         L.lcma_split_group_scratch_bytes.argtypes = []
         L.lcma_split_group_scratch_bytes.restype = i64
         L.lcma_static_scratch_bytes.argtypes = []
@@ -289,6 +290,17 @@ def lcma_fp16_range_flags(X) -> int:
     stream = torch.cuda.current_stream(X.device).cuda_stream
     _check(lib().lcma_fp16_range_flags(X.shape[0], X.shape[1], X.data_ptr(), X.stride(0), flags.data_ptr(), stream))
     return int(flags.item())
+
+
+def lcma_mfma_probe(operands, sink, iters: int) -> float:
+    """Launches the matrix-pipe probe on the fp16 values in `operands` (device, >= 64 KiB); returns the flops of the launch."""
+    import torch
+    assert operands.is_cuda and operands.is_contiguous() and operands.numel() * operands.element_size() >= 65536
+    assert sink.is_cuda and sink.is_contiguous() and sink.numel() * sink.element_size() >= 2 * 1024 * 1024
+    flops = ctypes.c_double(0.0)
+    stream = torch.cuda.current_stream(operands.device).cuda_stream
+    _check(lib().lcma_mfma_probe(operands.data_ptr(), sink.data_ptr(), iters, ctypes.byref(flops), stream))
+    return flops.value
 
 
 def lcma_split_group_scratch_bytes() -> int:

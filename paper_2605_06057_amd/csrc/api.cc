@@ -453,6 +453,17 @@ extern "C" lcma_status lcma_fp16_range_flags(int64_t rows, int64_t cols, const v
     return LCMA_OK;
 }
 
+extern "C" lcma_status lcma_mfma_probe(const void *operands, void *sink, int64_t iters, double *flops, void *stream) {
+    const char *who = "lcma_mfma_probe";
+    if (!operands || !sink || ((uintptr_t)operands & 15) || ((uintptr_t)sink & 3))
+        return fail(LCMA_ERR_ARG, "%s: operands (64 KiB, 16-byte aligned) and sink (2 MiB, 4-byte aligned) are required", who);
+    if (iters < 1 || iters > 10000000) return fail(LCMA_ERR_ARG, "%s: iters must be between 1 and 10^7", who);
+    if (flops) *flops = 2048.0 * 4.0 * (double)iters * 8.0 * (2.0 * 32 * 32 * 16);
+    if (const int err = lcma_launch_mfma_probe(operands, sink, (int)iters, stream))
+        return fail(LCMA_ERR_HIP, "%s: launch failed with HIP error %d", who, err);
+    return LCMA_OK;
+}
+
 extern "C" lcma_status lcma_set_tuning(const char *key, const char *value) {
     if (!key) return fail(LCMA_ERR_ARG, "lcma_set_tuning: null key");
     init_tuning();

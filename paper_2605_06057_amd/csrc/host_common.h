@@ -136,3 +136,4 @@ bool variant_fits(const Variant &v, int64_t M, int64_t N, int64_t K);
 // hand-written auxiliary kernels (csrc/lcma_aux.hip); return a hipError_t
 extern "C" int lcma_launch_range_flags_bf16(const void *X, int64_t rows, int64_t row_bytes, int64_t ld_bytes, void *flags, void *stream);
 extern "C" int lcma_launch_scale_c(void *C, int64_t rows, int64_t row_bytes, int64_t ld_bytes, int dtype, float beta, void *stream);
+extern "C" int lcma_launch_mfma_probe(const void *src, void *sink, int iters, void *stream);

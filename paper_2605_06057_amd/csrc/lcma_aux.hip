@@ -54,7 +54,38 @@ __global__ __launch_bounds__(256) void range_flags_bf16(const char *X, int64_t r
     if (found) atomicOr(flags, found);
 }
 __global__ void zero_word(uint32_t *w) { *w = 0; }
+// Measurement aid: what the matrix pipe sustains with no memory traffic at all.  Every wave takes eight fragments from
+// `src` (4096 vectors of eight fp16 values) and runs `iters` rounds of eight independent 32x32x16 fp16 instructions on them
+// (eight accumulator tiles, two waves per SIMD: the pipe is never waiting for a result).  On MI355X the rate depends on the
+// VALUES: the chip runs into its power limit on operands that toggle many bits.
+__global__ __launch_bounds__(256, 2) void mfma_probe(const f16x8 *src, float *sink, int iters) {
+    f16x8 a[4], b[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        a[i] = src[(threadIdx.x + 256 * i) & 4095];
+        b[i] = src[(threadIdx.x * 7 + 64 * i + 13) & 4095];
+    }
+    f32x16 acc[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) zero(acc[i]);
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[i & 3], b[(i >> 1) & 3], acc[i], 0, 0, 0);
+    }
+    float sum = 0.f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) sum += acc[i][e];
+    sink[blockIdx.x * 256 + threadIdx.x] = sum; // (keeps the loop alive)
+}
 } // namespace
+
+// 2048 work-groups of 256 threads; src: 64 KiB, sink: 2 MiB
+extern "C" int lcma_launch_mfma_probe(const void *src, void *sink, int iters, void *stream) {
+    mfma_probe<<<dim3(2048), dim3(256), 0, (hipStream_t)stream>>>((const f16x8 *)src, (float *)sink, iters);
+    return (int)hipGetLastError();
+}
 
 extern "C" int lcma_launch_range_flags_bf16(const void *X, int64_t rows, int64_t row_bytes, int64_t ld_bytes, void *flags, void *stream) {
     const hipStream_t st = (hipStream_t)stream;

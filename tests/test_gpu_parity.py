@@ -336,3 +336,17 @@ def test_wide_stores_keep_their_data_registers(B):
             run(c)
             torch.cuda.synchronize()
             assert np.array_equal(G.to_host_stored(c, dt).view(np.uint8), want.view(np.uint8)), (dt, name)
+
+
+def test_mfma_probe_counts_what_it_says(B):
+    """The matrix-pipe probe: on all-one fragments every accumulator value grows by 16 per round, a thread holds 8 tiles of 16
+    values, so it reports 2048 * iters; on zeros it reports zero; the flops are those of the launch."""
+    import torch
+    sink = torch.full((512 * 1024,), float("nan"), dtype=torch.float32, device="cuda")
+    for value, iters in ((1.0, 3), (0.0, 5)):
+        src = torch.full((32768,), value, dtype=torch.float16, device="cuda")
+        print(f"mfma probe value {value} iters {iters}", flush=True)
+        flops = B.lcma_mfma_probe(src, sink, iters)
+        torch.cuda.synchronize()
+        assert flops == 2048 * 4 * iters * 8 * 2 * 32 * 32 * 16
+        assert bool((sink == value * 2048 * iters).all().item())

@@ -358,6 +358,20 @@ def test_selector_over_both_dataflows(B):
     assert L.lcma_select_dataflow(0, 4096, 4096, bf16, 0, ctypes.byref(out)) == B.LCMA_ERR_ARG
 
 
+def test_mfma_probe_argument_checks(B):
+    """The matrix-pipe probe refuses bad arguments before it launches anything, and reports the flops of a launch."""
+    import ctypes
+    L = B.lib()
+    P = 0x100000
+    flops = ctypes.c_double(-1.0)
+    assert L.lcma_mfma_probe(None, P, 10, ctypes.byref(flops), None) == B.LCMA_ERR_ARG
+    assert L.lcma_mfma_probe(P, None, 10, ctypes.byref(flops), None) == B.LCMA_ERR_ARG
+    assert L.lcma_mfma_probe(P + 8, P, 10, ctypes.byref(flops), None) == B.LCMA_ERR_ARG
+    assert L.lcma_mfma_probe(P, P, 0, ctypes.byref(flops), None) == B.LCMA_ERR_ARG
+    assert L.lcma_mfma_probe(P, P, 10 ** 7 + 1, ctypes.byref(flops), None) == B.LCMA_ERR_ARG
+    assert flops.value == -1.0
+
+
 def test_wide_buffer_stores_have_a_literal_zero_scalar_offset():
     """A buffer store of more than 8 bytes whose scalar-offset operand is a register was seen to have its data
     registers overwritten by the next vector instruction (the compiler keeps the distance only without a scalar
