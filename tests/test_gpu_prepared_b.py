@@ -168,3 +168,25 @@ def test_prepared_error_paths_launch_nothing(B):
     torch.cuda.synchronize()
     assert torch.all(c == 3.0) and torch.all(bt3 == 0)
     B.lcma_gemm_prepared(b[:0], bt, torch.empty((0, 256), dtype=torch.float16, device="cuda"), h)  # M = 0
+
+
+@pytest.mark.parametrize("name,dt", [("laderman", "bf16"), ("laderman", "f16"), ("laderman", "f32"), ("strassen2", "bf16"),
+                                     ("strassen2", "f32")])
+def test_prepare_b_of_the_high_rank_schemes_bit_for_bit(B, name, dt):
+    """Combine B of <3,3,3;23> and <4,4,4;49> in both layouts of B against the oracle's stored Combine B, bit for bit; K/k is
+    one and a half times what a work-group of the K x N kernel covers, so its last work-group writes half a line."""
+    import torch
+    import gpu_util as G
+    s = S.by_name(name)
+    h = B.lcma_scheme_load("builtin:" + name)
+    kt = 16 if dt == "f32" else 32
+    N, K = s.n * 128, s.k * 3 * kt
+    print(f"prepare_b {name} {dt} N={N} K={K}", flush=True)
+    _, Bs = inp.matrices("uniform", "weights", 64, N, K, dt, seed=31)
+    want = oracle.combine_b_stored(s, inp.widen(Bs, dt), dt)
+    b = G.to_device(Bs, dt)
+    bt_b = B.lcma_prepare_b(b, h)
+    bt_w = B.lcma_prepare_bt(b.t().contiguous(), h)
+    assert tuple(bt_b.shape) == (s.R, N // s.n, K // s.k)
+    assert np.array_equal(prepared_to_host(bt_b), want)
+    assert torch.equal(bt_w.view(torch.uint8), bt_b.view(torch.uint8))
