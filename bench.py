@@ -512,7 +512,6 @@ def main():
         Aw, Bw = inp.widen(As, dt), inp.widen(Bs, dt)
         t0 = time.perf_counter()
         ref = oracle.gemm_rows(Aw, Bw, rows)
-        t_small = time.perf_counter() - t0
 
         def host(t):
             t = t[torch.from_numpy(rows).cuda()]
@@ -531,8 +530,12 @@ def main():
         if ablation:
             for key in ("algorithm1", "algorithm2_as_printed"):
                 ablation[key + "_rel_frobenius_error"] = oracle.rel_frobenius(host(ablation["_c" + key]), ref)
-        # timed sample: as many leading rows as fit the CPU budget, judged from the small run
-        rate = 2.0 * len(rows) * N * K / max(t_small, 1e-6)
+        # timed sample: as many leading rows as fit the CPU budget, judged from a run on 256 rows (the parity run on a
+        # handful of rows is too short to tell the rate of a long one)
+        probe_rows = int(min(M, 256))
+        t0 = time.perf_counter()
+        oracle.gemm_rows(Aw, Bw, np.arange(probe_rows))
+        rate = 2.0 * probe_rows * N * K / max(time.perf_counter() - t0, 1e-6)
         nrows = int(min(M, max(len(rows), args.cpu_seconds * rate / (2.0 * N * K))))
         t0 = time.perf_counter()
         oracle.gemm_rows(Aw, Bw, np.arange(nrows))
